@@ -1,0 +1,200 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused SwiGLU MLP hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+Workload (the configuration the headline metric is quoted on): the
+Llama-3-8B-shaped MLP layer, d_model=4096, d_ff=14336, bf16, at M in
+{1, 2, 4, 8, 16}.  One "step" is one pass of the whole hot path over one batch
+of synthetic input: one dfk_swiglu_mlp call for each M of the set, each call on
+the next of several distinct weight sets (so weights stream from HBM, never
+from the 256 MB last-level cache).  Inputs are seeded synthetic tensors,
+resident in HBM before the timed region.  Before timing, the profile-driven
+scheduler tunes the (variant, tile) choice per M - the pre-inference step of
+the method - and its picks are reported.
+
+Prints ONE JSON line: value = mean microseconds per call over the step's
+calls; roofline = algorithmic HBM bytes per call / measured time per call,
+against the 8 TB/s peak; cpu_baseline = the fp64 oracle on the host cores
+over one step of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+D_MODEL, D_FF = 4096, 14336
+M_SET = (1, 2, 4, 8, 16)
+WEIGHT_SETS = 4
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes(M, d_model, d_ff):
+    """Three bf16 weight matrices read once + X read + Y written."""
+    return 6 * d_model * d_ff + 2 * M * d_model + 2 * M * d_model
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-tune", action="store_true")
+    ap.add_argument("--force", choices=["auto", "fused", "unfused"], default="auto")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU by design (one MI355X); run with --gpus 1. "
+              "Values at more than one GPU are not produced.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import dfk_inputs as di
+    import paper_2602_11808_amd as dfk
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    Mmax = max(M_SET)
+
+    # ---- synthetic inputs, resident in HBM
+    layers = [di.mlp_inputs_torch(Mmax, D_MODEL, D_FF, seed=0, layer=l, device=dev)
+              for l in range(WEIGHT_SETS)]
+    X = {M: layers[0]["X"][:M].contiguous() for M in M_SET}
+    Y = {M: torch.empty_like(X[M]) for M in M_SET}
+    ws = dfk.new_workspace(Mmax, D_MODEL, D_FF, dev)
+    dfk.dfk_set_workspace(ws)
+
+    # ---- pre-inference scheduler step (not timed)
+    tune_s = 0.0
+    if not args.no_tune:
+        t0 = time.perf_counter()
+        scratch = torch.empty(dfk.dfk_tune_scratch_bytes(Mmax, D_MODEL, D_FF, dfk.DFK_BF16, 3),
+                              dtype=torch.uint8, device=dev)
+        dfk.dfk_tune(list(M_SET), D_MODEL, D_FF, dfk.DFK_BF16, scratch, sets=3, iters=12)
+        torch.cuda.synchronize()
+        del scratch
+        tune_s = time.perf_counter() - t0
+    picks = {}
+    for M in M_SET:
+        c, tuned = dfk.dfk_get_choice(M, D_MODEL, D_FF, dfk.DFK_BF16)
+        picks[str(M)] = dict(c.as_dict(), tuned=tuned)
+
+    call = {"auto": dfk.dfk_swiglu_mlp, "fused": dfk.dfk_swiglu_mlp_fused,
+            "unfused": dfk.dfk_swiglu_mlp_unfused}[args.force]
+    counter = [0]
+
+    def one_call(M):
+        w = layers[counter[0] % WEIGHT_SETS]
+        counter[0] += 1
+        call(X[M], w["Wg"], w["Wu"], w["Wd"], Y[M])
+
+    def step():
+        for M in M_SET:
+            one_call(M)
+
+    # ---- the contract's timed region: W warm-up steps, then exactly K steps
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ev_ms = e0.elapsed_time(e1)
+    ms_per_step = wall_ms / args.steps
+    calls_per_step = len(M_SET)
+    us_per_call = ms_per_step * 1e3 / calls_per_step
+
+    # ---- per-M breakdown with HIP events on the launch stream
+    per_m = {}
+    for M in M_SET:
+        for _ in range(5):
+            one_call(M)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        n = max(50, args.steps)
+        a.record()
+        for _ in range(n):
+            one_call(M)
+        b.record()
+        torch.cuda.synchronize()
+        us = a.elapsed_time(b) * 1e3 / n
+        per_m[str(M)] = {"us_per_call": round(us, 2),
+                         "tb_per_s": round(algorithmic_bytes(M, D_MODEL, D_FF) / us / 1e6, 3)}
+
+    # ---- read-stream ceiling of this machine (plain 128-bit streaming read of 1.4 GB)
+    big = layers[0]["Wg"]
+    sink = torch.zeros(2, dtype=torch.int32, device=dev)
+    srcs = [l[k] for l in layers for k in ("Wg", "Wu", "Wd")]
+    for s in srcs[:3]:
+        dfk.dfk_stream_read(s, sink)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for s in srcs:
+        dfk.dfk_stream_read(s, sink)
+    b.record()
+    torch.cuda.synchronize()
+    read_gbs = sum(s.numel() * 2 for s in srcs) / (a.elapsed_time(b) * 1e-3) / 1e9
+
+    # ---- roofline of the dominant kernel: algorithmic bytes per call / time per call
+    mean_bytes = sum(algorithmic_bytes(M, D_MODEL, D_FF) for M in M_SET) / calls_per_step
+    ev_us_per_call = ev_ms * 1e3 / (args.steps * calls_per_step)
+    achieved = mean_bytes / ev_us_per_call / 1e3   # GB/s
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "read_stream_ceiling_gbs": round(read_gbs, 1),
+                "frac_of_read_stream_ceiling": round(achieved / read_gbs, 4)}
+
+    # ---- the fp64 oracle on the host cores: one step of the same workload (+ parity of that step)
+    cpu = None
+    parity = None
+    if not args.no_cpu_baseline:
+        from oracle import oracle
+        host = {k: di.to_numpy(v) for k, v in layers[0].items()}
+        cores = oracle.default_threads()
+        worst = 0.0
+        t0 = time.perf_counter()
+        refs = {M: oracle.swiglu_mlp(host["X"][:M], host["Wg"], host["Wu"], host["Wd"], nthreads=cores)
+                for M in M_SET}
+        cpu_s = time.perf_counter() - t0
+        for M in M_SET:
+            w = layers[0]
+            call(X[M], w["Wg"], w["Wu"], w["Wd"], Y[M])
+            torch.cuda.synchronize()
+            y = di.as_f64(di.to_numpy(Y[M]))
+            worst = max(worst, float(np.max(np.abs(y - refs[M])) / np.max(np.abs(refs[M]))))
+        cpu = {"value": round(cpu_s * 1e6 / calls_per_step, 1), "unit": "us/call", "cores": cores,
+               "kind": "oracle",
+               "sample": "one step of the same workload: M=1,2,4,8,16 once each on weight set 0 "
+                         f"({cpu_s:.1f} s of fp64 CPU work)"}
+        parity = {"max_rel_err_vs_oracle": worst, "tolerance": 2e-2}
+
+    out = {
+        "metric": "fused SwiGLU us/call, d=4096 ff=14336 bf16, mean over M in {1,2,4,8,16}",
+        "value": round(us_per_call, 2), "unit": "us/call",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "llama3-8b-shaped SwiGLU MLP layer, d_model=4096 d_ff=14336, "
+                               "M in {1,2,4,8,16}, one call per M per step, 4 rotating weight sets",
+                   "entry": args.force, "calls_per_step": calls_per_step},
+        "achieved_tb_per_s": round(achieved / 1e3, 3),
+        "per_M": per_m, "scheduler_picks": picks, "tune_seconds": round(tune_s, 2),
+        "roofline": roofline, "cpu_baseline": cpu, "parity": parity,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

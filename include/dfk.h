@@ -1,0 +1,233 @@
+/*
+ * dfk.h - C ABI of the deeply fused SwiGLU MLP library for AMD MI355X (gfx950).
+ *
+ * The operation (Background section, SwiGLU equations; Method section,
+ * two-stage split):
+ *
+ *     A_2 = (X W_up) (x) SiLU(X W_gate),      Y = A_2 W_down,
+ *     SiLU(g) = Sigmoid(g) * g,               (x) = elementwise product,
+ *
+ * with W_gate, W_up in R^{d_model x d_ff} and W_down in R^{d_ff x d_model}.
+ *
+ * Storage layouts (fixed by this ABI; the paper gives mathematical shapes only).
+ * All tensors are dense, row-major, in DEVICE memory, 16-byte aligned:
+ *     X      [M,    d_model]   activations, read-only
+ *     W_gate [d_ff, d_model]   transposed mathematical shape (row j = column j of W_gate)
+ *     W_up   [d_ff, d_model]   transposed mathematical shape
+ *     W_down [d_ff, d_model]   the mathematical shape
+ *     Y      [M,    d_model]   output, fully overwritten (never accumulated into)
+ * so that every d_ff slice of each weight matrix is one contiguous block.
+ * Element type: bfloat16 (inputs and Y; fp32 accumulation) or, in the fp32
+ * test mode, IEEE fp32 for inputs and Y.  Y must not overlap any input.
+ *
+ * Ownership and execution: the caller owns every buffer, including the
+ * workspace.  No entry point on the call path allocates or frees device
+ * memory or synchronises the host; work is enqueued on `stream` (a
+ * hipStream_t passed as void*, NULL = the default stream) and the call
+ * returns at once.  The workspace holds partial sums and arrival counters; its
+ * counters must be zero before the first call (dfk_workspace_init) and every
+ * call leaves them zero again, so a workspace may be reused by successive calls
+ * on ONE stream.  Calls that share a workspace and overlap in time race.
+ *
+ * Errors: every function returns a dfk_status_t (or a plain value where
+ * noted) and never throws or aborts.  All argument errors are detected on the
+ * host before any HIP call is made.
+ */
+#ifndef DFK_H
+#define DFK_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DFK_OK = 0,
+    DFK_ERR_INVALID_ARG = -1,        /* null pointer, M < 1, d_model < 1, d_ff < 1, bad enum */
+    DFK_ERR_UNSUPPORTED_SHAPE = -2,  /* d_model % 8, d_ff % 8, M > DFK_MAX_M, or config not valid for shape */
+    DFK_ERR_ALIGNMENT = -3,          /* a device pointer is not 16-byte aligned */
+    DFK_ERR_ALIAS = -4,              /* Y overlaps X, W_gate, W_up or W_down */
+    DFK_ERR_WORKSPACE = -5,          /* workspace missing or smaller than dfk_workspace_bytes() */
+    DFK_ERR_HIP = -6,                /* a HIP call failed; see dfk_last_hip_error() */
+    DFK_ERR_IO = -7,                 /* tuning file could not be read / written / parsed */
+    DFK_ERR_NOT_FOUND = -8           /* no tuned entry / no such candidate */
+} dfk_status_t;
+
+typedef enum { DFK_BF16 = 0, DFK_FP32 = 1 } dfk_dtype_t;
+
+/* Fusion depth (Method section; Figure 1 b/c): one launch for the whole block,
+ * or two launches cut after A_2. */
+typedef enum { DFK_VARIANT_AUTO = 0, DFK_VARIANT_FUSED = 1, DFK_VARIANT_TWO_KERNEL = 2 } dfk_variant_t;
+
+/* How the contractions are computed. */
+typedef enum { DFK_PATH_VALU = 0, DFK_PATH_MFMA = 1 } dfk_path_t;
+
+/* How the split-d_ff partial sums of the down projection are combined. */
+typedef enum { DFK_REDUCE_ATOMIC = 0, DFK_REDUCE_TICKET = 1 } dfk_reduce_t;
+
+#define DFK_MAX_M 256            /* largest token count one call accepts */
+
+/*
+ * One candidate kernel configuration (Method section: tiling / loop-order
+ * variants and tile sizes; the scheduler chooses among these).
+ *   variant        DFK_VARIANT_FUSED or DFK_VARIANT_TWO_KERNEL
+ *   path           DFK_PATH_VALU (any supported shape, both dtypes) or
+ *                  DFK_PATH_MFMA (bf16 only, shape constraints, see dfk_config_valid)
+ *   splits         number of d_ff slices = workgroups of the fused kernel, or of
+ *                  the first kernel of the two-kernel variant
+ *   waves          wavefronts (64 lanes) per workgroup
+ *   depth          software pipeline depth of the weight stream (tiles or loads in flight)
+ *   reduce         dfk_reduce_t
+ *   k2_splits      two-kernel variant: d_ff splits of the down projection
+ *   k2_col_blocks  two-kernel variant: column blocks of the down projection
+ *                  (grid of the second kernel = k2_splits * k2_col_blocks)
+ *   a2_dtype       two-kernel variant: type A_2 is stored in between the
+ *                  kernels, DFK_BF16 or DFK_FP32
+ */
+typedef struct dfk_config_t {
+    int variant;
+    int path;
+    int splits;
+    int waves;
+    int depth;
+    int reduce;
+    int k2_splits;
+    int k2_col_blocks;
+    int a2_dtype;
+    int reserved;
+} dfk_config_t;
+
+/* ---------------------------------------------------------------- the block */
+
+/*
+ * Y = (SiLU(X W_gate) (x) (X W_up)) W_down in bfloat16 with fp32 accumulation;
+ * the scheduler picks variant and tile configuration for (M, d_model, d_ff)
+ * (tuned entry if dfk_tune / dfk_load_tuning / dfk_set_choice provided one,
+ * else a built-in heuristic).  Uses the workspace registered with
+ * dfk_set_workspace (DFK_ERR_WORKSPACE if none or too small).
+ * All pointers are device pointers.
+ */
+dfk_status_t dfk_swiglu_mlp(const void* X, const void* W_gate, const void* W_up,
+                            const void* W_down, void* Y,
+                            int M, int d_model, int d_ff, void* stream);
+
+/* Same, forcing the single-launch deeply fused kernel (Figure 1c). */
+dfk_status_t dfk_swiglu_mlp_fused(const void* X, const void* W_gate, const void* W_up,
+                                  const void* W_down, void* Y,
+                                  int M, int d_model, int d_ff, void* stream);
+
+/* Same, forcing the two-kernel layout cut after A_2 (Figure 1b; Method, the
+ * two-stage split). A_2 lives in the workspace between the two launches. */
+dfk_status_t dfk_swiglu_mlp_unfused(const void* X, const void* W_gate, const void* W_up,
+                                    const void* W_down, void* Y,
+                                    int M, int d_model, int d_ff, void* stream);
+
+/*
+ * Fully explicit form.  dtype selects bf16 or the fp32 test mode (all five
+ * tensors in that type).  cfg == NULL means "scheduler's choice"; otherwise
+ * cfg must satisfy dfk_config_valid for the shape.  workspace is a device
+ * buffer of at least dfk_workspace_bytes(M, d_model, d_ff) bytes, 256-byte
+ * aligned, initialised once with dfk_workspace_init.
+ */
+dfk_status_t dfk_swiglu_mlp_ex(const void* X, const void* W_gate, const void* W_up,
+                               const void* W_down, void* Y,
+                               int M, int d_model, int d_ff, dfk_dtype_t dtype,
+                               const dfk_config_t* cfg,
+                               void* workspace, size_t workspace_bytes, void* stream);
+
+/* Host-only argument check: exactly the validation the calls above perform,
+ * with no HIP call.  cfg may be NULL.  workspace may be NULL only if
+ * workspace_bytes is 0, in which case the workspace checks are skipped. */
+dfk_status_t dfk_check_args(const void* X, const void* W_gate, const void* W_up,
+                            const void* W_down, const void* Y,
+                            int M, int d_model, int d_ff, dfk_dtype_t dtype,
+                            const dfk_config_t* cfg,
+                            const void* workspace, size_t workspace_bytes);
+
+/* ---------------------------------------------------------------- workspace */
+
+/* Upper bound, over every configuration the library can pick, of the workspace
+ * a call with M <= M_max needs.  Returns 0 for invalid arguments. */
+size_t dfk_workspace_bytes(int M_max, int d_model, int d_ff);
+
+/* Enqueue the zero-initialisation of a workspace (a fill kernel; capturable). */
+dfk_status_t dfk_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
+
+/* Register the workspace the non-_ex calls use (per process; the pointer is
+ * kept, not copied).  The caller must have initialised it. NULL unregisters. */
+dfk_status_t dfk_set_workspace(void* workspace, size_t workspace_bytes);
+
+/* ---------------------------------------------------------------- scheduler
+ * Profile-driven kernel scheduler (Method, last paragraph; Experiments: the
+ * scheduler benchmarks the candidate kernels before inference on the target
+ * hardware and selects the fastest for the model shape and batch).  After
+ * tuning, a call costs one table lookup. */
+
+/* Number of candidate configurations for this problem, and the i-th one. */
+int dfk_num_candidates(int M, int d_model, int d_ff, dfk_dtype_t dtype);
+dfk_status_t dfk_get_candidate(int M, int d_model, int d_ff, dfk_dtype_t dtype, int i,
+                               dfk_config_t* out);
+
+/* 1 if cfg can run this problem, else 0. Host-only. */
+int dfk_config_valid(const dfk_config_t* cfg, int M, int d_model, int d_ff, dfk_dtype_t dtype);
+
+/* Bytes of device scratch dfk_tune needs: `sets` rotating copies of the three
+ * weight matrices (so timed launches stream from HBM, not from cache) plus X,
+ * Y and a workspace for the largest M in the list. */
+size_t dfk_tune_scratch_bytes(int M_max, int d_model, int d_ff, dfk_dtype_t dtype, int sets);
+
+/*
+ * Time every candidate for each M in M_list on the current device and record
+ * the fastest.  scratch is caller-owned device memory of at least
+ * dfk_tune_scratch_bytes(max M, ...) bytes; its previous contents are
+ * overwritten with synthetic values.  iters timed launches per candidate
+ * (after 2 warm-ups), rotating over `sets` weight copies.  Synchronises
+ * the stream (this is the pre-inference step, not the call path).
+ */
+dfk_status_t dfk_tune(const int* M_list, int nM, int d_model, int d_ff, dfk_dtype_t dtype,
+                      void* scratch, size_t scratch_bytes, int sets, int iters, void* stream);
+
+/* Time one configuration the same way; writes mean microseconds per call. */
+dfk_status_t dfk_time_config(const dfk_config_t* cfg, int M, int d_model, int d_ff,
+                             dfk_dtype_t dtype, void* scratch, size_t scratch_bytes,
+                             int sets, int iters, void* stream, double* usec_out);
+
+/* The configuration a call would use now (tuned entry, else heuristic).
+ * *tuned_out (may be NULL) is set to 1 if it came from the table. */
+dfk_status_t dfk_get_choice(int M, int d_model, int d_ff, dfk_dtype_t dtype,
+                            dfk_config_t* out, int* tuned_out);
+
+/* Enter / overwrite a table entry by hand (usec <= 0 means unknown). */
+dfk_status_t dfk_set_choice(int M, int d_model, int d_ff, dfk_dtype_t dtype,
+                            const dfk_config_t* cfg, double usec);
+
+/* Forget all tuned entries. */
+void dfk_clear_tuning(void);
+
+/* Persist / reload the table (plain text, one entry per line). */
+dfk_status_t dfk_save_tuning(const char* path);
+dfk_status_t dfk_load_tuning(const char* path);
+
+/* ---------------------------------------------------------------- measurement */
+
+/* Read-only streaming kernel over `bytes` of device memory (128-bit loads,
+ * XOR-folded into 8 bytes at sink): measures the achievable HBM read ceiling
+ * that the block's bandwidth is compared with.  bytes must be a multiple of 16. */
+dfk_status_t dfk_stream_read(const void* src, size_t bytes, void* sink, void* stream);
+
+/* Fill a device buffer with synthetic bf16 (or fp32) values in (-scale, scale),
+ * a cheap hash of the element index and seed.  Used by dfk_tune and by benchmarks. */
+dfk_status_t dfk_fill_synthetic(void* dst, size_t elems, dfk_dtype_t dtype, float scale,
+                                unsigned seed, void* stream);
+
+/* ---------------------------------------------------------------- misc */
+
+const char* dfk_status_string(dfk_status_t s);
+int dfk_last_hip_error(void);          /* hipError_t of the last DFK_ERR_HIP on this thread */
+const char* dfk_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DFK_H */

@@ -1,0 +1,522 @@
+// C ABI of libdfk: argument validation, the profile-driven scheduler and its
+// table, dispatch to the VALU / MFMA launchers.  Host code only.
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <tuple>
+#include <vector>
+
+#include "dfk_internal.h"
+
+namespace dfk {
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+dfk_status_t hip_fail(hipError_t e) {
+    g_last_hip_error = (int)e;
+    return DFK_ERR_HIP;
+}
+
+struct Registered {
+    void* ptr = nullptr;
+    size_t bytes = 0;
+};
+Registered g_ws;
+std::mutex g_mu;
+
+// ---------------------------------------------------------------- validation
+size_t elt_bytes(dfk_dtype_t d) { return d == DFK_FP32 ? 4 : 2; }
+
+bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
+    const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+    return a0 < b0 + nb && b0 < a0 + na;
+}
+
+bool config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype) {
+    if (c.path == DFK_PATH_VALU) return valu_config_valid(c, M, d_model, d_ff, dtype);
+    if (c.path == DFK_PATH_MFMA) return mfma_config_valid(c, M, d_model, d_ff, dtype);
+    return false;
+}
+
+dfk_status_t check(const void* X, const void* Wg, const void* Wu, const void* Wd, const void* Y,
+                   int M, int d_model, int d_ff, dfk_dtype_t dtype, const dfk_config_t* cfg,
+                   const void* ws, size_t ws_bytes, bool need_ws) {
+    if (!X || !Wg || !Wu || !Wd || !Y) return DFK_ERR_INVALID_ARG;
+    if (M < 1 || d_model < 1 || d_ff < 1) return DFK_ERR_INVALID_ARG;
+    if (dtype != DFK_BF16 && dtype != DFK_FP32) return DFK_ERR_INVALID_ARG;
+    if (d_model % 8 || d_ff % 8 || M > DFK_MAX_M) return DFK_ERR_UNSUPPORTED_SHAPE;
+    const void* ptrs[5] = {X, Wg, Wu, Wd, Y};
+    for (const void* p : ptrs)
+        if ((uintptr_t)p % 16) return DFK_ERR_ALIGNMENT;
+    const size_t eb = elt_bytes(dtype);
+    const size_t nx = (size_t)M * d_model * eb, nw = (size_t)d_ff * d_model * eb;
+    if (overlaps(Y, nx, X, nx) || overlaps(Y, nx, Wg, nw) || overlaps(Y, nx, Wu, nw) ||
+        overlaps(Y, nx, Wd, nw))
+        return DFK_ERR_ALIAS;
+    if (cfg) {
+        if (cfg->variant != DFK_VARIANT_FUSED && cfg->variant != DFK_VARIANT_TWO_KERNEL)
+            return DFK_ERR_INVALID_ARG;
+        if (cfg->path != DFK_PATH_VALU && cfg->path != DFK_PATH_MFMA) return DFK_ERR_INVALID_ARG;
+        if (!config_valid(*cfg, M, d_model, d_ff, dtype)) return DFK_ERR_UNSUPPORTED_SHAPE;
+    }
+    if (need_ws || ws || ws_bytes) {
+        if (!ws) return DFK_ERR_WORKSPACE;
+        if ((uintptr_t)ws % 256) return DFK_ERR_ALIGNMENT;
+        if (ws_bytes < ws_layout(M, d_model, d_ff).total) return DFK_ERR_WORKSPACE;
+        if (overlaps(ws, ws_bytes, Y, nx) || overlaps(ws, ws_bytes, X, nx) ||
+            overlaps(ws, ws_bytes, Wg, nw) || overlaps(ws, ws_bytes, Wu, nw) ||
+            overlaps(ws, ws_bytes, Wd, nw))
+            return DFK_ERR_ALIAS;
+    }
+    return DFK_OK;
+}
+
+// ---------------------------------------------------------------- candidates and heuristic
+int clamp_splits(int want, int d_ff) { return std::max(1, std::min(want, d_ff / 8)); }
+
+dfk_config_t make_cfg(int variant, int path, int splits, int waves, int depth, int k2s, int k2c,
+                      int a2dt) {
+    dfk_config_t c;
+    std::memset(&c, 0, sizeof c);
+    c.variant = variant; c.path = path; c.splits = splits; c.waves = waves; c.depth = depth;
+    c.reduce = DFK_REDUCE_ATOMIC; c.k2_splits = k2s; c.k2_col_blocks = k2c; c.a2_dtype = a2dt;
+    return c;
+}
+
+bool same_cfg(const dfk_config_t& a, const dfk_config_t& b) {
+    return a.variant == b.variant && a.path == b.path && a.splits == b.splits && a.waves == b.waves &&
+           a.depth == b.depth && a.reduce == b.reduce && a.k2_splits == b.k2_splits &&
+           a.k2_col_blocks == b.k2_col_blocks && a.a2_dtype == b.a2_dtype;
+}
+
+// The candidate set of the scheduler (Method: tiling variants x tile sizes).
+std::vector<dfk_config_t> candidates(int M, int d_model, int d_ff, dfk_dtype_t dtype) {
+    std::vector<dfk_config_t> out;
+    auto push = [&](const dfk_config_t& c) {
+        if (!config_valid(c, M, d_model, d_ff, dtype)) return;
+        for (const auto& o : out)
+            if (same_cfg(o, c)) return;
+        out.push_back(c);
+    };
+    const int a2dt = dtype == DFK_FP32 ? DFK_FP32 : DFK_BF16;
+    if (dtype == DFK_BF16) {
+        // MFMA path: d_ff slices ("column-major tiling": each workgroup owns a
+        // block of weight rows and reuses it for every token).
+        for (int splits : {256, 512})
+            for (int waves : {8, 16})
+                for (int depth : {3, 4, 6})
+                    push(make_cfg(DFK_VARIANT_FUSED, DFK_PATH_MFMA, clamp_splits(splits, d_ff), waves,
+                                  depth, 0, 0, a2dt));
+        for (int splits : {256, 512})
+            for (int waves : {8, 16})
+                for (int k2s : {8, 16, 32})
+                    push(make_cfg(DFK_VARIANT_TWO_KERNEL, DFK_PATH_MFMA, clamp_splits(splits, d_ff),
+                                  waves, 4, clamp_splits(k2s, d_ff), 0, a2dt));
+    }
+    for (int splits : {256, 512, 1024})
+        for (int waves : {4, 8})
+            push(make_cfg(DFK_VARIANT_FUSED, DFK_PATH_VALU, clamp_splits(splits, d_ff), waves, 0, 0, 0,
+                          a2dt));
+    const int nchunk = d_model / (dtype == DFK_BF16 ? 8 : 4);
+    for (int splits : {512, 1024})
+        for (int k2s : {8, 16, 32}) {
+            const int k2 = clamp_splits(k2s, d_ff);
+            const int cb = std::max(1, std::min(nchunk / 64 > 0 ? nchunk / 64 : 1, std::max(1, 512 / k2)));
+            push(make_cfg(DFK_VARIANT_TWO_KERNEL, DFK_PATH_VALU, clamp_splits(splits, d_ff), 8, 0, k2,
+                          cb, a2dt));
+        }
+    return out;
+}
+
+// Untuned default: first valid candidate of the preferred variant for this M.
+bool heuristic(int M, int d_model, int d_ff, dfk_dtype_t dtype, int want_variant, dfk_config_t* out) {
+    auto cands = candidates(M, d_model, d_ff, dtype);
+    int variant = want_variant;
+    if (variant == DFK_VARIANT_AUTO) variant = M <= 8 ? DFK_VARIANT_FUSED : DFK_VARIANT_TWO_KERNEL;
+    for (const auto& c : cands)
+        if (c.variant == variant) { *out = c; return true; }
+    if (want_variant == DFK_VARIANT_AUTO && !cands.empty()) { *out = cands[0]; return true; }
+    return false;
+}
+
+// ---------------------------------------------------------------- tuning table
+struct Entry {
+    dfk_config_t cfg;
+    double usec;
+};
+using Key = std::tuple<int, int, int, int>;  // M, d_model, d_ff, dtype
+std::map<Key, Entry> g_table;
+
+int m_bucket(int M) {
+    int b = 1;
+    while (b < M) b <<= 1;
+    return b;
+}
+
+bool lookup(int M, int d_model, int d_ff, dfk_dtype_t dtype, int want_variant, dfk_config_t* out) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    for (int m : {M, m_bucket(M)}) {
+        auto it = g_table.find(Key(m, d_model, d_ff, (int)dtype));
+        if (it == g_table.end()) continue;
+        const dfk_config_t& c = it->second.cfg;
+        if (want_variant != DFK_VARIANT_AUTO && c.variant != want_variant) continue;
+        if (!config_valid(c, M, d_model, d_ff, dtype)) continue;
+        *out = c;
+        return true;
+    }
+    return false;
+}
+
+bool choose(int M, int d_model, int d_ff, dfk_dtype_t dtype, int want_variant, dfk_config_t* out,
+            int* tuned) {
+    if (lookup(M, d_model, d_ff, dtype, want_variant, out)) {
+        if (tuned) *tuned = 1;
+        return true;
+    }
+    if (tuned) *tuned = 0;
+    return heuristic(M, d_model, d_ff, dtype, want_variant, out);
+}
+
+// ---------------------------------------------------------------- dispatch
+dfk_status_t run(const void* X, const void* Wg, const void* Wu, const void* Wd, void* Y, int M,
+                 int d_model, int d_ff, dfk_dtype_t dtype, const dfk_config_t& c, void* ws,
+                 hipStream_t st) {
+    const WsLayout l = ws_layout(M, d_model, d_ff);
+    MlpArgs a;
+    std::memset(&a, 0, sizeof a);
+    a.X = X; a.Wg = Wg; a.Wu = Wu; a.Wd = Wd; a.Y = Y;
+    a.M = M; a.d_model = d_model; a.d_ff = d_ff;
+    a.splits = c.splits; a.k2_splits = c.k2_splits; a.k2_col_blocks = c.k2_col_blocks;
+    a.a2_is_fp32 = c.a2_dtype == DFK_FP32;
+    a.tickets = (unsigned*)((char*)ws + l.tickets_off);
+    a.yacc = (float*)((char*)ws + l.yacc_off);
+    a.a2 = (char*)ws + l.a2_off;
+    // Token chunking on the host: a launch handles at most `per` tokens; further
+    // chunks are further launches on the same stream (they re-stream the weights).
+    const int per = c.path == DFK_PATH_MFMA ? mfma_max_tokens_per_launch() : DFK_MAX_M;
+    for (int m0 = 0; m0 < M; m0 += per) {
+        a.m_base = m0;
+        a.m_count = std::min(per, M - m0);
+        hipError_t e = c.path == DFK_PATH_MFMA ? launch_mfma(a, c, st) : launch_valu(a, c, dtype, st);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    return DFK_OK;
+}
+
+dfk_status_t call(const void* X, const void* Wg, const void* Wu, const void* Wd, void* Y, int M,
+                  int d_model, int d_ff, dfk_dtype_t dtype, const dfk_config_t* cfg, int want_variant,
+                  void* ws, size_t ws_bytes, void* stream) {
+    dfk_status_t s = check(X, Wg, Wu, Wd, Y, M, d_model, d_ff, dtype, cfg, ws, ws_bytes, true);
+    if (s != DFK_OK) return s;
+    dfk_config_t c;
+    if (cfg) c = *cfg;
+    else if (!choose(M, d_model, d_ff, dtype, want_variant, &c, nullptr)) return DFK_ERR_UNSUPPORTED_SHAPE;
+    return run(X, Wg, Wu, Wd, Y, M, d_model, d_ff, dtype, c, ws, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------- tuning scratch
+struct Scratch {
+    size_t w_bytes, x_bytes, ws_bytes, set_bytes, total;
+};
+Scratch scratch_layout(int M, int d_model, int d_ff, dfk_dtype_t dtype, int sets) {
+    Scratch s;
+    s.w_bytes = align_up((size_t)d_ff * d_model * elt_bytes(dtype), 256);
+    s.x_bytes = align_up((size_t)M * d_model * elt_bytes(dtype), 256);
+    s.ws_bytes = align_up(ws_layout(M, d_model, d_ff).total, 256);
+    s.set_bytes = 3 * s.w_bytes;
+    s.total = (size_t)sets * s.set_bytes + 2 * s.x_bytes + s.ws_bytes;
+    return s;
+}
+
+dfk_status_t time_config(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype,
+                         void* scratch, int sets, int iters, hipStream_t st, bool fill, double* usec) {
+    const Scratch s = scratch_layout(M, d_model, d_ff, dtype, sets);
+    char* base = (char*)scratch;
+    char* X = base + (size_t)sets * s.set_bytes;
+    char* Y = X + s.x_bytes;
+    char* ws = Y + s.x_bytes;
+    hipError_t e;
+    if (fill) {
+        const float sg = sqrtf(3.0f / (float)d_model), sd = sqrtf(3.0f / (float)d_ff);
+        for (int i = 0; i < sets; ++i) {
+            char* w = base + (size_t)i * s.set_bytes;
+            const size_t n = (size_t)d_ff * d_model;
+            if ((e = launch_fill(w, n, dtype, sg, 11u + 3u * i, st)) != hipSuccess) return hip_fail(e);
+            if ((e = launch_fill(w + s.w_bytes, n, dtype, sg, 12u + 3u * i, st)) != hipSuccess) return hip_fail(e);
+            if ((e = launch_fill(w + 2 * s.w_bytes, n, dtype, sd, 13u + 3u * i, st)) != hipSuccess) return hip_fail(e);
+        }
+        if ((e = launch_fill(X, (size_t)M * d_model, dtype, 1.7320508f, 7u, st)) != hipSuccess) return hip_fail(e);
+        if ((e = launch_zero(ws, s.ws_bytes, st)) != hipSuccess) return hip_fail(e);
+    }
+    hipEvent_t t0, t1;
+    if ((e = hipEventCreate(&t0)) != hipSuccess) return hip_fail(e);
+    if ((e = hipEventCreate(&t1)) != hipSuccess) { (void)hipEventDestroy(t0); return hip_fail(e); }
+    dfk_status_t rc = DFK_OK;
+    for (int it = -2; it < iters && rc == DFK_OK; ++it) {
+        if (it == 0 && (e = hipEventRecord(t0, st)) != hipSuccess) { rc = hip_fail(e); break; }
+        char* w = base + (size_t)((it + 2) % sets) * s.set_bytes;
+        rc = run(X, w, w + s.w_bytes, w + 2 * s.w_bytes, Y, M, d_model, d_ff, dtype, c, ws, st);
+    }
+    if (rc == DFK_OK) {
+        if ((e = hipEventRecord(t1, st)) != hipSuccess) rc = hip_fail(e);
+        else if ((e = hipEventSynchronize(t1)) != hipSuccess) rc = hip_fail(e);
+        else {
+            float ms = 0.f;
+            if ((e = hipEventElapsedTime(&ms, t0, t1)) != hipSuccess) rc = hip_fail(e);
+            else *usec = (double)ms * 1000.0 / iters;
+        }
+    }
+    (void)hipEventDestroy(t0);
+    (void)hipEventDestroy(t1);
+    return rc;
+}
+
+}  // namespace
+}  // namespace dfk
+
+using namespace dfk;
+
+extern "C" {
+
+dfk_status_t dfk_swiglu_mlp(const void* X, const void* Wg, const void* Wu, const void* Wd, void* Y,
+                            int M, int d_model, int d_ff, void* stream) {
+    return call(X, Wg, Wu, Wd, Y, M, d_model, d_ff, DFK_BF16, nullptr, DFK_VARIANT_AUTO, g_ws.ptr,
+                g_ws.bytes, stream);
+}
+
+dfk_status_t dfk_swiglu_mlp_fused(const void* X, const void* Wg, const void* Wu, const void* Wd,
+                                  void* Y, int M, int d_model, int d_ff, void* stream) {
+    return call(X, Wg, Wu, Wd, Y, M, d_model, d_ff, DFK_BF16, nullptr, DFK_VARIANT_FUSED, g_ws.ptr,
+                g_ws.bytes, stream);
+}
+
+dfk_status_t dfk_swiglu_mlp_unfused(const void* X, const void* Wg, const void* Wu, const void* Wd,
+                                    void* Y, int M, int d_model, int d_ff, void* stream) {
+    return call(X, Wg, Wu, Wd, Y, M, d_model, d_ff, DFK_BF16, nullptr, DFK_VARIANT_TWO_KERNEL,
+                g_ws.ptr, g_ws.bytes, stream);
+}
+
+dfk_status_t dfk_swiglu_mlp_ex(const void* X, const void* Wg, const void* Wu, const void* Wd, void* Y,
+                               int M, int d_model, int d_ff, dfk_dtype_t dtype,
+                               const dfk_config_t* cfg, void* workspace, size_t workspace_bytes,
+                               void* stream) {
+    return call(X, Wg, Wu, Wd, Y, M, d_model, d_ff, dtype, cfg, DFK_VARIANT_AUTO, workspace,
+                workspace_bytes, stream);
+}
+
+dfk_status_t dfk_check_args(const void* X, const void* Wg, const void* Wu, const void* Wd,
+                            const void* Y, int M, int d_model, int d_ff, dfk_dtype_t dtype,
+                            const dfk_config_t* cfg, const void* workspace, size_t workspace_bytes) {
+    return check(X, Wg, Wu, Wd, Y, M, d_model, d_ff, dtype, cfg, workspace, workspace_bytes, false);
+}
+
+size_t dfk_workspace_bytes(int M_max, int d_model, int d_ff) {
+    if (M_max < 1 || M_max > DFK_MAX_M || d_model < 1 || d_ff < 1) return 0;
+    return ws_layout(M_max, d_model, d_ff).total;
+}
+
+dfk_status_t dfk_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
+    if (!workspace || workspace_bytes == 0) return DFK_ERR_INVALID_ARG;
+    if ((uintptr_t)workspace % 256) return DFK_ERR_ALIGNMENT;
+    hipError_t e = launch_zero(workspace, workspace_bytes, (hipStream_t)stream);
+    return e == hipSuccess ? DFK_OK : hip_fail(e);
+}
+
+dfk_status_t dfk_set_workspace(void* workspace, size_t workspace_bytes) {
+    if (workspace && (uintptr_t)workspace % 256) return DFK_ERR_ALIGNMENT;
+    if (workspace && workspace_bytes == 0) return DFK_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_ws.ptr = workspace;
+    g_ws.bytes = workspace ? workspace_bytes : 0;
+    return DFK_OK;
+}
+
+int dfk_num_candidates(int M, int d_model, int d_ff, dfk_dtype_t dtype) {
+    if (M < 1 || M > DFK_MAX_M || d_model < 8 || d_ff < 8 || d_model % 8 || d_ff % 8) return 0;
+    return (int)candidates(M, d_model, d_ff, dtype).size();
+}
+
+dfk_status_t dfk_get_candidate(int M, int d_model, int d_ff, dfk_dtype_t dtype, int i,
+                               dfk_config_t* out) {
+    if (!out) return DFK_ERR_INVALID_ARG;
+    if (M < 1 || M > DFK_MAX_M || d_model < 8 || d_ff < 8 || d_model % 8 || d_ff % 8)
+        return DFK_ERR_UNSUPPORTED_SHAPE;
+    auto c = candidates(M, d_model, d_ff, dtype);
+    if (i < 0 || i >= (int)c.size()) return DFK_ERR_NOT_FOUND;
+    *out = c[i];
+    return DFK_OK;
+}
+
+int dfk_config_valid(const dfk_config_t* cfg, int M, int d_model, int d_ff, dfk_dtype_t dtype) {
+    if (!cfg || M < 1 || M > DFK_MAX_M) return 0;
+    return config_valid(*cfg, M, d_model, d_ff, dtype) ? 1 : 0;
+}
+
+size_t dfk_tune_scratch_bytes(int M_max, int d_model, int d_ff, dfk_dtype_t dtype, int sets) {
+    if (M_max < 1 || M_max > DFK_MAX_M || d_model < 1 || d_ff < 1 || sets < 1) return 0;
+    return scratch_layout(M_max, d_model, d_ff, dtype, sets).total;
+}
+
+dfk_status_t dfk_time_config(const dfk_config_t* cfg, int M, int d_model, int d_ff, dfk_dtype_t dtype,
+                             void* scratch, size_t scratch_bytes, int sets, int iters, void* stream,
+                             double* usec_out) {
+    if (!cfg || !scratch || !usec_out || sets < 1 || iters < 1) return DFK_ERR_INVALID_ARG;
+    if (M < 1 || d_model < 1 || d_ff < 1) return DFK_ERR_INVALID_ARG;
+    if (M > DFK_MAX_M || d_model % 8 || d_ff % 8) return DFK_ERR_UNSUPPORTED_SHAPE;
+    if (!config_valid(*cfg, M, d_model, d_ff, dtype)) return DFK_ERR_UNSUPPORTED_SHAPE;
+    if ((uintptr_t)scratch % 256) return DFK_ERR_ALIGNMENT;
+    if (scratch_bytes < scratch_layout(M, d_model, d_ff, dtype, sets).total) return DFK_ERR_WORKSPACE;
+    return time_config(*cfg, M, d_model, d_ff, dtype, scratch, sets, iters, (hipStream_t)stream, true,
+                       usec_out);
+}
+
+dfk_status_t dfk_tune(const int* M_list, int nM, int d_model, int d_ff, dfk_dtype_t dtype,
+                      void* scratch, size_t scratch_bytes, int sets, int iters, void* stream) {
+    if (!M_list || nM < 1 || !scratch || sets < 1 || iters < 1) return DFK_ERR_INVALID_ARG;
+    if (d_model < 1 || d_ff < 1) return DFK_ERR_INVALID_ARG;
+    if (d_model % 8 || d_ff % 8) return DFK_ERR_UNSUPPORTED_SHAPE;
+    if ((uintptr_t)scratch % 256) return DFK_ERR_ALIGNMENT;
+    for (int i = 0; i < nM; ++i) {
+        if (M_list[i] < 1) return DFK_ERR_INVALID_ARG;
+        if (M_list[i] > DFK_MAX_M) return DFK_ERR_UNSUPPORTED_SHAPE;
+        if (scratch_bytes < scratch_layout(M_list[i], d_model, d_ff, dtype, sets).total)
+            return DFK_ERR_WORKSPACE;
+    }
+    for (int i = 0; i < nM; ++i) {
+        const int M = M_list[i];
+        auto cands = candidates(M, d_model, d_ff, dtype);
+        if (cands.empty()) return DFK_ERR_UNSUPPORTED_SHAPE;
+        Entry best;
+        best.usec = -1.0;
+        bool fill = true;  // scratch layout depends on M: refill once per M
+        for (const auto& c : cands) {
+            double us = 0.0;
+            dfk_status_t s = time_config(c, M, d_model, d_ff, dtype, scratch, sets, iters,
+                                         (hipStream_t)stream, fill, &us);
+            fill = false;
+            if (s != DFK_OK) return s;
+            if (best.usec < 0.0 || us < best.usec) { best.cfg = c; best.usec = us; }
+        }
+        std::lock_guard<std::mutex> lk(g_mu);
+        g_table[Key(M, d_model, d_ff, (int)dtype)] = best;
+    }
+    return DFK_OK;
+}
+
+dfk_status_t dfk_get_choice(int M, int d_model, int d_ff, dfk_dtype_t dtype, dfk_config_t* out,
+                            int* tuned_out) {
+    if (!out) return DFK_ERR_INVALID_ARG;
+    if (M < 1 || d_model < 1 || d_ff < 1) return DFK_ERR_INVALID_ARG;
+    if (M > DFK_MAX_M || d_model % 8 || d_ff % 8) return DFK_ERR_UNSUPPORTED_SHAPE;
+    return choose(M, d_model, d_ff, dtype, DFK_VARIANT_AUTO, out, tuned_out) ? DFK_OK
+                                                                             : DFK_ERR_UNSUPPORTED_SHAPE;
+}
+
+dfk_status_t dfk_set_choice(int M, int d_model, int d_ff, dfk_dtype_t dtype, const dfk_config_t* cfg,
+                            double usec) {
+    if (!cfg || M < 1 || d_model < 1 || d_ff < 1) return DFK_ERR_INVALID_ARG;
+    if (M > DFK_MAX_M || d_model % 8 || d_ff % 8) return DFK_ERR_UNSUPPORTED_SHAPE;
+    if (!config_valid(*cfg, M, d_model, d_ff, dtype)) return DFK_ERR_UNSUPPORTED_SHAPE;
+    std::lock_guard<std::mutex> lk(g_mu);
+    Entry e;
+    e.cfg = *cfg;
+    e.usec = usec;
+    g_table[Key(M, d_model, d_ff, (int)dtype)] = e;
+    return DFK_OK;
+}
+
+void dfk_clear_tuning(void) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_table.clear();
+}
+
+dfk_status_t dfk_save_tuning(const char* path) {
+    if (!path) return DFK_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lk(g_mu);
+    FILE* f = std::fopen(path, "w");
+    if (!f) return DFK_ERR_IO;
+    std::fprintf(f, "# dfk tuning table v1: M d_model d_ff dtype variant path splits waves depth reduce "
+                    "k2_splits k2_col_blocks a2_dtype usec\n");
+    for (const auto& kv : g_table) {
+        const dfk_config_t& c = kv.second.cfg;
+        std::fprintf(f, "%d %d %d %d %d %d %d %d %d %d %d %d %d %.3f\n", std::get<0>(kv.first),
+                     std::get<1>(kv.first), std::get<2>(kv.first), std::get<3>(kv.first), c.variant,
+                     c.path, c.splits, c.waves, c.depth, c.reduce, c.k2_splits, c.k2_col_blocks,
+                     c.a2_dtype, kv.second.usec);
+    }
+    const bool ok = std::fclose(f) == 0;
+    return ok ? DFK_OK : DFK_ERR_IO;
+}
+
+dfk_status_t dfk_load_tuning(const char* path) {
+    if (!path) return DFK_ERR_INVALID_ARG;
+    FILE* f = std::fopen(path, "r");
+    if (!f) return DFK_ERR_IO;
+    std::map<Key, Entry> fresh;
+    char line[512];
+    dfk_status_t rc = DFK_OK;
+    while (std::fgets(line, sizeof line, f)) {
+        const char* p = line;
+        while (*p == ' ' || *p == '\t') ++p;
+        if (*p == '#' || *p == '\n' || *p == '\r' || *p == 0) continue;
+        int M, dm, df, dt;
+        Entry e;
+        std::memset(&e, 0, sizeof e);
+        const int n = std::sscanf(p, "%d %d %d %d %d %d %d %d %d %d %d %d %d %lf", &M, &dm, &df, &dt,
+                                  &e.cfg.variant, &e.cfg.path, &e.cfg.splits, &e.cfg.waves, &e.cfg.depth,
+                                  &e.cfg.reduce, &e.cfg.k2_splits, &e.cfg.k2_col_blocks, &e.cfg.a2_dtype,
+                                  &e.usec);
+        if (n != 14 || M < 1 || M > DFK_MAX_M || (dt != DFK_BF16 && dt != DFK_FP32) || dm < 8 ||
+            df < 8 || dm % 8 || df % 8 || !config_valid(e.cfg, M, dm, df, (dfk_dtype_t)dt)) {
+            rc = DFK_ERR_IO;
+            break;
+        }
+        fresh[Key(M, dm, df, dt)] = e;
+    }
+    std::fclose(f);
+    if (rc != DFK_OK) return rc;  // table left untouched on a malformed file
+    std::lock_guard<std::mutex> lk(g_mu);
+    for (const auto& kv : fresh) g_table[kv.first] = kv.second;
+    return DFK_OK;
+}
+
+dfk_status_t dfk_stream_read(const void* src, size_t bytes, void* sink, void* stream) {
+    if (!src || !sink || bytes == 0) return DFK_ERR_INVALID_ARG;
+    if (bytes % 16) return DFK_ERR_UNSUPPORTED_SHAPE;
+    if ((uintptr_t)src % 16 || (uintptr_t)sink % 8) return DFK_ERR_ALIGNMENT;
+    hipError_t e = launch_stream_read(src, bytes, sink, (hipStream_t)stream);
+    return e == hipSuccess ? DFK_OK : hip_fail(e);
+}
+
+dfk_status_t dfk_fill_synthetic(void* dst, size_t elems, dfk_dtype_t dtype, float scale, unsigned seed,
+                                void* stream) {
+    if (!dst || elems == 0) return DFK_ERR_INVALID_ARG;
+    if (dtype != DFK_BF16 && dtype != DFK_FP32) return DFK_ERR_INVALID_ARG;
+    if ((uintptr_t)dst % 4) return DFK_ERR_ALIGNMENT;
+    hipError_t e = launch_fill(dst, elems, dtype, scale, seed, (hipStream_t)stream);
+    return e == hipSuccess ? DFK_OK : hip_fail(e);
+}
+
+const char* dfk_status_string(dfk_status_t s) {
+    switch (s) {
+        case DFK_OK: return "ok";
+        case DFK_ERR_INVALID_ARG: return "invalid argument";
+        case DFK_ERR_UNSUPPORTED_SHAPE: return "unsupported shape or configuration";
+        case DFK_ERR_ALIGNMENT: return "pointer not sufficiently aligned";
+        case DFK_ERR_ALIAS: return "output or workspace overlaps an input";
+        case DFK_ERR_WORKSPACE: return "workspace missing or too small";
+        case DFK_ERR_HIP: return "HIP call failed";
+        case DFK_ERR_IO: return "tuning file could not be read, written or parsed";
+        case DFK_ERR_NOT_FOUND: return "not found";
+    }
+    return "unknown status";
+}
+
+int dfk_last_hip_error(void) { return g_last_hip_error; }
+
+const char* dfk_version(void) { return "dfk 0.1 (gfx950)"; }
+
+}  // extern "C"

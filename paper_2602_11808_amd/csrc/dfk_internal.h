@@ -1,0 +1,81 @@
+// Internal declarations shared by the translation units of libdfk (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "dfk.h"
+
+namespace dfk {
+
+// ---------------------------------------------------------------- workspace layout
+// [0, 4096)            arrival counters (unsigned), zero between calls
+// [4096, +M*d_model*4) fp32 accumulator of Y, zero between calls
+// [..,  +M*d_ff*4)     A_2 between the two launches of the two-kernel variant
+constexpr size_t kWsHeaderBytes = 4096;
+constexpr int kMaxTickets = 1024;
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct WsLayout {
+    size_t tickets_off, yacc_off, a2_off, total;
+};
+
+inline WsLayout ws_layout(int M, int d_model, int d_ff) {
+    WsLayout l;
+    l.tickets_off = 0;
+    l.yacc_off = kWsHeaderBytes;
+    l.a2_off = l.yacc_off + align_up((size_t)M * d_model * 4, 256);
+    l.total = l.a2_off + align_up((size_t)M * d_ff * 4, 256);
+    return l;
+}
+
+// ---------------------------------------------------------------- kernel arguments
+struct MlpArgs {
+    const void* X;
+    const void* Wg;
+    const void* Wu;
+    const void* Wd;
+    void* Y;
+    int M, d_model, d_ff;
+    int m_base;        // first token this launch handles (host-side token chunking)
+    int m_count;       // tokens this launch handles
+    int splits;        // d_ff slices (grid of the fused kernel / first kernel)
+    int k2_splits, k2_col_blocks;
+    int a2_is_fp32;    // storage type of A_2 in the workspace (two-kernel variant)
+    float* yacc;       // [M, d_model] fp32, zero on entry and on exit
+    unsigned* tickets; // zero on entry and on exit
+    void* a2;          // [M, d_ff] in the workspace
+};
+
+// d_ff is cut into slices at multiples of 8 rows: slice s of S covers the
+// 8-row groups [s*NG/S, (s+1)*NG/S), NG = d_ff/8.
+__host__ __device__ inline void slice_rows(int d_ff, int S, int s, int& j0, int& j1) {
+    const long long ng = d_ff / 8;
+    j0 = (int)(ng * s / S) * 8;
+    j1 = (int)(ng * (s + 1) / S) * 8;
+}
+
+inline int max_slice_rows(int d_ff, int S) {
+    const long long ng = d_ff / 8;
+    return (int)((ng + S - 1) / S) * 8;
+}
+
+// ---------------------------------------------------------------- launchers (defined per path)
+// Each returns hipSuccess or the launch error.  No allocation, no sync.
+hipError_t launch_valu(const MlpArgs& a, const dfk_config_t& c, dfk_dtype_t dtype, hipStream_t st);
+hipError_t launch_mfma(const MlpArgs& a, const dfk_config_t& c, hipStream_t st);
+
+// Host-only validity of a configuration for a problem.
+bool valu_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype);
+bool mfma_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype);
+int mfma_max_tokens_per_launch();
+
+// utility kernels
+hipError_t launch_zero(void* p, size_t bytes, hipStream_t st);
+hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, hipStream_t st);
+hipError_t launch_fill(void* dst, size_t elems, dfk_dtype_t dtype, float scale, unsigned seed,
+                       hipStream_t st);
+
+}  // namespace dfk

@@ -1,0 +1,96 @@
+// Utility kernels: workspace zeroing, synthetic fill, and the read-stream probe.
+#include "dfk_device.h"
+#include "dfk_internal.h"
+
+namespace dfk {
+namespace {
+
+__global__ void k_zero(u32x4* p, size_t n16, unsigned char* tail, size_t ntail) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride)
+        p[i] = u32x4{0, 0, 0, 0};
+    if (blockIdx.x == 0 && threadIdx.x < ntail) tail[threadIdx.x] = 0;
+}
+
+__device__ __forceinline__ uint32_t mix32(uint32_t x) {
+    x ^= x >> 16; x *= 0x7FEB352Du;
+    x ^= x >> 15; x *= 0x846CA68Bu;
+    x ^= x >> 16;
+    return x;
+}
+
+__global__ void k_fill(void* dst, size_t n, int is_fp32, float scale, uint32_t seed) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const uint32_t h = mix32((uint32_t)i * 0x9E3779B9u + mix32(seed + (uint32_t)(i >> 32)));
+        const float u = ((float)(h >> 8) * (1.0f / 8388608.0f) - 1.0f) * scale;  // (-scale, scale)
+        if (is_fp32) ((float*)dst)[i] = u;
+        else ((uint16_t*)dst)[i] = (uint16_t)f32_to_bf16_bits(u);
+    }
+}
+
+constexpr int kReadThreads = 256;
+constexpr int kReadUnroll = 8;
+
+__global__ __launch_bounds__(kReadThreads) void k_stream_read(const u32x4* __restrict__ src, size_t n16,
+                                                              unsigned* sink) {
+    const size_t tile = (size_t)kReadThreads * kReadUnroll;
+    u32x4 acc = {0, 0, 0, 0};
+    for (size_t base = (size_t)blockIdx.x * tile; base < n16; base += (size_t)gridDim.x * tile) {
+        u32x4 v[kReadUnroll];
+#pragma unroll
+        for (int u = 0; u < kReadUnroll; ++u) {
+            const size_t i = base + (size_t)u * kReadThreads + threadIdx.x;
+            v[u] = i < n16 ? __builtin_nontemporal_load(src + i) : u32x4{0, 0, 0, 0};
+        }
+#pragma unroll
+        for (int u = 0; u < kReadUnroll; ++u) {
+            acc ^= v[u];
+        }
+    }
+    unsigned a = acc.x ^ acc.z, b = acc.y ^ acc.w;
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+        a ^= __shfl_xor(a, o);
+        b ^= __shfl_xor(b, o);
+    }
+    if ((threadIdx.x & 63) == 0) {
+        atomicXor(sink, a);
+        atomicXor(sink + 1, b);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_zero(void* p, size_t bytes, hipStream_t st) {
+    const size_t n16 = bytes / 16, ntail = bytes % 16;
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(k_zero, dim3((unsigned)blocks), dim3(256), 0, st, (u32x4*)p, n16,
+                       (unsigned char*)p + n16 * 16, ntail);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill(void* dst, size_t elems, dfk_dtype_t dtype, float scale, unsigned seed,
+                       hipStream_t st) {
+    size_t blocks = (elems + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(k_fill, dim3((unsigned)blocks), dim3(256), 0, st, dst, elems,
+                       dtype == DFK_FP32 ? 1 : 0, scale, seed);
+    return hipGetLastError();
+}
+
+hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, hipStream_t st) {
+    const size_t n16 = bytes / 16;
+    const size_t tile = (size_t)kReadThreads * kReadUnroll;
+    size_t blocks = (n16 + tile - 1) / tile;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 256 * 8) blocks = 256 * 8;
+    hipLaunchKernelGGL(k_stream_read, dim3((unsigned)blocks), dim3(kReadThreads), 0, st,
+                       (const u32x4*)src, n16, (unsigned*)sink);
+    return hipGetLastError();
+}
+
+}  // namespace dfk

@@ -1,0 +1,149 @@
+"""Host-side checks that need no GPU: the library loads, exports every symbol
+the header declares, validates arguments before touching HIP, and keeps the
+scheduler table (set / get / save / load / clear)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2602_11808_amd as dfk
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+D, FF = 4096, 14336
+A = 0x10000000          # fake, well-aligned, non-overlapping "device" addresses
+X, WG, WU, WD, Y, WS = A, 2 * A, 3 * A, 4 * A, 5 * A, 6 * A
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "dfk.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(dfk_[a-z_0-9]+)\s*\(", header))
+    assert len(declared) >= 20
+    l = ctypes.CDLL(dfk.LIB_PATH)
+    for name in declared:
+        assert hasattr(l, name), f"{name} declared in dfk.h but not exported"
+    bound = {n for n, _, _ in dfk.binding.SIGNATURES}
+    assert declared == bound, declared ^ bound
+    for name in declared:
+        if name.startswith("dfk_") and name not in ("dfk_config_t",):
+            assert hasattr(dfk, name), f"binding lacks {name}"
+    assert "gfx950" in dfk.dfk_version()
+
+
+def chk(**kw):
+    a = dict(X=X, W_gate=WG, W_up=WU, W_down=WD, Y=Y, M=1, d_model=D, d_ff=FF)
+    a.update(kw)
+    return dfk.dfk_check_args(**a)
+
+
+def test_valid_arguments_pass():
+    assert chk() == dfk.DFK_OK
+    assert chk(M=256) == dfk.DFK_OK
+    assert chk(dtype=dfk.DFK_FP32) == dfk.DFK_OK
+    n = dfk.dfk_workspace_bytes(16, D, FF)
+    assert chk(M=16, workspace=WS, workspace_bytes=n) == dfk.DFK_OK
+
+
+def test_invalid_arguments():
+    for name in ("X", "W_gate", "W_up", "W_down", "Y"):
+        assert chk(**{name: 0}) == dfk.DFK_ERR_INVALID_ARG
+    assert chk(M=0) == dfk.DFK_ERR_INVALID_ARG
+    assert chk(M=-3) == dfk.DFK_ERR_INVALID_ARG
+    assert chk(d_model=0) == dfk.DFK_ERR_INVALID_ARG
+    assert chk(d_ff=-8) == dfk.DFK_ERR_INVALID_ARG
+    assert chk(dtype=7) == dfk.DFK_ERR_INVALID_ARG
+
+
+def test_unsupported_shapes():
+    assert chk(d_model=4100) == dfk.DFK_ERR_UNSUPPORTED_SHAPE
+    assert chk(d_ff=14340) == dfk.DFK_ERR_UNSUPPORTED_SHAPE
+    assert chk(M=dfk.DFK_MAX_M + 1) == dfk.DFK_ERR_UNSUPPORTED_SHAPE
+
+
+def test_alignment_and_alias():
+    assert chk(X=X + 8) == dfk.DFK_ERR_ALIGNMENT
+    assert chk(W_down=WD + 2) == dfk.DFK_ERR_ALIGNMENT
+    assert chk(Y=X) == dfk.DFK_ERR_ALIAS
+    assert chk(Y=WG + 4096) == dfk.DFK_ERR_ALIAS              # inside W_gate
+    assert chk(M=4, Y=X + 2 * D * 2) == dfk.DFK_ERR_ALIAS      # overlaps later rows of X
+    assert chk(M=1, Y=X + 1 * D * 2) == dfk.DFK_OK             # just past a 1-row X
+
+
+def test_workspace_checks():
+    n = dfk.dfk_workspace_bytes(8, D, FF)
+    assert n >= 4096 + 8 * D * 4 + 8 * FF * 4
+    assert dfk.dfk_workspace_bytes(0, D, FF) == 0 and dfk.dfk_workspace_bytes(1, 0, FF) == 0
+    assert chk(M=8, workspace=0, workspace_bytes=n) == dfk.DFK_ERR_WORKSPACE
+    assert chk(M=8, workspace=WS, workspace_bytes=n - 1) == dfk.DFK_ERR_WORKSPACE
+    assert chk(M=8, workspace=WS + 16, workspace_bytes=n) == dfk.DFK_ERR_ALIGNMENT
+    assert chk(M=8, workspace=Y, workspace_bytes=n) == dfk.DFK_ERR_ALIAS
+    # the non-_ex entry points refuse to run without a registered workspace (no HIP call made)
+    dfk.dfk_set_workspace(None)
+    st = dfk.lib().dfk_swiglu_mlp(X, WG, WU, WD, Y, 1, D, FF, None)
+    assert st == dfk.DFK_ERR_WORKSPACE
+    assert dfk.lib().dfk_swiglu_mlp_fused(X, WG, WU, WD, Y, 0, D, FF, None) == dfk.DFK_ERR_INVALID_ARG
+    assert dfk.lib().dfk_swiglu_mlp_unfused(0, WG, WU, WD, Y, 1, D, FF, None) == dfk.DFK_ERR_INVALID_ARG
+
+
+def test_config_validation():
+    n = dfk.dfk_num_candidates(4, D, FF, dfk.DFK_BF16)
+    assert n > 0
+    seen_variants = set()
+    for i in range(n):
+        c = dfk.dfk_get_candidate(4, D, FF, dfk.DFK_BF16, i)
+        assert dfk.dfk_config_valid(c, 4, D, FF, dfk.DFK_BF16)
+        assert chk(M=4, cfg=c) == dfk.DFK_OK
+        seen_variants.add(c.variant)
+    assert seen_variants == {dfk.DFK_VARIANT_FUSED, dfk.DFK_VARIANT_TWO_KERNEL}
+    with pytest.raises(dfk.DfkError):
+        dfk.dfk_get_candidate(4, D, FF, dfk.DFK_BF16, n)
+    bad = dfk.dfk_get_candidate(4, D, FF, dfk.DFK_BF16, 0)
+    bad.splits = 0
+    assert not dfk.dfk_config_valid(bad, 4, D, FF, dfk.DFK_BF16)
+    assert chk(M=4, cfg=bad) == dfk.DFK_ERR_UNSUPPORTED_SHAPE
+    bad.splits, bad.variant = 256, 9
+    assert chk(M=4, cfg=bad) == dfk.DFK_ERR_INVALID_ARG
+    # fp32 test mode never gets the bf16 MFMA path
+    for i in range(dfk.dfk_num_candidates(4, D, FF, dfk.DFK_FP32)):
+        assert dfk.dfk_get_candidate(4, D, FF, dfk.DFK_FP32, i).path == dfk.DFK_PATH_VALU
+    assert dfk.dfk_num_candidates(4, 4100, FF, dfk.DFK_BF16) == 0
+
+
+def test_scheduler_table_roundtrip(tmp_path):
+    dfk.dfk_clear_tuning()
+    c0, tuned = dfk.dfk_get_choice(2, D, FF, dfk.DFK_BF16)
+    assert not tuned and dfk.dfk_config_valid(c0, 2, D, FF, dfk.DFK_BF16)
+    n = dfk.dfk_num_candidates(2, D, FF, dfk.DFK_BF16)
+    pick = dfk.dfk_get_candidate(2, D, FF, dfk.DFK_BF16, n - 1)
+    dfk.dfk_set_choice(2, D, FF, dfk.DFK_BF16, pick, 61.5)
+    c1, tuned = dfk.dfk_get_choice(2, D, FF, dfk.DFK_BF16)
+    assert tuned and c1.as_dict() == pick.as_dict()
+    # a power-of-two bucket entry serves the M values below it
+    pick8 = dfk.dfk_get_candidate(8, D, FF, dfk.DFK_BF16, 0)
+    dfk.dfk_set_choice(8, D, FF, dfk.DFK_BF16, pick8, 70.0)
+    c5, tuned5 = dfk.dfk_get_choice(5, D, FF, dfk.DFK_BF16)
+    assert tuned5 and c5.as_dict() == pick8.as_dict()
+    path = str(tmp_path / "tuning.txt")
+    dfk.dfk_save_tuning(path)
+    dfk.dfk_clear_tuning()
+    assert not dfk.dfk_get_choice(2, D, FF, dfk.DFK_BF16)[1]
+    dfk.dfk_load_tuning(path)
+    c2, tuned = dfk.dfk_get_choice(2, D, FF, dfk.DFK_BF16)
+    assert tuned and c2.as_dict() == pick.as_dict()
+    # malformed file: error, table untouched
+    with open(path, "a") as f:
+        f.write("1 2 3 oops\n")
+    with pytest.raises(dfk.DfkError) as ei:
+        dfk.dfk_load_tuning(path)
+    assert ei.value.status == dfk.DFK_ERR_IO
+    assert dfk.dfk_get_choice(2, D, FF, dfk.DFK_BF16)[1]
+    with pytest.raises(dfk.DfkError):
+        dfk.dfk_load_tuning(str(tmp_path / "missing.txt"))
+    dfk.dfk_clear_tuning()
+
+
+def test_status_strings():
+    for s in range(0, -9, -1):
+        assert dfk.dfk_status_string(s) not in ("", "unknown status")
+    assert dfk.dfk_status_string(-99) == "unknown status"

@@ -1,0 +1,217 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU
+oracle on the same seeded inputs, element by element.
+
+Bar: max|Y - Yref| / max|Yref| <= 2e-2 for bf16 inputs with fp32 accumulation,
+<= 1e-5 in the fp32 test mode.
+"""
+import numpy as np
+import pytest
+import torch
+
+import dfk_inputs as di
+import paper_2602_11808_amd as dfk
+from oracle import oracle
+from tests.helpers import TOL_BF16, TOL_FP32, rel_err
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def _dt(dtype):
+    return dfk.DFK_BF16 if dtype == "bf16" else dfk.DFK_FP32
+
+
+def _tol(dtype):
+    return TOL_BF16 if dtype == "bf16" else TOL_FP32
+
+
+def gpu_inputs(t):
+    return {k: di.to_torch(v, DEV) for k, v in t.items()}
+
+
+def run_ex(g, cfg, ws=None):
+    M, d = g["X"].shape
+    ff = g["Wg"].shape[0]
+    if ws is None:
+        ws = dfk.new_workspace(M, d, ff, DEV)
+    Y = torch.full_like(g["X"], float("nan"))
+    dfk.dfk_swiglu_mlp_ex(g["X"], g["Wg"], g["Wu"], g["Wd"], Y, cfg, ws)
+    torch.cuda.synchronize()
+    return Y, ws
+
+
+def y64(Y):
+    return di.as_f64(di.to_numpy(Y))
+
+
+def workspace_is_clean(ws, M, d):
+    """Counters and the fp32 accumulator must be zero again after a call."""
+    head = ws[: 4096 + M * d * 4]
+    return int(torch.count_nonzero(head).item()) == 0
+
+
+SMALL = [
+    # (M, d_model, d_ff): the tiny configuration, ragged tails, several slices
+    (1, 512, 1536),
+    (1, 8, 8),
+    (2, 264, 1000),
+    (3, 1024, 2056),
+    (5, 520, 4104),
+    (8, 512, 1536),
+    (9, 256, 520),
+    (16, 512, 1536),
+    (17, 128, 264),
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+@pytest.mark.parametrize("shape", SMALL, ids=lambda s: "M%d_d%d_ff%d" % s)
+def test_every_candidate_matches_oracle_small(shape, dtype):
+    M, d, ff = shape
+    t = di.mlp_inputs(M, d, ff, seed=0, dtype=dtype)
+    ref = oracle.swiglu_mlp(t["X"], t["Wg"], t["Wu"], t["Wd"])
+    g = gpu_inputs(t)
+    n = dfk.dfk_num_candidates(M, d, ff, _dt(dtype))
+    assert n > 0
+    ws = None
+    seen = set()
+    for i in range(n):
+        cfg = dfk.dfk_get_candidate(M, d, ff, _dt(dtype), i)
+        print("case", shape, dtype, cfg, flush=True)
+        Y, ws = run_ex(g, cfg, ws)
+        err = rel_err(y64(Y), ref)
+        assert err <= _tol(dtype), (shape, dtype, cfg, err)
+        assert workspace_is_clean(ws, M, d), (shape, dtype, cfg)
+        seen.add((cfg.variant, cfg.path))
+    assert any(v == dfk.DFK_VARIANT_FUSED for v, _ in seen)
+    assert any(v == dfk.DFK_VARIANT_TWO_KERNEL for v, _ in seen)
+
+
+def test_tiny_config_against_stored_oracle_output():
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "c1_tiny_y.txt")
+    want = np.array([float.fromhex(l) for l in open(path) if not l.startswith("#")])[None]
+    g = gpu_inputs(di.mlp_inputs(1, 512, 1536, seed=0))
+    ws = dfk.new_workspace(1, 512, 1536, DEV)
+    dfk.dfk_set_workspace(ws)
+    for fn in (dfk.dfk_swiglu_mlp, dfk.dfk_swiglu_mlp_fused, dfk.dfk_swiglu_mlp_unfused):
+        Y = torch.empty_like(g["X"])
+        fn(g["X"], g["Wg"], g["Wu"], g["Wd"], Y)
+        torch.cuda.synchronize()
+        assert rel_err(y64(Y), want) <= TOL_BF16, fn.__name__
+    dfk.dfk_set_workspace(None)
+
+
+FULL = [
+    # the configurations the benchmark times, at their real sizes
+    ("llama3-8b", 4096, 14336, (1, 2, 4, 8, 16)),
+    ("qwen2.5-32b", 5120, 27648, (1, 8)),
+    ("llama3-70b", 8192, 28672, (1, 16)),
+]
+
+
+@pytest.mark.parametrize("name,d,ff,Ms", FULL, ids=[f[0] for f in FULL])
+def test_full_size_entry_points_match_oracle(name, d, ff, Ms):
+    """Default entry points (scheduler's choice, forced fused, forced two-kernel)
+    at full size, in the launch configuration the benchmark uses."""
+    Mmax = max(Ms)
+    g = di.mlp_inputs_torch(Mmax, d, ff, seed=0, device=DEV)
+    host = {k: di.to_numpy(v) for k, v in g.items()}
+    ws = dfk.new_workspace(Mmax, d, ff, DEV)
+    dfk.dfk_set_workspace(ws)
+    try:
+        for M in Ms:
+            X = g["X"][:M].contiguous()
+            ref = oracle.swiglu_mlp(host["X"][:M], host["Wg"], host["Wu"], host["Wd"])
+            assert 0.05 < np.abs(ref).max() < 50.0
+            for fn in (dfk.dfk_swiglu_mlp, dfk.dfk_swiglu_mlp_fused, dfk.dfk_swiglu_mlp_unfused):
+                print("case", name, "M", M, fn.__name__, flush=True)
+                Y = torch.full_like(X, float("nan"))
+                fn(X, g["Wg"], g["Wu"], g["Wd"], Y)
+                torch.cuda.synchronize()
+                err = rel_err(y64(Y), ref)
+                assert err <= TOL_BF16, (name, M, fn.__name__, err)
+                assert workspace_is_clean(ws, M, d)
+    finally:
+        dfk.dfk_set_workspace(None)
+
+
+@pytest.mark.parametrize("M", [33, 64, 100, 256])
+def test_large_token_counts(M):
+    d, ff = 1024, 2816
+    t = di.mlp_inputs(M, d, ff, seed=3)
+    ref = oracle.swiglu_mlp(t["X"], t["Wg"], t["Wu"], t["Wd"])
+    g = gpu_inputs(t)
+    ws = dfk.new_workspace(M, d, ff, DEV)
+    for variant in (dfk.DFK_VARIANT_FUSED, dfk.DFK_VARIANT_TWO_KERNEL):
+        for i in range(dfk.dfk_num_candidates(M, d, ff, dfk.DFK_BF16)):
+            cfg = dfk.dfk_get_candidate(M, d, ff, dfk.DFK_BF16, i)
+            if cfg.variant != variant:
+                continue
+            print("case M", M, cfg, flush=True)
+            Y, _ = run_ex(g, cfg, ws)
+            assert rel_err(y64(Y), ref) <= TOL_BF16, (M, cfg)
+            assert workspace_is_clean(ws, M, d)
+            break
+
+
+def test_degenerate_inputs():
+    M, d, ff = 4, 512, 1536
+    t = di.mlp_inputs(M, d, ff, seed=5)
+    g = gpu_inputs(t)
+    ws = dfk.new_workspace(M, d, ff, DEV)
+    n = dfk.dfk_num_candidates(M, d, ff, dfk.DFK_BF16)
+    cfgs = [dfk.dfk_get_candidate(M, d, ff, dfk.DFK_BF16, i) for i in range(n)]
+    for cfg in cfgs:
+        for zero in ("X", "Wg", "Wu", "Wd"):
+            gz = dict(g)
+            gz[zero] = torch.zeros_like(g[zero])
+            Y, _ = run_ex(gz, cfg, ws)
+            assert int(torch.count_nonzero(Y.float()).item()) == 0, (zero, cfg)   # exactly zero
+    # extreme gate pre-activations: SiLU -> g for g >> 0, -> 0 for g << 0, no NaN
+    big = dict(g)
+    big["X"] = g["X"] * 64.0
+    big["Wg"] = g["Wg"] * 64.0
+    tb = {k: di.to_numpy(v) for k, v in big.items()}
+    ref = oracle.swiglu_mlp(tb["X"], tb["Wg"], tb["Wu"], tb["Wd"])
+    for cfg in cfgs:
+        Y, _ = run_ex(big, cfg, ws)
+        assert rel_err(y64(Y), ref) <= TOL_BF16, cfg
+
+
+def test_repeated_calls_share_a_workspace_and_stay_correct():
+    M, d, ff = 4, 1024, 4096
+    t = di.mlp_inputs(M, d, ff, seed=9)
+    ref = oracle.swiglu_mlp(t["X"], t["Wg"], t["Wu"], t["Wd"])
+    g = gpu_inputs(t)
+    ws = dfk.new_workspace(M, d, ff, DEV)
+    n = dfk.dfk_num_candidates(M, d, ff, dfk.DFK_BF16)
+    side = torch.cuda.Stream()
+    for i in range(n):
+        cfg = dfk.dfk_get_candidate(M, d, ff, dfk.DFK_BF16, i)
+        Ys = [torch.empty_like(g["X"]) for _ in range(50)]
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):            # a non-default stream, back-to-back launches
+            for Y in Ys:
+                dfk.dfk_swiglu_mlp_ex(g["X"], g["Wg"], g["Wu"], g["Wd"], Y, cfg, ws)
+        torch.cuda.synchronize()
+        worst = max(rel_err(y64(Y), ref) for Y in Ys)
+        assert worst <= TOL_BF16, (cfg, worst)
+        assert workspace_is_clean(ws, M, d)
+
+
+def test_split_identity_on_gpu():
+    # Appendix A.1 algebra through the GPU path: d_ff shards' outputs sum to the whole.
+    M, d, ff = 2, 512, 2048
+    t = di.mlp_inputs(M, d, ff, seed=13, dtype="fp32")
+    g = gpu_inputs(t)
+    ws = dfk.new_workspace(M, d, ff, DEV)
+    full, _ = run_ex(g, None, ws)
+    tot = torch.zeros_like(full)
+    for lo, hi in ((0, 512), (512, 1288), (1288, 2048)):
+        gs = {"X": g["X"], "Wg": g["Wg"][lo:hi].contiguous(), "Wu": g["Wu"][lo:hi].contiguous(),
+              "Wd": g["Wd"][lo:hi].contiguous()}
+        part, _ = run_ex(gs, None, dfk.new_workspace(M, d, hi - lo, DEV))
+        tot += part
+    assert rel_err(tot.double().cpu().numpy(), full.double().cpu().numpy()) <= 1e-5
