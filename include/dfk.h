@@ -24,10 +24,12 @@
  * workspace.  No entry point on the call path allocates or frees device
  * memory or synchronises the host; work is enqueued on `stream` (a
  * hipStream_t passed as void*, NULL = the default stream) and the call
- * returns at once.  The workspace holds partial sums and arrival counters; its
- * counters must be zero before the first call (dfk_workspace_init) and every
- * call leaves them zero again, so a workspace may be reused by successive calls
- * on ONE stream.  Calls that share a workspace and overlap in time race.
+ * returns at once.  The workspace holds the fp32 accumulator of Y, arrival
+ * counters and (two-kernel variant) A_2; accumulator and counters must be zero
+ * before the first call (dfk_workspace_init) and every call leaves them zero
+ * again, so a workspace may be reused by successive calls, with any M, on ONE
+ * stream as long as d_model stays the same (initialise it again before using it
+ * with another d_model).  Calls that share a workspace and overlap in time race.
  *
  * Errors: every function returns a dfk_status_t (or a plain value where
  * noted) and never throws or aborts.  All argument errors are detected on the
@@ -211,9 +213,10 @@ dfk_status_t dfk_load_tuning(const char* path);
 
 /* ---------------------------------------------------------------- measurement */
 
-/* Read-only streaming kernel over `bytes` of device memory (128-bit loads,
- * XOR-folded into 8 bytes at sink): measures the achievable HBM read ceiling
- * that the block's bandwidth is compared with.  bytes must be a multiple of 16. */
+/* Read-only streaming kernel over `bytes` of device memory (128-bit loads whose
+ * XOR fold is compared with a magic value; sink, 8 bytes, is written only on a
+ * match, i.e. practically never): measures the achievable HBM read ceiling that
+ * the block's bandwidth is compared with.  bytes must be a multiple of 16. */
 dfk_status_t dfk_stream_read(const void* src, size_t bytes, void* sink, void* stream);
 
 /* Fill a device buffer with synthetic bf16 (or fp32) values in (-scale, scale),

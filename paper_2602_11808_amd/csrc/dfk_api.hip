@@ -106,15 +106,23 @@ std::vector<dfk_config_t> candidates(int M, int d_model, int d_ff, dfk_dtype_t d
         // MFMA path: d_ff slices ("column-major tiling": each workgroup owns a
         // block of weight rows and reuses it for every token).
         for (int splits : {256, 512})
-            for (int waves : {8, 16})
-                for (int depth : {3, 4, 6})
+            for (int waves : {4, 8, 16})
+                for (int depth : {2, 3, 4, 6, 8})
                     push(make_cfg(DFK_VARIANT_FUSED, DFK_PATH_MFMA, clamp_splits(splits, d_ff), waves,
                                   depth, 0, 0, a2dt));
+        // two-kernel: the down projection is tiled (d_ff splits) x (column blocks of
+        // waves*128 or 2*waves*128 columns), about one or two workgroups per CU
+        const int nblk = d_model / 128;
         for (int splits : {256, 512})
-            for (int waves : {8, 16})
-                for (int k2s : {8, 16, 32})
-                    push(make_cfg(DFK_VARIANT_TWO_KERNEL, DFK_PATH_MFMA, clamp_splits(splits, d_ff),
-                                  waves, 4, clamp_splits(k2s, d_ff), 0, a2dt));
+            for (int waves : {4, 8, 16})
+                for (int per_wave : {1, 2}) {
+                    const int wg_blocks = waves * per_wave;
+                    if (wg_blocks > nblk || nblk % wg_blocks) continue;
+                    const int k2c = nblk / wg_blocks;
+                    for (int grid : {256, 512})
+                        push(make_cfg(DFK_VARIANT_TWO_KERNEL, DFK_PATH_MFMA, clamp_splits(splits, d_ff),
+                                      waves, 4, clamp_splits(std::max(1, grid / k2c), d_ff), k2c, a2dt));
+                }
     }
     for (int splits : {256, 512, 1024})
         for (int waves : {4, 8})
@@ -196,7 +204,7 @@ dfk_status_t run(const void* X, const void* Wg, const void* Wu, const void* Wd, 
     a.a2 = (char*)ws + l.a2_off;
     // Token chunking on the host: a launch handles at most `per` tokens; further
     // chunks are further launches on the same stream (they re-stream the weights).
-    const int per = c.path == DFK_PATH_MFMA ? mfma_max_tokens_per_launch() : DFK_MAX_M;
+    const int per = c.path == DFK_PATH_MFMA ? mfma_max_tokens_per_launch(c) : DFK_MAX_M;
     for (int m0 = 0; m0 < M; m0 += per) {
         a.m_base = m0;
         a.m_count = std::min(per, M - m0);

@@ -67,6 +67,13 @@ __device__ __forceinline__ float acc_take(float* p) {
     return __hip_atomic_exchange(p, 0.0f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Device-scope fences.  A release makes the calling wavefront wait until all
+// of its earlier stores and atomics have been performed for the whole device; it
+// must be executed by every wavefront whose writes the arrival below publishes
+// (a workgroup barrier alone does not wait for other wavefronts' memory traffic).
+__device__ __forceinline__ void release_device() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent"); }
+__device__ __forceinline__ void acquire_device() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent"); }
+
 // Arrival counter: returns true for the last of `expected` arrivals, and resets
 // the counter for the next call.  Release/acquire at device scope orders every
 // earlier accumulate of the caller before the count, and the drain after it.

@@ -10,9 +10,12 @@
 namespace dfk {
 
 // ---------------------------------------------------------------- workspace layout
-// [0, 4096)            arrival counters (unsigned), zero between calls
-// [4096, +M*d_model*4) fp32 accumulator of Y, zero between calls
-// [..,  +M*d_ff*4)     A_2 between the two launches of the two-kernel variant
+// [0, 4096)                      arrival counters (unsigned), zero between calls
+// [4096, +DFK_MAX_M*d_model*4)   fp32 accumulator of Y, zero between calls
+// [.., +M*d_ff*4)                A_2 between the two launches of the two-kernel variant
+// The zero-between-calls part comes first and its size does not depend on M, so
+// calls with different M on one workspace never put scratch where another call
+// expects zeros.
 constexpr size_t kWsHeaderBytes = 4096;
 constexpr int kMaxTickets = 1024;
 
@@ -26,7 +29,7 @@ inline WsLayout ws_layout(int M, int d_model, int d_ff) {
     WsLayout l;
     l.tickets_off = 0;
     l.yacc_off = kWsHeaderBytes;
-    l.a2_off = l.yacc_off + align_up((size_t)M * d_model * 4, 256);
+    l.a2_off = l.yacc_off + align_up((size_t)DFK_MAX_M * d_model * 4, 256);
     l.total = l.a2_off + align_up((size_t)M * d_ff * 4, 256);
     return l;
 }
@@ -70,7 +73,7 @@ hipError_t launch_mfma(const MlpArgs& a, const dfk_config_t& c, hipStream_t st);
 // Host-only validity of a configuration for a problem.
 bool valu_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype);
 bool mfma_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype);
-int mfma_max_tokens_per_launch();
+int mfma_max_tokens_per_launch(const dfk_config_t& c);
 
 // utility kernels
 hipError_t launch_zero(void* p, size_t bytes, hipStream_t st);

@@ -1,9 +1,458 @@
-// MFMA path (placeholder while the tiles are being written): reports itself
-// unavailable, so the scheduler never selects it.
+// MFMA path (bf16 inputs, fp32 accumulation) for gfx950.
+//
+// One kernel template covers the deeply fused single launch (MODE_FUSED) and
+// the two launches of the two-kernel variant (MODE_GATEUP, MODE_DOWN).
+//
+// Work split ("column-major tiling" of the Method section: a workgroup owns a
+// block of weight rows and reuses it for every token): workgroup s owns the
+// d_ff slice [j0, j1).  Inside it, every wavefront consumes its own stream of
+// 4 KB weight tiles that it brings from HBM straight into a private LDS ring
+// with asynchronous 128-bit global->LDS loads (no VGPR staging, no workgroup
+// barrier in the streaming loops).  The stream holds first the stage-one tiles
+// (W_gate / W_up) and then, without a gap, the stage-two tiles (W_down), whose
+// addresses do not depend on stage one, so HBM stays busy across the SiLU
+// epilogue.
+//
+// Stage one (A_2 = (X W_up) (x) SiLU(X W_gate)): wavefront w owns the k-range
+// [w*KW, (w+1)*KW) of d_model.  A tile is 16 weight rows (8 of W_gate, the same
+// 8 of W_up) x 128 k; it is the A operand of v_mfma_f32_16x16x32_bf16 (4 k-steps
+// per tile), X^T (tokens padded to 16 per token tile) is the B operand, kept
+// in registers per 128-k chunk.  16-byte chunks are XOR-swizzled by row on the
+// way into LDS (by permuting which global chunk each lane fetches), so the
+// operand reads are bank-conflict free.  The wavefronts' k-partial sums meet
+// in an LDS array through ds_add_f32; then SiLU(G)*U is applied and A_2 is left
+// in LDS as bf16 [token][j] (or written to the workspace in MODE_GATEUP).
+//
+// Stage two (Y += A_2 W_down over the slice): wavefront w owns 128-column blocks
+// of d_model.  A tile is 4 row-groups of W_down: lane (q, g) fetches 16 bytes
+// (8 consecutive columns) of row 8g+r.  After two tiles a lane holds an 8x8
+// block (8 rows x 8 columns); v_perm_b32 regroups it into, per column, the 8
+// consecutive-j values the MFMA B operand wants - a per-lane transpose, no
+// cross-lane traffic.  A_2 (bf16, from LDS) is the A operand.  The fp32 block
+// of partial Y is added into the device-wide fp32 accumulator with hardware
+// float atomics; the last workgroup to arrive drains it into Y as bf16.
+#include "dfk_device.h"
 #include "dfk_internal.h"
 
 namespace dfk {
-bool mfma_config_valid(const dfk_config_t&, int, int, int, dfk_dtype_t) { return false; }
-int mfma_max_tokens_per_launch() { return 64; }
-hipError_t launch_mfma(const MlpArgs&, const dfk_config_t&, hipStream_t) { return hipErrorNotSupported; }
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+
+constexpr int MODE_FUSED = 0, MODE_GATEUP = 1, MODE_DOWN = 2;
+constexpr int kTileBytes = 4096;   // one ring slot = 4 global->LDS instructions of 1 KB
+constexpr int kKC = 128;           // k extent of a stage-one tile
+constexpr int kGT = 8;             // stage-one row tiles accumulated together
+constexpr int kLdsLimit = 160 * 1024;
+
+struct Geom {
+    int depth;      // ring slots per wavefront
+    int gu_off;     // LDS byte offset of the fp32 gate/up sums [nt*16][16*TT]
+    int a2s_off;    // LDS byte offset of A_2 as bf16 [16*TT][a2_stride]
+    int a2_stride;  // elements
+};
+
+#define DFK_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+// s_waitcnt with only vmcnt constrained (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4]<<14)
+#define DFK_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | ((((n) >> 4) & 3) << 14))
+#define DFK_WAIT_LGKM0() __builtin_amdgcn_s_waitcnt(0xC07F)
+
+__device__ __forceinline__ void wait_tiles_in_flight(int newer_tiles) {
+    // 4 load instructions per tile; loads complete in issue order.
+    switch (newer_tiles) {
+        case 0: DFK_WAIT_VM(0); break;
+        case 1: DFK_WAIT_VM(4); break;
+        case 2: DFK_WAIT_VM(8); break;
+        case 3: DFK_WAIT_VM(12); break;
+        case 4: DFK_WAIT_VM(16); break;
+        case 5: DFK_WAIT_VM(20); break;
+        case 6: DFK_WAIT_VM(24); break;
+        case 7: DFK_WAIT_VM(28); break;
+        case 8: DFK_WAIT_VM(32); break;
+        case 9: DFK_WAIT_VM(36); break;
+        case 10: DFK_WAIT_VM(40); break;
+        case 11: DFK_WAIT_VM(44); break;
+        case 12: DFK_WAIT_VM(48); break;
+        case 13: DFK_WAIT_VM(52); break;
+        case 14: DFK_WAIT_VM(56); break;
+        default: DFK_WAIT_VM(60); break;
+    }
+    asm volatile("" ::: "memory");
+}
+
+__device__ __forceinline__ bf16x8 as_bf16x8(const u32x4& v) {
+    union { u32x4 u; bf16x8 b; } c;
+    c.u = v;
+    return c.b;
+}
+
+// Per-wavefront producer/consumer of the weight-tile stream.
+template <int NW, int MODE>
+struct TileStream {
+    // problem
+    const uint16_t *Wg, *Wu, *Wd;
+    int d_model, d_ff;
+    int j0, nt, njb;          // slice start row, stage-one row tiles, stage-two 32-row blocks
+    int kbase, nkc;           // this wavefront's k range start, number of 128-k chunks
+    int blk_lo, blk_cnt;      // stage two: first 128-column block and block count of the workgroup
+    int wave, q, g;
+    // ring
+    unsigned char* ring;
+    int depth;
+    int T1, T;                // stage-one tiles, all tiles
+    int issued, issue_slot;   // producer position
+    int taken, take_slot;     // consumer position
+    // producer coordinates
+    int p_g0, p_kc, p_r;      // stage one: group start tile, k chunk, tile in group
+    int p_bi, p_jb, p_h;      // stage two: block index (wave, wave+NW, ...), 32-row block, half
+
+    __device__ __forceinline__ void issue() {
+        unsigned char* slot = ring + issue_slot * kTileBytes;
+        if (MODE != MODE_DOWN && issued < T1) {
+            const size_t rowbase = (size_t)(j0 + 8 * (p_g0 + p_r)) * d_model + kbase + p_kc * kKC;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = 4 * u + g;   // row of the 16-row tile this lane fetches
+                const int c = q ^ i;       // logical 16-byte chunk stored at position q of row i
+                const uint16_t* base = (u < 2) ? Wg : Wu;
+                const uint16_t* src = base + rowbase + (size_t)(i & 7) * d_model + c * 8;
+                __builtin_amdgcn_global_load_lds(src, DFK_LDS_PTR(slot + u * 1024), 16, 0, 0);
+            }
+            const int gsz = min(kGT, nt - p_g0);
+            if (++p_r == gsz) {
+                p_r = 0;
+                if (++p_kc == nkc) { p_kc = 0; p_g0 += kGT; }
+            }
+        } else if (MODE != MODE_GATEUP) {
+            const int nb = (blk_lo + p_bi) * 128;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int r = 4 * p_h + u;
+                const int row = min(j0 + p_jb * 32 + 8 * g + r, d_ff - 1);   // stay inside W_down
+                const uint16_t* src = Wd + (size_t)row * d_model + nb + 8 * q;
+                __builtin_amdgcn_global_load_lds(src, DFK_LDS_PTR(slot + u * 1024), 16, 0, 0);
+            }
+            p_h ^= 1;
+            if (p_h == 0 && ++p_jb == njb) { p_jb = 0; p_bi += NW; }
+        }
+        ++issued;
+        if (++issue_slot == depth) issue_slot = 0;
+    }
+
+    __device__ __forceinline__ void start() {
+        issued = 0; issue_slot = 0; taken = 0; take_slot = 0;
+        p_g0 = 0; p_kc = 0; p_r = 0; p_bi = wave; p_jb = 0; p_h = 0;
+        const int ahead = min(depth - 1, T);
+        for (int i = 0; i < ahead; ++i) issue();
+    }
+
+    // Returns the LDS address of the next tile, landed and readable by this wavefront.
+    __device__ __forceinline__ const unsigned char* acquire() {
+        // Reads of the slot about to be refilled must have returned before its refill is issued.
+        DFK_WAIT_LGKM0();
+        asm volatile("" ::: "memory");
+        if (issued < T) {
+            issue();
+            wait_tiles_in_flight(depth - 1);
+        } else {
+            wait_tiles_in_flight(0);
+        }
+        const unsigned char* slot = ring + take_slot * kTileBytes;
+        ++taken;
+        if (++take_slot == depth) take_slot = 0;
+        return slot;
+    }
+};
+
+template <int NW, int TT, int MODE>
+__global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    constexpr int TOK = 16 * TT;
+    constexpr int NTHREADS = NW * 64;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int q = lane & 15, g = lane >> 4;
+    float* gu = (float*)(lds + geo.gu_off);
+    uint16_t* a2s = (uint16_t*)(lds + geo.a2s_off);
+    const uint16_t* X = (const uint16_t*)a.X;
+
+    // ---- geometry
+    int j0, j1, blk_lo = 0, blk_cnt = a.d_model / 128;
+    if (MODE == MODE_DOWN) {
+        const int js = blockIdx.x / a.k2_col_blocks;
+        const int cb = blockIdx.x - js * a.k2_col_blocks;
+        slice_rows(a.d_ff, a.k2_splits, js, j0, j1);
+        blk_cnt = blk_cnt / a.k2_col_blocks;
+        blk_lo = cb * blk_cnt;
+    } else {
+        slice_rows(a.d_ff, a.splits, blockIdx.x, j0, j1);
+    }
+    const int rows = j1 - j0;
+    const int nt = rows / 8;
+    const int rows_pad = (rows + 31) & ~31;
+    const int njb = rows_pad / 32;
+    const int KW = a.d_model / NW;
+    const int nkc = KW / kKC;
+    const int my_blocks = wave < blk_cnt ? (blk_cnt - wave + NW - 1) / NW : 0;
+
+    TileStream<NW, MODE> ts;
+    ts.Wg = (const uint16_t*)a.Wg; ts.Wu = (const uint16_t*)a.Wu; ts.Wd = (const uint16_t*)a.Wd;
+    ts.d_model = a.d_model; ts.d_ff = a.d_ff;
+    ts.j0 = j0; ts.nt = nt; ts.njb = njb;
+    ts.kbase = wave * KW; ts.nkc = nkc;
+    ts.blk_lo = blk_lo; ts.blk_cnt = blk_cnt;
+    ts.wave = wave; ts.q = q; ts.g = g;
+    ts.ring = lds + wave * geo.depth * kTileBytes;
+    ts.depth = geo.depth;
+    ts.T1 = (MODE != MODE_DOWN) ? nt * nkc : 0;
+    ts.T = ts.T1 + ((MODE != MODE_GATEUP) ? my_blocks * njb * 2 : 0);
+    ts.start();
+
+    // ---- stage one
+    if (MODE != MODE_DOWN) {
+        for (int i = tid; i < nt * 16 * TOK; i += NTHREADS) gu[i] = 0.f;
+        __syncthreads();
+        for (int g0 = 0; g0 < nt; g0 += kGT) {
+            const int gsz = min(kGT, nt - g0);
+            f32x4 acc[kGT][TT];
+#pragma unroll
+            for (int r = 0; r < kGT; ++r)
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) acc[r][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            u32x4 xcur[TT][4], xnext[TT][4];
+            auto load_x = [&](u32x4 (&x)[TT][4], int kc) {
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) {
+                    const int token = tt * 16 + q;
+#pragma unroll
+                    for (int s = 0; s < 4; ++s) {
+                        x[tt][s] = u32x4{0, 0, 0, 0};
+                        if (token < a.m_count)
+                            x[tt][s] = ld16(X, ((size_t)(a.m_base + token) * a.d_model + ts.kbase + kc * kKC) / 8 + 4 * s + g);
+                    }
+                }
+            };
+            load_x(xcur, 0);
+            for (int kc = 0; kc < nkc; ++kc) {
+                if (kc + 1 < nkc) load_x(xnext, kc + 1);
+#pragma unroll
+                for (int r = 0; r < kGT; ++r) {
+                    if (r < gsz) {
+                        const unsigned char* slot = ts.acquire();
+#pragma unroll
+                        for (int s = 0; s < 4; ++s) {
+                            const bf16x8 av = *(const bf16x8*)(slot + (q * 16 + ((4 * s + g) ^ q)) * 16);
+#pragma unroll
+                            for (int tt = 0; tt < TT; ++tt)
+                                acc[r][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, as_bf16x8(xcur[tt][s]),
+                                                                                    acc[r][tt], 0, 0, 0);
+                        }
+                    }
+                }
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                    for (int s = 0; s < 4; ++s) xcur[tt][s] = xnext[tt][s];
+            }
+            // k-partial sums of all wavefronts meet in LDS
+#pragma unroll
+            for (int r = 0; r < kGT; ++r) {
+                if (r < gsz) {
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            atomicAdd(&gu[((g0 + r) * 16 + 4 * g + i) * TOK + tt * 16 + q], acc[r][tt][i]);
+                }
+            }
+        }
+        __syncthreads();
+        // SiLU(G) * U  ->  A_2
+        for (int idx = tid; idx < rows_pad * TOK; idx += NTHREADS) {
+            const int j = idx / TOK, m = idx - j * TOK;
+            float v = 0.f;
+            if (j < rows) {
+                const int tile = j >> 3, jr = j & 7;
+                v = silu_mul(gu[(tile * 16 + jr) * TOK + m], gu[(tile * 16 + 8 + jr) * TOK + m]);
+            }
+            if (MODE == MODE_FUSED) {
+                a2s[m * geo.a2_stride + j] = (uint16_t)f32_to_bf16_bits(v);
+            } else if (j < rows && m < a.m_count) {
+                const size_t o = (size_t)(a.m_base + m) * a.d_ff + j0 + j;
+                if (a.a2_is_fp32) ((float*)a.a2)[o] = v;
+                else ((uint16_t*)a.a2)[o] = (uint16_t)f32_to_bf16_bits(v);
+            }
+        }
+        if (MODE == MODE_FUSED) __syncthreads();
+    }
+    if (MODE == MODE_GATEUP) return;
+
+    // ---- stage two
+    if (MODE == MODE_DOWN) {
+        for (int idx = tid; idx < rows_pad * TOK; idx += NTHREADS) {
+            const int m = idx / rows_pad, j = idx - m * rows_pad;
+            uint16_t v = 0;
+            if (j < rows && m < a.m_count) {
+                const size_t o = (size_t)(a.m_base + m) * a.d_ff + j0 + j;
+                v = a.a2_is_fp32 ? (uint16_t)f32_to_bf16_bits(((const float*)a.a2)[o]) : ((const uint16_t*)a.a2)[o];
+            }
+            a2s[m * geo.a2_stride + j] = v;
+        }
+        __syncthreads();
+    }
+    for (int bi = wave; bi < blk_cnt; bi += NW) {
+        const int nb = (blk_lo + bi) * 128;
+        f32x4 acc2[8][TT];
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) acc2[c][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int jb = 0; jb < njb; ++jb) {
+            u32x4 w[8];
+            const unsigned char* sa = ts.acquire();
+#pragma unroll
+            for (int u = 0; u < 4; ++u) w[u] = *(const u32x4*)(sa + u * 1024 + lane * 16);
+            const unsigned char* sb = ts.acquire();
+#pragma unroll
+            for (int u = 0; u < 4; ++u) w[4 + u] = *(const u32x4*)(sb + u * 1024 + lane * 16);
+            if (jb * 32 + 32 > rows) {   // rows past the slice contribute nothing
+#pragma unroll
+                for (int r = 0; r < 8; ++r)
+                    if (jb * 32 + 8 * g + r >= rows) w[r] = u32x4{0, 0, 0, 0};
+            }
+            bf16x8 av[TT];
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt)
+                av[tt] = *(const bf16x8*)(a2s + (tt * 16 + q) * geo.a2_stride + jb * 32 + 8 * g);
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
+                u32x4 b;
+#pragma unroll
+                for (int p = 0; p < 4; ++p)
+                    b[p] = __builtin_amdgcn_perm(w[2 * p + 1][c >> 1], w[2 * p][c >> 1], sel);
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt)
+                    acc2[c][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[tt], as_bf16x8(b), acc2[c][tt], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int token = tt * 16 + 4 * g + i;
+                if (token < a.m_count) {
+                    float* dst = a.yacc + (size_t)(a.m_base + token) * a.d_model + nb + 8 * q;
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) acc_add(dst + c, acc2[c][tt][i]);
+                }
+            }
+    }
+
+    // ---- last workgroup drains the accumulator into Y (bf16), leaving zeros behind
+    __shared__ int is_last;
+    release_device();
+    __syncthreads();
+    if (tid == 0) {
+        const unsigned expected = MODE == MODE_DOWN ? (unsigned)(a.k2_splits * a.k2_col_blocks) : (unsigned)a.splits;
+        is_last = arrive_last(a.tickets, expected) ? 1 : 0;
+    }
+    __syncthreads();
+    if (!is_last) return;
+    acquire_device();
+    const size_t lo = (size_t)a.m_base * a.d_model;
+    const size_t npair = (size_t)a.m_count * a.d_model / 2;
+    uint32_t* Y2 = (uint32_t*)((uint16_t*)a.Y + lo);
+    for (size_t i = tid; i < npair; i += NTHREADS) {
+        const float v0 = acc_take(a.yacc + lo + 2 * i), v1 = acc_take(a.yacc + lo + 2 * i + 1);
+        Y2[i] = pack_bf16x2(v0, v1);
+    }
+}
+
+struct Sizes {
+    Geom geo;
+    size_t lds;
+};
+
+// tokens per launch: one or two token tiles of 16
+int token_tiles(const dfk_config_t& c, int m_count) { return (c.waves == 16 || m_count <= 16) ? 1 : 2; }
+
+Sizes sizes(const dfk_config_t& c, int mode, int TT, int d_ff) {
+    Sizes s;
+    const int S = mode == MODE_DOWN ? c.k2_splits : c.splits;
+    const int maxrows = max_slice_rows(d_ff, S);
+    const int rows_pad = (maxrows + 31) & ~31;
+    const int TOK = 16 * TT;
+    size_t off = (size_t)c.waves * c.depth * kTileBytes;
+    s.geo.depth = c.depth;
+    s.geo.gu_off = (int)off;
+    if (mode != MODE_DOWN) off += (size_t)(maxrows / 8) * 16 * TOK * 4;
+    s.geo.a2s_off = (int)off;
+    s.geo.a2_stride = rows_pad + 8;
+    if (mode != MODE_GATEUP) off += (size_t)TOK * s.geo.a2_stride * 2;
+    s.lds = off;
+    return s;
+}
+
+template <int NW, int TT, int MODE>
+hipError_t launch_one(const MlpArgs& a, const dfk_config_t& c, int grid, hipStream_t st) {
+    static size_t configured = 0;   // largest dynamic LDS size this instantiation was allowed so far
+    const Sizes s = sizes(c, MODE, TT, a.d_ff);
+    if (s.lds > configured) {
+        hipError_t e = hipFuncSetAttribute((const void*)k_mfma<NW, TT, MODE>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)s.lds);
+        if (e != hipSuccess) return e;
+        configured = s.lds;
+    }
+    hipLaunchKernelGGL((k_mfma<NW, TT, MODE>), dim3(grid), dim3(NW * 64), s.lds, st, a, s.geo);
+    return hipGetLastError();
+}
+
+template <int NW, int TT>
+hipError_t launch_nt(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
+    if (c.variant == DFK_VARIANT_FUSED) return launch_one<NW, TT, MODE_FUSED>(a, c, a.splits, st);
+    hipError_t e = launch_one<NW, TT, MODE_GATEUP>(a, c, a.splits, st);
+    if (e != hipSuccess) return e;
+    return launch_one<NW, TT, MODE_DOWN>(a, c, a.k2_splits * a.k2_col_blocks, st);
+}
+
+}  // namespace
+
+int mfma_max_tokens_per_launch(const dfk_config_t& c) { return c.waves == 16 ? 16 : 32; }
+
+bool mfma_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype) {
+    if (c.path != DFK_PATH_MFMA || dtype != DFK_BF16) return false;
+    if (c.variant != DFK_VARIANT_FUSED && c.variant != DFK_VARIANT_TWO_KERNEL) return false;
+    if (c.reduce != DFK_REDUCE_ATOMIC) return false;
+    if (c.waves != 4 && c.waves != 8 && c.waves != 16) return false;
+    if (c.depth < 2 || c.depth > 16) return false;
+    if (M < 1 || d_model < 8 || d_ff < 8 || d_ff % 8) return false;
+    if (d_model % (kKC * c.waves)) return false;   // each wavefront owns whole 128-k chunks
+    const int ng = d_ff / 8;
+    if (c.splits < 1 || c.splits > ng) return false;
+    const int TT = token_tiles(c, M);
+    if (c.variant == DFK_VARIANT_FUSED) return sizes(c, MODE_FUSED, TT, d_ff).lds <= (size_t)kLdsLimit;
+    if (c.k2_splits < 1 || c.k2_splits > ng) return false;
+    const int nblk = d_model / 128;
+    if (c.k2_col_blocks < 1 || nblk % c.k2_col_blocks) return false;
+    if ((long long)c.k2_splits * c.k2_col_blocks > 65535) return false;
+    if (c.a2_dtype != DFK_BF16 && c.a2_dtype != DFK_FP32) return false;
+    return sizes(c, MODE_GATEUP, TT, d_ff).lds <= (size_t)kLdsLimit &&
+           sizes(c, MODE_DOWN, TT, d_ff).lds <= (size_t)kLdsLimit;
+}
+
+hipError_t launch_mfma(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
+    const int TT = token_tiles(c, a.m_count);
+    switch (c.waves * 10 + TT) {
+        case 41: return launch_nt<4, 1>(a, c, st);
+        case 42: return launch_nt<4, 2>(a, c, st);
+        case 81: return launch_nt<8, 1>(a, c, st);
+        case 82: return launch_nt<8, 2>(a, c, st);
+        case 161: return launch_nt<16, 1>(a, c, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
 }  // namespace dfk

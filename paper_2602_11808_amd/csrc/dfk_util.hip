@@ -35,29 +35,25 @@ constexpr int kReadUnroll = 8;
 __global__ __launch_bounds__(kReadThreads) void k_stream_read(const u32x4* __restrict__ src, size_t n16,
                                                               unsigned* sink) {
     const size_t tile = (size_t)kReadThreads * kReadUnroll;
+    const size_t full = n16 / tile;
     u32x4 acc = {0, 0, 0, 0};
-    for (size_t base = (size_t)blockIdx.x * tile; base < n16; base += (size_t)gridDim.x * tile) {
+    // whole tiles: kReadUnroll independent 16-byte loads per lane in flight, no bounds checks
+    for (size_t t = blockIdx.x; t < full; t += gridDim.x) {
+        const u32x4* p = src + t * tile + threadIdx.x;
         u32x4 v[kReadUnroll];
 #pragma unroll
-        for (int u = 0; u < kReadUnroll; ++u) {
-            const size_t i = base + (size_t)u * kReadThreads + threadIdx.x;
-            v[u] = i < n16 ? __builtin_nontemporal_load(src + i) : u32x4{0, 0, 0, 0};
-        }
+        for (int u = 0; u < kReadUnroll; ++u) v[u] = __builtin_nontemporal_load(p + (size_t)u * kReadThreads);
 #pragma unroll
-        for (int u = 0; u < kReadUnroll; ++u) {
-            acc ^= v[u];
-        }
+        for (int u = 0; u < kReadUnroll; ++u) acc ^= v[u];
     }
-    unsigned a = acc.x ^ acc.z, b = acc.y ^ acc.w;
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) {
-        a ^= __shfl_xor(a, o);
-        b ^= __shfl_xor(b, o);
-    }
-    if ((threadIdx.x & 63) == 0) {
-        atomicXor(sink, a);
-        atomicXor(sink + 1, b);
-    }
+    // ragged tail
+    for (size_t i = full * tile + (size_t)blockIdx.x * kReadThreads + threadIdx.x; i < n16;
+         i += (size_t)gridDim.x * kReadThreads)
+        acc ^= src[i];
+    // Keep the loads alive without a contended atomic: the fold is compared with a
+    // value it practically never takes.
+    const unsigned a = acc.x ^ acc.z, b = acc.y ^ acc.w;
+    if (a == 0x9E3779B9u && b == 0x7F4A7C15u) sink[0] = 1u;
 }
 
 }  // namespace

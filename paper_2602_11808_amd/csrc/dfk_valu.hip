@@ -101,10 +101,14 @@ __device__ __forceinline__ void stage2_valu(const MlpArgs& a, int j0, int rows, 
 template <typename E>
 __device__ __forceinline__ void finalize_valu(const MlpArgs& a, unsigned expected) {
     __shared__ int is_last;
+    // Every wavefront waits for its own accumulates to be performed device-wide
+    // before the workgroup's single arrival is counted.
+    release_device();
     __syncthreads();
     if (threadIdx.x == 0) is_last = arrive_last(a.tickets, expected) ? 1 : 0;
     __syncthreads();
     if (!is_last) return;
+    acquire_device();
     const size_t lo = (size_t)a.m_base * a.d_model;
     const size_t n = (size_t)a.m_count * a.d_model;
     for (size_t i = threadIdx.x; i < n; i += blockDim.x) E::store(a.Y, lo + i, acc_take(a.yacc + lo + i));

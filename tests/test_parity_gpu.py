@@ -47,7 +47,7 @@ def y64(Y):
 
 def workspace_is_clean(ws, M, d):
     """Counters and the fp32 accumulator must be zero again after a call."""
-    head = ws[: 4096 + M * d * 4]
+    head = ws[: 4096 + dfk.DFK_MAX_M * d * 4]
     return int(torch.count_nonzero(head).item()) == 0
 
 
@@ -199,6 +199,27 @@ def test_repeated_calls_share_a_workspace_and_stay_correct():
         worst = max(rel_err(y64(Y), ref) for Y in Ys)
         assert worst <= TOL_BF16, (cfg, worst)
         assert workspace_is_clean(ws, M, d)
+
+
+def test_one_workspace_serves_calls_of_different_token_counts():
+    # scratch of one call must never land where a later call with another M expects zeros
+    d, ff = 512, 1536
+    t = di.mlp_inputs(8, d, ff, seed=17)
+    g = gpu_inputs(t)
+    ws = dfk.new_workspace(8, d, ff, DEV)
+    dfk.dfk_set_workspace(ws)
+    try:
+        for M in (1, 8, 2, 5, 1, 3):
+            ref = oracle.swiglu_mlp(t["X"][:M], t["Wg"], t["Wu"], t["Wd"])
+            X = g["X"][:M].contiguous()
+            for fn in (dfk.dfk_swiglu_mlp_unfused, dfk.dfk_swiglu_mlp_fused, dfk.dfk_swiglu_mlp):
+                Y = torch.full_like(X, float("nan"))
+                fn(X, g["Wg"], g["Wu"], g["Wd"], Y)
+                torch.cuda.synchronize()
+                assert rel_err(y64(Y), ref) <= TOL_BF16, (M, fn.__name__)
+                assert workspace_is_clean(ws, M, d)
+    finally:
+        dfk.dfk_set_workspace(None)
 
 
 def test_split_identity_on_gpu():
