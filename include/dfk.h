@@ -24,12 +24,12 @@
  * workspace.  No entry point on the call path allocates or frees device
  * memory or synchronises the host; work is enqueued on `stream` (a
  * hipStream_t passed as void*, NULL = the default stream) and the call
- * returns at once.  The workspace holds the fp32 accumulator of Y, arrival
- * counters and (two-kernel variant) A_2; accumulator and counters must be zero
- * before the first call (dfk_workspace_init) and every call leaves them zero
- * again, so a workspace may be reused by successive calls, with any M, on ONE
- * stream as long as d_model stays the same (initialise it again before using it
- * with another d_model).  Calls that share a workspace and overlap in time race.
+ * returns at once.  The workspace holds arrival counters (its first 4096
+ * bytes), the fp32 partial sums of Y and (two-kernel variant) A_2.  The counters
+ * must be zero before the first call (dfk_workspace_init) and every call leaves
+ * them zero again, so a workspace may be reused by successive calls, of any
+ * shape that fits, on ONE stream.  Calls that share a workspace and overlap in
+ * time race.
  *
  * Errors: every function returns a dfk_status_t (or a plain value where
  * noted) and never throws or aborts.  All argument errors are detected on the
@@ -65,8 +65,12 @@ typedef enum { DFK_VARIANT_AUTO = 0, DFK_VARIANT_FUSED = 1, DFK_VARIANT_TWO_KERN
 /* How the contractions are computed. */
 typedef enum { DFK_PATH_VALU = 0, DFK_PATH_MFMA = 1 } dfk_path_t;
 
-/* How the split-d_ff partial sums of the down projection are combined. */
-typedef enum { DFK_REDUCE_ATOMIC = 0, DFK_REDUCE_TICKET = 1 } dfk_reduce_t;
+/* How the split-d_ff partial sums of the down projection are combined.
+ * DFK_REDUCE_TICKET: partial blocks in the workspace, summed in a fixed order by
+ * the last workgroup to arrive at each of two levels of arrival counters;
+ * run-to-run bitwise deterministic.  DFK_REDUCE_ATOMIC (device-wide fp32 atomic
+ * adds) is reserved: no kernel offers it. */
+typedef enum { DFK_REDUCE_TICKET = 0, DFK_REDUCE_ATOMIC = 1 } dfk_reduce_t;
 
 #define DFK_MAX_M 256            /* largest token count one call accepts */
 

@@ -27,7 +27,7 @@ DFK_ERR_NOT_FOUND = -8
 DFK_BF16, DFK_FP32 = 0, 1
 DFK_VARIANT_AUTO, DFK_VARIANT_FUSED, DFK_VARIANT_TWO_KERNEL = 0, 1, 2
 DFK_PATH_VALU, DFK_PATH_MFMA = 0, 1
-DFK_REDUCE_ATOMIC, DFK_REDUCE_TICKET = 0, 1
+DFK_REDUCE_TICKET, DFK_REDUCE_ATOMIC = 0, 1
 DFK_MAX_M = 256
 
 

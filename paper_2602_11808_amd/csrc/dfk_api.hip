@@ -82,7 +82,7 @@ dfk_config_t make_cfg(int variant, int path, int splits, int waves, int depth, i
     dfk_config_t c;
     std::memset(&c, 0, sizeof c);
     c.variant = variant; c.path = path; c.splits = splits; c.waves = waves; c.depth = depth;
-    c.reduce = DFK_REDUCE_ATOMIC; c.k2_splits = k2s; c.k2_col_blocks = k2c; c.a2_dtype = a2dt;
+    c.reduce = DFK_REDUCE_TICKET; c.k2_splits = k2s; c.k2_col_blocks = k2c; c.a2_dtype = a2dt;
     return c;
 }
 
@@ -200,11 +200,12 @@ dfk_status_t run(const void* X, const void* Wg, const void* Wu, const void* Wd, 
     a.splits = c.splits; a.k2_splits = c.k2_splits; a.k2_col_blocks = c.k2_col_blocks;
     a.a2_is_fp32 = c.a2_dtype == DFK_FP32;
     a.tickets = (unsigned*)((char*)ws + l.tickets_off);
-    a.yacc = (float*)((char*)ws + l.yacc_off);
+    a.P = (float*)((char*)ws + l.p_off);
+    a.Q = (float*)((char*)ws + l.q_off);
     a.a2 = (char*)ws + l.a2_off;
     // Token chunking on the host: a launch handles at most `per` tokens; further
     // chunks are further launches on the same stream (they re-stream the weights).
-    const int per = c.path == DFK_PATH_MFMA ? mfma_max_tokens_per_launch(c) : DFK_MAX_M;
+    const int per = c.path == DFK_PATH_MFMA ? mfma_max_tokens_per_launch(c) : valu_max_tokens_per_launch();
     for (int m0 = 0; m0 < M; m0 += per) {
         a.m_base = m0;
         a.m_count = std::min(per, M - m0);

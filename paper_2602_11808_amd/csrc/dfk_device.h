@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "dfk_internal.h"
+
 namespace dfk {
 
 // 16 bytes as a native vector (what global_load_dwordx4 moves)
@@ -41,6 +43,13 @@ struct BF16 {
     __device__ static __forceinline__ void store(void* Y, size_t i, float v) {
         ((uint16_t*)Y)[i] = (uint16_t)f32_to_bf16_bits(v);
     }
+    // four consecutive outputs, i a multiple of 4
+    __device__ static __forceinline__ void store4(void* Y, size_t i, float a, float b, float c, float d) {
+        uint2 v;
+        v.x = pack_bf16x2(a, b);
+        v.y = pack_bf16x2(c, d);
+        *(uint2*)((uint16_t*)Y + i) = v;
+    }
 };
 struct FP32 {
     static constexpr int VEC = 4;
@@ -50,40 +59,144 @@ struct FP32 {
         f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
     }
     __device__ static __forceinline__ void store(void* Y, size_t i, float v) { ((float*)Y)[i] = v; }
+    __device__ static __forceinline__ void store4(void* Y, size_t i, float a, float b, float c, float d) {
+        *(float4*)((float*)Y + i) = make_float4(a, b, c, d);
+    }
 };
 
 __device__ __forceinline__ u32x4 ld16(const void* base, size_t vec_index) {
     return ((const u32x4*)base)[vec_index];
 }
-
-// ---- device-scope fp32 accumulate / drain ----------------------------------
-// Hardware float atomic add without return (device scope, relaxed).
-__device__ __forceinline__ void acc_add(float* p, float v) {
-    __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-// Read the accumulated value and leave zero behind, at the same coherence
-// point as the adds (no plain load of memory other agents' atomics touched).
-__device__ __forceinline__ float acc_take(float* p) {
-    return __hip_atomic_exchange(p, 0.0f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+// Same for data that is read exactly once (the weight stream): non-temporal hint.
+__device__ __forceinline__ u32x4 ld16_stream(const void* base, size_t vec_index) {
+    return __builtin_nontemporal_load((const u32x4*)base + vec_index);
 }
 
-// Device-scope fences.  A release makes the calling wavefront wait until all
-// of its earlier stores and atomics have been performed for the whole device; it
-// must be executed by every wavefront whose writes the arrival below publishes
-// (a workgroup barrier alone does not wait for other wavefronts' memory traffic).
-__device__ __forceinline__ void release_device() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent"); }
+// ---- publishing partial sums to other workgroups ------------------------------
+// Partial sums are published with device-scope (write-through) stores, so they
+// are visible to the whole device once the issuing wavefront's memory counter
+// has drained; no L2 write-back fence is needed on the writer side (such a fence
+// executed by every wavefront was measured to dominate the kernel).  A reader
+// invalidates its caches once (acquire_device) before it loads them.
+__device__ __forceinline__ void store2_device(float* p, float a, float b) {
+    union { float f[2]; unsigned long long u; } c;
+    c.f[0] = a; c.f[1] = b;
+    __hip_atomic_store((unsigned long long*)p, c.u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store4_device(float* p, float a, float b, float c, float d) {
+    store2_device(p, a, b);
+    store2_device(p + 2, c, d);
+}
+// Wait until every memory operation this wavefront has issued has completed.
+__device__ __forceinline__ void drain_own_memory_ops() {
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    asm volatile("" ::: "memory");
+}
 __device__ __forceinline__ void acquire_device() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent"); }
 
 // Arrival counter: returns true for the last of `expected` arrivals, and resets
-// the counter for the next call.  Release/acquire at device scope orders every
-// earlier accumulate of the caller before the count, and the drain after it.
+// the counter for the next call.  The caller orders its published stores before
+// it (drain_own_memory_ops in every wavefront, then a workgroup barrier).
 __device__ __forceinline__ bool arrive_last(unsigned* ticket, unsigned expected) {
-    unsigned old = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned old = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (old == expected - 1u) {
         __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return true;
     }
     return false;
+}
+
+// ---- split-d_ff reduction ----------------------------------------------------
+// Every workgroup has published its fp32 partial block of Y ([m_count][d_model]
+// floats, block index p) with store4_device.  Workgroups are gathered in
+// first-level groups; the last of a group to arrive sums the group's blocks in
+// a fixed order into the group block Q[q_slot] (or, if there is only one group
+// for these columns, straight into Y); the last group to arrive sums the group
+// blocks, again in a fixed order, and writes Y.  No workgroup ever waits for
+// another, and the result does not depend on arrival order.
+struct ReducePlan {
+    float* P;
+    float* Q;
+    unsigned* tickets;
+    int m_count, d_model;
+    int c_lo, c_hi;             // columns (floats, multiples of 4) this group is responsible for
+    int p_first, p_stride, n1;  // first-level members: blocks p_first + i*p_stride, i < n1
+    int t1;                     // first-level counter
+    int q_slot, n2, t2;         // second level: own group block, number of group blocks, counter
+};
+
+// Plan of the fused kernel (and of any kernel whose workgroup s of `S` holds a
+// partial of all d_model columns): groups are the residues s mod NG, NG = ceil(S/16).
+__device__ __forceinline__ ReducePlan plan_full_width(const MlpArgs& a, int s, int S) {
+    ReducePlan r;
+    const int ng = (S + kGroupSize - 1) / kGroupSize;
+    const int g = s % ng;
+    r.P = a.P; r.Q = a.Q; r.tickets = a.tickets;
+    r.m_count = a.m_count; r.d_model = a.d_model;
+    r.c_lo = 0; r.c_hi = a.d_model;
+    r.p_first = g; r.p_stride = ng; r.n1 = (S - g + ng - 1) / ng;
+    r.t1 = g;
+    r.q_slot = g; r.n2 = ng; r.t2 = kTicketLevel2;
+    return r;
+}
+
+// Plan of the second kernel of the two-kernel variant: workgroup (js, cb) holds
+// the partial of d_ff split js for columns [c_lo, c_hi); one level.
+__device__ __forceinline__ ReducePlan plan_column_block(const MlpArgs& a, int cb, int c_lo, int c_hi) {
+    ReducePlan r;
+    r.P = a.P; r.Q = a.Q; r.tickets = a.tickets;
+    r.m_count = a.m_count; r.d_model = a.d_model;
+    r.c_lo = c_lo; r.c_hi = c_hi;
+    r.p_first = cb; r.p_stride = a.k2_col_blocks; r.n1 = a.k2_splits;
+    r.t1 = cb;
+    r.q_slot = 0; r.n2 = 1; r.t2 = kTicketLevel2;
+    return r;
+}
+
+template <typename E>
+__device__ __forceinline__ void reduce_store(const ReducePlan& r, void* Y, int m_base, int* flag) {
+    const int tid = threadIdx.x, nth = blockDim.x;
+    const int w4 = (r.c_hi - r.c_lo) >> 2;
+    const size_t blk = (size_t)r.m_count * r.d_model;
+    // Every wavefront waits for its own published stores before the workgroup's
+    // single arrival is counted.
+    drain_own_memory_ops();
+    __syncthreads();
+    if (tid == 0) *flag = arrive_last(r.tickets + r.t1, (unsigned)r.n1) ? 1 : 0;
+    __syncthreads();
+    if (!*flag) return;
+    acquire_device();
+    for (int idx = tid; idx < r.m_count * w4; idx += nth) {
+        const int m = idx / w4, c4 = idx - m * w4;
+        const size_t off = (size_t)m * r.d_model + r.c_lo + 4 * c4;
+        const float* src = r.P + (size_t)r.p_first * blk + off;
+        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 8
+        for (int i = 0; i < r.n1; ++i) {
+            const float4 v = *(const float4*)(src + (size_t)i * r.p_stride * blk);
+            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+        }
+        if (r.n2 == 1) E::store4(Y, (size_t)(m_base + m) * r.d_model + r.c_lo + 4 * c4, s.x, s.y, s.z, s.w);
+        else store4_device(r.Q + (size_t)r.q_slot * blk + off, s.x, s.y, s.z, s.w);
+    }
+    if (r.n2 == 1) return;
+    drain_own_memory_ops();
+    __syncthreads();
+    if (tid == 0) *flag = arrive_last(r.tickets + r.t2, (unsigned)r.n2) ? 1 : 0;
+    __syncthreads();
+    if (!*flag) return;
+    acquire_device();
+    for (int idx = tid; idx < r.m_count * w4; idx += nth) {
+        const int m = idx / w4, c4 = idx - m * w4;
+        const size_t off = (size_t)m * r.d_model + r.c_lo + 4 * c4;
+        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 8
+        for (int i = 0; i < r.n2; ++i) {
+            const float4 v = *(const float4*)(r.Q + (size_t)i * blk + off);
+            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+        }
+        E::store4(Y, (size_t)(m_base + m) * r.d_model + r.c_lo + 4 * c4, s.x, s.y, s.z, s.w);
+    }
 }
 
 }  // namespace dfk

@@ -10,28 +10,45 @@
 namespace dfk {
 
 // ---------------------------------------------------------------- workspace layout
-// [0, 4096)                      arrival counters (unsigned), zero between calls
-// [4096, +DFK_MAX_M*d_model*4)   fp32 accumulator of Y, zero between calls
-// [.., +M*d_ff*4)                A_2 between the two launches of the two-kernel variant
-// The zero-between-calls part comes first and its size does not depend on M, so
-// calls with different M on one workspace never put scratch where another call
-// expects zeros.
+// [0, 4096)      arrival counters (unsigned), zero between calls
+// [4096, +P)     fp32 partial sums of Y, one [tokens, d_model] block per workgroup slice
+// [.., +Q)       fp32 group sums (second level of the reduction)
+// [.., +M*d_ff*4) A_2 between the two launches of the two-kernel variant
+// Only the counters have to be zero between calls; nothing else is read before
+// it is written within a call.
 constexpr size_t kWsHeaderBytes = 4096;
 constexpr int kMaxTickets = 1024;
+constexpr int kTicketLevel2 = 512;          // counters [0,512): level 1, [512,1024): level 2
+constexpr int kMaxTokensPerLaunch = 32;     // a launch handles at most this many tokens
+constexpr size_t kPartialCapBytes = (size_t)128 << 20;
+constexpr int kGroupSize = 16;              // workgroup partials summed per first-level group
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+inline size_t partial_bytes(int M, int d_model) {
+    const size_t want = (size_t)1024 * (M < kMaxTokensPerLaunch ? M : kMaxTokensPerLaunch) * d_model * 4;
+    return want < kPartialCapBytes ? want : kPartialCapBytes;
+}
+
 struct WsLayout {
-    size_t tickets_off, yacc_off, a2_off, total;
+    size_t tickets_off, p_off, q_off, a2_off, total;
 };
 
 inline WsLayout ws_layout(int M, int d_model, int d_ff) {
     WsLayout l;
     l.tickets_off = 0;
-    l.yacc_off = kWsHeaderBytes;
-    l.a2_off = l.yacc_off + align_up((size_t)DFK_MAX_M * d_model * 4, 256);
+    l.p_off = kWsHeaderBytes;
+    l.q_off = l.p_off + align_up(partial_bytes(M, d_model), 256);
+    l.a2_off = l.q_off + align_up(partial_bytes(M, d_model) / 8, 256);
     l.total = l.a2_off + align_up((size_t)M * d_ff * 4, 256);
     return l;
+}
+
+// true if `splits` partial blocks of `tokens` x d_model fp32 fit the partial area sized for M
+inline bool partials_fit(int splits, int tokens, int M, int d_model) {
+    const size_t need = (size_t)splits * tokens * d_model * 4;
+    const size_t groups = (size_t)(splits + kGroupSize - 1) / kGroupSize;
+    return need <= partial_bytes(M, d_model) && groups * tokens * d_model * 4 <= partial_bytes(M, d_model) / 8;
 }
 
 // ---------------------------------------------------------------- kernel arguments
@@ -43,11 +60,12 @@ struct MlpArgs {
     void* Y;
     int M, d_model, d_ff;
     int m_base;        // first token this launch handles (host-side token chunking)
-    int m_count;       // tokens this launch handles
+    int m_count;       // tokens this launch handles (<= kMaxTokensPerLaunch)
     int splits;        // d_ff slices (grid of the fused kernel / first kernel)
     int k2_splits, k2_col_blocks;
     int a2_is_fp32;    // storage type of A_2 in the workspace (two-kernel variant)
-    float* yacc;       // [M, d_model] fp32, zero on entry and on exit
+    float* P;          // partial sums [slice][m_count][d_model]
+    float* Q;          // group sums   [group][m_count][d_model]
     unsigned* tickets; // zero on entry and on exit
     void* a2;          // [M, d_ff] in the workspace
 };
@@ -74,6 +92,7 @@ hipError_t launch_mfma(const MlpArgs& a, const dfk_config_t& c, hipStream_t st);
 bool valu_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype);
 bool mfma_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype);
 int mfma_max_tokens_per_launch(const dfk_config_t& c);
+int valu_max_tokens_per_launch();
 
 // utility kernels
 hipError_t launch_zero(void* p, size_t bytes, hipStream_t st);

@@ -29,8 +29,9 @@
 // block (8 rows x 8 columns); v_perm_b32 regroups it into, per column, the 8
 // consecutive-j values the MFMA B operand wants - a per-lane transpose, no
 // cross-lane traffic.  A_2 (bf16, from LDS) is the A operand.  The fp32 block
-// of partial Y is added into the device-wide fp32 accumulator with hardware
-// float atomics; the last workgroup to arrive drains it into Y as bf16.
+// of partial Y is published to the workspace with device-scope stores and combined
+// by the two-level arrival-counter reduction (reduce_store); device-wide float
+// atomics were measured at ~10 G adds/s on MI355X and are not used.
 #include "dfk_device.h"
 #include "dfk_internal.h"
 
@@ -45,6 +46,7 @@ constexpr int kTileBytes = 4096;   // one ring slot = 4 global->LDS instructions
 constexpr int kKC = 128;           // k extent of a stage-one tile
 constexpr int kGT = 8;             // stage-one row tiles accumulated together
 constexpr int kLdsLimit = 160 * 1024;
+constexpr int kAuxNonTemporal = 2;  // cache-policy bit "nt": the weight stream is read once
 
 struct Geom {
     int depth;      // ring slots per wavefront
@@ -117,7 +119,7 @@ struct TileStream {
                 const int c = q ^ i;       // logical 16-byte chunk stored at position q of row i
                 const uint16_t* base = (u < 2) ? Wg : Wu;
                 const uint16_t* src = base + rowbase + (size_t)(i & 7) * d_model + c * 8;
-                __builtin_amdgcn_global_load_lds(src, DFK_LDS_PTR(slot + u * 1024), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds(src, DFK_LDS_PTR(slot + u * 1024), 16, 0, kAuxNonTemporal);
             }
             const int gsz = min(kGT, nt - p_g0);
             if (++p_r == gsz) {
@@ -131,7 +133,7 @@ struct TileStream {
                 const int r = 4 * p_h + u;
                 const int row = min(j0 + p_jb * 32 + 8 * g + r, d_ff - 1);   // stay inside W_down
                 const uint16_t* src = Wd + (size_t)row * d_model + nb + 8 * q;
-                __builtin_amdgcn_global_load_lds(src, DFK_LDS_PTR(slot + u * 1024), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds(src, DFK_LDS_PTR(slot + u * 1024), 16, 0, kAuxNonTemporal);
             }
             p_h ^= 1;
             if (p_h == 0 && ++p_jb == njb) { p_jb = 0; p_bi += NW; }
@@ -344,30 +346,20 @@ __global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
             for (int i = 0; i < 4; ++i) {
                 const int token = tt * 16 + 4 * g + i;
                 if (token < a.m_count) {
-                    float* dst = a.yacc + (size_t)(a.m_base + token) * a.d_model + nb + 8 * q;
-#pragma unroll
-                    for (int c = 0; c < 8; ++c) acc_add(dst + c, acc2[c][tt][i]);
+                    float* dst = a.P + ((size_t)blockIdx.x * a.m_count + token) * a.d_model + nb + 8 * q;
+                    store4_device(dst, acc2[0][tt][i], acc2[1][tt][i], acc2[2][tt][i], acc2[3][tt][i]);
+                    store4_device(dst + 4, acc2[4][tt][i], acc2[5][tt][i], acc2[6][tt][i], acc2[7][tt][i]);
                 }
             }
     }
 
-    // ---- last workgroup drains the accumulator into Y (bf16), leaving zeros behind
-    __shared__ int is_last;
-    release_device();
-    __syncthreads();
-    if (tid == 0) {
-        const unsigned expected = MODE == MODE_DOWN ? (unsigned)(a.k2_splits * a.k2_col_blocks) : (unsigned)a.splits;
-        is_last = arrive_last(a.tickets, expected) ? 1 : 0;
-    }
-    __syncthreads();
-    if (!is_last) return;
-    acquire_device();
-    const size_t lo = (size_t)a.m_base * a.d_model;
-    const size_t npair = (size_t)a.m_count * a.d_model / 2;
-    uint32_t* Y2 = (uint32_t*)((uint16_t*)a.Y + lo);
-    for (size_t i = tid; i < npair; i += NTHREADS) {
-        const float v0 = acc_take(a.yacc + lo + 2 * i), v1 = acc_take(a.yacc + lo + 2 * i + 1);
-        Y2[i] = pack_bf16x2(v0, v1);
+    // ---- split-d_ff reduction and the bf16 store of Y
+    __shared__ int flag;
+    if (MODE == MODE_DOWN) {
+        const int cb = blockIdx.x % a.k2_col_blocks;
+        reduce_store<BF16>(plan_column_block(a, cb, blk_lo * 128, (blk_lo + blk_cnt) * 128), a.Y, a.m_base, &flag);
+    } else {
+        reduce_store<BF16>(plan_full_width(a, blockIdx.x, a.splits), a.Y, a.m_base, &flag);
     }
 }
 
@@ -425,7 +417,7 @@ int mfma_max_tokens_per_launch(const dfk_config_t& c) { return c.waves == 16 ? 1
 bool mfma_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype) {
     if (c.path != DFK_PATH_MFMA || dtype != DFK_BF16) return false;
     if (c.variant != DFK_VARIANT_FUSED && c.variant != DFK_VARIANT_TWO_KERNEL) return false;
-    if (c.reduce != DFK_REDUCE_ATOMIC) return false;
+    if (c.reduce != DFK_REDUCE_TICKET) return false;
     if (c.waves != 4 && c.waves != 8 && c.waves != 16) return false;
     if (c.depth < 2 || c.depth > 16) return false;
     if (M < 1 || d_model < 8 || d_ff < 8 || d_ff % 8) return false;
@@ -433,11 +425,17 @@ bool mfma_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_
     const int ng = d_ff / 8;
     if (c.splits < 1 || c.splits > ng) return false;
     const int TT = token_tiles(c, M);
-    if (c.variant == DFK_VARIANT_FUSED) return sizes(c, MODE_FUSED, TT, d_ff).lds <= (size_t)kLdsLimit;
+    const int per = mfma_max_tokens_per_launch(c);
+    const int tokens = M < per ? M : per;
+    if (c.variant == DFK_VARIANT_FUSED)
+        return (c.splits + kGroupSize - 1) / kGroupSize <= kTicketLevel2 &&
+               partials_fit(c.splits, tokens, M, d_model) &&
+               sizes(c, MODE_FUSED, TT, d_ff).lds <= (size_t)kLdsLimit;
     if (c.k2_splits < 1 || c.k2_splits > ng) return false;
     const int nblk = d_model / 128;
     if (c.k2_col_blocks < 1 || nblk % c.k2_col_blocks) return false;
-    if ((long long)c.k2_splits * c.k2_col_blocks > 65535) return false;
+    if ((long long)c.k2_splits * c.k2_col_blocks > 65535 || c.k2_col_blocks > kTicketLevel2) return false;
+    if (!partials_fit(c.k2_splits * c.k2_col_blocks, tokens, M, d_model)) return false;
     if (c.a2_dtype != DFK_BF16 && c.a2_dtype != DFK_FP32) return false;
     return sizes(c, MODE_GATEUP, TT, d_ff).lds <= (size_t)kLdsLimit &&
            sizes(c, MODE_DOWN, TT, d_ff).lds <= (size_t)kLdsLimit;

@@ -8,8 +8,8 @@
 // G[m,j], U[m,j]; lane 0 applies SiLU(G)*U and leaves A_2[m,j] in LDS.
 // Stage two (Method, second stage): each thread owns 16-byte column chunks of
 // W_down and accumulates A_2[m,j] * W_down[j, chunk] over the slice's rows.
-// The slice's partial Y is added into the fp32 accumulator with device-scope
-// float atomics; the last workgroup to arrive drains it into Y.
+// The slice's fp32 partial Y is published to the workspace and is
+// combined by the two-level arrival-counter reduction (reduce_store).
 #include "dfk_device.h"
 #include "dfk_internal.h"
 
@@ -34,8 +34,8 @@ __device__ __forceinline__ void stage1_valu(const MlpArgs& a, int j0, int rows, 
 #pragma unroll 4
         for (int c = lane; c < nchunk; c += 64) {
             float wg[VEC], wu[VEC];
-            E::widen(ld16(a.Wg, rowv + c), wg);
-            E::widen(ld16(a.Wu, rowv + c), wu);
+            E::widen(ld16_stream(a.Wg, rowv + c), wg);
+            E::widen(ld16_stream(a.Wu, rowv + c), wu);
 #pragma unroll
             for (int m = 0; m < MT; ++m) {
                 if (m < mt) {
@@ -61,10 +61,10 @@ __device__ __forceinline__ void stage1_valu(const MlpArgs& a, int j0, int rows, 
     }
 }
 
-// Accumulates columns [c_lo, c_hi) (in 16-byte chunks) of the partial Y of rows
-// [j0, j0+rows) into yacc.
+// Columns [c_lo, c_hi) (in 16-byte chunks) of the partial Y of rows [j0, j0+rows)
+// -> partial block p of the workspace.
 template <typename E, int MT>
-__device__ __forceinline__ void stage2_valu(const MlpArgs& a, int j0, int rows, int m0, int mt,
+__device__ __forceinline__ void stage2_valu(const MlpArgs& a, int j0, int rows, int mt, int p,
                                             const float* a2s, int a2_stride, int c_lo, int c_hi) {
     constexpr int VEC = E::VEC;
     const int nchunk = a.d_model / VEC;
@@ -77,7 +77,7 @@ __device__ __forceinline__ void stage2_valu(const MlpArgs& a, int j0, int rows, 
 #pragma unroll 8
         for (int j = 0; j < rows; ++j) {
             float w[VEC];
-            E::widen(ld16(a.Wd, (size_t)(j0 + j) * nchunk + c), w);
+            E::widen(ld16_stream(a.Wd, (size_t)(j0 + j) * nchunk + c), w);
 #pragma unroll
             for (int m = 0; m < MT; ++m) {
                 const float s = a2s[m * a2_stride + j];
@@ -88,47 +88,27 @@ __device__ __forceinline__ void stage2_valu(const MlpArgs& a, int j0, int rows, 
 #pragma unroll
         for (int m = 0; m < MT; ++m) {
             if (m < mt) {
-                float* dst = a.yacc + (size_t)(m0 + m) * a.d_model + (size_t)c * VEC;
+                float* dst = a.P + ((size_t)p * a.m_count + m) * a.d_model + (size_t)c * VEC;
 #pragma unroll
-                for (int v = 0; v < VEC; ++v) acc_add(dst + v, acc[m][v]);
+                for (int v = 0; v < VEC; v += 4)
+                    store4_device(dst + v, acc[m][v], acc[m][v + 1], acc[m][v + 2], acc[m][v + 3]);
             }
         }
     }
 }
 
-// Last workgroup of `expected` drains the accumulator of tokens
-// [m_base, m_base+m_count) into Y and leaves accumulator and counter zero.
-template <typename E>
-__device__ __forceinline__ void finalize_valu(const MlpArgs& a, unsigned expected) {
-    __shared__ int is_last;
-    // Every wavefront waits for its own accumulates to be performed device-wide
-    // before the workgroup's single arrival is counted.
-    release_device();
-    __syncthreads();
-    if (threadIdx.x == 0) is_last = arrive_last(a.tickets, expected) ? 1 : 0;
-    __syncthreads();
-    if (!is_last) return;
-    acquire_device();
-    const size_t lo = (size_t)a.m_base * a.d_model;
-    const size_t n = (size_t)a.m_count * a.d_model;
-    for (size_t i = threadIdx.x; i < n; i += blockDim.x) E::store(a.Y, lo + i, acc_take(a.yacc + lo + i));
-}
-
 template <typename E, int MT>
 __global__ __launch_bounds__(512) void k_fused_valu(MlpArgs a, int a2_stride) {
     extern __shared__ float a2s[];
+    __shared__ int flag;
     int j0, j1;
     slice_rows(a.d_ff, a.splits, blockIdx.x, j0, j1);
     const int rows = j1 - j0;
     const int nchunk = a.d_model / E::VEC;
-    for (int m0 = a.m_base; m0 < a.m_base + a.m_count; m0 += MT) {
-        const int mt = min(MT, a.m_base + a.m_count - m0);
-        stage1_valu<E, MT>(a, j0, rows, m0, mt, a2s, a2_stride);
-        __syncthreads();
-        stage2_valu<E, MT>(a, j0, rows, m0, mt, a2s, a2_stride, 0, nchunk);
-        __syncthreads();
-    }
-    finalize_valu<E>(a, (unsigned)a.splits);
+    stage1_valu<E, MT>(a, j0, rows, a.m_base, a.m_count, a2s, a2_stride);
+    __syncthreads();
+    stage2_valu<E, MT>(a, j0, rows, a.m_count, blockIdx.x, a2s, a2_stride, 0, nchunk);
+    reduce_store<E>(plan_full_width(a, blockIdx.x, a.splits), a.Y, a.m_base, &flag);
 }
 
 // First kernel of the two-kernel variant: A_2 slice -> workspace.
@@ -138,18 +118,14 @@ __global__ __launch_bounds__(512) void k_gateup_valu(MlpArgs a, int a2_stride) {
     int j0, j1;
     slice_rows(a.d_ff, a.splits, blockIdx.x, j0, j1);
     const int rows = j1 - j0;
-    for (int m0 = a.m_base; m0 < a.m_base + a.m_count; m0 += MT) {
-        const int mt = min(MT, a.m_base + a.m_count - m0);
-        stage1_valu<E, MT>(a, j0, rows, m0, mt, a2s, a2_stride);
-        __syncthreads();
-        for (int i = threadIdx.x; i < mt * rows; i += blockDim.x) {
-            const int m = i / rows, r = i - m * rows;
-            const size_t o = (size_t)(m0 + m) * a.d_ff + j0 + r;
-            const float v = a2s[m * a2_stride + r];
-            if (a.a2_is_fp32) ((float*)a.a2)[o] = v;
-            else ((uint16_t*)a.a2)[o] = (uint16_t)f32_to_bf16_bits(v);
-        }
-        __syncthreads();
+    stage1_valu<E, MT>(a, j0, rows, a.m_base, a.m_count, a2s, a2_stride);
+    __syncthreads();
+    for (int i = threadIdx.x; i < a.m_count * rows; i += blockDim.x) {
+        const int m = i / rows, r = i - m * rows;
+        const size_t o = (size_t)(a.m_base + m) * a.d_ff + j0 + r;
+        const float v = a2s[m * a2_stride + r];
+        if (a.a2_is_fp32) ((float*)a.a2)[o] = v;
+        else ((uint16_t*)a.a2)[o] = (uint16_t)f32_to_bf16_bits(v);
     }
 }
 
@@ -157,6 +133,7 @@ __global__ __launch_bounds__(512) void k_gateup_valu(MlpArgs a, int a2_stride) {
 template <typename E, int MT>
 __global__ __launch_bounds__(512) void k_down_valu(MlpArgs a, int a2_stride) {
     extern __shared__ float a2s[];
+    __shared__ int flag;
     const int js = blockIdx.x / a.k2_col_blocks;
     const int cb = blockIdx.x - js * a.k2_col_blocks;
     int j0, j1;
@@ -165,26 +142,23 @@ __global__ __launch_bounds__(512) void k_down_valu(MlpArgs a, int a2_stride) {
     const int nchunk = a.d_model / E::VEC;
     const int c_lo = (int)((long long)nchunk * cb / a.k2_col_blocks);
     const int c_hi = (int)((long long)nchunk * (cb + 1) / a.k2_col_blocks);
-    for (int m0 = a.m_base; m0 < a.m_base + a.m_count; m0 += MT) {
-        const int mt = min(MT, a.m_base + a.m_count - m0);
-        for (int i = threadIdx.x; i < MT * rows; i += blockDim.x) {
-            const int m = i / rows, r = i - m * rows;
-            float v = 0.f;
-            if (m < mt) {
-                const size_t o = (size_t)(m0 + m) * a.d_ff + j0 + r;
-                v = a.a2_is_fp32 ? ((const float*)a.a2)[o]
-                                 : __uint_as_float((uint32_t)((const uint16_t*)a.a2)[o] << 16);
-            }
-            a2s[m * a2_stride + r] = v;
+    for (int i = threadIdx.x; i < MT * rows; i += blockDim.x) {
+        const int m = i / rows, r = i - m * rows;
+        float v = 0.f;
+        if (m < a.m_count) {
+            const size_t o = (size_t)(a.m_base + m) * a.d_ff + j0 + r;
+            v = a.a2_is_fp32 ? ((const float*)a.a2)[o]
+                             : __uint_as_float((uint32_t)((const uint16_t*)a.a2)[o] << 16);
         }
-        __syncthreads();
-        stage2_valu<E, MT>(a, j0, rows, m0, mt, a2s, a2_stride, c_lo, c_hi);
-        __syncthreads();
+        a2s[m * a2_stride + r] = v;
     }
-    finalize_valu<E>(a, (unsigned)(a.k2_splits * a.k2_col_blocks));
+    __syncthreads();
+    stage2_valu<E, MT>(a, j0, rows, a.m_count, blockIdx.x, a2s, a2_stride, c_lo, c_hi);
+    reduce_store<E>(plan_column_block(a, cb, c_lo * E::VEC, c_hi * E::VEC), a.Y, a.m_base, &flag);
 }
 
-int pick_mt(int m_count) { return m_count >= 8 ? 8 : m_count >= 4 ? 4 : m_count >= 2 ? 2 : 1; }
+// smallest token-tile width that holds the launch's tokens (a launch has at most 8)
+int pick_mt(int m_count) { return m_count > 4 ? 8 : m_count > 2 ? 4 : m_count > 1 ? 2 : 1; }
 
 template <typename E, int MT>
 hipError_t launch_t(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
@@ -222,23 +196,31 @@ bool valu_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_
     (void)dtype;
     if (c.path != DFK_PATH_VALU) return false;
     if (c.variant != DFK_VARIANT_FUSED && c.variant != DFK_VARIANT_TWO_KERNEL) return false;
-    if (c.reduce != DFK_REDUCE_ATOMIC) return false;
+    if (c.reduce != DFK_REDUCE_TICKET) return false;
     if (c.waves < 1 || c.waves > 8) return false;  // kernels are built for <= 512 threads
     if (M < 1 || d_model < 8 || d_ff < 8 || d_model % 8 || d_ff % 8) return false;
     const int ng = d_ff / 8;
     if (c.splits < 1 || c.splits > ng) return false;
     const int mt = pick_mt(M);
+    const int tokens = M < 8 ? M : 8;
     if ((long long)mt * max_slice_rows(d_ff, c.splits) > kMaxRowsLds * 8) return false;
+    if (c.variant == DFK_VARIANT_FUSED) {
+        if ((c.splits + kGroupSize - 1) / kGroupSize > kTicketLevel2) return false;
+        if (!partials_fit(c.splits, tokens, M, d_model)) return false;
+    }
     if (c.variant == DFK_VARIANT_TWO_KERNEL) {
         if (c.k2_splits < 1 || c.k2_splits > ng) return false;
         const int nchunk = d_model / (dtype == DFK_BF16 ? 8 : 4);
-        if (c.k2_col_blocks < 1 || c.k2_col_blocks > nchunk) return false;
+        if (c.k2_col_blocks < 1 || c.k2_col_blocks > nchunk || c.k2_col_blocks > kTicketLevel2) return false;
+        if (!partials_fit(c.k2_splits * c.k2_col_blocks, tokens, M, d_model)) return false;
         if ((long long)c.k2_splits * c.k2_col_blocks > 65535) return false;
         if ((long long)mt * max_slice_rows(d_ff, c.k2_splits) > kMaxRowsLds * 8) return false;
         if (c.a2_dtype != DFK_BF16 && c.a2_dtype != DFK_FP32) return false;
     }
     return true;
 }
+
+int valu_max_tokens_per_launch() { return 8; }
 
 hipError_t launch_valu(const MlpArgs& a, const dfk_config_t& c, dfk_dtype_t dtype, hipStream_t st) {
     return dtype == DFK_BF16 ? launch_e<BF16>(a, c, st) : launch_e<FP32>(a, c, st);
