@@ -205,7 +205,7 @@ dfk_status_t run(const void* X, const void* Wg, const void* Wu, const void* Wd, 
     a.a2 = (char*)ws + l.a2_off;
     // Token chunking on the host: a launch handles at most `per` tokens; further
     // chunks are further launches on the same stream (they re-stream the weights).
-    const int per = c.path == DFK_PATH_MFMA ? mfma_max_tokens_per_launch(c) : valu_max_tokens_per_launch();
+    const int per = c.path == DFK_PATH_MFMA ? mfma_max_tokens_per_launch(c, d_model) : valu_max_tokens_per_launch();
     for (int m0 = 0; m0 < M; m0 += per) {
         a.m_base = m0;
         a.m_count = std::min(per, M - m0);

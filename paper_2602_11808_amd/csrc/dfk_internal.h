@@ -91,7 +91,7 @@ hipError_t launch_mfma(const MlpArgs& a, const dfk_config_t& c, hipStream_t st);
 // Host-only validity of a configuration for a problem.
 bool valu_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype);
 bool mfma_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype);
-int mfma_max_tokens_per_launch(const dfk_config_t& c);
+int mfma_max_tokens_per_launch(const dfk_config_t& c, int d_model);
 int valu_max_tokens_per_launch();
 
 // utility kernels

@@ -16,8 +16,9 @@
 // Stage one (A_2 = (X W_up) (x) SiLU(X W_gate)): wavefront w owns the k-range
 // [w*KW, (w+1)*KW) of d_model.  A tile is 16 weight rows (8 of W_gate, the same
 // 8 of W_up) x 128 k; it is the A operand of v_mfma_f32_16x16x32_bf16 (4 k-steps
-// per tile), X^T (tokens padded to 16 per token tile) is the B operand, kept
-// in registers per 128-k chunk.  16-byte chunks are XOR-swizzled by row on the
+// per tile), X^T (tokens padded to 16 per token tile) is the B operand; the
+// wavefront's whole k-range of X is loaded into registers once, before the
+// stream starts, so that nothing but tile loads sits in the memory queue.  16-byte chunks are XOR-swizzled by row on the
 // way into LDS (by permuting which global chunk each lane fetches), so the
 // operand reads are bank-conflict free.  The wavefronts' k-partial sums meet
 // in an LDS array through ds_add_f32; then SiLU(G)*U is applied and A_2 is left
@@ -44,7 +45,6 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 constexpr int MODE_FUSED = 0, MODE_GATEUP = 1, MODE_DOWN = 2;
 constexpr int kTileBytes = 4096;   // one ring slot = 4 global->LDS instructions of 1 KB
 constexpr int kKC = 128;           // k extent of a stage-one tile
-constexpr int kGT = 8;             // stage-one row tiles accumulated together
 constexpr int kLdsLimit = 160 * 1024;
 constexpr int kAuxNonTemporal = 2;  // cache-policy bit "nt": the weight stream is read once
 
@@ -60,9 +60,10 @@ struct Geom {
 #define DFK_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | ((((n) >> 4) & 3) << 14))
 #define DFK_WAIT_LGKM0() __builtin_amdgcn_s_waitcnt(0xC07F)
 
-__device__ __forceinline__ void wait_tiles_in_flight(int newer_tiles) {
-    // 4 load instructions per tile; loads complete in issue order.
-    switch (newer_tiles) {
+// Wait until at most `newer_ops` of this wavefront's vector-memory operations
+// are outstanding (loads complete in issue order); newer_ops is a multiple of 4.
+__device__ __forceinline__ void wait_vm_ops(int newer_ops) {
+    switch (newer_ops >> 2) {
         case 0: DFK_WAIT_VM(0); break;
         case 1: DFK_WAIT_VM(4); break;
         case 2: DFK_WAIT_VM(8); break;
@@ -83,57 +84,104 @@ __device__ __forceinline__ void wait_tiles_in_flight(int newer_tiles) {
     asm volatile("" ::: "memory");
 }
 
+// LDS stores and LDS atomics issued while tile loads are in flight go through
+// these raw forms: for an LDS write the compiler sees, it first waits for every
+// outstanding global->LDS load (it cannot tell the ring from the other arrays),
+// which would drain the stream each time.  The arrays written here are never a
+// target of tile loads.  Completion is awaited in lds_barrier.
+__device__ __forceinline__ unsigned lds_addr(const void* p) {
+    return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
+__device__ __forceinline__ void lds_add_f32_raw(unsigned addr, float v) {
+    asm volatile("ds_add_f32 %0, %1" : : "v"(addr), "v"(v) : "memory");
+}
+__device__ __forceinline__ void lds_write_b16_raw(unsigned addr, unsigned v) {
+    asm volatile("ds_write_b16 %0, %1" : : "v"(addr), "v"(v) : "memory");
+}
+
+// Workgroup barrier that orders LDS traffic only: it does not wait for the
+// global->LDS tile loads in flight (a full __syncthreads would drain them).
+// Written raw for the same reason: a fence the compiler sees waits for the tile
+// loads, which also write LDS.
+__device__ __forceinline__ void lds_barrier() {
+    DFK_WAIT_LGKM0();
+    asm volatile("s_barrier" ::: "memory");
+}
+
 __device__ __forceinline__ bf16x8 as_bf16x8(const u32x4& v) {
     union { u32x4 u; bf16x8 b; } c;
     c.u = v;
     return c.b;
 }
 
+// 16-byte B-operand registers a wavefront may spend on X: cap * 4 per lane.
+__host__ __device__ constexpr int x_chunk_cap(int nw) { return nw == 16 ? 4 : 8; }
+
 // Per-wavefront producer/consumer of the weight-tile stream.
+// Stage-one tiles come row-tile-major (tile (rt, kc): 16 rows x 128 k), then the
+// stage-two tiles (block bi, 32-row block jb, half h: 16 rows x 128 columns).
 template <int NW, int MODE>
 struct TileStream {
-    // problem
-    const uint16_t *Wg, *Wu, *Wd;
+    const char *Wg, *Wu, *Wd;
     int d_model, d_ff;
     int j0, nt, njb;          // slice start row, stage-one row tiles, stage-two 32-row blocks
-    int kbase, nkc;           // this wavefront's k range start, number of 128-k chunks
-    int blk_lo, blk_cnt;      // stage two: first 128-column block and block count of the workgroup
+    int nkc;                  // 128-k chunks of this wavefront's k range
+    int blk_lo;               // stage two: first 128-column block of the workgroup
     int wave, q, g;
+    // per-lane byte offsets inside a tile, fixed for the whole kernel
+    unsigned off1[4];         // stage one, instruction u
+    unsigned off2;            // stage two: (8g)*row_bytes + 16q
+    size_t base1;             // stage one: byte offset of tile (0, 0) of this wavefront
+    size_t row_bytes;
     // ring
     unsigned char* ring;
     int depth;
     int T1, T;                // stage-one tiles, all tiles
     int issued, issue_slot;   // producer position
-    int taken, take_slot;     // consumer position
-    // producer coordinates
-    int p_g0, p_kc, p_r;      // stage one: group start tile, k chunk, tile in group
-    int p_bi, p_jb, p_h;      // stage two: block index (wave, wave+NW, ...), 32-row block, half
+    int take_slot;            // consumer position
+    int p_rt, p_kc;           // producer coordinates, stage one
+    int p_bi, p_jb, p_h;      // producer coordinates, stage two
+
+    __device__ __forceinline__ void init(const MlpArgs& a, int kbase) {
+        row_bytes = (size_t)d_model * 2;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = 4 * u + g;   // row of the 16-row tile this lane fetches
+            const int c = q ^ i;       // logical 16-byte chunk stored at position q of row i
+            off1[u] = (unsigned)((i & 7) * row_bytes + c * 16);
+        }
+        off2 = (unsigned)(8 * g * row_bytes + 16 * q);
+        base1 = (size_t)j0 * row_bytes + (size_t)kbase * 2;
+        (void)a;
+    }
 
     __device__ __forceinline__ void issue() {
         unsigned char* slot = ring + issue_slot * kTileBytes;
         if (MODE != MODE_DOWN && issued < T1) {
-            const size_t rowbase = (size_t)(j0 + 8 * (p_g0 + p_r)) * d_model + kbase + p_kc * kKC;
+            const size_t tb = base1 + (size_t)p_rt * 8 * row_bytes + (size_t)p_kc * (kKC * 2);
+            const char* gb = Wg + tb;   // uniform
+            const char* ub = Wu + tb;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int i = 4 * u + g;   // row of the 16-row tile this lane fetches
-                const int c = q ^ i;       // logical 16-byte chunk stored at position q of row i
-                const uint16_t* base = (u < 2) ? Wg : Wu;
-                const uint16_t* src = base + rowbase + (size_t)(i & 7) * d_model + c * 8;
-                __builtin_amdgcn_global_load_lds(src, DFK_LDS_PTR(slot + u * 1024), 16, 0, kAuxNonTemporal);
-            }
-            const int gsz = min(kGT, nt - p_g0);
-            if (++p_r == gsz) {
-                p_r = 0;
-                if (++p_kc == nkc) { p_kc = 0; p_g0 += kGT; }
-            }
+            for (int u = 0; u < 4; ++u)
+                __builtin_amdgcn_global_load_lds((u < 2 ? gb : ub) + off1[u], DFK_LDS_PTR(slot + u * 1024), 16, 0,
+                                                 kAuxNonTemporal);
+            if (++p_kc == nkc) { p_kc = 0; ++p_rt; }
         } else if (MODE != MODE_GATEUP) {
-            const int nb = (blk_lo + p_bi) * 128;
+            const int row0 = j0 + p_jb * 32 + 4 * p_h;   // first row of this half (lane adds 8g + u)
+            const size_t colb = (size_t)(blk_lo + p_bi) * 256;
+            if (row0 + 28 < d_ff) {      // every row of the tile exists: uniform base + lane offset
+                const char* b = Wd + (size_t)row0 * row_bytes + colb;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int r = 4 * p_h + u;
-                const int row = min(j0 + p_jb * 32 + 8 * g + r, d_ff - 1);   // stay inside W_down
-                const uint16_t* src = Wd + (size_t)row * d_model + nb + 8 * q;
-                __builtin_amdgcn_global_load_lds(src, DFK_LDS_PTR(slot + u * 1024), 16, 0, kAuxNonTemporal);
+                for (int u = 0; u < 4; ++u)
+                    __builtin_amdgcn_global_load_lds(b + (size_t)u * row_bytes + off2, DFK_LDS_PTR(slot + u * 1024), 16,
+                                                     0, kAuxNonTemporal);
+            } else {                     // last rows of W_down: clamp per lane (values are masked later)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int row = min(row0 + 8 * g + u, d_ff - 1);
+                    __builtin_amdgcn_global_load_lds(Wd + (size_t)row * row_bytes + colb + 16 * q,
+                                                     DFK_LDS_PTR(slot + u * 1024), 16, 0, kAuxNonTemporal);
+                }
             }
             p_h ^= 1;
             if (p_h == 0 && ++p_jb == njb) { p_jb = 0; p_bi += NW; }
@@ -143,8 +191,8 @@ struct TileStream {
     }
 
     __device__ __forceinline__ void start() {
-        issued = 0; issue_slot = 0; taken = 0; take_slot = 0;
-        p_g0 = 0; p_kc = 0; p_r = 0; p_bi = wave; p_jb = 0; p_h = 0;
+        issued = 0; issue_slot = 0; take_slot = 0;
+        p_rt = 0; p_kc = 0; p_bi = wave; p_jb = 0; p_h = 0;
         const int ahead = min(depth - 1, T);
         for (int i = 0; i < ahead; ++i) issue();
     }
@@ -156,12 +204,11 @@ struct TileStream {
         asm volatile("" ::: "memory");
         if (issued < T) {
             issue();
-            wait_tiles_in_flight(depth - 1);
+            wait_vm_ops(4 * (depth - 1));   // only tile loads are in the queue: depth-1 newer tiles
         } else {
-            wait_tiles_in_flight(0);
+            wait_vm_ops(0);
         }
         const unsigned char* slot = ring + take_slot * kTileBytes;
-        ++taken;
         if (++take_slot == depth) take_slot = 0;
         return slot;
     }
@@ -172,12 +219,14 @@ __global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     constexpr int TOK = 16 * TT;
     constexpr int NTHREADS = NW * 64;
+    constexpr int NKC = x_chunk_cap(NW) / TT;   // 128-k chunks of X a wavefront can hold
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int q = lane & 15, g = lane >> 4;
     float* gu = (float*)(lds + geo.gu_off);
     uint16_t* a2s = (uint16_t*)(lds + geo.a2s_off);
+    const unsigned gu_addr = lds_addr(gu), a2s_addr = lds_addr(a2s);
     const uint16_t* X = (const uint16_t*)a.X;
 
     // ---- geometry
@@ -200,77 +249,73 @@ __global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
     const int my_blocks = wave < blk_cnt ? (blk_cnt - wave + NW - 1) / NW : 0;
 
     TileStream<NW, MODE> ts;
-    ts.Wg = (const uint16_t*)a.Wg; ts.Wu = (const uint16_t*)a.Wu; ts.Wd = (const uint16_t*)a.Wd;
+    ts.Wg = (const char*)a.Wg; ts.Wu = (const char*)a.Wu; ts.Wd = (const char*)a.Wd;
     ts.d_model = a.d_model; ts.d_ff = a.d_ff;
     ts.j0 = j0; ts.nt = nt; ts.njb = njb;
-    ts.kbase = wave * KW; ts.nkc = nkc;
-    ts.blk_lo = blk_lo; ts.blk_cnt = blk_cnt;
+    ts.nkc = nkc;
+    ts.blk_lo = blk_lo;
     ts.wave = wave; ts.q = q; ts.g = g;
     ts.ring = lds + wave * geo.depth * kTileBytes;
     ts.depth = geo.depth;
     ts.T1 = (MODE != MODE_DOWN) ? nt * nkc : 0;
     ts.T = ts.T1 + ((MODE != MODE_GATEUP) ? my_blocks * njb * 2 : 0);
+    ts.init(a, wave * KW);
+
+    // The LDS sums are cleared before the first tile load is issued, so this
+    // barrier has nothing in flight to wait for.
+    if (MODE != MODE_DOWN) {
+        for (int i = tid; i < nt * 16 * TOK; i += NTHREADS) gu[i] = 0.f;
+        lds_barrier();
+    }
     ts.start();
 
     // ---- stage one
     if (MODE != MODE_DOWN) {
-        for (int i = tid; i < nt * 16 * TOK; i += NTHREADS) gu[i] = 0.f;
-        __syncthreads();
-        for (int g0 = 0; g0 < nt; g0 += kGT) {
-            const int gsz = min(kGT, nt - g0);
-            f32x4 acc[kGT][TT];
+        // B operand: this wavefront's k range of X^T for every token tile, loaded once.
+        // (The first use waits for everything issued so far, i.e. for the first
+        // tiles of the stream too, which are needed at that point anyway.)
+        u32x4 x[TT][NKC][4];
 #pragma unroll
-            for (int r = 0; r < kGT; ++r)
+        for (int tt = 0; tt < TT; ++tt) {
+            const int token = tt * 16 + q;
 #pragma unroll
-                for (int tt = 0; tt < TT; ++tt) acc[r][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
-            u32x4 xcur[TT][4], xnext[TT][4];
-            auto load_x = [&](u32x4 (&x)[TT][4], int kc) {
+            for (int kc = 0; kc < NKC; ++kc)
 #pragma unroll
-                for (int tt = 0; tt < TT; ++tt) {
-                    const int token = tt * 16 + q;
+                for (int s = 0; s < 4; ++s) {
+                    x[tt][kc][s] = u32x4{0, 0, 0, 0};
+                    if (token < a.m_count && kc < nkc)
+                        x[tt][kc][s] = ld16(X, ((size_t)(a.m_base + token) * a.d_model + wave * KW + kc * kKC) / 8 + 4 * s + g);
+                }
+        }
+        for (int rt = 0; rt < nt; ++rt) {
+            f32x4 acc[TT];
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) acc[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kc = 0; kc < NKC; ++kc) {
+                if (kc < nkc) {
+                    const unsigned char* slot = ts.acquire();
 #pragma unroll
                     for (int s = 0; s < 4; ++s) {
-                        x[tt][s] = u32x4{0, 0, 0, 0};
-                        if (token < a.m_count)
-                            x[tt][s] = ld16(X, ((size_t)(a.m_base + token) * a.d_model + ts.kbase + kc * kKC) / 8 + 4 * s + g);
+                        const bf16x8 av = *(const bf16x8*)(slot + (q * 16 + ((4 * s + g) ^ q)) * 16);
+#pragma unroll
+                        for (int tt = 0; tt < TT; ++tt)
+                            acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, as_bf16x8(x[tt][kc][s]), acc[tt], 0, 0, 0);
                     }
                 }
-            };
-            load_x(xcur, 0);
-            for (int kc = 0; kc < nkc; ++kc) {
-                if (kc + 1 < nkc) load_x(xnext, kc + 1);
-#pragma unroll
-                for (int r = 0; r < kGT; ++r) {
-                    if (r < gsz) {
-                        const unsigned char* slot = ts.acquire();
-#pragma unroll
-                        for (int s = 0; s < 4; ++s) {
-                            const bf16x8 av = *(const bf16x8*)(slot + (q * 16 + ((4 * s + g) ^ q)) * 16);
-#pragma unroll
-                            for (int tt = 0; tt < TT; ++tt)
-                                acc[r][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, as_bf16x8(xcur[tt][s]),
-                                                                                    acc[r][tt], 0, 0, 0);
-                        }
-                    }
-                }
-#pragma unroll
-                for (int tt = 0; tt < TT; ++tt)
-#pragma unroll
-                    for (int s = 0; s < 4; ++s) xcur[tt][s] = xnext[tt][s];
             }
-            // k-partial sums of all wavefronts meet in LDS
+            // k-partial sums of all wavefronts meet in LDS.  The raw LDS atomics are
+            // invisible to the compiler's hazard handling, so the wait states an MFMA
+            // result needs before an LDS instruction may read it are inserted by hand.
 #pragma unroll
-            for (int r = 0; r < kGT; ++r) {
-                if (r < gsz) {
+            for (int tt = 0; tt < TT; ++tt) asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" : "+v"(acc[tt]));
 #pragma unroll
-                    for (int tt = 0; tt < TT; ++tt)
+            for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
-                        for (int i = 0; i < 4; ++i)
-                            atomicAdd(&gu[((g0 + r) * 16 + 4 * g + i) * TOK + tt * 16 + q], acc[r][tt][i]);
-                }
-            }
+                for (int i = 0; i < 4; ++i)
+                    lds_add_f32_raw(gu_addr + 4u * (unsigned)((rt * 16 + 4 * g + i) * TOK + tt * 16 + q), acc[tt][i]);
         }
-        __syncthreads();
+        lds_barrier();
         // SiLU(G) * U  ->  A_2
         for (int idx = tid; idx < rows_pad * TOK; idx += NTHREADS) {
             const int j = idx / TOK, m = idx - j * TOK;
@@ -280,14 +325,14 @@ __global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
                 v = silu_mul(gu[(tile * 16 + jr) * TOK + m], gu[(tile * 16 + 8 + jr) * TOK + m]);
             }
             if (MODE == MODE_FUSED) {
-                a2s[m * geo.a2_stride + j] = (uint16_t)f32_to_bf16_bits(v);
+                lds_write_b16_raw(a2s_addr + 2u * (unsigned)(m * geo.a2_stride + j), f32_to_bf16_bits(v));
             } else if (j < rows && m < a.m_count) {
                 const size_t o = (size_t)(a.m_base + m) * a.d_ff + j0 + j;
                 if (a.a2_is_fp32) ((float*)a.a2)[o] = v;
                 else ((uint16_t*)a.a2)[o] = (uint16_t)f32_to_bf16_bits(v);
             }
         }
-        if (MODE == MODE_FUSED) __syncthreads();
+        if (MODE == MODE_FUSED) lds_barrier();
     }
     if (MODE == MODE_GATEUP) return;
 
@@ -300,9 +345,9 @@ __global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
                 const size_t o = (size_t)(a.m_base + m) * a.d_ff + j0 + j;
                 v = a.a2_is_fp32 ? (uint16_t)f32_to_bf16_bits(((const float*)a.a2)[o]) : ((const uint16_t*)a.a2)[o];
             }
-            a2s[m * geo.a2_stride + j] = v;
+            lds_write_b16_raw(a2s_addr + 2u * (unsigned)(m * geo.a2_stride + j), v);
         }
-        __syncthreads();
+        lds_barrier();
     }
     for (int bi = wave; bi < blk_cnt; bi += NW) {
         const int nb = (blk_lo + bi) * 128;
@@ -368,8 +413,13 @@ struct Sizes {
     size_t lds;
 };
 
-// tokens per launch: one or two token tiles of 16
-int token_tiles(const dfk_config_t& c, int m_count) { return (c.waves == 16 || m_count <= 16) ? 1 : 2; }
+// token tiles (of 16) per launch: two if the wavefront can hold X for both, else one
+int max_token_tiles(const dfk_config_t& c, int d_model) {
+    const int nkc = d_model / c.waves / kKC;
+    if (c.waves == 16) return 1;   // 128 registers per lane: no room for a second token tile
+    return 2 * nkc <= x_chunk_cap(c.waves) ? 2 : 1;
+}
+int token_tiles(const dfk_config_t& c, int m_count) { return m_count <= 16 ? 1 : 2; }
 
 Sizes sizes(const dfk_config_t& c, int mode, int TT, int d_ff) {
     Sizes s;
@@ -412,7 +462,7 @@ hipError_t launch_nt(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
 
 }  // namespace
 
-int mfma_max_tokens_per_launch(const dfk_config_t& c) { return c.waves == 16 ? 16 : 32; }
+int mfma_max_tokens_per_launch(const dfk_config_t& c, int d_model) { return 16 * max_token_tiles(c, d_model); }
 
 bool mfma_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype) {
     if (c.path != DFK_PATH_MFMA || dtype != DFK_BF16) return false;
@@ -424,8 +474,9 @@ bool mfma_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_
     if (d_model % (kKC * c.waves)) return false;   // each wavefront owns whole 128-k chunks
     const int ng = d_ff / 8;
     if (c.splits < 1 || c.splits > ng) return false;
-    const int TT = token_tiles(c, M);
-    const int per = mfma_max_tokens_per_launch(c);
+    if (d_model / c.waves / kKC > x_chunk_cap(c.waves)) return false;   // X of a wavefront's k range must fit its registers
+    const int per = mfma_max_tokens_per_launch(c, d_model);
+    const int TT = token_tiles(c, M < per ? M : per);
     const int tokens = M < per ? M : per;
     if (c.variant == DFK_VARIANT_FUSED)
         return (c.splits + kGroupSize - 1) / kGroupSize <= kTicketLevel2 &&
