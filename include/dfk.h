@@ -24,8 +24,9 @@
  * workspace.  No entry point on the call path allocates or frees device
  * memory or synchronises the host; work is enqueued on `stream` (a
  * hipStream_t passed as void*, NULL = the default stream) and the call
- * returns at once.  The workspace holds arrival counters (its first 4096
- * bytes), the fp32 partial sums of Y and (two-kernel variant) A_2.  The counters
+ * returns at once.  The workspace holds arrival counters and the fp32
+ * accumulator of the atomic reduction (its first 4 MiB + 4 KiB), the fp32
+ * partial sums of Y and (two-kernel variant) A_2.  Counters and accumulator
  * must be zero before the first call (dfk_workspace_init) and every call leaves
  * them zero again, so a workspace may be reused by successive calls, of any
  * shape that fits, on ONE stream.  Calls that share a workspace and overlap in
@@ -47,7 +48,7 @@ extern "C" {
 typedef enum {
     DFK_OK = 0,
     DFK_ERR_INVALID_ARG = -1,        /* null pointer, M < 1, d_model < 1, d_ff < 1, bad enum */
-    DFK_ERR_UNSUPPORTED_SHAPE = -2,  /* d_model % 8, d_ff % 8, M > DFK_MAX_M, or config not valid for shape */
+    DFK_ERR_UNSUPPORTED_SHAPE = -2,  /* d_model % 8, d_ff % 8, M > DFK_MAX_M, d_model > 32768, or config not valid for shape */
     DFK_ERR_ALIGNMENT = -3,          /* a device pointer is not 16-byte aligned */
     DFK_ERR_ALIAS = -4,              /* Y overlaps X, W_gate, W_up or W_down */
     DFK_ERR_WORKSPACE = -5,          /* workspace missing or smaller than dfk_workspace_bytes() */
@@ -68,8 +69,11 @@ typedef enum { DFK_PATH_VALU = 0, DFK_PATH_MFMA = 1 } dfk_path_t;
 /* How the split-d_ff partial sums of the down projection are combined.
  * DFK_REDUCE_TICKET: partial blocks in the workspace, summed in a fixed order by
  * the last workgroup to arrive at each of two levels of arrival counters;
- * run-to-run bitwise deterministic.  DFK_REDUCE_ATOMIC (device-wide fp32 atomic
- * adds) is reserved: no kernel offers it. */
+ * run-to-run bitwise deterministic.
+ * DFK_REDUCE_ATOMIC: device-wide fp32 atomic adds into an accumulator in the
+ * workspace, drained per 128-column block by the last wavefront to arrive;
+ * shorter tail, summation order (hence the last bits) varies from run to run.
+ * MFMA path only. */
 typedef enum { DFK_REDUCE_TICKET = 0, DFK_REDUCE_ATOMIC = 1 } dfk_reduce_t;
 
 #define DFK_MAX_M 256            /* largest token count one call accepts */
@@ -227,6 +231,13 @@ dfk_status_t dfk_stream_read(const void* src, size_t bytes, void* sink, void* st
  * a cheap hash of the element index and seed.  Used by dfk_tune and by benchmarks. */
 dfk_status_t dfk_fill_synthetic(void* dst, size_t elems, dfk_dtype_t dtype, float scale,
                                 unsigned seed, void* stream);
+
+/* Optional in-kernel timeline for profiling the MFMA kernels: while a device buffer
+ * of at least 64 bytes per workgroup of the launch is registered, each workgroup
+ * writes up to 8 wall-clock stamps (100 MHz counter): [0] start, [1] first tile
+ * landed, [2] stage one streamed, [3] A_2 ready, [4] stage two streamed,
+ * [5] partial published, [6] end of first reduction level (or exit), [7] Y written by the last group.  NULL unregisters.  Off by default. */
+dfk_status_t dfk_set_trace_buffer(void* buffer, size_t bytes);
 
 /* ---------------------------------------------------------------- misc */
 

@@ -78,6 +78,7 @@ SIGNATURES = [
     ("dfk_load_tuning", _ci, [ctypes.c_char_p]),
     ("dfk_stream_read", _ci, [_vp, _sz, _vp, _vp]),
     ("dfk_fill_synthetic", _ci, [_vp, _sz, _ci, ctypes.c_float, ctypes.c_uint, _vp]),
+    ("dfk_set_trace_buffer", _ci, [_vp, _sz]),
     ("dfk_status_string", ctypes.c_char_p, [_ci]),
     ("dfk_last_hip_error", _ci, []),
     ("dfk_version", ctypes.c_char_p, []),
@@ -278,6 +279,13 @@ def dfk_stream_read(src, sink, stream=None):
 def dfk_fill_synthetic(dst, scale: float, seed: int, stream=None):
     _check(lib().dfk_fill_synthetic(_ptr(dst), dst.numel(), _dtype_code(dst), scale, seed,
                                     _stream(stream)), "dfk_fill_synthetic")
+
+
+def dfk_set_trace_buffer(buf):
+    if buf is None:
+        _check(lib().dfk_set_trace_buffer(None, 0), "dfk_set_trace_buffer")
+    else:
+        _check(lib().dfk_set_trace_buffer(_ptr(buf), buf.numel() * buf.element_size()), "dfk_set_trace_buffer")
 
 
 def dfk_status_string(status: int) -> str:

@@ -25,6 +25,7 @@ struct Registered {
     size_t bytes = 0;
 };
 Registered g_ws;
+Registered g_trace;
 std::mutex g_mu;
 
 // ---------------------------------------------------------------- validation
@@ -47,7 +48,7 @@ dfk_status_t check(const void* X, const void* Wg, const void* Wu, const void* Wd
     if (!X || !Wg || !Wu || !Wd || !Y) return DFK_ERR_INVALID_ARG;
     if (M < 1 || d_model < 1 || d_ff < 1) return DFK_ERR_INVALID_ARG;
     if (dtype != DFK_BF16 && dtype != DFK_FP32) return DFK_ERR_INVALID_ARG;
-    if (d_model % 8 || d_ff % 8 || M > DFK_MAX_M) return DFK_ERR_UNSUPPORTED_SHAPE;
+    if (d_model % 8 || d_ff % 8 || M > DFK_MAX_M || d_model > kMaxDModel) return DFK_ERR_UNSUPPORTED_SHAPE;
     const void* ptrs[5] = {X, Wg, Wu, Wd, Y};
     for (const void* p : ptrs)
         if ((uintptr_t)p % 16) return DFK_ERR_ALIGNMENT;
@@ -78,11 +79,11 @@ dfk_status_t check(const void* X, const void* Wg, const void* Wu, const void* Wd
 int clamp_splits(int want, int d_ff) { return std::max(1, std::min(want, d_ff / 8)); }
 
 dfk_config_t make_cfg(int variant, int path, int splits, int waves, int depth, int k2s, int k2c,
-                      int a2dt) {
+                      int a2dt, int reduce = DFK_REDUCE_TICKET) {
     dfk_config_t c;
     std::memset(&c, 0, sizeof c);
     c.variant = variant; c.path = path; c.splits = splits; c.waves = waves; c.depth = depth;
-    c.reduce = DFK_REDUCE_TICKET; c.k2_splits = k2s; c.k2_col_blocks = k2c; c.a2_dtype = a2dt;
+    c.reduce = reduce; c.k2_splits = k2s; c.k2_col_blocks = k2c; c.a2_dtype = a2dt;
     return c;
 }
 
@@ -108,8 +109,9 @@ std::vector<dfk_config_t> candidates(int M, int d_model, int d_ff, dfk_dtype_t d
         for (int splits : {256, 512})
             for (int waves : {4, 8, 16})
                 for (int depth : {2, 3, 4, 6, 8})
-                    push(make_cfg(DFK_VARIANT_FUSED, DFK_PATH_MFMA, clamp_splits(splits, d_ff), waves,
-                                  depth, 0, 0, a2dt));
+                    for (int reduce : {DFK_REDUCE_ATOMIC, DFK_REDUCE_TICKET})
+                        push(make_cfg(DFK_VARIANT_FUSED, DFK_PATH_MFMA, clamp_splits(splits, d_ff), waves,
+                                      depth, 0, 0, a2dt, reduce));
         // two-kernel: the down projection is tiled (d_ff splits) x (column blocks of
         // waves*128 or 2*waves*128 columns), about one or two workgroups per CU
         const int nblk = d_model / 128;
@@ -120,8 +122,10 @@ std::vector<dfk_config_t> candidates(int M, int d_model, int d_ff, dfk_dtype_t d
                     if (wg_blocks > nblk || nblk % wg_blocks) continue;
                     const int k2c = nblk / wg_blocks;
                     for (int grid : {256, 512})
-                        push(make_cfg(DFK_VARIANT_TWO_KERNEL, DFK_PATH_MFMA, clamp_splits(splits, d_ff),
-                                      waves, 4, clamp_splits(std::max(1, grid / k2c), d_ff), k2c, a2dt));
+                        for (int reduce : {DFK_REDUCE_ATOMIC, DFK_REDUCE_TICKET})
+                            push(make_cfg(DFK_VARIANT_TWO_KERNEL, DFK_PATH_MFMA, clamp_splits(splits, d_ff),
+                                          waves, 4, clamp_splits(std::max(1, grid / k2c), d_ff), k2c, a2dt,
+                                          reduce));
                 }
     }
     for (int splits : {256, 512, 1024})
@@ -200,9 +204,17 @@ dfk_status_t run(const void* X, const void* Wg, const void* Wu, const void* Wd, 
     a.splits = c.splits; a.k2_splits = c.k2_splits; a.k2_col_blocks = c.k2_col_blocks;
     a.a2_is_fp32 = c.a2_dtype == DFK_FP32;
     a.tickets = (unsigned*)((char*)ws + l.tickets_off);
+    a.reduce_mode = c.reduce;
+    a.yacc = (float*)((char*)ws + l.yacc_off);
     a.P = (float*)((char*)ws + l.p_off);
     a.Q = (float*)((char*)ws + l.q_off);
     a.a2 = (char*)ws + l.a2_off;
+    a.trace = nullptr;
+    {
+        const size_t grid = (size_t)std::max(c.splits, c.k2_splits * std::max(1, c.k2_col_blocks));
+        if (g_trace.ptr && g_trace.bytes >= grid * 8 * sizeof(unsigned long long))
+            a.trace = (unsigned long long*)g_trace.ptr;
+    }
     // Token chunking on the host: a launch handles at most `per` tokens; further
     // chunks are further launches on the same stream (they re-stream the weights).
     const int per = c.path == DFK_PATH_MFMA ? mfma_max_tokens_per_launch(c, d_model) : valu_max_tokens_per_launch();
@@ -340,6 +352,14 @@ dfk_status_t dfk_set_workspace(void* workspace, size_t workspace_bytes) {
     std::lock_guard<std::mutex> lk(g_mu);
     g_ws.ptr = workspace;
     g_ws.bytes = workspace ? workspace_bytes : 0;
+    return DFK_OK;
+}
+
+dfk_status_t dfk_set_trace_buffer(void* buffer, size_t bytes) {
+    if (buffer && (uintptr_t)buffer % 8) return DFK_ERR_ALIGNMENT;
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_trace.ptr = buffer;
+    g_trace.bytes = buffer ? bytes : 0;
     return DFK_OK;
 }
 

@@ -94,6 +94,15 @@ __device__ __forceinline__ void drain_own_memory_ops() {
 }
 __device__ __forceinline__ void acquire_device() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent"); }
 
+// Device-wide fp32 accumulate (hardware float atomic, no return) and the matching
+// read-and-clear, performed at the same coherence point as the adds.
+__device__ __forceinline__ void acc_add(float* p, float v) {
+    __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float acc_take(float* p) {
+    return __hip_atomic_exchange(p, 0.0f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // Arrival counter: returns true for the last of `expected` arrivals, and resets
 // the counter for the next call.  The caller orders its published stores before
 // it (drain_own_memory_ops in every wavefront, then a workgroup barrier).
@@ -154,7 +163,8 @@ __device__ __forceinline__ ReducePlan plan_column_block(const MlpArgs& a, int cb
 }
 
 template <typename E>
-__device__ __forceinline__ void reduce_store(const ReducePlan& r, void* Y, int m_base, int* flag) {
+__device__ __forceinline__ void reduce_store(const ReducePlan& r, void* Y, int m_base, int* flag,
+                                             unsigned long long* trace = nullptr) {
     const int tid = threadIdx.x, nth = blockDim.x;
     const int w4 = (r.c_hi - r.c_lo) >> 2;
     const size_t blk = (size_t)r.m_count * r.d_model;
@@ -162,9 +172,10 @@ __device__ __forceinline__ void reduce_store(const ReducePlan& r, void* Y, int m
     // single arrival is counted.
     drain_own_memory_ops();
     __syncthreads();
+    if (trace && tid == 0) trace[(size_t)blockIdx.x * 8 + 5] = wall_clock64();
     if (tid == 0) *flag = arrive_last(r.tickets + r.t1, (unsigned)r.n1) ? 1 : 0;
     __syncthreads();
-    if (!*flag) return;
+    if (!*flag) { if (trace && tid == 0) trace[(size_t)blockIdx.x * 8 + 6] = wall_clock64(); return; }
     acquire_device();
     for (int idx = tid; idx < r.m_count * w4; idx += nth) {
         const int m = idx / w4, c4 = idx - m * w4;
@@ -179,11 +190,12 @@ __device__ __forceinline__ void reduce_store(const ReducePlan& r, void* Y, int m
         if (r.n2 == 1) E::store4(Y, (size_t)(m_base + m) * r.d_model + r.c_lo + 4 * c4, s.x, s.y, s.z, s.w);
         else store4_device(r.Q + (size_t)r.q_slot * blk + off, s.x, s.y, s.z, s.w);
     }
-    if (r.n2 == 1) return;
+    if (r.n2 == 1) { if (trace && tid == 0) trace[(size_t)blockIdx.x * 8 + 6] = wall_clock64(); return; }
     drain_own_memory_ops();
     __syncthreads();
     if (tid == 0) *flag = arrive_last(r.tickets + r.t2, (unsigned)r.n2) ? 1 : 0;
     __syncthreads();
+    if (trace && tid == 0) trace[(size_t)blockIdx.x * 8 + 6] = wall_clock64();
     if (!*flag) return;
     acquire_device();
     for (int idx = tid; idx < r.m_count * w4; idx += nth) {
@@ -197,6 +209,7 @@ __device__ __forceinline__ void reduce_store(const ReducePlan& r, void* Y, int m
         }
         E::store4(Y, (size_t)(m_base + m) * r.d_model + r.c_lo + 4 * c4, s.x, s.y, s.z, s.w);
     }
+    if (trace && tid == 0) trace[(size_t)blockIdx.x * 8 + 7] = wall_clock64();
 }
 
 }  // namespace dfk

@@ -10,16 +10,22 @@
 namespace dfk {
 
 // ---------------------------------------------------------------- workspace layout
-// [0, 4096)      arrival counters (unsigned), zero between calls
-// [4096, +P)     fp32 partial sums of Y, one [tokens, d_model] block per workgroup slice
-// [.., +Q)       fp32 group sums (second level of the reduction)
-// [.., +M*d_ff*4) A_2 between the two launches of the two-kernel variant
-// Only the counters have to be zero between calls; nothing else is read before
-// it is written within a call.
+// [0, 4096)        arrival counters (unsigned), zero between calls
+// [4096, +4 MiB)   fp32 accumulator of Y for one launch (kMaxTokensPerLaunch x kMaxDModel),
+//                  zero between calls (atomic reduction)
+// [.., +P)         fp32 partial sums of Y, one [tokens, d_model] block per workgroup slice
+//                  (counter reduction)
+// [.., +Q)         fp32 group sums (second level of the counter reduction)
+// [.., +M*d_ff*4)  A_2 between the two launches of the two-kernel variant
+// The part that has to be zero between calls comes first and has a fixed size, so
+// calls of different shapes on one workspace never put scratch where another call
+// expects zeros.
 constexpr size_t kWsHeaderBytes = 4096;
 constexpr int kMaxTickets = 1024;
-constexpr int kTicketLevel2 = 512;          // counters [0,512): level 1, [512,1024): level 2
+constexpr int kTicketLevel2 = 512;          // counters [0,512): level 1 / column blocks, [512,1024): level 2
 constexpr int kMaxTokensPerLaunch = 32;     // a launch handles at most this many tokens
+constexpr int kMaxDModel = 32768;
+constexpr size_t kYaccBytes = (size_t)kMaxTokensPerLaunch * kMaxDModel * 4;
 constexpr size_t kPartialCapBytes = (size_t)128 << 20;
 constexpr int kGroupSize = 16;              // workgroup partials summed per first-level group
 
@@ -31,13 +37,14 @@ inline size_t partial_bytes(int M, int d_model) {
 }
 
 struct WsLayout {
-    size_t tickets_off, p_off, q_off, a2_off, total;
+    size_t tickets_off, yacc_off, p_off, q_off, a2_off, total;
 };
 
 inline WsLayout ws_layout(int M, int d_model, int d_ff) {
     WsLayout l;
     l.tickets_off = 0;
-    l.p_off = kWsHeaderBytes;
+    l.yacc_off = kWsHeaderBytes;
+    l.p_off = l.yacc_off + kYaccBytes;
     l.q_off = l.p_off + align_up(partial_bytes(M, d_model), 256);
     l.a2_off = l.q_off + align_up(partial_bytes(M, d_model) / 8, 256);
     l.total = l.a2_off + align_up((size_t)M * d_ff * 4, 256);
@@ -64,10 +71,13 @@ struct MlpArgs {
     int splits;        // d_ff slices (grid of the fused kernel / first kernel)
     int k2_splits, k2_col_blocks;
     int a2_is_fp32;    // storage type of A_2 in the workspace (two-kernel variant)
+    int reduce_mode;   // dfk_reduce_t
+    float* yacc;       // [m_count, d_model] fp32 accumulator, zero on entry and on exit (atomic reduction)
     float* P;          // partial sums [slice][m_count][d_model]
     float* Q;          // group sums   [group][m_count][d_model]
     unsigned* tickets; // zero on entry and on exit
     void* a2;          // [M, d_ff] in the workspace
+    unsigned long long* trace;  // optional [workgroup][8] wall-clock stamps (NULL = off)
 };
 
 // d_ff is cut into slices at multiples of 8 rows: slice s of S covers the

@@ -59,6 +59,7 @@ struct Geom {
 // s_waitcnt with only vmcnt constrained (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4]<<14)
 #define DFK_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | ((((n) >> 4) & 3) << 14))
 #define DFK_WAIT_LGKM0() __builtin_amdgcn_s_waitcnt(0xC07F)
+#define DFK_STAMP(k) do { if (a.trace && tid == 0) a.trace[(size_t)blockIdx.x * 8 + (k)] = wall_clock64(); } while (0)
 
 // Wait until at most `newer_ops` of this wavefront's vector-memory operations
 // are outstanding (loads complete in issue order); newer_ops is a multiple of 4.
@@ -247,6 +248,7 @@ __global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
     const int KW = a.d_model / NW;
     const int nkc = KW / kKC;
     const int my_blocks = wave < blk_cnt ? (blk_cnt - wave + NW - 1) / NW : 0;
+    const bool atomic_mode = a.reduce_mode == DFK_REDUCE_ATOMIC;
 
     TileStream<NW, MODE> ts;
     ts.Wg = (const char*)a.Wg; ts.Wu = (const char*)a.Wu; ts.Wd = (const char*)a.Wd;
@@ -267,6 +269,7 @@ __global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
         for (int i = tid; i < nt * 16 * TOK; i += NTHREADS) gu[i] = 0.f;
         lds_barrier();
     }
+    DFK_STAMP(0);
     ts.start();
 
     // ---- stage one
@@ -288,6 +291,7 @@ __global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
                 }
         }
         for (int rt = 0; rt < nt; ++rt) {
+            if (rt == 1) DFK_STAMP(1);
             f32x4 acc[TT];
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) acc[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -315,6 +319,7 @@ __global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
                 for (int i = 0; i < 4; ++i)
                     lds_add_f32_raw(gu_addr + 4u * (unsigned)((rt * 16 + 4 * g + i) * TOK + tt * 16 + q), acc[tt][i]);
         }
+        DFK_STAMP(2);
         lds_barrier();
         // SiLU(G) * U  ->  A_2
         for (int idx = tid; idx < rows_pad * TOK; idx += NTHREADS) {
@@ -333,6 +338,7 @@ __global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
             }
         }
         if (MODE == MODE_FUSED) lds_barrier();
+        DFK_STAMP(3);
     }
     if (MODE == MODE_GATEUP) return;
 
@@ -391,20 +397,53 @@ __global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
             for (int i = 0; i < 4; ++i) {
                 const int token = tt * 16 + 4 * g + i;
                 if (token < a.m_count) {
-                    float* dst = a.P + ((size_t)blockIdx.x * a.m_count + token) * a.d_model + nb + 8 * q;
-                    store4_device(dst, acc2[0][tt][i], acc2[1][tt][i], acc2[2][tt][i], acc2[3][tt][i]);
-                    store4_device(dst + 4, acc2[4][tt][i], acc2[5][tt][i], acc2[6][tt][i], acc2[7][tt][i]);
+                    if (atomic_mode) {
+                        float* dst = a.yacc + (size_t)token * a.d_model + nb + 8 * q;
+#pragma unroll
+                        for (int c = 0; c < 8; ++c) acc_add(dst + c, acc2[c][tt][i]);
+                    } else {
+                        float* dst = a.P + ((size_t)blockIdx.x * a.m_count + token) * a.d_model + nb + 8 * q;
+                        store4_device(dst, acc2[0][tt][i], acc2[1][tt][i], acc2[2][tt][i], acc2[3][tt][i]);
+                        store4_device(dst + 4, acc2[4][tt][i], acc2[5][tt][i], acc2[6][tt][i], acc2[7][tt][i]);
+                    }
                 }
             }
     }
 
+    DFK_STAMP(4);
     // ---- split-d_ff reduction and the bf16 store of Y
+    if (atomic_mode) {
+        // Per wavefront, no workgroup barrier: once its adds have been performed, the
+        // wavefront counts one arrival for each 128-column block it owns (one lane per
+        // block); whoever arrives last at a block reads-and-clears its accumulator
+        // columns and writes them to Y.
+        drain_own_memory_ops();
+        const unsigned expected = MODE == MODE_DOWN ? (unsigned)a.k2_splits : (unsigned)a.splits;
+        int blk = -1;
+        bool won = false;
+        if (lane < my_blocks) {
+            blk = blk_lo + wave + lane * NW;
+            won = arrive_last(a.tickets + blk, expected);
+        }
+        unsigned long long mask = __ballot(won);
+        while (mask) {
+            const int b = __builtin_ctzll(mask);
+            mask &= mask - 1;
+            const int nb = __shfl(blk, b) * 128;
+            for (int m = 0; m < a.m_count; ++m) {
+                float* src = a.yacc + (size_t)m * a.d_model + nb + 2 * lane;
+                const float v0 = acc_take(src), v1 = acc_take(src + 1);
+                *(uint32_t*)((uint16_t*)a.Y + (size_t)(a.m_base + m) * a.d_model + nb + 2 * lane) = pack_bf16x2(v0, v1);
+            }
+        }
+        return;
+    }
     __shared__ int flag;
     if (MODE == MODE_DOWN) {
         const int cb = blockIdx.x % a.k2_col_blocks;
-        reduce_store<BF16>(plan_column_block(a, cb, blk_lo * 128, (blk_lo + blk_cnt) * 128), a.Y, a.m_base, &flag);
+        reduce_store<BF16>(plan_column_block(a, cb, blk_lo * 128, (blk_lo + blk_cnt) * 128), a.Y, a.m_base, &flag, a.trace);
     } else {
-        reduce_store<BF16>(plan_full_width(a, blockIdx.x, a.splits), a.Y, a.m_base, &flag);
+        reduce_store<BF16>(plan_full_width(a, blockIdx.x, a.splits), a.Y, a.m_base, &flag, a.trace);
     }
 }
 
@@ -467,7 +506,8 @@ int mfma_max_tokens_per_launch(const dfk_config_t& c, int d_model) { return 16 *
 bool mfma_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype) {
     if (c.path != DFK_PATH_MFMA || dtype != DFK_BF16) return false;
     if (c.variant != DFK_VARIANT_FUSED && c.variant != DFK_VARIANT_TWO_KERNEL) return false;
-    if (c.reduce != DFK_REDUCE_TICKET) return false;
+    if (c.reduce != DFK_REDUCE_TICKET && c.reduce != DFK_REDUCE_ATOMIC) return false;
+    if (d_model > kMaxDModel) return false;
     if (c.waves != 4 && c.waves != 8 && c.waves != 16) return false;
     if (c.depth < 2 || c.depth > 16) return false;
     if (M < 1 || d_model < 8 || d_ff < 8 || d_ff % 8) return false;
@@ -478,15 +518,16 @@ bool mfma_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_
     const int per = mfma_max_tokens_per_launch(c, d_model);
     const int TT = token_tiles(c, M < per ? M : per);
     const int tokens = M < per ? M : per;
+    const bool ticket = c.reduce == DFK_REDUCE_TICKET;
     if (c.variant == DFK_VARIANT_FUSED)
-        return (c.splits + kGroupSize - 1) / kGroupSize <= kTicketLevel2 &&
-               partials_fit(c.splits, tokens, M, d_model) &&
+        return (!ticket || ((c.splits + kGroupSize - 1) / kGroupSize <= kTicketLevel2 &&
+                            partials_fit(c.splits, tokens, M, d_model))) &&
                sizes(c, MODE_FUSED, TT, d_ff).lds <= (size_t)kLdsLimit;
     if (c.k2_splits < 1 || c.k2_splits > ng) return false;
     const int nblk = d_model / 128;
     if (c.k2_col_blocks < 1 || nblk % c.k2_col_blocks) return false;
     if ((long long)c.k2_splits * c.k2_col_blocks > 65535 || c.k2_col_blocks > kTicketLevel2) return false;
-    if (!partials_fit(c.k2_splits * c.k2_col_blocks, tokens, M, d_model)) return false;
+    if (ticket && !partials_fit(c.k2_splits * c.k2_col_blocks, tokens, M, d_model)) return false;
     if (c.a2_dtype != DFK_BF16 && c.a2_dtype != DFK_FP32) return false;
     return sizes(c, MODE_GATEUP, TT, d_ff).lds <= (size_t)kLdsLimit &&
            sizes(c, MODE_DOWN, TT, d_ff).lds <= (size_t)kLdsLimit;

@@ -46,8 +46,8 @@ def y64(Y):
 
 
 def workspace_is_clean(ws, M, d):
-    """The arrival counters must be zero again after a call."""
-    head = ws[:4096]
+    """Arrival counters and the atomic accumulator must be zero again after a call."""
+    head = ws[:4096 + 32 * 32768 * 4]
     return int(torch.count_nonzero(head).item()) == 0
 
 
