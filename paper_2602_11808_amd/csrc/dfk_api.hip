@@ -107,8 +107,8 @@ std::vector<dfk_config_t> candidates(int M, int d_model, int d_ff, dfk_dtype_t d
         // MFMA path: d_ff slices ("column-major tiling": each workgroup owns a
         // block of weight rows and reuses it for every token).
         for (int splits : {256, 512})
-            for (int waves : {4, 8, 16})
-                for (int depth : {2, 3, 4, 6, 8})
+            for (int waves : {4, 8})
+                for (int depth : {2, 4, 6, 8})
                     for (int reduce : {DFK_REDUCE_ATOMIC, DFK_REDUCE_TICKET})
                         push(make_cfg(DFK_VARIANT_FUSED, DFK_PATH_MFMA, clamp_splits(splits, d_ff), waves,
                                       depth, 0, 0, a2dt, reduce));
@@ -116,7 +116,7 @@ std::vector<dfk_config_t> candidates(int M, int d_model, int d_ff, dfk_dtype_t d
         // waves*128 or 2*waves*128 columns), about one or two workgroups per CU
         const int nblk = d_model / 128;
         for (int splits : {256, 512})
-            for (int waves : {4, 8, 16})
+            for (int waves : {4, 8})
                 for (int per_wave : {1, 2}) {
                     const int wg_blocks = waves * per_wave;
                     if (wg_blocks > nblk || nblk % wg_blocks) continue;

@@ -21,15 +21,22 @@
 // stream starts, so that nothing but tile loads sits in the memory queue.  16-byte chunks are XOR-swizzled by row on the
 // way into LDS (by permuting which global chunk each lane fetches), so the
 // operand reads are bank-conflict free.  The wavefronts' k-partial sums meet
-// in an LDS array through ds_add_f32; then SiLU(G)*U is applied and A_2 is left
-// in LDS as bf16 [token][j] (or written to the workspace in MODE_GATEUP).
+// in an LDS array through ds_add_f32.  In the fused kernel there is no workgroup
+// barrier between the stages: the wavefront that contributes last to a row tile
+// (an LDS counter per row tile tells) applies SiLU(G)*U for it, leaves A_2 in LDS
+// as bf16 [token][j] and raises the row tile's ready flag.  (MODE_GATEUP instead
+// ends with a barrier and writes A_2 to the workspace.)
 //
 // Stage two (Y += A_2 W_down over the slice): wavefront w owns 128-column blocks
 // of d_model.  A tile is 4 row-groups of W_down: lane (q, g) fetches 16 bytes
 // (8 consecutive columns) of row 8g+r.  After two tiles a lane holds an 8x8
 // block (8 rows x 8 columns); v_perm_b32 regroups it into, per column, the 8
 // consecutive-j values the MFMA B operand wants - a per-lane transpose, no
-// cross-lane traffic.  A_2 (bf16, from LDS) is the A operand.  The fp32 block
+// cross-lane traffic.  A_2 (bf16, from LDS) is the A operand.  Stage two first
+// does the slice's first 32 rows for all of the wavefront's column blocks (they
+// need only row tiles whose flags were raised long ago, which absorbs the skew
+// between wavefronts), then finishes and flushes one block after the other.
+// The fp32 block
 // of partial Y is published to the workspace with device-scope stores and combined
 // by the two-level arrival-counter reduction (reduce_store); device-wide float
 // atomics were measured at ~10 G adds/s on MI355X and are not used.
@@ -53,6 +60,8 @@ struct Geom {
     int gu_off;     // LDS byte offset of the fp32 gate/up sums [nt*16][16*TT]
     int a2s_off;    // LDS byte offset of A_2 as bf16 [16*TT][a2_stride]
     int a2_stride;  // elements
+    int sync_off;   // LDS byte offset of the row-tile arrival counters and ready flags
+    int sync_cap;   // entries in each of the two (a multiple of 4, > row tiles)
 };
 
 #define DFK_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
@@ -100,6 +109,16 @@ __device__ __forceinline__ void lds_write_b16_raw(unsigned addr, unsigned v) {
     asm volatile("ds_write_b16 %0, %1" : : "v"(addr), "v"(v) : "memory");
 }
 
+__device__ __forceinline__ void lds_write_b32_raw(unsigned addr, unsigned v) {
+    asm volatile("ds_write_b32 %0, %1" : : "v"(addr), "v"(v) : "memory");
+}
+// LDS counter increment that returns the previous value (waits for it).
+__device__ __forceinline__ unsigned lds_inc_rtn_raw(unsigned addr) {
+    unsigned old, one = 1u;
+    asm volatile("ds_add_rtn_u32 %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=v"(old) : "v"(addr), "v"(one) : "memory");
+    return old;
+}
+
 // Workgroup barrier that orders LDS traffic only: it does not wait for the
 // global->LDS tile loads in flight (a full __syncthreads would drain them).
 // Written raw for the same reason: a fence the compiler sees waits for the tile
@@ -117,17 +136,21 @@ __device__ __forceinline__ bf16x8 as_bf16x8(const u32x4& v) {
 
 // 16-byte B-operand registers a wavefront may spend on X: cap * 4 per lane.
 __host__ __device__ constexpr int x_chunk_cap(int nw) { return nw == 16 ? 4 : 8; }
+// 128-column blocks whose stage-two accumulators a wavefront holds at once.
+__host__ __device__ constexpr int block_group(int tt) { return 4 / tt; }
 
 // Per-wavefront producer/consumer of the weight-tile stream.
-// Stage-one tiles come row-tile-major (tile (rt, kc): 16 rows x 128 k), then the
-// stage-two tiles (block bi, 32-row block jb, half h: 16 rows x 128 columns).
-template <int NW, int MODE>
+// Stage-one tiles come row-tile-major (tile (rt, kc): 16 rows x 128 k).  Stage-two
+// tiles (16 rows x 128 columns; two per 32-row block jb) come per group of BG
+// column blocks: first jb = 0 of every block of the group, then, block by block,
+// jb = 1 .. njb-1.
+template <int NW, int MODE, int BG>
 struct TileStream {
     const char *Wg, *Wu, *Wd;
     int d_model, d_ff;
     int j0, nt, njb;          // slice start row, stage-one row tiles, stage-two 32-row blocks
     int nkc;                  // 128-k chunks of this wavefront's k range
-    int blk_lo;               // stage two: first 128-column block of the workgroup
+    int blk_lo, my_blocks;    // stage two: first 128-column block of the workgroup, blocks of this wavefront
     int wave, q, g;
     // per-lane byte offsets inside a tile, fixed for the whole kernel
     unsigned off1[4];         // stage one, instruction u
@@ -139,11 +162,11 @@ struct TileStream {
     int depth;
     int T1, T;                // stage-one tiles, all tiles
     int issued, issue_slot;   // producer position
-    int take_slot;            // consumer position
+    int take_slot, taken;     // consumer position, tiles consumed
     int p_rt, p_kc;           // producer coordinates, stage one
-    int p_bi, p_jb, p_h;      // producer coordinates, stage two
+    int p_bg, p_phase, p_b, p_jb, p_h;   // producer coordinates, stage two
 
-    __device__ __forceinline__ void init(const MlpArgs& a, int kbase) {
+    __device__ __forceinline__ void init(int kbase) {
         row_bytes = (size_t)d_model * 2;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -153,7 +176,6 @@ struct TileStream {
         }
         off2 = (unsigned)(8 * g * row_bytes + 16 * q);
         base1 = (size_t)j0 * row_bytes + (size_t)kbase * 2;
-        (void)a;
     }
 
     __device__ __forceinline__ void issue() {
@@ -168,9 +190,10 @@ struct TileStream {
                                                  kAuxNonTemporal);
             if (++p_kc == nkc) { p_kc = 0; ++p_rt; }
         } else if (MODE != MODE_GATEUP) {
-            const int row0 = j0 + p_jb * 32 + 4 * p_h;   // first row of this half (lane adds 8g + u)
-            const size_t colb = (size_t)(blk_lo + p_bi) * 256;
-            if (row0 + 28 < d_ff) {      // every row of the tile exists: uniform base + lane offset
+            const int jb = p_phase ? p_jb : 0;
+            const int row0 = j0 + jb * 32 + 4 * p_h;   // first row of this half (lane adds 8g + u)
+            const size_t colb = (size_t)(blk_lo + wave + (p_bg + p_b) * NW) * 256;
+            if (row0 + 28 <= d_ff) {     // every row of the tile exists: uniform base + lane offset
                 const char* b = Wd + (size_t)row0 * row_bytes + colb;
 #pragma unroll
                 for (int u = 0; u < 4; ++u)
@@ -185,32 +208,56 @@ struct TileStream {
                 }
             }
             p_h ^= 1;
-            if (p_h == 0 && ++p_jb == njb) { p_jb = 0; p_bi += NW; }
+            if (p_h == 0) {              // a 32-row chunk is complete: advance (phase, block, jb)
+                const int nbk = min(BG, my_blocks - p_bg);
+                if (p_phase == 0) {
+                    if (++p_b == nbk) {
+                        p_b = 0;
+                        if (njb > 1) { p_phase = 1; p_jb = 1; } else { p_bg += BG; }
+                    }
+                } else if (++p_jb == njb) {
+                    p_jb = 1;
+                    if (++p_b == nbk) { p_b = 0; p_phase = 0; p_bg += BG; }
+                }
+            }
         }
         ++issued;
         if (++issue_slot == depth) issue_slot = 0;
     }
 
     __device__ __forceinline__ void start() {
-        issued = 0; issue_slot = 0; take_slot = 0;
-        p_rt = 0; p_kc = 0; p_bi = wave; p_jb = 0; p_h = 0;
+        issued = 0; issue_slot = 0; take_slot = 0; taken = 0;
+        p_rt = 0; p_kc = 0; p_bg = 0; p_phase = 0; p_b = 0; p_jb = 1; p_h = 0;
         const int ahead = min(depth - 1, T);
         for (int i = 0; i < ahead; ++i) issue();
     }
 
     // Returns the LDS address of the next tile, landed and readable by this wavefront.
+    // Only loads count: with at most 4*(depth-1) operations outstanding, at most that
+    // many loads are, and loads complete in issue order, so the wanted tile is in.
     __device__ __forceinline__ const unsigned char* acquire() {
         // Reads of the slot about to be refilled must have returned before its refill is issued.
         DFK_WAIT_LGKM0();
         asm volatile("" ::: "memory");
         if (issued < T) {
             issue();
-            wait_vm_ops(4 * (depth - 1));   // only tile loads are in the queue: depth-1 newer tiles
+            wait_vm_ops(4 * (depth - 1));
         } else {
             wait_vm_ops(0);
         }
         const unsigned char* slot = ring + take_slot * kTileBytes;
         if (++take_slot == depth) take_slot = 0;
+        // The CU serves the memory requests of the wavefront with the higher priority
+        // (oldest first at equal priority) ahead of its SIMD neighbour's, which lets one
+        // of the two run ~30% ahead.  Swapping the priorities of the two halves of the
+        // workgroup every few tiles keeps them level.
+        if (NW > 4) {
+            ++taken;
+            if ((taken & 3) == 0) {
+                if (((taken >> 2) ^ (wave >= NW / 2 ? 1 : 0)) & 1) __builtin_amdgcn_s_setprio(2);
+                else __builtin_amdgcn_s_setprio(0);
+            }
+        }
         return slot;
     }
 };
@@ -221,13 +268,15 @@ __global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
     constexpr int TOK = 16 * TT;
     constexpr int NTHREADS = NW * 64;
     constexpr int NKC = x_chunk_cap(NW) / TT;   // 128-k chunks of X a wavefront can hold
+    constexpr int BG = block_group(TT);
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int q = lane & 15, g = lane >> 4;
     float* gu = (float*)(lds + geo.gu_off);
     uint16_t* a2s = (uint16_t*)(lds + geo.a2s_off);
-    const unsigned gu_addr = lds_addr(gu), a2s_addr = lds_addr(a2s);
+    unsigned* sync = (unsigned*)(lds + geo.sync_off);   // [0, cap): arrivals per row tile, [cap, 2cap): ready flags
+    const unsigned gu_addr = lds_addr(gu), a2s_addr = lds_addr(a2s), sync_addr = lds_addr(sync);
     const uint16_t* X = (const uint16_t*)a.X;
 
     // ---- geometry
@@ -250,23 +299,27 @@ __global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
     const int my_blocks = wave < blk_cnt ? (blk_cnt - wave + NW - 1) / NW : 0;
     const bool atomic_mode = a.reduce_mode == DFK_REDUCE_ATOMIC;
 
-    TileStream<NW, MODE> ts;
+    TileStream<NW, MODE, BG> ts;
     ts.Wg = (const char*)a.Wg; ts.Wu = (const char*)a.Wu; ts.Wd = (const char*)a.Wd;
     ts.d_model = a.d_model; ts.d_ff = a.d_ff;
     ts.j0 = j0; ts.nt = nt; ts.njb = njb;
     ts.nkc = nkc;
-    ts.blk_lo = blk_lo;
+    ts.blk_lo = blk_lo; ts.my_blocks = my_blocks;
     ts.wave = wave; ts.q = q; ts.g = g;
     ts.ring = lds + wave * geo.depth * kTileBytes;
     ts.depth = geo.depth;
     ts.T1 = (MODE != MODE_DOWN) ? nt * nkc : 0;
     ts.T = ts.T1 + ((MODE != MODE_GATEUP) ? my_blocks * njb * 2 : 0);
-    ts.init(a, wave * KW);
+    ts.init(wave * KW);
 
-    // The LDS sums are cleared before the first tile load is issued, so this
-    // barrier has nothing in flight to wait for.
+    // Everything in LDS that must start from a known value is set before the first
+    // tile load is issued, so this barrier has nothing in flight to wait for.
     if (MODE != MODE_DOWN) {
         for (int i = tid; i < nt * 16 * TOK; i += NTHREADS) gu[i] = 0.f;
+        if (MODE == MODE_FUSED) {
+            for (int i = tid; i < 2 * geo.sync_cap; i += NTHREADS) sync[i] = (i >= geo.sync_cap + nt) ? 1u : 0u;
+            for (int i = tid; i < TOK * geo.a2_stride / 2; i += NTHREADS) ((uint32_t*)a2s)[i] = 0u;
+        }
         lds_barrier();
     }
     DFK_STAMP(0);
@@ -318,29 +371,41 @@ __global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
                     lds_add_f32_raw(gu_addr + 4u * (unsigned)((rt * 16 + 4 * g + i) * TOK + tt * 16 + q), acc[tt][i]);
+            if (MODE == MODE_FUSED) {
+                // Count this wavefront's arrival at row tile rt (LDS executes a wavefront's
+                // instructions in order, so its sums are in before its count).  The last of
+                // the NW arrivals turns the row tile's sums into A_2 and raises its flag.
+                unsigned old = 0;
+                if (lane == 0) old = lds_inc_rtn_raw(sync_addr + 4u * (unsigned)rt);
+                old = __builtin_amdgcn_readfirstlane(old);
+                if (old == NW - 1) {
+                    for (int e = lane; e < 8 * TOK; e += 64) {
+                        const int jr = e / TOK, m = e - jr * TOK;
+                        const float v = silu_mul(gu[(rt * 16 + jr) * TOK + m], gu[(rt * 16 + 8 + jr) * TOK + m]);
+                        lds_write_b16_raw(a2s_addr + 2u * (unsigned)(m * geo.a2_stride + rt * 8 + jr), f32_to_bf16_bits(v));
+                    }
+                    DFK_WAIT_LGKM0();
+                    if (lane == 0) lds_write_b32_raw(sync_addr + 4u * (unsigned)(geo.sync_cap + rt), 1u);
+                }
+            }
         }
         DFK_STAMP(2);
-        lds_barrier();
-        // SiLU(G) * U  ->  A_2
-        for (int idx = tid; idx < rows_pad * TOK; idx += NTHREADS) {
-            const int j = idx / TOK, m = idx - j * TOK;
-            float v = 0.f;
-            if (j < rows) {
-                const int tile = j >> 3, jr = j & 7;
-                v = silu_mul(gu[(tile * 16 + jr) * TOK + m], gu[(tile * 16 + 8 + jr) * TOK + m]);
+        if (MODE == MODE_GATEUP) {
+            lds_barrier();
+            // SiLU(G) * U  ->  A_2 in the workspace
+            for (int idx = tid; idx < rows * TOK; idx += NTHREADS) {
+                const int j = idx / TOK, m = idx - j * TOK;
+                if (m < a.m_count) {
+                    const int tile = j >> 3, jr = j & 7;
+                    const float v = silu_mul(gu[(tile * 16 + jr) * TOK + m], gu[(tile * 16 + 8 + jr) * TOK + m]);
+                    const size_t o = (size_t)(a.m_base + m) * a.d_ff + j0 + j;
+                    if (a.a2_is_fp32) ((float*)a.a2)[o] = v;
+                    else ((uint16_t*)a.a2)[o] = (uint16_t)f32_to_bf16_bits(v);
+                }
             }
-            if (MODE == MODE_FUSED) {
-                lds_write_b16_raw(a2s_addr + 2u * (unsigned)(m * geo.a2_stride + j), f32_to_bf16_bits(v));
-            } else if (j < rows && m < a.m_count) {
-                const size_t o = (size_t)(a.m_base + m) * a.d_ff + j0 + j;
-                if (a.a2_is_fp32) ((float*)a.a2)[o] = v;
-                else ((uint16_t*)a.a2)[o] = (uint16_t)f32_to_bf16_bits(v);
-            }
+            return;
         }
-        if (MODE == MODE_FUSED) lds_barrier();
-        DFK_STAMP(3);
     }
-    if (MODE == MODE_GATEUP) return;
 
     // ---- stage two
     if (MODE == MODE_DOWN) {
@@ -355,14 +420,26 @@ __global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
         }
         lds_barrier();
     }
-    for (int bi = wave; bi < blk_cnt; bi += NW) {
-        const int nb = (blk_lo + bi) * 128;
-        f32x4 acc2[8][TT];
+
+    // Waits (fused kernel only) until the row tiles feeding the 32-row block jb have their A_2.
+    auto wait_rows_ready = [&](int jb) {
+        if (MODE != MODE_FUSED) return;
+        const volatile unsigned* ready = sync + geo.sync_cap + 4 * jb;
+        while ((ready[0] & ready[1] & ready[2] & ready[3]) == 0u) __builtin_amdgcn_s_sleep(1);
+        asm volatile("" ::: "memory");
+    };
+
+    for (int bg = 0; bg < my_blocks; bg += BG) {
+        f32x4 acc2[BG][8][TT];
 #pragma unroll
-        for (int c = 0; c < 8; ++c)
+        for (int b = 0; b < BG; ++b)
 #pragma unroll
-            for (int tt = 0; tt < TT; ++tt) acc2[c][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
-        for (int jb = 0; jb < njb; ++jb) {
+            for (int c = 0; c < 8; ++c)
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) acc2[b][c][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+        // One 32-row chunk (two tiles) of one column block.
+        auto chunk = [&](f32x4 (&acc)[8][TT], int jb) {
             u32x4 w[8];
             const unsigned char* sa = ts.acquire();
 #pragma unroll
@@ -388,29 +465,71 @@ __global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
                     b[p] = __builtin_amdgcn_perm(w[2 * p + 1][c >> 1], w[2 * p][c >> 1], sel);
 #pragma unroll
                 for (int tt = 0; tt < TT; ++tt)
-                    acc2[c][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[tt], as_bf16x8(b), acc2[c][tt], 0, 0, 0);
+                    acc[c][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[tt], as_bf16x8(b), acc[c][tt], 0, 0, 0);
+            }
+        };
+
+        // The finished fp32 block of partial Y of one column block leaves the wavefront.
+        auto flush = [&](f32x4 (&acc)[8][TT], int bi) {
+            const int nb = (blk_lo + wave + bi * NW) * 128;
+            if (atomic_mode) {
+                // Regroup through lane permutes so that one atomic instruction covers 64
+                // consecutive floats: lane L adds columns nb+L and nb+64+L of one token.
+                // (Column 8q'+c of token 4g'+i sits in lane 16g'+q', register [c][tt][i].)
+                for (int token = 0; token < a.m_count; ++token) {
+                    const int tt = token >> 4, gsrc = (token >> 2) & 3, i = token & 3;
+                    float lo = 0.f, hi = 0.f;
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) {
+                        float v = 0.f;
+#pragma unroll
+                        for (int t2 = 0; t2 < TT; ++t2)
+#pragma unroll
+                            for (int i2 = 0; i2 < 4; ++i2)
+                                if (t2 == tt && i2 == i) v = acc[c][t2][i2];
+                        const float va = __shfl(v, 16 * gsrc + (lane >> 3));
+                        const float vb = __shfl(v, 16 * gsrc + 8 + (lane >> 3));
+                        if ((lane & 7) == c) { lo = va; hi = vb; }
+                    }
+                    float* dst = a.yacc + (size_t)token * a.d_model + nb + lane;
+                    acc_add(dst, lo);
+                    acc_add(dst + 64, hi);
+                }
+            } else {
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int token = tt * 16 + 4 * g + i;
+                        if (token < a.m_count) {
+                            float* dst = a.P + ((size_t)blockIdx.x * a.m_count + token) * a.d_model + nb + 8 * q;
+                            store4_device(dst, acc[0][tt][i], acc[1][tt][i], acc[2][tt][i], acc[3][tt][i]);
+                            store4_device(dst + 4, acc[4][tt][i], acc[5][tt][i], acc[6][tt][i], acc[7][tt][i]);
+                        }
+                    }
+            }
+        };
+
+        // first 32 rows of every block of the group
+        wait_rows_ready(0);
+#pragma unroll
+        for (int b = 0; b < BG; ++b)
+            if (bg + b < my_blocks) chunk(acc2[b], 0);
+        if (bg == 0) DFK_STAMP(3);
+        // then each block to its end
+#pragma unroll
+        for (int b = 0; b < BG; ++b) {
+            if (bg + b < my_blocks) {
+                for (int jb = 1; jb < njb; ++jb) {
+                    if (bg == 0 && b == 0) wait_rows_ready(jb);
+                    chunk(acc2[b], jb);
+                }
+                flush(acc2[b], bg + b);
             }
         }
-#pragma unroll
-        for (int tt = 0; tt < TT; ++tt)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int token = tt * 16 + 4 * g + i;
-                if (token < a.m_count) {
-                    if (atomic_mode) {
-                        float* dst = a.yacc + (size_t)token * a.d_model + nb + 8 * q;
-#pragma unroll
-                        for (int c = 0; c < 8; ++c) acc_add(dst + c, acc2[c][tt][i]);
-                    } else {
-                        float* dst = a.P + ((size_t)blockIdx.x * a.m_count + token) * a.d_model + nb + 8 * q;
-                        store4_device(dst, acc2[0][tt][i], acc2[1][tt][i], acc2[2][tt][i], acc2[3][tt][i]);
-                        store4_device(dst + 4, acc2[4][tt][i], acc2[5][tt][i], acc2[6][tt][i], acc2[7][tt][i]);
-                    }
-                }
-            }
     }
-
     DFK_STAMP(4);
+
     // ---- split-d_ff reduction and the bf16 store of Y
     if (atomic_mode) {
         // Per wavefront, no workgroup barrier: once its adds have been performed, the
@@ -436,6 +555,7 @@ __global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
                 *(uint32_t*)((uint16_t*)a.Y + (size_t)(a.m_base + m) * a.d_model + nb + 2 * lane) = pack_bf16x2(v0, v1);
             }
         }
+        if (a.trace && tid == 0) a.trace[(size_t)blockIdx.x * 8 + 7] = wall_clock64();
         return;
     }
     __shared__ int flag;
@@ -473,6 +593,10 @@ Sizes sizes(const dfk_config_t& c, int mode, int TT, int d_ff) {
     s.geo.a2s_off = (int)off;
     s.geo.a2_stride = rows_pad + 8;
     if (mode != MODE_GATEUP) off += (size_t)TOK * s.geo.a2_stride * 2;
+    off = (off + 15) & ~(size_t)15;
+    s.geo.sync_off = (int)off;
+    s.geo.sync_cap = ((maxrows / 8 + 4) + 3) & ~3;
+    if (mode == MODE_FUSED) off += (size_t)2 * s.geo.sync_cap * 4;
     s.lds = off;
     return s;
 }
