@@ -162,7 +162,7 @@ struct TileStream {
     int depth;
     int T1, T;                // stage-one tiles, all tiles
     int issued, issue_slot;   // producer position
-    int take_slot, taken;     // consumer position, tiles consumed
+    int take_slot;            // consumer position
     int p_rt, p_kc;           // producer coordinates, stage one
     int p_bg, p_phase, p_b, p_jb, p_h;   // producer coordinates, stage two
 
@@ -226,7 +226,7 @@ struct TileStream {
     }
 
     __device__ __forceinline__ void start() {
-        issued = 0; issue_slot = 0; take_slot = 0; taken = 0;
+        issued = 0; issue_slot = 0; take_slot = 0;
         p_rt = 0; p_kc = 0; p_bg = 0; p_phase = 0; p_b = 0; p_jb = 1; p_h = 0;
         const int ahead = min(depth - 1, T);
         for (int i = 0; i < ahead; ++i) issue();
@@ -247,17 +247,6 @@ struct TileStream {
         }
         const unsigned char* slot = ring + take_slot * kTileBytes;
         if (++take_slot == depth) take_slot = 0;
-        // The CU serves the memory requests of the wavefront with the higher priority
-        // (oldest first at equal priority) ahead of its SIMD neighbour's, which lets one
-        // of the two run ~30% ahead.  Swapping the priorities of the two halves of the
-        // workgroup every few tiles keeps them level.
-        if (NW > 4) {
-            ++taken;
-            if ((taken & 3) == 0) {
-                if (((taken >> 2) ^ (wave >= NW / 2 ? 1 : 0)) & 1) __builtin_amdgcn_s_setprio(2);
-                else __builtin_amdgcn_s_setprio(0);
-            }
-        }
         return slot;
     }
 };
@@ -312,18 +301,20 @@ __global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
     ts.T = ts.T1 + ((MODE != MODE_GATEUP) ? my_blocks * njb * 2 : 0);
     ts.init(wave * KW);
 
-    // Everything in LDS that must start from a known value is set before the first
-    // tile load is issued, so this barrier has nothing in flight to wait for.
+    // The tile stream starts first: nothing it needs depends on the LDS arrays below.
+    DFK_STAMP(0);
+    ts.start();
+
+    // Everything in LDS that must start from a known value (raw stores: see lds_add_f32_raw).
     if (MODE != MODE_DOWN) {
-        for (int i = tid; i < nt * 16 * TOK; i += NTHREADS) gu[i] = 0.f;
+        for (int i = tid; i < nt * 16 * TOK; i += NTHREADS) lds_write_b32_raw(gu_addr + 4u * (unsigned)i, 0u);
         if (MODE == MODE_FUSED) {
-            for (int i = tid; i < 2 * geo.sync_cap; i += NTHREADS) sync[i] = (i >= geo.sync_cap + nt) ? 1u : 0u;
-            for (int i = tid; i < TOK * geo.a2_stride / 2; i += NTHREADS) ((uint32_t*)a2s)[i] = 0u;
+            for (int i = tid; i < 2 * geo.sync_cap; i += NTHREADS)
+                lds_write_b32_raw(sync_addr + 4u * (unsigned)i, (i >= geo.sync_cap + nt) ? 1u : 0u);
+            for (int i = tid; i < TOK * geo.a2_stride / 2; i += NTHREADS) lds_write_b32_raw(a2s_addr + 4u * (unsigned)i, 0u);
         }
         lds_barrier();
     }
-    DFK_STAMP(0);
-    ts.start();
 
     // ---- stage one
     if (MODE != MODE_DOWN) {
