@@ -162,6 +162,34 @@ __device__ __forceinline__ ReducePlan plan_column_block(const MlpArgs& a, int cb
     return r;
 }
 
+// Sums, in ascending block order, the float4 at two positions (idx0 and idx0+nth of a
+// [m][w4] index space) over n blocks `stride` floats apart.  All loads of a batch of
+// 16 blocks for both positions are issued before the first add, so a reducer pays
+// one memory round trip per 16 blocks instead of one per few loads.
+__device__ __forceinline__ void sum_blocks2(const float* base, size_t stride, int n, int idx0, int nth, int total,
+                                            int w4, int d_model, int c_lo, float4 (&s)[2], size_t (&off)[2]) {
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int idx = min(idx0 + u * nth, total - 1);   // a clamped duplicate is computed and dropped by the caller
+        const int m = idx / w4, c4 = idx - m * w4;
+        off[u] = (size_t)m * d_model + c_lo + 4 * c4;
+        s[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    for (int i0 = 0; i0 < n; i0 += 16) {
+        float4 v[2][16];
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int k = 0; k < 16; ++k)
+                v[u][k] = (i0 + k < n) ? *(const float4*)(base + (size_t)(i0 + k) * stride + off[u])
+                                       : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int k = 0; k < 16; ++k) { s[u].x += v[u][k].x; s[u].y += v[u][k].y; s[u].z += v[u][k].z; s[u].w += v[u][k].w; }
+    }
+}
+
 template <typename E>
 __device__ __forceinline__ void reduce_store(const ReducePlan& r, void* Y, int m_base, int* flag,
                                              unsigned long long* trace = nullptr) {
@@ -177,18 +205,20 @@ __device__ __forceinline__ void reduce_store(const ReducePlan& r, void* Y, int m
     __syncthreads();
     if (!*flag) { if (trace && tid == 0) trace[(size_t)blockIdx.x * 8 + 6] = wall_clock64(); return; }
     acquire_device();
-    for (int idx = tid; idx < r.m_count * w4; idx += nth) {
-        const int m = idx / w4, c4 = idx - m * w4;
-        const size_t off = (size_t)m * r.d_model + r.c_lo + 4 * c4;
-        const float* src = r.P + (size_t)r.p_first * blk + off;
-        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll 8
-        for (int i = 0; i < r.n1; ++i) {
-            const float4 v = *(const float4*)(src + (size_t)i * r.p_stride * blk);
-            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    for (int idx0 = tid; idx0 < r.m_count * w4; idx0 += 2 * nth) {
+        float4 s[2];
+        size_t off[2];
+        sum_blocks2(r.P + (size_t)r.p_first * blk, (size_t)r.p_stride * blk, r.n1, idx0, nth, r.m_count * w4, w4,
+                    r.d_model, r.c_lo, s, off);
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int idx = idx0 + u * nth;
+            if (idx < r.m_count * w4) {
+                const int m = idx / w4, c4 = idx - m * w4;
+                if (r.n2 == 1) E::store4(Y, (size_t)(m_base + m) * r.d_model + r.c_lo + 4 * c4, s[u].x, s[u].y, s[u].z, s[u].w);
+                else store4_device(r.Q + (size_t)r.q_slot * blk + off[u], s[u].x, s[u].y, s[u].z, s[u].w);
+            }
         }
-        if (r.n2 == 1) E::store4(Y, (size_t)(m_base + m) * r.d_model + r.c_lo + 4 * c4, s.x, s.y, s.z, s.w);
-        else store4_device(r.Q + (size_t)r.q_slot * blk + off, s.x, s.y, s.z, s.w);
     }
     if (r.n2 == 1) { if (trace && tid == 0) trace[(size_t)blockIdx.x * 8 + 6] = wall_clock64(); return; }
     drain_own_memory_ops();
@@ -198,16 +228,18 @@ __device__ __forceinline__ void reduce_store(const ReducePlan& r, void* Y, int m
     if (trace && tid == 0) trace[(size_t)blockIdx.x * 8 + 6] = wall_clock64();
     if (!*flag) return;
     acquire_device();
-    for (int idx = tid; idx < r.m_count * w4; idx += nth) {
-        const int m = idx / w4, c4 = idx - m * w4;
-        const size_t off = (size_t)m * r.d_model + r.c_lo + 4 * c4;
-        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll 8
-        for (int i = 0; i < r.n2; ++i) {
-            const float4 v = *(const float4*)(r.Q + (size_t)i * blk + off);
-            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    for (int idx0 = tid; idx0 < r.m_count * w4; idx0 += 2 * nth) {
+        float4 s[2];
+        size_t off[2];
+        sum_blocks2(r.Q, blk, r.n2, idx0, nth, r.m_count * w4, w4, r.d_model, r.c_lo, s, off);
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int idx = idx0 + u * nth;
+            if (idx < r.m_count * w4) {
+                const int m = idx / w4, c4 = idx - m * w4;
+                E::store4(Y, (size_t)(m_base + m) * r.d_model + r.c_lo + 4 * c4, s[u].x, s[u].y, s[u].z, s[u].w);
+            }
         }
-        E::store4(Y, (size_t)(m_base + m) * r.d_model + r.c_lo + 4 * c4, s.x, s.y, s.z, s.w);
     }
     if (trace && tid == 0) trace[(size_t)blockIdx.x * 8 + 7] = wall_clock64();
 }

@@ -135,7 +135,7 @@ __device__ __forceinline__ bf16x8 as_bf16x8(const u32x4& v) {
 }
 
 // 16-byte B-operand registers a wavefront may spend on X: cap * 4 per lane.
-__host__ __device__ constexpr int x_chunk_cap(int nw) { return nw == 16 ? 4 : 8; }
+__host__ __device__ constexpr int x_chunk_cap(int) { return 8; }
 // 128-column blocks whose stage-two accumulators a wavefront holds at once.
 __host__ __device__ constexpr int block_group(int tt) { return 4 / tt; }
 
@@ -566,7 +566,6 @@ struct Sizes {
 // token tiles (of 16) per launch: two if the wavefront can hold X for both, else one
 int max_token_tiles(const dfk_config_t& c, int d_model) {
     const int nkc = d_model / c.waves / kKC;
-    if (c.waves == 16) return 1;   // 128 registers per lane: no room for a second token tile
     return 2 * nkc <= x_chunk_cap(c.waves) ? 2 : 1;
 }
 int token_tiles(const dfk_config_t& c, int m_count) { return m_count <= 16 ? 1 : 2; }
@@ -623,7 +622,7 @@ bool mfma_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_
     if (c.variant != DFK_VARIANT_FUSED && c.variant != DFK_VARIANT_TWO_KERNEL) return false;
     if (c.reduce != DFK_REDUCE_TICKET && c.reduce != DFK_REDUCE_ATOMIC) return false;
     if (d_model > kMaxDModel) return false;
-    if (c.waves != 4 && c.waves != 8 && c.waves != 16) return false;
+    if (c.waves != 4 && c.waves != 8) return false;   // one or two wavefronts per SIMD
     if (c.depth < 2 || c.depth > 16) return false;
     if (M < 1 || d_model < 8 || d_ff < 8 || d_ff % 8) return false;
     if (d_model % (kKC * c.waves)) return false;   // each wavefront owns whole 128-k chunks
@@ -655,7 +654,6 @@ hipError_t launch_mfma(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) 
         case 42: return launch_nt<4, 2>(a, c, st);
         case 81: return launch_nt<8, 1>(a, c, st);
         case 82: return launch_nt<8, 2>(a, c, st);
-        case 161: return launch_nt<16, 1>(a, c, st);
         default: return hipErrorInvalidValue;
     }
 }
