@@ -236,3 +236,130 @@ def test_split_identity_on_gpu():
         part, _ = run_ex(gs, None, dfk.new_workspace(M, d, hi - lo, DEV))
         tot += part
     assert rel_err(tot.double().cpu().numpy(), full.double().cpu().numpy()) <= 1e-5
+
+
+def _cfgs(M, d, ff, pred):
+    out = []
+    for i in range(dfk.dfk_num_candidates(M, d, ff, dfk.DFK_BF16)):
+        c = dfk.dfk_get_candidate(M, d, ff, dfk.DFK_BF16, i)
+        if pred(c):
+            out.append(c)
+    return out
+
+
+@pytest.mark.parametrize("M", [1, 7, 16, 32])
+def test_both_reduction_modes_of_the_mfma_path(M):
+    d, ff = 1024, 2816
+    t = di.mlp_inputs(M, d, ff, seed=23)
+    ref = oracle.swiglu_mlp(t["X"], t["Wg"], t["Wu"], t["Wd"])
+    g = gpu_inputs(t)
+    ws = dfk.new_workspace(M, d, ff, DEV)
+    seen = set()
+    for c in _cfgs(M, d, ff, lambda c: c.path == dfk.DFK_PATH_MFMA):
+        print("case M", M, c, flush=True)
+        Y, _ = run_ex(g, c, ws)
+        assert rel_err(y64(Y), ref) <= TOL_BF16, (M, c)
+        assert workspace_is_clean(ws, M, d)
+        seen.add((c.variant, c.reduce))
+    for v in (dfk.DFK_VARIANT_FUSED, dfk.DFK_VARIANT_TWO_KERNEL):
+        for r in (dfk.DFK_REDUCE_TICKET, dfk.DFK_REDUCE_ATOMIC):
+            assert (v, r) in seen
+
+
+def test_counter_reduction_is_bitwise_reproducible_on_the_valu_path():
+    # fixed summation order everywhere on this path: identical bits run after run
+    M, d, ff = 4, 1024, 4096
+    g = gpu_inputs(di.mlp_inputs(M, d, ff, seed=29))
+    ws = dfk.new_workspace(M, d, ff, DEV)
+    for c in _cfgs(M, d, ff, lambda c: c.path == dfk.DFK_PATH_VALU)[:4]:
+        first, _ = run_ex(g, c, ws)
+        for _ in range(20):
+            again, _ = run_ex(g, c, ws)
+            assert torch.equal(first.view(torch.int16), again.view(torch.int16)), c
+
+
+def test_trace_buffer_records_a_monotone_timeline():
+    M, d, ff = 1, 1024, 2816
+    g = gpu_inputs(di.mlp_inputs(M, d, ff, seed=31))
+    ws = dfk.new_workspace(M, d, ff, DEV)
+    c = _cfgs(M, d, ff, lambda c: c.path == dfk.DFK_PATH_MFMA and c.variant == dfk.DFK_VARIANT_FUSED
+              and c.reduce == dfk.DFK_REDUCE_TICKET)[0]
+    tr = torch.zeros(c.splits * 8, dtype=torch.int64, device=DEV)
+    dfk.dfk_set_trace_buffer(tr)
+    try:
+        run_ex(g, c, ws)
+    finally:
+        dfk.dfk_set_trace_buffer(None)
+    t = tr.cpu().numpy().reshape(-1, 8)
+    assert (t[:, 0] > 0).all() and (t[:, 4] >= t[:, 2]).all() and (t[:, 2] >= t[:, 0]).all()
+    assert (t[:, 5] >= t[:, 4]).all()
+    assert (t[:, 7] > 0).sum() == 1                      # exactly one workgroup wrote Y last
+    before = tr.clone()
+    run_ex(g, c, ws)                                      # unregistered: nothing is written any more
+    assert torch.equal(before, tr)
+
+
+def test_calls_can_be_captured_in_a_graph_and_replayed():
+    # the deployment mode of the method: the chosen kernels are captured once and replayed;
+    # arrival counters reset themselves, so every replay must equal the eager result
+    M, d, ff = 4, 1024, 2816
+    t = di.mlp_inputs(M, d, ff, seed=37)
+    ref = oracle.swiglu_mlp(t["X"], t["Wg"], t["Wu"], t["Wd"])
+    g = gpu_inputs(t)
+    ws = dfk.new_workspace(M, d, ff, DEV)
+    dfk.dfk_set_workspace(ws)
+    try:
+        for fn in (dfk.dfk_swiglu_mlp_fused, dfk.dfk_swiglu_mlp_unfused):
+            Y = torch.zeros_like(g["X"])
+            fn(g["X"], g["Wg"], g["Wu"], g["Wd"], Y)          # eager warm-up (kernel attributes get set here)
+            torch.cuda.synchronize()
+            eager = Y.clone()
+            side = torch.cuda.Stream()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(graph, stream=side):
+                    fn(g["X"], g["Wg"], g["Wu"], g["Wd"], Y, stream=side)
+            for rep in range(5):
+                Y.zero_()
+                torch.cuda.synchronize()
+                graph.replay()
+                torch.cuda.synchronize()
+                assert rel_err(y64(Y), ref) <= TOL_BF16, (fn.__name__, rep)
+                assert rel_err(y64(Y), y64(eager)) <= 1e-2
+                # eager work of the program between replays
+                fn(g["X"], g["Wg"], g["Wu"], g["Wd"], torch.empty_like(Y))
+                torch.cuda.synchronize()
+                assert workspace_is_clean(ws, M, d)
+    finally:
+        dfk.dfk_set_workspace(None)
+
+
+def test_chained_layers_teacher_forced():
+    """Decode sweep shape: distinct 8B-shaped layers chained in stream order, with a
+    weight-free RMS normalisation between layers (random SwiGLU layers otherwise
+    shrink the activations to zero within a few layers).  Parity is per layer: the
+    oracle gets the exact bf16 input the GPU layer got."""
+    d, ff, L = 4096, 14336, 6
+    for M in (1, 16):
+        layers = [di.mlp_inputs_torch(M, d, ff, seed=1000, layer=l, device=DEV) for l in range(L)]
+        ws = dfk.new_workspace(M, d, ff, DEV)
+        dfk.dfk_set_workspace(ws)
+        try:
+            X = layers[0]["X"]
+            xs, ys = [], []
+            for l in range(L):
+                Y = torch.empty_like(X)
+                dfk.dfk_swiglu_mlp(X, layers[l]["Wg"], layers[l]["Wu"], layers[l]["Wd"], Y)
+                xs.append(X)
+                ys.append(Y)
+                Yf = Y.float()
+                X = (Yf / Yf.pow(2).mean(dim=1, keepdim=True).sqrt()).to(torch.bfloat16)
+            torch.cuda.synchronize()
+            for l in (0, L // 2, L - 1):
+                w = layers[l]
+                ref = oracle.swiglu_mlp(di.to_numpy(xs[l]), di.to_numpy(w["Wg"]), di.to_numpy(w["Wu"]),
+                                        di.to_numpy(w["Wd"]))
+                assert np.abs(ref).max() > 1e-2
+                assert rel_err(y64(ys[l]), ref) <= TOL_BF16, (M, l)
+        finally:
+            dfk.dfk_set_workspace(None)
