@@ -94,6 +94,11 @@ typedef enum { DFK_REDUCE_TICKET = 0, DFK_REDUCE_ATOMIC = 1 } dfk_reduce_t;
  *                  (grid of the second kernel = k2_splits * k2_col_blocks)
  *   a2_dtype       two-kernel variant: type A_2 is stored in between the
  *                  kernels, DFK_BF16 or DFK_FP32
+ *   k2_rows_by_wave  two-kernel variant, MFMA path: 0 = in the down projection each
+ *                  wavefront owns 128-column blocks of the workgroup's columns;
+ *                  1 = the wavefronts share the workgroup's (at most 4) column blocks
+ *                  and divide its d_ff rows (meant for few d_ff splits: a short
+ *                  cross-workgroup sum whatever the token count)
  */
 typedef struct dfk_config_t {
     int variant;
@@ -105,7 +110,7 @@ typedef struct dfk_config_t {
     int k2_splits;
     int k2_col_blocks;
     int a2_dtype;
-    int reserved;
+    int k2_rows_by_wave;
 } dfk_config_t;
 
 /* ---------------------------------------------------------------- the block */

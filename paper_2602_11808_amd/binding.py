@@ -34,10 +34,10 @@ DFK_MAX_M = 256
 class dfk_config_t(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int) for n in (
         "variant", "path", "splits", "waves", "depth", "reduce",
-        "k2_splits", "k2_col_blocks", "a2_dtype", "reserved")]
+        "k2_splits", "k2_col_blocks", "a2_dtype", "k2_rows_by_wave")]
 
     def as_dict(self):
-        return {n: getattr(self, n) for n, _ in self._fields_ if n != "reserved"}
+        return {n: getattr(self, n) for n, _ in self._fields_}
 
     def __repr__(self):
         return "dfk_config_t(" + ", ".join(f"{k}={v}" for k, v in self.as_dict().items()) + ")"

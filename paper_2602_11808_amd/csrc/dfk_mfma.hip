@@ -49,10 +49,10 @@ namespace {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 
-constexpr int MODE_FUSED = 0, MODE_GATEUP = 1, MODE_DOWN = 2;
+constexpr int MODE_FUSED = 0, MODE_GATEUP = 1, MODE_DOWN = 2, MODE_DOWN_ROWS = 3;
 constexpr int kTileBytes = 4096;   // one ring slot = 4 global->LDS instructions of 1 KB
 constexpr int kKC = 128;           // k extent of a stage-one tile
-constexpr int kLdsLimit = 160 * 1024;
+constexpr int kLdsLimit = 160 * 1024 - 256;   // dynamic part; a few static words (flags) come on top
 constexpr int kAuxNonTemporal = 2;  // cache-policy bit "nt": the weight stream is read once
 
 struct Geom {
@@ -150,7 +150,9 @@ struct TileStream {
     int d_model, d_ff;
     int j0, nt, njb;          // slice start row, stage-one row tiles, stage-two 32-row blocks
     int nkc;                  // 128-k chunks of this wavefront's k range
-    int blk_lo, my_blocks;    // stage two: first 128-column block of the workgroup, blocks of this wavefront
+    int blk_first, blk_step, my_blocks;   // stage two: this wavefront's 128-column blocks: blk_first + i*blk_step
+    int jb_lo;                // stage two: first 32-row block of the slice this wavefront handles
+    bool jb_major;            // stage two order: every column block of the group per 32-row block (rows-split kernel)
     int wave, q, g;
     // per-lane byte offsets inside a tile, fixed for the whole kernel
     unsigned off1[4];         // stage one, instruction u
@@ -190,9 +192,9 @@ struct TileStream {
                                                  kAuxNonTemporal);
             if (++p_kc == nkc) { p_kc = 0; ++p_rt; }
         } else if (MODE != MODE_GATEUP) {
-            const int jb = p_phase ? p_jb : 0;
-            const int row0 = j0 + jb * 32 + 4 * p_h;   // first row of this half (lane adds 8g + u)
-            const size_t colb = (size_t)(blk_lo + wave + (p_bg + p_b) * NW) * 256;
+            const int jb = (p_phase || jb_major) ? p_jb : 0;
+            const int row0 = j0 + (jb_lo + jb) * 32 + 4 * p_h;   // first row of this half (lane adds 8g + u)
+            const size_t colb = (size_t)(blk_first + (p_bg + p_b) * blk_step) * 256;
             if (row0 + 28 <= d_ff) {     // every row of the tile exists: uniform base + lane offset
                 const char* b = Wd + (size_t)row0 * row_bytes + colb;
 #pragma unroll
@@ -210,7 +212,12 @@ struct TileStream {
             p_h ^= 1;
             if (p_h == 0) {              // a 32-row chunk is complete: advance (phase, block, jb)
                 const int nbk = min(BG, my_blocks - p_bg);
-                if (p_phase == 0) {
+                if (jb_major) {
+                    if (++p_b == nbk) {
+                        p_b = 0;
+                        if (++p_jb == njb) { p_jb = 0; p_bg += BG; }
+                    }
+                } else if (p_phase == 0) {
                     if (++p_b == nbk) {
                         p_b = 0;
                         if (njb > 1) { p_phase = 1; p_jb = 1; } else { p_bg += BG; }
@@ -227,7 +234,7 @@ struct TileStream {
 
     __device__ __forceinline__ void start() {
         issued = 0; issue_slot = 0; take_slot = 0;
-        p_rt = 0; p_kc = 0; p_bg = 0; p_phase = 0; p_b = 0; p_jb = 1; p_h = 0;
+        p_rt = 0; p_kc = 0; p_bg = 0; p_phase = 0; p_b = 0; p_jb = jb_major ? 0 : 1; p_h = 0;
         const int ahead = min(depth - 1, T);
         for (int i = 0; i < ahead; ++i) issue();
     }
@@ -293,7 +300,7 @@ __global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
     ts.d_model = a.d_model; ts.d_ff = a.d_ff;
     ts.j0 = j0; ts.nt = nt; ts.njb = njb;
     ts.nkc = nkc;
-    ts.blk_lo = blk_lo; ts.my_blocks = my_blocks;
+    ts.blk_first = blk_lo + wave; ts.blk_step = NW; ts.my_blocks = my_blocks; ts.jb_lo = 0; ts.jb_major = false;
     ts.wave = wave; ts.q = q; ts.g = g;
     ts.ring = lds + wave * geo.depth * kTileBytes;
     ts.depth = geo.depth;
@@ -558,6 +565,173 @@ __global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
     }
 }
 
+// Second kernel of the two-kernel variant, rows split over the wavefronts: workgroup
+// (js, cb) owns CB <= 4 adjacent 128-column blocks of W_down over the d_ff split js;
+// its wavefronts share the columns and divide the split's 32-row blocks among
+// themselves.  A_2 (bf16, from the workspace) for a wavefront's rows sits in its
+// registers as the MFMA A operand; the wavefronts' fp32 results meet in LDS and the
+// workgroup publishes one [tokens][CB*128] block.  With few d_ff splits (8..16) the
+// cross-workgroup sum is short for any number of tokens.
+constexpr int kRowsModeMaxJb = 8;   // 32-row blocks per wavefront (A operand registers)
+
+template <int NW, int TT>
+__global__ __launch_bounds__(NW * 64) void k_down_rows(MlpArgs a, Geom geo) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    constexpr int TOK = 16 * TT;
+    constexpr int NTHREADS = NW * 64;
+    constexpr int BG = block_group(TT);
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int q = lane & 15, g = lane >> 4;
+    float* red = (float*)(lds + geo.gu_off);              // [TOK][CB*128] fp32
+    const unsigned red_addr = lds_addr(red);
+
+    const int js = blockIdx.x / a.k2_col_blocks;
+    const int cb = blockIdx.x - js * a.k2_col_blocks;
+    int j0, j1;
+    slice_rows(a.d_ff, a.k2_splits, js, j0, j1);
+    const int rows = j1 - j0;
+    const int CB = a.d_model / 128 / a.k2_col_blocks;      // <= BG, checked on the host
+    const int blk_lo = cb * CB;
+    const int njb_all = (rows + 31) / 32;
+    const int jb_lo = (int)((long long)njb_all * wave / NW);
+    const int njb = (int)((long long)njb_all * (wave + 1) / NW) - jb_lo;   // <= kRowsModeMaxJb, checked on the host
+    const int width = CB * 128;
+
+    TileStream<NW, MODE_DOWN, BG> ts;
+    ts.Wg = ts.Wu = nullptr; ts.Wd = (const char*)a.Wd;
+    ts.d_model = a.d_model; ts.d_ff = a.d_ff;
+    ts.j0 = j0; ts.nt = 0; ts.njb = njb; ts.nkc = 0;
+    ts.blk_first = blk_lo; ts.blk_step = 1; ts.my_blocks = njb > 0 ? CB : 0; ts.jb_lo = jb_lo; ts.jb_major = true;
+    ts.wave = wave; ts.q = q; ts.g = g;
+    ts.ring = lds + wave * geo.depth * kTileBytes;
+    ts.depth = geo.depth;
+    ts.T1 = 0;
+    ts.T = ts.my_blocks * njb * 2;
+    ts.init(0);
+    DFK_STAMP(0);
+    ts.start();
+
+    for (int i = tid; i < TOK * width; i += NTHREADS) lds_write_b32_raw(red_addr + 4u * (unsigned)i, 0u);
+    lds_barrier();
+
+    // A operand: A_2[token][8 consecutive j] for every 32-row block of this wavefront
+    u32x4 av[TT][kRowsModeMaxJb];
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) {
+        const int token = tt * 16 + q;
+#pragma unroll
+        for (int jbi = 0; jbi < kRowsModeMaxJb; ++jbi) {
+            av[tt][jbi] = u32x4{0, 0, 0, 0};
+            const int j = (jb_lo + jbi) * 32 + 8 * g;
+            if (jbi < njb && token < a.m_count && j < rows)
+                av[tt][jbi] = ld16((const uint16_t*)a.a2, ((size_t)(a.m_base + token) * a.d_ff + j0 + j) / 8);
+        }
+    }
+
+    f32x4 acc2[BG][8][TT];
+#pragma unroll
+    for (int b = 0; b < BG; ++b)
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) acc2[b][c][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    auto chunk = [&](f32x4 (&acc)[8][TT], int jb, const u32x4 (&avj)[TT]) {
+        u32x4 w[8];
+        const unsigned char* sa = ts.acquire();
+#pragma unroll
+        for (int u = 0; u < 4; ++u) w[u] = *(const u32x4*)(sa + u * 1024 + lane * 16);
+        const unsigned char* sb = ts.acquire();
+#pragma unroll
+        for (int u = 0; u < 4; ++u) w[4 + u] = *(const u32x4*)(sb + u * 1024 + lane * 16);
+        if (jb * 32 + 32 > rows) {   // rows past the split contribute nothing
+#pragma unroll
+            for (int r = 0; r < 8; ++r)
+                if (jb * 32 + 8 * g + r >= rows) w[r] = u32x4{0, 0, 0, 0};
+        }
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
+            u32x4 b;
+#pragma unroll
+            for (int p = 0; p < 4; ++p) b[p] = __builtin_amdgcn_perm(w[2 * p + 1][c >> 1], w[2 * p][c >> 1], sel);
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt)
+                acc[c][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(avj[tt]), as_bf16x8(b), acc[c][tt], 0, 0, 0);
+        }
+    };
+
+    // same order as the tile stream: 32-row block after 32-row block, every column block each time
+    for (int jbi = 0; jbi < njb; ++jbi) {
+        u32x4 avj[TT];
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+            avj[tt] = av[tt][0];
+#pragma unroll
+            for (int k = 1; k < kRowsModeMaxJb; ++k)
+                if (jbi == k) avj[tt] = av[tt][k];
+        }
+#pragma unroll
+        for (int b = 0; b < BG; ++b)
+            if (b < CB) chunk(acc2[b], jb_lo + jbi, avj);
+    }
+    DFK_STAMP(4);
+
+    // the wavefronts' sums over their rows meet in LDS (raw atomics: wait states by hand)
+#pragma unroll
+    for (int b = 0; b < BG; ++b)
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" : "+v"(acc2[b][c][tt]));
+#pragma unroll
+    for (int b = 0; b < BG; ++b)
+        if (b < CB) {
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int token = tt * 16 + 4 * g + i;
+                    if (token < a.m_count) {
+#pragma unroll
+                        for (int c = 0; c < 8; ++c)
+                            lds_add_f32_raw(red_addr + 4u * (unsigned)(token * width + b * 128 + 8 * q + c), acc2[b][c][tt][i]);
+                    }
+                }
+        }
+    lds_barrier();
+    const bool atomic_mode = a.reduce_mode == DFK_REDUCE_ATOMIC;
+    const int w4 = width / 4;
+    for (int idx = tid; idx < a.m_count * w4; idx += NTHREADS) {
+        const int m = idx / w4, c4 = idx - m * w4;
+        const float4 v = *(const float4*)(red + m * width + 4 * c4);
+        if (atomic_mode) {
+            float* dst = a.yacc + (size_t)m * a.d_model + blk_lo * 128 + 4 * c4;
+            acc_add(dst, v.x); acc_add(dst + 1, v.y); acc_add(dst + 2, v.z); acc_add(dst + 3, v.w);
+        } else {
+            store4_device(a.P + ((size_t)blockIdx.x * a.m_count + m) * a.d_model + blk_lo * 128 + 4 * c4, v.x, v.y, v.z, v.w);
+        }
+    }
+    __shared__ int flag;
+    if (atomic_mode) {
+        drain_own_memory_ops();
+        __syncthreads();
+        if (tid == 0) flag = arrive_last(a.tickets + cb, (unsigned)a.k2_splits) ? 1 : 0;
+        __syncthreads();
+        if (!flag) return;
+        for (int idx = tid; idx < a.m_count * (width / 2); idx += NTHREADS) {
+            const int m = idx / (width / 2), c2 = idx - m * (width / 2);
+            float* src = a.yacc + (size_t)m * a.d_model + blk_lo * 128 + 2 * c2;
+            const float v0 = acc_take(src), v1 = acc_take(src + 1);
+            *(uint32_t*)((uint16_t*)a.Y + (size_t)(a.m_base + m) * a.d_model + blk_lo * 128 + 2 * c2) = pack_bf16x2(v0, v1);
+        }
+        return;
+    }
+    reduce_store<BF16>(plan_column_block(a, cb, blk_lo * 128, blk_lo * 128 + width), a.Y, a.m_base, &flag, a.trace);
+}
+
 struct Sizes {
     Geom geo;
     size_t lds;
@@ -570,15 +744,23 @@ int max_token_tiles(const dfk_config_t& c, int d_model) {
 }
 int token_tiles(const dfk_config_t& c, int m_count) { return m_count <= 16 ? 1 : 2; }
 
-Sizes sizes(const dfk_config_t& c, int mode, int TT, int d_ff) {
+Sizes sizes(const dfk_config_t& c, int mode, int TT, int d_ff, int d_model) {
     Sizes s;
-    const int S = mode == MODE_DOWN ? c.k2_splits : c.splits;
+    const int S = (mode == MODE_DOWN || mode == MODE_DOWN_ROWS) ? c.k2_splits : c.splits;
     const int maxrows = max_slice_rows(d_ff, S);
     const int rows_pad = (maxrows + 31) & ~31;
     const int TOK = 16 * TT;
     size_t off = (size_t)c.waves * c.depth * kTileBytes;
     s.geo.depth = c.depth;
     s.geo.gu_off = (int)off;
+    if (mode == MODE_DOWN_ROWS) {   // only the [TOK][CB*128] fp32 meeting place of the wavefronts
+        off += (size_t)TOK * (d_model / c.k2_col_blocks) * 4;
+        s.geo.a2s_off = s.geo.sync_off = (int)off;
+        s.geo.a2_stride = 0;
+        s.geo.sync_cap = 0;
+        s.lds = off;
+        return s;
+    }
     if (mode != MODE_DOWN) off += (size_t)(maxrows / 8) * 16 * TOK * 4;
     s.geo.a2s_off = (int)off;
     s.geo.a2_stride = rows_pad + 8;
@@ -594,14 +776,17 @@ Sizes sizes(const dfk_config_t& c, int mode, int TT, int d_ff) {
 template <int NW, int TT, int MODE>
 hipError_t launch_one(const MlpArgs& a, const dfk_config_t& c, int grid, hipStream_t st) {
     static size_t configured = 0;   // largest dynamic LDS size this instantiation was allowed so far
-    const Sizes s = sizes(c, MODE, TT, a.d_ff);
+    const Sizes s = sizes(c, MODE, TT, a.d_ff, a.d_model);
+    const void* fn = MODE == MODE_DOWN_ROWS ? (const void*)k_down_rows<NW, TT> : (const void*)k_mfma<NW, TT, MODE == MODE_DOWN_ROWS ? MODE_DOWN : MODE>;
     if (s.lds > configured) {
-        hipError_t e = hipFuncSetAttribute((const void*)k_mfma<NW, TT, MODE>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)s.lds);
+        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s.lds);
         if (e != hipSuccess) return e;
         configured = s.lds;
     }
-    hipLaunchKernelGGL((k_mfma<NW, TT, MODE>), dim3(grid), dim3(NW * 64), s.lds, st, a, s.geo);
+    if (MODE == MODE_DOWN_ROWS)
+        hipLaunchKernelGGL((k_down_rows<NW, TT>), dim3(grid), dim3(NW * 64), s.lds, st, a, s.geo);
+    else
+        hipLaunchKernelGGL((k_mfma<NW, TT, MODE == MODE_DOWN_ROWS ? MODE_DOWN : MODE>), dim3(grid), dim3(NW * 64), s.lds, st, a, s.geo);
     return hipGetLastError();
 }
 
@@ -610,6 +795,7 @@ hipError_t launch_nt(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
     if (c.variant == DFK_VARIANT_FUSED) return launch_one<NW, TT, MODE_FUSED>(a, c, a.splits, st);
     hipError_t e = launch_one<NW, TT, MODE_GATEUP>(a, c, a.splits, st);
     if (e != hipSuccess) return e;
+    if (c.k2_rows_by_wave) return launch_one<NW, TT, MODE_DOWN_ROWS>(a, c, a.k2_splits * a.k2_col_blocks, st);
     return launch_one<NW, TT, MODE_DOWN>(a, c, a.k2_splits * a.k2_col_blocks, st);
 }
 
@@ -636,15 +822,22 @@ bool mfma_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_
     if (c.variant == DFK_VARIANT_FUSED)
         return (!ticket || ((c.splits + kGroupSize - 1) / kGroupSize <= kTicketLevel2 &&
                             partials_fit(c.splits, tokens, M, d_model))) &&
-               sizes(c, MODE_FUSED, TT, d_ff).lds <= (size_t)kLdsLimit;
+               sizes(c, MODE_FUSED, TT, d_ff, d_model).lds <= (size_t)kLdsLimit;
     if (c.k2_splits < 1 || c.k2_splits > ng) return false;
     const int nblk = d_model / 128;
     if (c.k2_col_blocks < 1 || nblk % c.k2_col_blocks) return false;
     if ((long long)c.k2_splits * c.k2_col_blocks > 65535 || c.k2_col_blocks > kTicketLevel2) return false;
     if (ticket && !partials_fit(c.k2_splits * c.k2_col_blocks, tokens, M, d_model)) return false;
     if (c.a2_dtype != DFK_BF16 && c.a2_dtype != DFK_FP32) return false;
-    return sizes(c, MODE_GATEUP, TT, d_ff).lds <= (size_t)kLdsLimit &&
-           sizes(c, MODE_DOWN, TT, d_ff).lds <= (size_t)kLdsLimit;
+    if (sizes(c, MODE_GATEUP, TT, d_ff, d_model).lds > (size_t)kLdsLimit) return false;
+    if (c.k2_rows_by_wave) {
+        if (c.k2_rows_by_wave != 1 || c.a2_dtype != DFK_BF16) return false;
+        if (nblk / c.k2_col_blocks > block_group(TT)) return false;             // accumulators of the column blocks
+        const int njb_all = (max_slice_rows(d_ff, c.k2_splits) + 31) / 32;
+        if ((njb_all + c.waves - 1) / c.waves > kRowsModeMaxJb) return false;   // A operand registers
+        return sizes(c, MODE_DOWN_ROWS, TT, d_ff, d_model).lds <= (size_t)kLdsLimit;
+    }
+    return sizes(c, MODE_DOWN, TT, d_ff, d_model).lds <= (size_t)kLdsLimit;
 }
 
 hipError_t launch_mfma(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
