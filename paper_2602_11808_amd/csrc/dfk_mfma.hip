@@ -359,6 +359,7 @@ __global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
                     }
                 }
             }
+
             // k-partial sums of all wavefronts meet in LDS.  The raw LDS atomics are
             // invisible to the compiler's hazard handling, so the wait states an MFMA
             // result needs before an LDS instruction may read it are inserted by hand.
@@ -407,14 +408,24 @@ __global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
 
     // ---- stage two
     if (MODE == MODE_DOWN) {
-        for (int idx = tid; idx < rows_pad * TOK; idx += NTHREADS) {
-            const int m = idx / rows_pad, j = idx - m * rows_pad;
-            uint16_t v = 0;
-            if (j < rows && m < a.m_count) {
-                const size_t o = (size_t)(a.m_base + m) * a.d_ff + j0 + j;
-                v = a.a2_is_fp32 ? (uint16_t)f32_to_bf16_bits(((const float*)a.a2)[o]) : ((const uint16_t*)a.a2)[o];
+        if (!a.a2_is_fp32) {
+            // eight bf16 per load; slices start and end on multiples of 8 rows
+            const int groups = rows_pad / 8;
+            for (int idx = tid; idx < groups * TOK; idx += NTHREADS) {
+                const int m = idx / groups, j = (idx - m * groups) * 8;
+                u32x4 v = u32x4{0, 0, 0, 0};
+                if (j < rows && m < a.m_count)
+                    v = ld16((const uint16_t*)a.a2, ((size_t)(a.m_base + m) * a.d_ff + j0 + j) / 8);
+                *(u32x4*)(a2s + m * geo.a2_stride + j) = v;
             }
-            lds_write_b16_raw(a2s_addr + 2u * (unsigned)(m * geo.a2_stride + j), v);
+        } else {
+            for (int idx = tid; idx < rows_pad * TOK; idx += NTHREADS) {
+                const int m = idx / rows_pad, j = idx - m * rows_pad;
+                uint16_t v = 0;
+                if (j < rows && m < a.m_count)
+                    v = (uint16_t)f32_to_bf16_bits(((const float*)a.a2)[(size_t)(a.m_base + m) * a.d_ff + j0 + j]);
+                lds_write_b16_raw(a2s_addr + 2u * (unsigned)(m * geo.a2_stride + j), v);
+            }
         }
         lds_barrier();
     }
@@ -584,8 +595,6 @@ __global__ __launch_bounds__(NW * 64) void k_down_rows(MlpArgs a, Geom geo) {
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int q = lane & 15, g = lane >> 4;
-    float* red = (float*)(lds + geo.gu_off);              // [TOK][CB*128] fp32
-    const unsigned red_addr = lds_addr(red);
 
     const int js = blockIdx.x / a.k2_col_blocks;
     const int cb = blockIdx.x - js * a.k2_col_blocks;
@@ -612,9 +621,6 @@ __global__ __launch_bounds__(NW * 64) void k_down_rows(MlpArgs a, Geom geo) {
     ts.init(0);
     DFK_STAMP(0);
     ts.start();
-
-    for (int i = tid; i < TOK * width; i += NTHREADS) lds_write_b32_raw(red_addr + 4u * (unsigned)i, 0u);
-    lds_barrier();
 
     // A operand: A_2[token][8 consecutive j] for every 32-row block of this wavefront
     u32x4 av[TT][kRowsModeMaxJb];
@@ -679,39 +685,45 @@ __global__ __launch_bounds__(NW * 64) void k_down_rows(MlpArgs a, Geom geo) {
     }
     DFK_STAMP(4);
 
-    // the wavefronts' sums over their rows meet in LDS (raw atomics: wait states by hand)
+    // The wavefronts' sums over their rows meet in LDS, one column block at a time:
+    // each wavefront stores its [TOK][128] block into a stage of its own (the tile
+    // rings are drained by now and the stages lie over them), then the workgroup adds
+    // the NW stages in wavefront order and publishes the result.
+    const bool atomic_mode = a.reduce_mode == DFK_REDUCE_ATOMIC;
+    float* stage = (float*)lds;                           // [NW][TOK][128]
+    __syncthreads();                                      // every wavefront is done with its ring
 #pragma unroll
-    for (int b = 0; b < BG; ++b)
-#pragma unroll
-        for (int c = 0; c < 8; ++c)
-#pragma unroll
-            for (int tt = 0; tt < TT; ++tt) asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" : "+v"(acc2[b][c][tt]));
-#pragma unroll
-    for (int b = 0; b < BG; ++b)
+    for (int b = 0; b < BG; ++b) {
         if (b < CB) {
+            float* mine = stage + (size_t)wave * TOK * 128;
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const int token = tt * 16 + 4 * g + i;
-                    if (token < a.m_count) {
-#pragma unroll
-                        for (int c = 0; c < 8; ++c)
-                            lds_add_f32_raw(red_addr + 4u * (unsigned)(token * width + b * 128 + 8 * q + c), acc2[b][c][tt][i]);
-                    }
+                    float* dst = mine + token * 128 + 8 * q;
+                    *(f32x4*)dst = f32x4{acc2[b][0][tt][i], acc2[b][1][tt][i], acc2[b][2][tt][i], acc2[b][3][tt][i]};
+                    *(f32x4*)(dst + 4) = f32x4{acc2[b][4][tt][i], acc2[b][5][tt][i], acc2[b][6][tt][i], acc2[b][7][tt][i]};
                 }
-        }
-    lds_barrier();
-    const bool atomic_mode = a.reduce_mode == DFK_REDUCE_ATOMIC;
-    const int w4 = width / 4;
-    for (int idx = tid; idx < a.m_count * w4; idx += NTHREADS) {
-        const int m = idx / w4, c4 = idx - m * w4;
-        const float4 v = *(const float4*)(red + m * width + 4 * c4);
-        if (atomic_mode) {
-            float* dst = a.yacc + (size_t)m * a.d_model + blk_lo * 128 + 4 * c4;
-            acc_add(dst, v.x); acc_add(dst + 1, v.y); acc_add(dst + 2, v.z); acc_add(dst + 3, v.w);
-        } else {
-            store4_device(a.P + ((size_t)blockIdx.x * a.m_count + m) * a.d_model + blk_lo * 128 + 4 * c4, v.x, v.y, v.z, v.w);
+            __syncthreads();
+            const int nb = (blk_lo + b) * 128;
+            if (atomic_mode) {
+                for (int idx = tid; idx < a.m_count * 128; idx += NTHREADS) {
+                    float v = 0.f;
+#pragma unroll
+                    for (int w = 0; w < NW; ++w) v += stage[w * TOK * 128 + idx];
+                    acc_add(a.yacc + (size_t)(idx >> 7) * a.d_model + nb + (idx & 127), v);
+                }
+            } else {
+                for (int idx = tid; idx < a.m_count * 32; idx += NTHREADS) {
+                    f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int w = 0; w < NW; ++w) v += *(const f32x4*)(stage + w * TOK * 128 + 4 * idx);
+                    const int m = idx >> 5, c4 = idx & 31;
+                    store4_device(a.P + ((size_t)blockIdx.x * a.m_count + m) * a.d_model + nb + 4 * c4, v[0], v[1], v[2], v[3]);
+                }
+            }
+            __syncthreads();                              // stages are rewritten by the next column block
         }
     }
     __shared__ int flag;
@@ -753,8 +765,8 @@ Sizes sizes(const dfk_config_t& c, int mode, int TT, int d_ff, int d_model) {
     size_t off = (size_t)c.waves * c.depth * kTileBytes;
     s.geo.depth = c.depth;
     s.geo.gu_off = (int)off;
-    if (mode == MODE_DOWN_ROWS) {   // only the [TOK][CB*128] fp32 meeting place of the wavefronts
-        off += (size_t)TOK * (d_model / c.k2_col_blocks) * 4;
+    if (mode == MODE_DOWN_ROWS) {   // the [waves][TOK][128] fp32 stages overlay the drained rings
+        off = std::max(off, (size_t)c.waves * TOK * 128 * 4);
         s.geo.a2s_off = s.geo.sync_off = (int)off;
         s.geo.a2_stride = 0;
         s.geo.sync_cap = 0;
