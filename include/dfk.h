@@ -208,6 +208,16 @@ dfk_status_t dfk_time_config(const dfk_config_t* cfg, int M, int d_model, int d_
                              dfk_dtype_t dtype, void* scratch, size_t scratch_bytes,
                              int sets, int iters, void* stream, double* usec_out);
 
+/* Time the launches of one configuration separately, same protocol: `iters` launches
+ * of the first kernel back to back between two HIP events on `stream`, then the same
+ * for the second.  usec_out[0] = the fused kernel, or the gate/up kernel of the
+ * two-kernel variant; usec_out[1] = its down-projection kernel (0 for the fused
+ * variant).  M must fit one launch of the configuration (16 or 32 tokens on the MFMA
+ * path, 8 on the VALU path), else DFK_ERR_UNSUPPORTED_SHAPE; iters <= 1024. */
+dfk_status_t dfk_time_kernels(const dfk_config_t* cfg, int M, int d_model, int d_ff,
+                              dfk_dtype_t dtype, void* scratch, size_t scratch_bytes,
+                              int sets, int iters, void* stream, double* usec_out);
+
 /* The configuration a call would use now (tuned entry, else heuristic).
  * *tuned_out (may be NULL) is set to 1 if it came from the table. */
 dfk_status_t dfk_get_choice(int M, int d_model, int d_ff, dfk_dtype_t dtype,

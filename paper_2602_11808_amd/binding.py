@@ -71,6 +71,7 @@ SIGNATURES = [
     ("dfk_tune_scratch_bytes", _sz, [_ci] * 5),
     ("dfk_tune", _ci, [ctypes.POINTER(_ci), _ci, _ci, _ci, _ci, _vp, _sz, _ci, _ci, _vp]),
     ("dfk_time_config", _ci, [_cfgp] + [_ci] * 4 + [_vp, _sz, _ci, _ci, _vp, ctypes.POINTER(ctypes.c_double)]),
+    ("dfk_time_kernels", _ci, [_cfgp] + [_ci] * 4 + [_vp, _sz, _ci, _ci, _vp, ctypes.POINTER(ctypes.c_double)]),
     ("dfk_get_choice", _ci, [_ci] * 4 + [_cfgp, ctypes.POINTER(_ci)]),
     ("dfk_set_choice", _ci, [_ci] * 4 + [_cfgp, ctypes.c_double]),
     ("dfk_clear_tuning", None, []),
@@ -243,6 +244,15 @@ def dfk_time_config(cfg, M, d_model, d_ff, dtype, scratch, sets=4, iters=20, str
                                  scratch.numel() * scratch.element_size(), sets, iters,
                                  _stream(stream), ctypes.byref(us)), "dfk_time_config")
     return us.value
+
+
+def dfk_time_kernels(cfg, M, d_model, d_ff, dtype, scratch, sets=4, iters=20, stream=None):
+    """Mean microseconds of the first and of the second launch of a call, (us1, us2)."""
+    us = (ctypes.c_double * 2)(0.0, 0.0)
+    _check(lib().dfk_time_kernels(ctypes.byref(cfg), M, d_model, d_ff, dtype, _ptr(scratch),
+                                  scratch.numel() * scratch.element_size(), sets, iters,
+                                  _stream(stream), us), "dfk_time_kernels")
+    return us[0], us[1]
 
 
 def dfk_get_choice(M, d_model, d_ff, dtype=DFK_BF16):

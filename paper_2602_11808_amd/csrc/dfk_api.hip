@@ -11,6 +11,8 @@
 #include "dfk_internal.h"
 
 namespace dfk {
+thread_local int g_stage_mask = 3;
+
 namespace {
 
 thread_local int g_last_hip_error = 0;
@@ -308,6 +310,45 @@ dfk_status_t time_config(const dfk_config_t& c, int M, int d_model, int d_ff, df
     return rc;
 }
 
+// Same protocol as time_config, for each launch of the call on its own: `iters` gate/up
+// launches back to back between two events, then `iters` down launches (they read the A_2
+// the last gate/up launch left; every launch leaves the workspace clean).
+dfk_status_t time_kernels(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype,
+                          void* scratch, int sets, int iters, hipStream_t st, double* usec2) {
+    double whole = 0.0;
+    dfk_status_t rc = time_config(c, M, d_model, d_ff, dtype, scratch, sets, 1, st, true, &whole);   // fill + warm-up
+    if (rc != DFK_OK) return rc;
+    const Scratch s = scratch_layout(M, d_model, d_ff, dtype, sets);
+    char* base = (char*)scratch;
+    char* X = base + (size_t)sets * s.set_bytes;
+    char* Y = X + s.x_bytes;
+    char* ws = Y + s.x_bytes;
+    hipEvent_t t0, t1;
+    hipError_t e;
+    if ((e = hipEventCreate(&t0)) != hipSuccess) return hip_fail(e);
+    if ((e = hipEventCreate(&t1)) != hipSuccess) { (void)hipEventDestroy(t0); return hip_fail(e); }
+    usec2[0] = usec2[1] = 0.0;
+    const int stages = c.variant == DFK_VARIANT_FUSED ? 1 : 2;
+    for (int k = 0; k < stages && rc == DFK_OK; ++k) {
+        g_stage_mask = 1 << k;
+        for (int it = -2; it < iters && rc == DFK_OK; ++it) {
+            if (it == 0 && (e = hipEventRecord(t0, st)) != hipSuccess) { rc = hip_fail(e); break; }
+            char* w = base + (size_t)((it + 2) % sets) * s.set_bytes;
+            rc = run(X, w, w + s.w_bytes, w + 2 * s.w_bytes, Y, M, d_model, d_ff, dtype, c, ws, st);
+        }
+        g_stage_mask = 3;
+        if (rc != DFK_OK) break;
+        float ms = 0.f;
+        if ((e = hipEventRecord(t1, st)) != hipSuccess || (e = hipEventSynchronize(t1)) != hipSuccess ||
+            (e = hipEventElapsedTime(&ms, t0, t1)) != hipSuccess) { rc = hip_fail(e); break; }
+        usec2[k] = (double)ms * 1000.0 / iters;
+    }
+    g_stage_mask = 3;
+    (void)hipEventDestroy(t0);
+    (void)hipEventDestroy(t1);
+    return rc;
+}
+
 }  // namespace
 }  // namespace dfk
 
@@ -413,6 +454,20 @@ dfk_status_t dfk_time_config(const dfk_config_t* cfg, int M, int d_model, int d_
     if (scratch_bytes < scratch_layout(M, d_model, d_ff, dtype, sets).total) return DFK_ERR_WORKSPACE;
     return time_config(*cfg, M, d_model, d_ff, dtype, scratch, sets, iters, (hipStream_t)stream, true,
                        usec_out);
+}
+
+dfk_status_t dfk_time_kernels(const dfk_config_t* cfg, int M, int d_model, int d_ff, dfk_dtype_t dtype,
+                              void* scratch, size_t scratch_bytes, int sets, int iters, void* stream,
+                              double* usec_out) {
+    if (!cfg || !scratch || !usec_out || sets < 1 || iters < 1 || iters > 1024) return DFK_ERR_INVALID_ARG;
+    if (M < 1 || d_model < 1 || d_ff < 1) return DFK_ERR_INVALID_ARG;
+    if (M > DFK_MAX_M || d_model % 8 || d_ff % 8) return DFK_ERR_UNSUPPORTED_SHAPE;
+    if (!config_valid(*cfg, M, d_model, d_ff, dtype)) return DFK_ERR_UNSUPPORTED_SHAPE;
+    const int per = cfg->path == DFK_PATH_MFMA ? mfma_max_tokens_per_launch(*cfg, d_model) : valu_max_tokens_per_launch();
+    if (M > per) return DFK_ERR_UNSUPPORTED_SHAPE;   // one set of launches per call only
+    if ((uintptr_t)scratch % 256) return DFK_ERR_ALIGNMENT;
+    if (scratch_bytes < scratch_layout(M, d_model, d_ff, dtype, sets).total) return DFK_ERR_WORKSPACE;
+    return time_kernels(*cfg, M, d_model, d_ff, dtype, scratch, sets, iters, (hipStream_t)stream, usec_out);
 }
 
 dfk_status_t dfk_tune(const int* M_list, int nM, int d_model, int d_ff, dfk_dtype_t dtype,

@@ -93,6 +93,12 @@ inline int max_slice_rows(int d_ff, int S) {
     return (int)((ng + S - 1) / S) * 8;
 }
 
+// ---------------------------------------------------------------- per-launch timing
+// Which launches of a call the launchers issue on the calling thread: bit 0 the first
+// (fused kernel, or gate/up kernel), bit 1 the second (down kernel).  3 except inside
+// dfk_time_kernels, which times each launch on its own, back to back.
+extern thread_local int g_stage_mask;
+
 // ---------------------------------------------------------------- launchers (defined per path)
 // Each returns hipSuccess or the launch error.  No allocation, no sync.
 hipError_t launch_valu(const MlpArgs& a, const dfk_config_t& c, dfk_dtype_t dtype, hipStream_t st);

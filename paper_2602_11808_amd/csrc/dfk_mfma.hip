@@ -804,9 +804,13 @@ hipError_t launch_one(const MlpArgs& a, const dfk_config_t& c, int grid, hipStre
 
 template <int NW, int TT>
 hipError_t launch_nt(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
-    if (c.variant == DFK_VARIANT_FUSED) return launch_one<NW, TT, MODE_FUSED>(a, c, a.splits, st);
-    hipError_t e = launch_one<NW, TT, MODE_GATEUP>(a, c, a.splits, st);
-    if (e != hipSuccess) return e;
+    if (c.variant == DFK_VARIANT_FUSED)
+        return (g_stage_mask & 1) ? launch_one<NW, TT, MODE_FUSED>(a, c, a.splits, st) : hipSuccess;
+    if (g_stage_mask & 1) {
+        hipError_t e = launch_one<NW, TT, MODE_GATEUP>(a, c, a.splits, st);
+        if (e != hipSuccess) return e;
+    }
+    if (!(g_stage_mask & 2)) return hipSuccess;
     if (c.k2_rows_by_wave) return launch_one<NW, TT, MODE_DOWN_ROWS>(a, c, a.k2_splits * a.k2_col_blocks, st);
     return launch_one<NW, TT, MODE_DOWN>(a, c, a.k2_splits * a.k2_col_blocks, st);
 }

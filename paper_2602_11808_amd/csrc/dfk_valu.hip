@@ -164,16 +164,20 @@ template <typename E, int MT>
 hipError_t launch_t(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
     const int threads = c.waves * 64;
     if (c.variant == DFK_VARIANT_FUSED) {
+        if (!(g_stage_mask & 1)) return hipSuccess;
         const int stride = max_slice_rows(a.d_ff, a.splits);
         hipLaunchKernelGGL((k_fused_valu<E, MT>), dim3(a.splits), dim3(threads),
                            (size_t)MT * stride * sizeof(float), st, a, stride);
         return hipGetLastError();
     }
-    const int s1 = max_slice_rows(a.d_ff, a.splits);
-    hipLaunchKernelGGL((k_gateup_valu<E, MT>), dim3(a.splits), dim3(threads),
-                       (size_t)MT * s1 * sizeof(float), st, a, s1);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    if (g_stage_mask & 1) {
+        const int s1 = max_slice_rows(a.d_ff, a.splits);
+        hipLaunchKernelGGL((k_gateup_valu<E, MT>), dim3(a.splits), dim3(threads),
+                           (size_t)MT * s1 * sizeof(float), st, a, s1);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (!(g_stage_mask & 2)) return hipSuccess;
     const int s2 = max_slice_rows(a.d_ff, a.k2_splits);
     hipLaunchKernelGGL((k_down_valu<E, MT>), dim3(a.k2_splits * a.k2_col_blocks), dim3(threads),
                        (size_t)MT * s2 * sizeof(float), st, a, s2);

@@ -143,6 +143,23 @@ def test_scheduler_table_roundtrip(tmp_path):
     dfk.dfk_clear_tuning()
 
 
+def test_timing_calls_check_their_arguments_on_the_host():
+    import ctypes
+    c = dfk.dfk_get_candidate(4, D, FF, dfk.DFK_BF16, 0)
+    us = (ctypes.c_double * 2)()
+    L = dfk.lib()
+    fake = 256 * 4096    # never dereferenced: every case below fails before any HIP call
+    assert L.dfk_time_kernels(None, 4, D, FF, 0, fake, 1 << 40, 2, 4, None, us) == dfk.DFK_ERR_INVALID_ARG
+    assert L.dfk_time_kernels(ctypes.byref(c), 4, D, FF, 0, None, 1 << 40, 2, 4, None, us) == dfk.DFK_ERR_INVALID_ARG
+    assert L.dfk_time_kernels(ctypes.byref(c), 4, D, FF, 0, fake, 1 << 40, 2, 0, None, us) == dfk.DFK_ERR_INVALID_ARG
+    assert L.dfk_time_kernels(ctypes.byref(c), 4, D, FF, 0, fake, 1 << 40, 2, 4, None, None) == dfk.DFK_ERR_INVALID_ARG
+    assert L.dfk_time_kernels(ctypes.byref(c), 4, D, FF, 0, fake + 8, 1 << 40, 2, 4, None, us) == dfk.DFK_ERR_ALIGNMENT
+    assert L.dfk_time_kernels(ctypes.byref(c), 4, D, FF, 0, fake, 1024, 2, 4, None, us) == dfk.DFK_ERR_WORKSPACE
+    # a token count that needs more than one set of launches cannot be split per kernel
+    big = dfk.dfk_get_candidate(64, D, FF, dfk.DFK_BF16, 0)
+    assert L.dfk_time_kernels(ctypes.byref(big), 64, D, FF, 0, fake, 1 << 40, 2, 4, None, us) == dfk.DFK_ERR_UNSUPPORTED_SHAPE
+
+
 def test_status_strings():
     for s in range(0, -9, -1):
         assert dfk.dfk_status_string(s) not in ("", "unknown status")

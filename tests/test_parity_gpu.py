@@ -299,6 +299,21 @@ def test_trace_buffer_records_a_monotone_timeline():
     assert torch.equal(before, tr)
 
 
+def test_per_launch_timing_splits_the_two_kernel_variant():
+    M, d, ff = 4, 1024, 2816
+    scratch = torch.empty(dfk.dfk_tune_scratch_bytes(M, d, ff, dfk.DFK_BF16, 2), dtype=torch.uint8, device=DEV)
+    for variant in (dfk.DFK_VARIANT_FUSED, dfk.DFK_VARIANT_TWO_KERNEL):
+        c = _cfgs(M, d, ff, lambda c: c.path == dfk.DFK_PATH_MFMA and c.variant == variant)[0]
+        whole = dfk.dfk_time_config(c, M, d, ff, dfk.DFK_BF16, scratch, sets=2, iters=10)
+        us1, us2 = dfk.dfk_time_kernels(c, M, d, ff, dfk.DFK_BF16, scratch, sets=2, iters=10)
+        assert us1 > 0 and whole > 0
+        if variant == dfk.DFK_VARIANT_FUSED:
+            assert us2 == 0
+        else:
+            assert us2 > 0
+        assert us1 + us2 < 3 * whole + 50      # same order as the whole-call time
+
+
 def test_calls_can_be_captured_in_a_graph_and_replayed():
     # the deployment mode of the method: the chosen kernels are captured once and replayed;
     # arrival counters reset themselves, so every replay must equal the eager result
