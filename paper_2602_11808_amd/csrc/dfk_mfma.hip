@@ -53,11 +53,13 @@ constexpr int MODE_FUSED = 0, MODE_GATEUP = 1, MODE_DOWN = 2, MODE_DOWN_ROWS = 3
 constexpr int kTileBytes = 4096;   // one ring slot = 4 global->LDS instructions of 1 KB
 constexpr int kKC = 128;           // k extent of a stage-one tile
 constexpr int kLdsLimit = 160 * 1024 - 256;   // dynamic part; a few static words (flags) come on top
+constexpr int kMaxPartialSlots = 4;  // row tiles whose k-partial sums LDS holds at a time, at most
 constexpr int kAuxNonTemporal = 2;  // cache-policy bit "nt": the weight stream is read once
 
 struct Geom {
     int depth;      // ring slots per wavefront
-    int gu_off;     // LDS byte offset of the fp32 gate/up sums [nt*16][16*TT]
+    int gu_off;     // LDS byte offset of the fp32 k-partial gate/up sums [slots][wavefronts][16*TT tokens][16 rows]
+    int slots;      // row tiles whose partial sums LDS holds at a time
     int a2s_off;    // LDS byte offset of A_2 as bf16 [16*TT][a2_stride]
     int a2_stride;  // elements
     int sync_off;   // LDS byte offset of the row-tile arrival counters and ready flags
@@ -68,6 +70,7 @@ struct Geom {
 // s_waitcnt with only vmcnt constrained (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4]<<14)
 #define DFK_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | ((((n) >> 4) & 3) << 14))
 #define DFK_WAIT_LGKM0() __builtin_amdgcn_s_waitcnt(0xC07F)
+#define DFK_WAIT_LGKM(n) __builtin_amdgcn_s_waitcnt(0xC07F | (((n) & 15) << 8))
 #define DFK_STAMP(k) do { if (a.trace && tid == 0) a.trace[(size_t)blockIdx.x * 8 + (k)] = wall_clock64(); } while (0)
 
 // Wait until at most `newer_ops` of this wavefront's vector-memory operations
@@ -111,6 +114,26 @@ __device__ __forceinline__ void lds_write_b16_raw(unsigned addr, unsigned v) {
 
 __device__ __forceinline__ void lds_write_b32_raw(unsigned addr, unsigned v) {
     asm volatile("ds_write_b32 %0, %1" : : "v"(addr), "v"(v) : "memory");
+}
+__device__ __forceinline__ void lds_write_b64_raw(unsigned addr, unsigned lo, unsigned hi) {
+    typedef __attribute__((__vector_size__(2 * sizeof(unsigned)))) unsigned u32x2;
+    const u32x2 v = u32x2{lo, hi};
+    asm volatile("ds_write_b64 %0, %1" : : "v"(addr), "v"(v) : "memory");
+}
+__device__ __forceinline__ void lds_write_b128_raw(unsigned addr, __attribute__((__vector_size__(4 * sizeof(float)))) float v) {
+    asm volatile("ds_write_b128 %0, %1" : : "v"(addr), "v"(v) : "memory");
+}
+// LDS reads of flags other wavefronts raise (waited for).  Through a plain volatile
+// pointer these become flat loads, whose wait also covers every tile load in flight.
+__device__ __forceinline__ unsigned lds_read_b32_raw(unsigned addr) {
+    unsigned v;
+    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(addr) : "memory");
+    return v;
+}
+__device__ __forceinline__ u32x4 lds_read_b128_raw(unsigned addr) {
+    u32x4 v;
+    asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(addr) : "memory");
+    return v;
 }
 // LDS counter increment that returns the previous value (waits for it).
 __device__ __forceinline__ unsigned lds_inc_rtn_raw(unsigned addr) {
@@ -242,9 +265,13 @@ struct TileStream {
     // Returns the LDS address of the next tile, landed and readable by this wavefront.
     // Only loads count: with at most 4*(depth-1) operations outstanding, at most that
     // many loads are, and loads complete in issue order, so the wanted tile is in.
+    // LDS_TAIL: LDS instructions this wavefront issued after its last read of a ring slot
+    // (the adds into the gate/up sums); LDS completes a wavefront's instructions in order,
+    // so the refill only has to wait until no more than those are outstanding.
+    template <int LDS_TAIL = 0>
     __device__ __forceinline__ const unsigned char* acquire() {
         // Reads of the slot about to be refilled must have returned before its refill is issued.
-        DFK_WAIT_LGKM0();
+        DFK_WAIT_LGKM(LDS_TAIL);
         asm volatile("" ::: "memory");
         if (issued < T) {
             issue();
@@ -269,10 +296,10 @@ __global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int q = lane & 15, g = lane >> 4;
-    float* gu = (float*)(lds + geo.gu_off);
+    const float* part = (const float*)(lds + geo.gu_off);   // k-partial sums [slot][wavefront][token][16 rows]
     uint16_t* a2s = (uint16_t*)(lds + geo.a2s_off);
     unsigned* sync = (unsigned*)(lds + geo.sync_off);   // [0, cap): arrivals per row tile, [cap, 2cap): ready flags
-    const unsigned gu_addr = lds_addr(gu), a2s_addr = lds_addr(a2s), sync_addr = lds_addr(sync);
+    const unsigned part_addr = lds_addr(part), a2s_addr = lds_addr(a2s), sync_addr = lds_addr(sync);
     const uint16_t* X = (const uint16_t*)a.X;
 
     // ---- geometry
@@ -314,12 +341,10 @@ __global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
 
     // Everything in LDS that must start from a known value (raw stores: see lds_add_f32_raw).
     if (MODE != MODE_DOWN) {
-        for (int i = tid; i < nt * 16 * TOK; i += NTHREADS) lds_write_b32_raw(gu_addr + 4u * (unsigned)i, 0u);
-        if (MODE == MODE_FUSED) {
-            for (int i = tid; i < 2 * geo.sync_cap; i += NTHREADS)
-                lds_write_b32_raw(sync_addr + 4u * (unsigned)i, (i >= geo.sync_cap + nt) ? 1u : 0u);
+        for (int i = tid; i < 2 * geo.sync_cap; i += NTHREADS)
+            lds_write_b32_raw(sync_addr + 4u * (unsigned)i, (i >= geo.sync_cap + nt) ? 1u : 0u);
+        if (MODE == MODE_FUSED)
             for (int i = tid; i < TOK * geo.a2_stride / 2; i += NTHREADS) lds_write_b32_raw(a2s_addr + 4u * (unsigned)i, 0u);
-        }
         lds_barrier();
     }
 
@@ -341,6 +366,7 @@ __global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
                         x[tt][kc][s] = ld16(X, ((size_t)(a.m_base + token) * a.d_model + wave * KW + kc * kKC) / 8 + 4 * s + g);
                 }
         }
+        int pslot = 0;   // rt % slots
         for (int rt = 0; rt < nt; ++rt) {
             if (rt == 1) DFK_STAMP(1);
             f32x4 acc[TT];
@@ -360,50 +386,60 @@ __global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
                 }
             }
 
-            // k-partial sums of all wavefronts meet in LDS.  The raw LDS atomics are
-            // invisible to the compiler's hazard handling, so the wait states an MFMA
-            // result needs before an LDS instruction may read it are inserted by hand.
+            // The k-partial sums of the NW wavefronts meet in LDS without atomics (LDS float
+            // atomics take about a cycle per lane and hold up the tile loads that land in
+            // LDS meanwhile): each wavefront stores its [token][16 rows] block in a place
+            // of its own in slot rt % slots, then counts its arrival at row tile rt; LDS
+            // executes a wavefront's instructions in order, so the block is in before the
+            // count.  The raw LDS stores are invisible to the compiler's hazard handling,
+            // so the wait states an MFMA result needs before an LDS instruction may read
+            // it are inserted by hand.
+            if (rt >= geo.slots) {   // the slot's previous row tile must have been summed
+                const unsigned freed = sync_addr + 4u * (unsigned)(geo.sync_cap + rt - geo.slots);
+                while (__builtin_amdgcn_readfirstlane(lds_read_b32_raw(freed)) == 0u) __builtin_amdgcn_s_sleep(1);
+            }
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" : "+v"(acc[tt]));
+            const unsigned slot_floats = (unsigned)(pslot * NW * TOK * 16);
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt)
+                lds_write_b128_raw(part_addr + 4u * (slot_floats + (unsigned)(((wave * TOK + tt * 16 + q) * 16) + 4 * g)), acc[tt]);
+            unsigned old = 0;
+            if (lane == 0) old = lds_inc_rtn_raw(sync_addr + 4u * (unsigned)rt);
+            old = __builtin_amdgcn_readfirstlane(old);
+            if (old == NW - 1) {
+                // Last arrival: add the NW blocks in wavefront order, apply SiLU(G)*U and hand
+                // A_2 on (LDS in the fused kernel, the workspace in the two-kernel variant),
+                // then raise the row tile's flag: A_2 ready / slot free.
+                // Task e: token e/2, rows 4*(e%2) .. +3 of the row tile (gate) and 8 further on (up).
+                for (int e = lane; e < 2 * TOK; e += 64) {
+                    const int m = e >> 1, h = e & 1;
+                    const float* src = part + slot_floats + m * 16 + 4 * h;
+                    f32x4 gs = f32x4{0.f, 0.f, 0.f, 0.f}, us = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    lds_add_f32_raw(gu_addr + 4u * (unsigned)((rt * 16 + 4 * g + i) * TOK + tt * 16 + q), acc[tt][i]);
-            if (MODE == MODE_FUSED) {
-                // Count this wavefront's arrival at row tile rt (LDS executes a wavefront's
-                // instructions in order, so its sums are in before its count).  The last of
-                // the NW arrivals turns the row tile's sums into A_2 and raises its flag.
-                unsigned old = 0;
-                if (lane == 0) old = lds_inc_rtn_raw(sync_addr + 4u * (unsigned)rt);
-                old = __builtin_amdgcn_readfirstlane(old);
-                if (old == NW - 1) {
-                    for (int e = lane; e < 8 * TOK; e += 64) {
-                        const int jr = e / TOK, m = e - jr * TOK;
-                        const float v = silu_mul(gu[(rt * 16 + jr) * TOK + m], gu[(rt * 16 + 8 + jr) * TOK + m]);
-                        lds_write_b16_raw(a2s_addr + 2u * (unsigned)(m * geo.a2_stride + rt * 8 + jr), f32_to_bf16_bits(v));
+                    for (int w = 0; w < NW; ++w) {
+                        gs += *(const f32x4*)(src + w * TOK * 16);
+                        us += *(const f32x4*)(src + w * TOK * 16 + 8);
                     }
-                    DFK_WAIT_LGKM0();
-                    if (lane == 0) lds_write_b32_raw(sync_addr + 4u * (unsigned)(geo.sync_cap + rt), 1u);
+                    float v[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) v[i] = silu_mul(gs[i], us[i]);
+                    if (MODE == MODE_FUSED) {
+                        lds_write_b64_raw(a2s_addr + 2u * (unsigned)(m * geo.a2_stride + rt * 8 + 4 * h),
+                                          pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+                    } else if (m < a.m_count) {
+                        const size_t o = (size_t)(a.m_base + m) * a.d_ff + j0 + rt * 8 + 4 * h;
+                        if (a.a2_is_fp32) *(f32x4*)((float*)a.a2 + o) = f32x4{v[0], v[1], v[2], v[3]};
+                        else *(uint2*)((uint16_t*)a.a2 + o) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+                    }
                 }
+                DFK_WAIT_LGKM0();
+                if (lane == 0) lds_write_b32_raw(sync_addr + 4u * (unsigned)(geo.sync_cap + rt), 1u);
             }
+            if (++pslot == geo.slots) pslot = 0;
         }
         DFK_STAMP(2);
-        if (MODE == MODE_GATEUP) {
-            lds_barrier();
-            // SiLU(G) * U  ->  A_2 in the workspace
-            for (int idx = tid; idx < rows * TOK; idx += NTHREADS) {
-                const int j = idx / TOK, m = idx - j * TOK;
-                if (m < a.m_count) {
-                    const int tile = j >> 3, jr = j & 7;
-                    const float v = silu_mul(gu[(tile * 16 + jr) * TOK + m], gu[(tile * 16 + 8 + jr) * TOK + m]);
-                    const size_t o = (size_t)(a.m_base + m) * a.d_ff + j0 + j;
-                    if (a.a2_is_fp32) ((float*)a.a2)[o] = v;
-                    else ((uint16_t*)a.a2)[o] = (uint16_t)f32_to_bf16_bits(v);
-                }
-            }
-            return;
-        }
+        if (MODE == MODE_GATEUP) return;   // every row tile's A_2 went out with its last arrival
     }
 
     // ---- stage two
@@ -433,9 +469,12 @@ __global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
     // Waits (fused kernel only) until the row tiles feeding the 32-row block jb have their A_2.
     auto wait_rows_ready = [&](int jb) {
         if (MODE != MODE_FUSED) return;
-        const volatile unsigned* ready = sync + geo.sync_cap + 4 * jb;
-        while ((ready[0] & ready[1] & ready[2] & ready[3]) == 0u) __builtin_amdgcn_s_sleep(1);
-        asm volatile("" ::: "memory");
+        const unsigned ready = sync_addr + 4u * (unsigned)(geo.sync_cap + 4 * jb);   // 16-byte aligned
+        for (;;) {
+            const u32x4 f = lds_read_b128_raw(ready);
+            if (__builtin_amdgcn_readfirstlane(f[0] & f[1] & f[2] & f[3]) != 0u) break;
+            __builtin_amdgcn_s_sleep(1);
+        }
     };
 
     for (int bg = 0; bg < my_blocks; bg += BG) {
@@ -619,7 +658,7 @@ __global__ __launch_bounds__(NW * 64) void k_down_rows(MlpArgs a, Geom geo) {
     ts.T1 = 0;
     ts.T = ts.my_blocks * njb * 2;
     ts.init(0);
-    DFK_STAMP(0);
+    DFK_STAMP(3);   // the down kernel starts where A_2 is ready
     ts.start();
 
     // A operand: A_2[token][8 consecutive j] for every 32-row block of this wavefront
@@ -773,14 +812,27 @@ Sizes sizes(const dfk_config_t& c, int mode, int TT, int d_ff, int d_model) {
         s.lds = off;
         return s;
     }
-    if (mode != MODE_DOWN) off += (size_t)(maxrows / 8) * 16 * TOK * 4;
+    // stage one: what is left of LDS after rings, A_2 and flags holds the k-partial sums of as
+    // many row tiles as fit (at most kMaxPartialSlots; at least two, or the configuration is invalid)
+    const size_t slot_bytes = (size_t)c.waves * TOK * 16 * 4;
+    const size_t a2s_bytes = (size_t)TOK * (rows_pad + 8) * 2;
+    s.geo.sync_cap = ((maxrows / 8 + 4) + 3) & ~3;
+    const size_t sync_bytes = (size_t)2 * s.geo.sync_cap * 4;
+    s.geo.slots = 0;
+    if (mode != MODE_DOWN) {
+        const size_t fixed = off + (mode == MODE_FUSED ? a2s_bytes : 0) + sync_bytes + 16;
+        const int nt_max = maxrows / 8;
+        const size_t fit = (size_t)kLdsLimit > fixed ? ((size_t)kLdsLimit - fixed) / slot_bytes : 0;
+        s.geo.slots = (int)std::min<size_t>((size_t)std::min(nt_max, kMaxPartialSlots), fit);
+        if (s.geo.slots < std::min(nt_max, 2)) { s.lds = (size_t)-1; return s; }   // does not fit
+        off += (size_t)s.geo.slots * slot_bytes;
+    }
     s.geo.a2s_off = (int)off;
     s.geo.a2_stride = rows_pad + 8;
-    if (mode != MODE_GATEUP) off += (size_t)TOK * s.geo.a2_stride * 2;
+    if (mode != MODE_GATEUP) off += a2s_bytes;
     off = (off + 15) & ~(size_t)15;
     s.geo.sync_off = (int)off;
-    s.geo.sync_cap = ((maxrows / 8 + 4) + 3) & ~3;
-    if (mode == MODE_FUSED) off += (size_t)2 * s.geo.sync_cap * 4;
+    if (mode != MODE_DOWN) off += sync_bytes;
     s.lds = off;
     return s;
 }
