@@ -411,26 +411,31 @@ __global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
                 // Last arrival: add the NW blocks in wavefront order, apply SiLU(G)*U and hand
                 // A_2 on (LDS in the fused kernel, the workspace in the two-kernel variant),
                 // then raise the row tile's flag: A_2 ready / slot free.
-                // Task e: token e/2, rows 4*(e%2) .. +3 of the row tile (gate) and 8 further on (up).
-                for (int e = lane; e < 2 * TOK; e += 64) {
-                    const int m = e >> 1, h = e & 1;
-                    const float* src = part + slot_floats + m * 16 + 4 * h;
+                // Task (token m, row quad h): rows 4h .. 4h+3 of the row tile (gate) and 8 further
+                // on (up).  Two lanes share a task: lane p adds the blocks of wavefronts
+                // [p*NW/2, (p+1)*NW/2), the halves are exchanged, and lane p finishes rows 2p, 2p+1.
+                for (int t = lane; t < 4 * TOK; t += 64) {   // 4*TOK is a multiple of 64: no lane idles
+                    const int p = t & 1, m = t >> 2, h = (t >> 1) & 1;
+                    const float* src = part + slot_floats + (p * (NW / 2) * TOK + m) * 16 + 4 * h;
                     f32x4 gs = f32x4{0.f, 0.f, 0.f, 0.f}, us = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int w = 0; w < NW; ++w) {
+                    for (int w = 0; w < NW / 2; ++w) {
                         gs += *(const f32x4*)(src + w * TOK * 16);
                         us += *(const f32x4*)(src + w * TOK * 16 + 8);
                     }
-                    float v[4];
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) v[i] = silu_mul(gs[i], us[i]);
+                    // lane p keeps rows 2p, 2p+1: it sends the other pair and receives its own
+                    const float g0 = (p ? gs[2] : gs[0]) + __shfl_xor(p ? gs[0] : gs[2], 1);
+                    const float g1 = (p ? gs[3] : gs[1]) + __shfl_xor(p ? gs[1] : gs[3], 1);
+                    const float u0 = (p ? us[2] : us[0]) + __shfl_xor(p ? us[0] : us[2], 1);
+                    const float u1 = (p ? us[3] : us[1]) + __shfl_xor(p ? us[1] : us[3], 1);
+                    const int jr = rt * 8 + 4 * h + 2 * p;   // first of this lane's two rows, inside the slice
                     if (MODE == MODE_FUSED) {
-                        lds_write_b64_raw(a2s_addr + 2u * (unsigned)(m * geo.a2_stride + rt * 8 + 4 * h),
-                                          pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+                        lds_write_b32_raw(a2s_addr + 2u * (unsigned)(m * geo.a2_stride + jr),
+                                          pack_bf16x2(silu_mul_fast(g0, u0), silu_mul_fast(g1, u1)));
                     } else if (m < a.m_count) {
-                        const size_t o = (size_t)(a.m_base + m) * a.d_ff + j0 + rt * 8 + 4 * h;
-                        if (a.a2_is_fp32) *(f32x4*)((float*)a.a2 + o) = f32x4{v[0], v[1], v[2], v[3]};
-                        else *(uint2*)((uint16_t*)a.a2 + o) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+                        const size_t o = (size_t)(a.m_base + m) * a.d_ff + j0 + jr;
+                        if (a.a2_is_fp32) *(float2*)((float*)a.a2 + o) = make_float2(silu_mul(g0, u0), silu_mul(g1, u1));
+                        else *(uint32_t*)((uint16_t*)a.a2 + o) = pack_bf16x2(silu_mul_fast(g0, u0), silu_mul_fast(g1, u1));
                     }
                 }
                 DFK_WAIT_LGKM0();
