@@ -25,7 +25,7 @@
  * memory or synchronises the host; work is enqueued on `stream` (a
  * hipStream_t passed as void*, NULL = the default stream) and the call
  * returns at once.  The workspace holds arrival counters and the fp32
- * accumulator of the atomic reduction (its first 4 MiB + 4 KiB), the fp32
+ * accumulator of the atomic reduction (its first 8 MiB + 4 KiB), the fp32
  * partial sums of Y and (two-kernel variant) A_2.  Counters and accumulator
  * must be zero before the first call (dfk_workspace_init) and every call leaves
  * them zero again, so a workspace may be reused by successive calls, of any
@@ -99,6 +99,11 @@ typedef enum { DFK_REDUCE_TICKET = 0, DFK_REDUCE_ATOMIC = 1 } dfk_reduce_t;
  *                  1 = the wavefronts share the workgroup's (at most 4) column blocks
  *                  and divide its d_ff rows (meant for few d_ff splits: a short
  *                  cross-workgroup sum whatever the token count)
+ *   kmajor         two-kernel variant, MFMA path: 1 = the pair of kernels that take up to 64
+ *                  tokens per launch (the activations travel through the same LDS rings
+ *                  as the weight tiles instead of sitting in registers; gate/up kernel
+ *                  k-major with all its row tiles accumulating in registers); needs
+ *                  waves = 8 and k2_rows_by_wave = 0; 0 = the kernels above
  */
 typedef struct dfk_config_t {
     int variant;
@@ -111,6 +116,7 @@ typedef struct dfk_config_t {
     int k2_col_blocks;
     int a2_dtype;
     int k2_rows_by_wave;
+    int kmajor;
 } dfk_config_t;
 
 /* ---------------------------------------------------------------- the block */
@@ -212,7 +218,7 @@ dfk_status_t dfk_time_config(const dfk_config_t* cfg, int M, int d_model, int d_
  * of the first kernel back to back between two HIP events on `stream`, then the same
  * for the second.  usec_out[0] = the fused kernel, or the gate/up kernel of the
  * two-kernel variant; usec_out[1] = its down-projection kernel (0 for the fused
- * variant).  M must fit one launch of the configuration (16 or 32 tokens on the MFMA
+ * variant).  M must fit one launch of the configuration (16, 32 or 64 tokens on the MFMA
  * path, 8 on the VALU path), else DFK_ERR_UNSUPPORTED_SHAPE; iters <= 1024. */
 dfk_status_t dfk_time_kernels(const dfk_config_t* cfg, int M, int d_model, int d_ff,
                               dfk_dtype_t dtype, void* scratch, size_t scratch_bytes,

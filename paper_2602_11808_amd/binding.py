@@ -34,7 +34,7 @@ DFK_MAX_M = 256
 class dfk_config_t(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int) for n in (
         "variant", "path", "splits", "waves", "depth", "reduce",
-        "k2_splits", "k2_col_blocks", "a2_dtype", "k2_rows_by_wave")]
+        "k2_splits", "k2_col_blocks", "a2_dtype", "k2_rows_by_wave", "kmajor")]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}

@@ -81,12 +81,13 @@ dfk_status_t check(const void* X, const void* Wg, const void* Wu, const void* Wd
 int clamp_splits(int want, int d_ff) { return std::max(1, std::min(want, d_ff / 8)); }
 
 dfk_config_t make_cfg(int variant, int path, int splits, int waves, int depth, int k2s, int k2c,
-                      int a2dt, int reduce = DFK_REDUCE_TICKET, int rows_by_wave = 0) {
+                      int a2dt, int reduce = DFK_REDUCE_TICKET, int rows_by_wave = 0, int kmajor = 0) {
     dfk_config_t c;
     std::memset(&c, 0, sizeof c);
     c.variant = variant; c.path = path; c.splits = splits; c.waves = waves; c.depth = depth;
     c.reduce = reduce; c.k2_splits = k2s; c.k2_col_blocks = k2c; c.a2_dtype = a2dt;
     c.k2_rows_by_wave = rows_by_wave;
+    c.kmajor = kmajor;
     return c;
 }
 
@@ -94,7 +95,7 @@ bool same_cfg(const dfk_config_t& a, const dfk_config_t& b) {
     return a.variant == b.variant && a.path == b.path && a.splits == b.splits && a.waves == b.waves &&
            a.depth == b.depth && a.reduce == b.reduce && a.k2_splits == b.k2_splits &&
            a.k2_col_blocks == b.k2_col_blocks && a.a2_dtype == b.a2_dtype &&
-           a.k2_rows_by_wave == b.k2_rows_by_wave;
+           a.k2_rows_by_wave == b.k2_rows_by_wave && a.kmajor == b.kmajor;
 }
 
 // The candidate set of the scheduler (Method: tiling variants x tile sizes).
@@ -141,6 +142,17 @@ std::vector<dfk_config_t> candidates(int M, int d_model, int d_ff, dfk_dtype_t d
                         for (int depth : {3, 4})
                             push(make_cfg(DFK_VARIANT_TWO_KERNEL, DFK_PATH_MFMA, clamp_splits(256, d_ff), waves, depth,
                                           clamp_splits(std::max(1, grid / k2c), d_ff), k2c, DFK_BF16, reduce, 1));
+            }
+        // two-kernel, activations through the tile rings: up to 64 tokens per launch
+        for (int splits : {256, 512})
+            for (int cbw : {1, 2}) {
+                if (nblk < cbw || nblk % cbw) continue;
+                const int k2c = nblk / cbw;
+                for (int grid : {256, 512})
+                    for (int reduce : {DFK_REDUCE_ATOMIC, DFK_REDUCE_TICKET})
+                        for (int depth : {3, 4})
+                            push(make_cfg(DFK_VARIANT_TWO_KERNEL, DFK_PATH_MFMA, clamp_splits(splits, d_ff), 8, depth,
+                                          clamp_splits(std::max(1, grid / k2c), d_ff), k2c, DFK_BF16, reduce, 0, 1));
             }
     }
     for (int splits : {256, 512, 1024})
@@ -536,13 +548,13 @@ dfk_status_t dfk_save_tuning(const char* path) {
     FILE* f = std::fopen(path, "w");
     if (!f) return DFK_ERR_IO;
     std::fprintf(f, "# dfk tuning table v2: M d_model d_ff dtype variant path splits waves depth reduce "
-                    "k2_splits k2_col_blocks a2_dtype k2_rows_by_wave usec\n");
+                    "k2_splits k2_col_blocks a2_dtype k2_rows_by_wave kmajor usec\n");
     for (const auto& kv : g_table) {
         const dfk_config_t& c = kv.second.cfg;
-        std::fprintf(f, "%d %d %d %d %d %d %d %d %d %d %d %d %d %d %.3f\n", std::get<0>(kv.first),
+        std::fprintf(f, "%d %d %d %d %d %d %d %d %d %d %d %d %d %d %d %.3f\n", std::get<0>(kv.first),
                      std::get<1>(kv.first), std::get<2>(kv.first), std::get<3>(kv.first), c.variant,
                      c.path, c.splits, c.waves, c.depth, c.reduce, c.k2_splits, c.k2_col_blocks,
-                     c.a2_dtype, c.k2_rows_by_wave, kv.second.usec);
+                     c.a2_dtype, c.k2_rows_by_wave, c.kmajor, kv.second.usec);
     }
     const bool ok = std::fclose(f) == 0;
     return ok ? DFK_OK : DFK_ERR_IO;
@@ -562,11 +574,11 @@ dfk_status_t dfk_load_tuning(const char* path) {
         int M, dm, df, dt;
         Entry e;
         std::memset(&e, 0, sizeof e);
-        const int n = std::sscanf(p, "%d %d %d %d %d %d %d %d %d %d %d %d %d %d %lf", &M, &dm, &df, &dt,
+        const int n = std::sscanf(p, "%d %d %d %d %d %d %d %d %d %d %d %d %d %d %d %lf", &M, &dm, &df, &dt,
                                   &e.cfg.variant, &e.cfg.path, &e.cfg.splits, &e.cfg.waves, &e.cfg.depth,
                                   &e.cfg.reduce, &e.cfg.k2_splits, &e.cfg.k2_col_blocks, &e.cfg.a2_dtype,
-                                  &e.cfg.k2_rows_by_wave, &e.usec);
-        if (n != 15 || M < 1 || M > DFK_MAX_M || (dt != DFK_BF16 && dt != DFK_FP32) || dm < 8 ||
+                                  &e.cfg.k2_rows_by_wave, &e.cfg.kmajor, &e.usec);
+        if (n != 16 || M < 1 || M > DFK_MAX_M || (dt != DFK_BF16 && dt != DFK_FP32) || dm < 8 ||
             df < 8 || dm % 8 || df % 8 || !config_valid(e.cfg, M, dm, df, (dfk_dtype_t)dt)) {
             rc = DFK_ERR_IO;
             break;

@@ -11,7 +11,7 @@ namespace dfk {
 
 // ---------------------------------------------------------------- workspace layout
 // [0, 4096)        arrival counters (unsigned), zero between calls
-// [4096, +4 MiB)   fp32 accumulator of Y for one launch (kMaxTokensPerLaunch x kMaxDModel),
+// [4096, +8 MiB)   fp32 accumulator of Y for one launch (kMaxTokensPerLaunch x kMaxDModel),
 //                  zero between calls (atomic reduction)
 // [.., +P)         fp32 partial sums of Y, one [tokens, d_model] block per workgroup slice
 //                  (counter reduction)
@@ -23,7 +23,7 @@ namespace dfk {
 constexpr size_t kWsHeaderBytes = 4096;
 constexpr int kMaxTickets = 1024;
 constexpr int kTicketLevel2 = 512;          // counters [0,512): level 1 / column blocks, [512,1024): level 2
-constexpr int kMaxTokensPerLaunch = 32;     // a launch handles at most this many tokens
+constexpr int kMaxTokensPerLaunch = 64;     // a launch handles at most this many tokens
 constexpr int kMaxDModel = 32768;
 constexpr size_t kYaccBytes = (size_t)kMaxTokensPerLaunch * kMaxDModel * 4;
 constexpr size_t kPartialCapBytes = (size_t)128 << 20;
@@ -108,6 +108,10 @@ hipError_t launch_mfma(const MlpArgs& a, const dfk_config_t& c, hipStream_t st);
 bool valu_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype);
 bool mfma_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype);
 int mfma_max_tokens_per_launch(const dfk_config_t& c, int d_model);
+// the pair of kernels for up to 64 tokens per launch (dfk_mfma_km.hip; config field kmajor)
+hipError_t launch_mfma_km(const MlpArgs& a, const dfk_config_t& c, hipStream_t st);
+bool mfma_km_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype);
+int mfma_km_tokens_per_launch();
 int valu_max_tokens_per_launch();
 
 // utility kernels

@@ -1,0 +1,500 @@
+// MFMA kernels of the two-kernel variant for up to 64 tokens per launch (gfx950).
+//
+// The kernels of dfk_mfma.hip keep the activations a wavefront needs (its k range
+// of X; A_2 for its rows) in registers for the whole launch, which caps a launch at
+// 32 tokens; more tokens mean further launches that stream the weights again.  Here
+// the activations ride the same per-wavefront LDS ring as the weight tiles, 4 KB
+// tiles fetched by the same asynchronous global->LDS loads in one in-order stream,
+// so their register cost is one tile at a time and a launch takes 4 token tiles of
+// 16 ("row-major" end of the Method section's tiling choice: X stays local while
+// more of it is reused per weight tile).
+//
+// Gate/up kernel (A_2 = (X W_up) (x) SiLU(X W_gate), same split as before: workgroup s
+// owns a d_ff slice of at most 8 row tiles of 8 rows, wavefront w the k range
+// [w*KW, (w+1)*KW)).  The stream is k-major: for every 128-k chunk first the X tiles
+// (16 tokens x 128 k each, same shape and swizzle as a weight tile; they become the
+// MFMA B operand registers of the chunk), then the weight tile of every row tile.
+// All row tiles accumulate in registers until the stream ends; the wavefronts' sums
+// then meet in LDS (over the drained rings, a few row tiles per pass) and all
+// threads of the workgroup finish SiLU(G)*U and store A_2 to the workspace.
+//
+// Down kernel (Y = A_2 W_down): workgroup (js, cb) owns CB adjacent 128-column blocks
+// over d_ff split js, its wavefronts divide the split's 32-row blocks.  Per 32-row
+// block the stream holds one A_2 tile ([token][8 rows] per lane, the MFMA A operand)
+// and then two W_down tiles per column block, regrouped per lane with v_perm_b32.
+// The end (per-wavefront LDS stages, ticket or atomic reduction) is that of
+// k_down_rows, one token tile at a time.
+//
+// Rows of X / A_2 past the launch's tokens are fetched from the last real token:
+// they only feed output rows that are never stored.
+#include "dfk_mfma_common.h"
+
+namespace dfk {
+namespace {
+
+constexpr int kKmMaxRowTiles = 8;   // row tiles per workgroup of the gate/up kernel (accumulators)
+constexpr int kKmTokensPerLaunch = 64;
+
+struct KmGeom {
+    int depth;   // ring slots per wavefront
+    int pass;    // gate/up kernel: row tiles whose partial sums LDS holds per pass at the end
+};
+
+// ---------------------------------------------------------------- gate/up kernel
+template <int NW, int TT>
+struct KmStream1 {
+    const char *Wg, *Wu, *X;
+    size_t row_bytes;          // d_model * 2
+    size_t w_base;             // byte offset of (row j0, this wavefront's first k)
+    size_t x_base;             // byte offset of (token m_base, this wavefront's first k)
+    int nt, nkc, m_count;
+    int q, g;
+    unsigned off1[4];
+    unsigned char* ring;
+    int depth, T, issued, issue_slot, take_slot;
+    int p_kc, p_idx;           // producer: chunk, position in the chunk (X tiles, then row tiles)
+
+    __device__ __forceinline__ void issue() {
+        unsigned char* slot = ring + issue_slot * kTileBytes;
+        if (p_idx < TT) {      // X tile: lane (q, g), instruction u -> token row 4u+g, chunk q ^ row
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = 4 * u + g;
+                const int token = min(p_idx * 16 + i, m_count - 1);
+                const char* src = X + x_base + (size_t)token * row_bytes + (size_t)p_kc * (kKC * 2) + ((q ^ i) * 16);
+                __builtin_amdgcn_global_load_lds(src, DFK_LDS_PTR(slot + u * 1024), 16, 0, 0);
+            }
+        } else {               // weight tile of row tile p_idx - TT: 8 rows of W_gate, the same 8 of W_up
+            const size_t tb = w_base + (size_t)(p_idx - TT) * 8 * row_bytes + (size_t)p_kc * (kKC * 2);
+            const char* gb = Wg + tb;
+            const char* ub = Wu + tb;
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                __builtin_amdgcn_global_load_lds((u < 2 ? gb : ub) + off1[u], DFK_LDS_PTR(slot + u * 1024), 16, 0,
+                                                 kAuxNonTemporal);
+        }
+        if (++p_idx == TT + nt) { p_idx = 0; ++p_kc; }
+        ++issued;
+        if (++issue_slot == depth) issue_slot = 0;
+    }
+    __device__ __forceinline__ void start() {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = 4 * u + g;
+            off1[u] = (unsigned)((i & 7) * row_bytes + (q ^ i) * 16);
+        }
+        T = nkc * (TT + nt);
+        issued = 0; issue_slot = 0; take_slot = 0; p_kc = 0; p_idx = 0;
+        const int ahead = min(depth - 1, T);
+        for (int i = 0; i < ahead; ++i) issue();
+    }
+    __device__ __forceinline__ const unsigned char* acquire() {
+        DFK_WAIT_LGKM0();   // reads of the slot about to be refilled have returned
+        asm volatile("" ::: "memory");
+        if (issued < T) {
+            issue();
+            wait_vm_ops(4 * (depth - 1));
+        } else {
+            wait_vm_ops(0);
+        }
+        const unsigned char* slot = ring + take_slot * kTileBytes;
+        if (++take_slot == depth) take_slot = 0;
+        return slot;
+    }
+};
+
+template <int NW, int TT>
+__global__ __launch_bounds__(NW * 64) void k_gateup_km(MlpArgs a, KmGeom geo) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    constexpr int TOK = 16 * TT;
+    constexpr int NTHREADS = NW * 64;
+    constexpr int NT = kKmMaxRowTiles;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int q = lane & 15, g = lane >> 4;
+    int j0, j1;
+    slice_rows(a.d_ff, a.splits, blockIdx.x, j0, j1);
+    const int nt = (j1 - j0) / 8;                 // <= NT, checked on the host
+    const int KW = a.d_model / NW;
+
+    KmStream1<NW, TT> ts;
+    ts.Wg = (const char*)a.Wg; ts.Wu = (const char*)a.Wu; ts.X = (const char*)a.X;
+    ts.row_bytes = (size_t)a.d_model * 2;
+    ts.w_base = (size_t)j0 * ts.row_bytes + (size_t)wave * KW * 2;
+    ts.x_base = (size_t)a.m_base * ts.row_bytes + (size_t)wave * KW * 2;
+    ts.nt = nt; ts.nkc = KW / kKC; ts.m_count = a.m_count;
+    ts.q = q; ts.g = g;
+    ts.ring = lds + wave * geo.depth * kTileBytes;
+    ts.depth = geo.depth;
+    DFK_STAMP(0);
+    ts.start();
+
+    f32x4 acc[NT][TT];
+#pragma unroll
+    for (int rt = 0; rt < NT; ++rt)
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) acc[rt][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    for (int kc = 0; kc < ts.nkc; ++kc) {
+        u32x4 xk[TT][4];       // B operand of this chunk: token q of each token tile, k group g of step c
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+            const unsigned char* slot = ts.acquire();
+#pragma unroll
+            for (int c = 0; c < 4; ++c) xk[tt][c] = *(const u32x4*)(slot + (q * 16 + ((4 * c + g) ^ q)) * 16);
+        }
+#pragma unroll
+        for (int rt = 0; rt < NT; ++rt) {
+            if (rt < nt) {
+                const unsigned char* slot = ts.acquire();
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const bf16x8 av = *(const bf16x8*)(slot + (q * 16 + ((4 * c + g) ^ q)) * 16);
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt)
+                        acc[rt][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, as_bf16x8(xk[tt][c]), acc[rt][tt], 0, 0, 0);
+                }
+            }
+        }
+    }
+    DFK_STAMP(2);
+
+    // Every wavefront's tile loads have landed (its last acquire waited for all of them), so
+    // after this barrier the rings are free.  The wavefronts' k-partial sums meet there,
+    // geo.pass row tiles at a time: [row tile][wavefront][token][16 rows] fp32.
+    __syncthreads();
+    float* stage = (float*)lds;
+    for (int rt0 = 0; rt0 < nt; rt0 += geo.pass) {
+        const int cnt = min(geo.pass, nt - rt0);
+#pragma unroll
+        for (int rt = 0; rt < NT; ++rt) {
+            if (rt >= rt0 && rt < rt0 + cnt) {
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt)
+                    *(f32x4*)(stage + ((size_t)((rt - rt0) * NW + wave) * TOK + tt * 16 + q) * 16 + 4 * g) = acc[rt][tt];
+            }
+        }
+        __syncthreads();
+        // task (row tile r of the pass, token m, row pair pr): rows 2pr, 2pr+1 (gate) and 8 further on (up)
+        for (int t = tid; t < cnt * TOK * 4; t += NTHREADS) {
+            const int r = t / (TOK * 4), rem = t - r * (TOK * 4);
+            const int m = rem >> 2, pr = rem & 3;
+            if (m < a.m_count) {
+                const float* src = stage + ((size_t)(r * NW) * TOK + m) * 16 + 2 * pr;
+                float g0 = 0.f, g1 = 0.f, u0 = 0.f, u1 = 0.f;
+#pragma unroll
+                for (int w = 0; w < NW; ++w) {
+                    const float2 gv = *(const float2*)(src + (size_t)w * TOK * 16);
+                    const float2 uv = *(const float2*)(src + (size_t)w * TOK * 16 + 8);
+                    g0 += gv.x; g1 += gv.y; u0 += uv.x; u1 += uv.y;
+                }
+                const size_t o = (size_t)(a.m_base + m) * a.d_ff + j0 + (rt0 + r) * 8 + 2 * pr;
+                *(uint32_t*)((uint16_t*)a.a2 + o) = pack_bf16x2(silu_mul_fast(g0, u0), silu_mul_fast(g1, u1));
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------- down kernel
+template <int NW, int TT>
+struct KmStream2 {
+    const char *Wd, *A2;
+    size_t row_bytes;          // d_model * 2
+    size_t a2_row_bytes;       // d_ff * 2
+    size_t a2_base;            // byte offset of (token m_base, row j0)
+    int d_ff, j0, rows, m_count;
+    int blk_first, CB;
+    int jb_lo, njb;
+    int q, g;
+    unsigned off2;
+    unsigned char* ring;
+    int depth, T, issued, issue_slot, take_slot;
+    int p_jbi, p_idx;          // producer: 32-row block, position in it (A tile, then 2 tiles per column block)
+
+    __device__ __forceinline__ void issue() {
+        unsigned char* slot = ring + issue_slot * kTileBytes;
+        const int jb = jb_lo + p_jbi;
+        if (p_idx == 0) {      // A tile: instruction u = token tile; lane (q, g): token q, rows 8g .. 8g+7 of the block
+            const int j = min(jb * 32 + 8 * g, rows - 8);   // past the split: any valid address (masked at use)
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int token = min(min(u, TT - 1) * 16 + q, m_count - 1);
+                const char* src = A2 + a2_base + (size_t)token * a2_row_bytes + (size_t)j * 2;
+                __builtin_amdgcn_global_load_lds(src, DFK_LDS_PTR(slot + u * 1024), 16, 0, 0);
+            }
+        } else {
+            const int b = (p_idx - 1) >> 1, h = (p_idx - 1) & 1;
+            const int row0 = j0 + jb * 32 + 4 * h;           // lane adds 8g + u
+            const size_t colb = (size_t)(blk_first + b) * 256;
+            if (row0 + 28 <= d_ff) {
+                const char* base = Wd + (size_t)row0 * row_bytes + colb;
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    __builtin_amdgcn_global_load_lds(base + (size_t)u * row_bytes + off2, DFK_LDS_PTR(slot + u * 1024), 16,
+                                                     0, kAuxNonTemporal);
+            } else {           // last rows of W_down: clamp per lane (values are masked later)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int row = min(row0 + 8 * g + u, d_ff - 1);
+                    __builtin_amdgcn_global_load_lds(Wd + (size_t)row * row_bytes + colb + 16 * q,
+                                                     DFK_LDS_PTR(slot + u * 1024), 16, 0, kAuxNonTemporal);
+                }
+            }
+        }
+        if (++p_idx == 1 + 2 * CB) { p_idx = 0; ++p_jbi; }
+        ++issued;
+        if (++issue_slot == depth) issue_slot = 0;
+    }
+    __device__ __forceinline__ void start() {
+        off2 = (unsigned)(8 * g * row_bytes + 16 * q);
+        T = njb * (1 + 2 * CB);
+        issued = 0; issue_slot = 0; take_slot = 0; p_jbi = 0; p_idx = 0;
+        const int ahead = min(depth - 1, T);
+        for (int i = 0; i < ahead; ++i) issue();
+    }
+    __device__ __forceinline__ const unsigned char* acquire() {
+        DFK_WAIT_LGKM0();
+        asm volatile("" ::: "memory");
+        if (issued < T) {
+            issue();
+            wait_vm_ops(4 * (depth - 1));
+        } else {
+            wait_vm_ops(0);
+        }
+        const unsigned char* slot = ring + take_slot * kTileBytes;
+        if (++take_slot == depth) take_slot = 0;
+        return slot;
+    }
+};
+
+__host__ __device__ constexpr int km_col_blocks(int tt) { return tt >= 4 ? 1 : 2; }   // accumulator budget
+
+template <int NW, int TT>
+__global__ __launch_bounds__(NW * 64) void k_down_km(MlpArgs a, KmGeom geo) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    __shared__ int flag;
+    constexpr int NTHREADS = NW * 64;
+    constexpr int CBM = km_col_blocks(TT);
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int q = lane & 15, g = lane >> 4;
+    const int js = blockIdx.x / a.k2_col_blocks;
+    const int cb = blockIdx.x - js * a.k2_col_blocks;
+    int j0, j1;
+    slice_rows(a.d_ff, a.k2_splits, js, j0, j1);
+    const int rows = j1 - j0;
+    const int CB = a.d_model / 128 / a.k2_col_blocks;      // <= CBM, checked on the host
+    const int blk_lo = cb * CB;
+    const int njb_all = (rows + 31) / 32;
+    const int jb_lo = (int)((long long)njb_all * wave / NW);
+    const int njb = (int)((long long)njb_all * (wave + 1) / NW) - jb_lo;
+
+    KmStream2<NW, TT> ts;
+    ts.Wd = (const char*)a.Wd; ts.A2 = (const char*)a.a2;
+    ts.row_bytes = (size_t)a.d_model * 2;
+    ts.a2_row_bytes = (size_t)a.d_ff * 2;
+    ts.a2_base = ((size_t)a.m_base * a.d_ff + j0) * 2;
+    ts.d_ff = a.d_ff; ts.j0 = j0; ts.rows = rows; ts.m_count = a.m_count;
+    ts.blk_first = blk_lo; ts.CB = CB;
+    ts.jb_lo = jb_lo; ts.njb = njb;
+    ts.q = q; ts.g = g;
+    ts.ring = lds + wave * geo.depth * kTileBytes;
+    ts.depth = geo.depth;
+    DFK_STAMP(3);
+    ts.start();
+
+    f32x4 acc2[CBM][8][TT];
+#pragma unroll
+    for (int b = 0; b < CBM; ++b)
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) acc2[b][c][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    for (int jbi = 0; jbi < njb; ++jbi) {
+        const int jb = jb_lo + jbi;
+        u32x4 av[TT];          // A operand: A_2[token q of tile tt][rows 8g .. 8g+7 of the block]
+        {
+            const unsigned char* slot = ts.acquire();
+            const bool past = jb * 32 + 8 * g >= rows;
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) {
+                const u32x4 v = *(const u32x4*)(slot + tt * 1024 + lane * 16);
+                av[tt] = past ? u32x4{0, 0, 0, 0} : v;
+            }
+        }
+#pragma unroll
+        for (int b = 0; b < CBM; ++b) {
+            if (b < CB) {
+                u32x4 w[8];
+                const unsigned char* sa = ts.acquire();
+#pragma unroll
+                for (int u = 0; u < 4; ++u) w[u] = *(const u32x4*)(sa + u * 1024 + lane * 16);
+                const unsigned char* sb = ts.acquire();
+#pragma unroll
+                for (int u = 0; u < 4; ++u) w[4 + u] = *(const u32x4*)(sb + u * 1024 + lane * 16);
+                if (jb * 32 + 32 > rows) {   // rows past the split contribute nothing
+#pragma unroll
+                    for (int r = 0; r < 8; ++r)
+                        if (jb * 32 + 8 * g + r >= rows) w[r] = u32x4{0, 0, 0, 0};
+                }
+#pragma unroll
+                for (int c = 0; c < 8; ++c) {
+                    const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
+                    u32x4 bb;
+#pragma unroll
+                    for (int p = 0; p < 4; ++p) bb[p] = __builtin_amdgcn_perm(w[2 * p + 1][c >> 1], w[2 * p][c >> 1], sel);
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt)
+                        acc2[b][c][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(av[tt]), as_bf16x8(bb), acc2[b][c][tt], 0, 0, 0);
+                }
+            }
+        }
+    }
+    DFK_STAMP(4);
+
+    // The wavefronts' sums over their rows meet in LDS, one column block and one token tile
+    // at a time: per-wavefront stages [16 tokens][128] over the drained rings.
+    const bool atomic_mode = a.reduce_mode == DFK_REDUCE_ATOMIC;
+    float* stage = (float*)lds;                           // [NW][16][128]
+    __syncthreads();
+#pragma unroll
+    for (int b = 0; b < CBM; ++b) {
+        if (b < CB) {
+            const int nb = (blk_lo + b) * 128;
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) {
+                if (tt * 16 < a.m_count) {                // uniform: token tiles past the launch's tokens hold nothing
+                    float* mine = stage + (size_t)wave * 16 * 128;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        float* dst = mine + (4 * g + i) * 128 + 8 * q;
+                        *(f32x4*)dst = f32x4{acc2[b][0][tt][i], acc2[b][1][tt][i], acc2[b][2][tt][i], acc2[b][3][tt][i]};
+                        *(f32x4*)(dst + 4) = f32x4{acc2[b][4][tt][i], acc2[b][5][tt][i], acc2[b][6][tt][i], acc2[b][7][tt][i]};
+                    }
+                    __syncthreads();
+                    const int mt = min(16, a.m_count - tt * 16);   // tokens of this tile
+                    if (atomic_mode) {
+                        for (int idx = tid; idx < mt * 128; idx += NTHREADS) {
+                            float v = 0.f;
+#pragma unroll
+                            for (int w = 0; w < NW; ++w) v += stage[w * 16 * 128 + idx];
+                            acc_add(a.yacc + (size_t)(tt * 16 + (idx >> 7)) * a.d_model + nb + (idx & 127), v);
+                        }
+                    } else {
+                        for (int idx = tid; idx < mt * 32; idx += NTHREADS) {
+                            f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                            for (int w = 0; w < NW; ++w) v += *(const f32x4*)(stage + w * 16 * 128 + 4 * idx);
+                            const int m = tt * 16 + (idx >> 5), c4 = idx & 31;
+                            store4_device(a.P + ((size_t)blockIdx.x * a.m_count + m) * a.d_model + nb + 4 * c4, v[0], v[1], v[2], v[3]);
+                        }
+                    }
+                    __syncthreads();
+                }
+            }
+        }
+    }
+    const int width = CB * 128;
+    if (atomic_mode) {
+        drain_own_memory_ops();
+        __syncthreads();
+        if (tid == 0) flag = arrive_last(a.tickets + cb, (unsigned)a.k2_splits) ? 1 : 0;
+        __syncthreads();
+        if (!flag) return;
+        for (int idx = tid; idx < a.m_count * (width / 2); idx += NTHREADS) {
+            const int m = idx / (width / 2), c2 = idx - m * (width / 2);
+            float* src = a.yacc + (size_t)m * a.d_model + blk_lo * 128 + 2 * c2;
+            const float v0 = acc_take(src), v1 = acc_take(src + 1);
+            *(uint32_t*)((uint16_t*)a.Y + (size_t)(a.m_base + m) * a.d_model + blk_lo * 128 + 2 * c2) = pack_bf16x2(v0, v1);
+        }
+        return;
+    }
+    reduce_store<BF16>(plan_column_block(a, cb, blk_lo * 128, blk_lo * 128 + width), a.Y, a.m_base, &flag, a.trace);
+}
+
+// ---------------------------------------------------------------- host side
+int km_token_tiles(int m_count) { return m_count <= 16 ? 1 : m_count <= 32 ? 2 : 4; }
+
+size_t km_lds_gateup(const dfk_config_t& c, int TT, int d_ff, KmGeom* geo) {
+    const int nt_max = max_slice_rows(d_ff, c.splits) / 8;
+    const size_t ring = (size_t)c.waves * c.depth * kTileBytes;
+    const size_t per_tile = (size_t)c.waves * 16 * TT * 16 * 4;   // partial sums of one row tile
+    const int fit = (int)((size_t)kLdsLimit / per_tile);
+    geo->depth = c.depth;
+    geo->pass = std::max(1, std::min(nt_max, fit));
+    return std::max(ring, (size_t)geo->pass * per_tile);
+}
+size_t km_lds_down(const dfk_config_t& c, KmGeom* geo) {
+    geo->depth = c.depth;
+    geo->pass = 0;
+    return std::max((size_t)c.waves * c.depth * kTileBytes, (size_t)c.waves * 16 * 128 * 4);
+}
+
+template <int NW, int TT>
+hipError_t launch_km_t(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
+    static size_t configured1 = 0, configured2 = 0;
+    if (g_stage_mask & 1) {
+        KmGeom geo;
+        const size_t lds = km_lds_gateup(c, TT, a.d_ff, &geo);
+        if (lds > configured1) {
+            hipError_t e = hipFuncSetAttribute((const void*)k_gateup_km<NW, TT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            configured1 = lds;
+        }
+        hipLaunchKernelGGL((k_gateup_km<NW, TT>), dim3(a.splits), dim3(NW * 64), lds, st, a, geo);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (g_stage_mask & 2) {
+        KmGeom geo;
+        const size_t lds = km_lds_down(c, &geo);
+        if (lds > configured2) {
+            hipError_t e = hipFuncSetAttribute((const void*)k_down_km<NW, TT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            configured2 = lds;
+        }
+        hipLaunchKernelGGL((k_down_km<NW, TT>), dim3(a.k2_splits * a.k2_col_blocks), dim3(NW * 64), lds, st, a, geo);
+        return hipGetLastError();
+    }
+    return hipSuccess;
+}
+
+}  // namespace
+
+int mfma_km_tokens_per_launch() { return kKmTokensPerLaunch; }
+
+bool mfma_km_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype) {
+    if (c.path != DFK_PATH_MFMA || dtype != DFK_BF16 || c.variant != DFK_VARIANT_TWO_KERNEL) return false;
+    if (c.kmajor != 1 || c.k2_rows_by_wave != 0 || c.a2_dtype != DFK_BF16) return false;
+    if (c.reduce != DFK_REDUCE_TICKET && c.reduce != DFK_REDUCE_ATOMIC) return false;
+    if (c.waves != 8 || c.depth < 2 || c.depth > 16) return false;
+    if (M < 1 || d_model < 8 || d_ff < 8 || d_ff % 8 || d_model > kMaxDModel) return false;
+    if (d_model % (kKC * c.waves)) return false;          // each wavefront owns whole 128-k chunks
+    const int ng = d_ff / 8;
+    if (c.splits < 1 || c.splits > ng || c.splits > 65535) return false;
+    if (max_slice_rows(d_ff, c.splits) / 8 > kKmMaxRowTiles) return false;   // accumulators of the row tiles
+    if (c.k2_splits < 1 || c.k2_splits > ng) return false;
+    const int nblk = d_model / 128;
+    if (c.k2_col_blocks < 1 || nblk % c.k2_col_blocks) return false;
+    if ((long long)c.k2_splits * c.k2_col_blocks > 65535 || c.k2_col_blocks > kTicketLevel2) return false;
+    const int tokens = std::min(M, kKmTokensPerLaunch);
+    const int TT = km_token_tiles(tokens);
+    if (nblk / c.k2_col_blocks > km_col_blocks(TT)) return false;
+    if (c.reduce == DFK_REDUCE_TICKET && !partials_fit(c.k2_splits * c.k2_col_blocks, tokens, M, d_model)) return false;
+    KmGeom geo;
+    return km_lds_gateup(c, TT, d_ff, &geo) <= (size_t)kLdsLimit && km_lds_down(c, &geo) <= (size_t)kLdsLimit;
+}
+
+hipError_t launch_mfma_km(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
+    switch (km_token_tiles(a.m_count)) {
+        case 1: return launch_km_t<8, 1>(a, c, st);
+        case 2: return launch_km_t<8, 2>(a, c, st);
+        default: return launch_km_t<8, 4>(a, c, st);
+    }
+}
+
+}  // namespace dfk

@@ -200,6 +200,7 @@ bool valu_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_
     (void)dtype;
     if (c.path != DFK_PATH_VALU) return false;
     if (c.variant != DFK_VARIANT_FUSED && c.variant != DFK_VARIANT_TWO_KERNEL) return false;
+    if (c.kmajor != 0) return false;
     if (c.reduce != DFK_REDUCE_TICKET || c.k2_rows_by_wave != 0) return false;
     if (c.waves < 1 || c.waves > 8) return false;  // kernels are built for <= 512 threads
     if (M < 1 || d_model < 8 || d_ff < 8 || d_model % 8 || d_ff % 8) return false;

@@ -72,7 +72,7 @@ def test_alignment_and_alias():
 
 def test_workspace_checks():
     n = dfk.dfk_workspace_bytes(8, D, FF)
-    assert n >= 4096 + 32 * 32768 * 4 + 256 * 8 * D * 4 + 8 * FF * 4
+    assert n >= 4096 + 64 * 32768 * 4 + 256 * 8 * D * 4 + 8 * FF * 4
     assert dfk.dfk_workspace_bytes(0, D, FF) == 0 and dfk.dfk_workspace_bytes(1, 0, FF) == 0
     assert chk(M=8, workspace=0, workspace_bytes=n) == dfk.DFK_ERR_WORKSPACE
     assert chk(M=8, workspace=WS, workspace_bytes=n - 1) == dfk.DFK_ERR_WORKSPACE

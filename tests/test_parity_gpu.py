@@ -47,7 +47,7 @@ def y64(Y):
 
 def workspace_is_clean(ws, M, d):
     """Arrival counters and the atomic accumulator must be zero again after a call."""
-    head = ws[:4096 + 32 * 32768 * 4]
+    head = ws[:4096 + 64 * 32768 * 4]
     return int(torch.count_nonzero(head).item()) == 0
 
 
@@ -154,6 +154,30 @@ def test_large_token_counts(M):
             assert rel_err(y64(Y), ref) <= TOL_BF16, (M, cfg)
             assert workspace_is_clean(ws, M, d)
             break
+
+
+@pytest.mark.parametrize("shape", [(1, 1024, 2816), (16, 1024, 4104), (17, 1024, 2816), (33, 2048, 4104),
+                                   (48, 1024, 2816), (64, 1024, 8200), (100, 1024, 2816)],
+                         ids=lambda s: "M%d_d%d_ff%d" % s)
+def test_kernels_for_up_to_64_tokens_per_launch(shape):
+    """Every candidate of the pair of kernels whose activations travel through the tile
+    rings (config field kmajor): one, two and four token tiles, ragged d_ff, both reductions,
+    and a token count that needs two launches."""
+    M, d, ff = shape
+    t = di.mlp_inputs(M, d, ff, seed=11)
+    ref = oracle.swiglu_mlp(t["X"], t["Wg"], t["Wu"], t["Wd"])
+    g = gpu_inputs(t)
+    ws = dfk.new_workspace(M, d, ff, DEV)
+    cfgs = _cfgs(M, d, ff, lambda c: c.kmajor == 1)
+    assert cfgs
+    assert {c.reduce for c in cfgs} == {dfk.DFK_REDUCE_TICKET, dfk.DFK_REDUCE_ATOMIC}
+    for cfg in cfgs:
+        print("case", shape, cfg, flush=True)
+        for _ in range(2):
+            Y, _ = run_ex(g, cfg, ws)
+            err = rel_err(y64(Y), ref)
+            assert err <= TOL_BF16, (shape, cfg, err)
+            assert workspace_is_clean(ws, M, d), (shape, cfg)
 
 
 def test_degenerate_inputs():
