@@ -103,7 +103,7 @@ typedef enum { DFK_REDUCE_TICKET = 0, DFK_REDUCE_ATOMIC = 1 } dfk_reduce_t;
  *                  tokens per launch (the activations travel through the same LDS rings
  *                  as the weight tiles instead of sitting in registers; gate/up kernel
  *                  k-major with all its row tiles accumulating in registers); needs
- *                  waves = 8 and k2_rows_by_wave = 0; 0 = the kernels above
+ *                  k2_rows_by_wave = 0; 0 = the kernels above
  */
 typedef struct dfk_config_t {
     int variant;

@@ -150,8 +150,8 @@ std::vector<dfk_config_t> candidates(int M, int d_model, int d_ff, dfk_dtype_t d
                 const int k2c = nblk / cbw;
                 for (int grid : {256, 512})
                     for (int reduce : {DFK_REDUCE_ATOMIC, DFK_REDUCE_TICKET})
-                        for (int depth : {3, 4})
-                            push(make_cfg(DFK_VARIANT_TWO_KERNEL, DFK_PATH_MFMA, clamp_splits(splits, d_ff), 8, depth,
+                        for (int wd : {83, 84, 46, 48})   // wavefronts, ring depth
+                            push(make_cfg(DFK_VARIANT_TWO_KERNEL, DFK_PATH_MFMA, clamp_splits(splits, d_ff), wd / 10, wd % 10,
                                           clamp_splits(std::max(1, grid / k2c), d_ff), k2c, DFK_BF16, reduce, 0, 1));
             }
     }

@@ -156,13 +156,14 @@ __device__ __forceinline__ ReducePlan plan_full_width(const MlpArgs& a, int s, i
 }
 
 // Plan of the second kernel of the two-kernel variant: workgroup (js, cb) holds
-// the partial of d_ff split js for columns [c_lo, c_hi); one level.
+// the partial of d_ff split js for columns [c_lo, c_hi) and has stored it in those
+// columns of block js (the workgroups of one split share a block); one level.
 __device__ __forceinline__ ReducePlan plan_column_block(const MlpArgs& a, int cb, int c_lo, int c_hi) {
     ReducePlan r;
     r.P = a.P; r.Q = a.Q; r.tickets = a.tickets;
     r.m_count = a.m_count; r.d_model = a.d_model;
     r.c_lo = c_lo; r.c_hi = c_hi;
-    r.p_first = cb; r.p_stride = a.k2_col_blocks; r.n1 = a.k2_splits;
+    r.p_first = 0; r.p_stride = 1; r.n1 = a.k2_splits;
     r.t1 = cb;
     r.q_slot = 0; r.n2 = 1; r.t2 = kTicketLevel2;
     return r;

@@ -223,6 +223,8 @@ __global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
     const int nkc = KW / kKC;
     const int my_blocks = wave < blk_cnt ? (blk_cnt - wave + NW - 1) / NW : 0;
     const bool atomic_mode = a.reduce_mode == DFK_REDUCE_ATOMIC;
+    // block of the partial-sum area: one per slice (fused), one per d_ff split (down kernel)
+    const int pblk = MODE == MODE_DOWN ? (int)blockIdx.x / a.k2_col_blocks : (int)blockIdx.x;
 
     TileStream<NW, MODE, BG> ts;
     ts.Wg = (const char*)a.Wg; ts.Wu = (const char*)a.Wu; ts.Wd = (const char*)a.Wd;
@@ -457,7 +459,7 @@ __global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
                     for (int i = 0; i < 4; ++i) {
                         const int token = tt * 16 + 4 * g + i;
                         if (token < a.m_count) {
-                            float* dst = a.P + ((size_t)blockIdx.x * a.m_count + token) * a.d_model + nb + 8 * q;
+                            float* dst = a.P + ((size_t)pblk * a.m_count + token) * a.d_model + nb + 8 * q;
                             store4_device(dst, acc[0][tt][i], acc[1][tt][i], acc[2][tt][i], acc[3][tt][i]);
                             store4_device(dst + 4, acc[4][tt][i], acc[5][tt][i], acc[6][tt][i], acc[7][tt][i]);
                         }
@@ -666,7 +668,7 @@ __global__ __launch_bounds__(NW * 64) void k_down_rows(MlpArgs a, Geom geo) {
 #pragma unroll
                     for (int w = 0; w < NW; ++w) v += *(const f32x4*)(stage + w * TOK * 128 + 4 * idx);
                     const int m = idx >> 5, c4 = idx & 31;
-                    store4_device(a.P + ((size_t)blockIdx.x * a.m_count + m) * a.d_model + nb + 4 * c4, v[0], v[1], v[2], v[3]);
+                    store4_device(a.P + ((size_t)js * a.m_count + m) * a.d_model + nb + 4 * c4, v[0], v[1], v[2], v[3]);
                 }
             }
             __syncthreads();                              // stages are rewritten by the next column block
@@ -805,7 +807,7 @@ bool mfma_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_
     const int nblk = d_model / 128;
     if (c.k2_col_blocks < 1 || nblk % c.k2_col_blocks) return false;
     if ((long long)c.k2_splits * c.k2_col_blocks > 65535 || c.k2_col_blocks > kTicketLevel2) return false;
-    if (ticket && !partials_fit(c.k2_splits * c.k2_col_blocks, tokens, M, d_model)) return false;
+    if (ticket && !partials_fit(c.k2_splits, tokens, M, d_model)) return false;
     if (c.a2_dtype != DFK_BF16 && c.a2_dtype != DFK_FP32) return false;
     if (sizes(c, MODE_GATEUP, TT, d_ff, d_model).lds > (size_t)kLdsLimit) return false;
     if (c.k2_rows_by_wave) {

@@ -195,6 +195,7 @@ __global__ __launch_bounds__(NW * 64) void k_gateup_km(MlpArgs a, KmGeom geo) {
         }
         __syncthreads();
     }
+    DFK_STAMP(1);   // A_2 stored
 }
 
 // ---------------------------------------------------------------- down kernel
@@ -390,7 +391,7 @@ __global__ __launch_bounds__(NW * 64) void k_down_km(MlpArgs a, KmGeom geo) {
 #pragma unroll
                             for (int w = 0; w < NW; ++w) v += *(const f32x4*)(stage + w * 16 * 128 + 4 * idx);
                             const int m = tt * 16 + (idx >> 5), c4 = idx & 31;
-                            store4_device(a.P + ((size_t)blockIdx.x * a.m_count + m) * a.d_model + nb + 4 * c4, v[0], v[1], v[2], v[3]);
+                            store4_device(a.P + ((size_t)js * a.m_count + m) * a.d_model + nb + 4 * c4, v[0], v[1], v[2], v[3]);
                         }
                     }
                     __syncthreads();
@@ -471,7 +472,7 @@ bool mfma_km_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, d
     if (c.path != DFK_PATH_MFMA || dtype != DFK_BF16 || c.variant != DFK_VARIANT_TWO_KERNEL) return false;
     if (c.kmajor != 1 || c.k2_rows_by_wave != 0 || c.a2_dtype != DFK_BF16) return false;
     if (c.reduce != DFK_REDUCE_TICKET && c.reduce != DFK_REDUCE_ATOMIC) return false;
-    if (c.waves != 8 || c.depth < 2 || c.depth > 16) return false;
+    if ((c.waves != 4 && c.waves != 8) || c.depth < 2 || c.depth > 16) return false;
     if (M < 1 || d_model < 8 || d_ff < 8 || d_ff % 8 || d_model > kMaxDModel) return false;
     if (d_model % (kKC * c.waves)) return false;          // each wavefront owns whole 128-k chunks
     const int ng = d_ff / 8;
@@ -484,16 +485,20 @@ bool mfma_km_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, d
     const int tokens = std::min(M, kKmTokensPerLaunch);
     const int TT = km_token_tiles(tokens);
     if (nblk / c.k2_col_blocks > km_col_blocks(TT)) return false;
-    if (c.reduce == DFK_REDUCE_TICKET && !partials_fit(c.k2_splits * c.k2_col_blocks, tokens, M, d_model)) return false;
+    if (c.reduce == DFK_REDUCE_TICKET && !partials_fit(c.k2_splits, tokens, M, d_model)) return false;
     KmGeom geo;
     return km_lds_gateup(c, TT, d_ff, &geo) <= (size_t)kLdsLimit && km_lds_down(c, &geo) <= (size_t)kLdsLimit;
 }
 
 hipError_t launch_mfma_km(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
-    switch (km_token_tiles(a.m_count)) {
-        case 1: return launch_km_t<8, 1>(a, c, st);
-        case 2: return launch_km_t<8, 2>(a, c, st);
-        default: return launch_km_t<8, 4>(a, c, st);
+    switch (c.waves * 10 + km_token_tiles(a.m_count)) {
+        case 41: return launch_km_t<4, 1>(a, c, st);
+        case 42: return launch_km_t<4, 2>(a, c, st);
+        case 44: return launch_km_t<4, 4>(a, c, st);
+        case 81: return launch_km_t<8, 1>(a, c, st);
+        case 82: return launch_km_t<8, 2>(a, c, st);
+        case 84: return launch_km_t<8, 4>(a, c, st);
+        default: return hipErrorInvalidValue;
     }
 }
 

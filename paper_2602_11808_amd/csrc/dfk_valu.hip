@@ -153,7 +153,7 @@ __global__ __launch_bounds__(512) void k_down_valu(MlpArgs a, int a2_stride) {
         a2s[m * a2_stride + r] = v;
     }
     __syncthreads();
-    stage2_valu<E, MT>(a, j0, rows, a.m_count, blockIdx.x, a2s, a2_stride, c_lo, c_hi);
+    stage2_valu<E, MT>(a, j0, rows, a.m_count, js, a2s, a2_stride, c_lo, c_hi);
     reduce_store<E>(plan_column_block(a, cb, c_lo * E::VEC, c_hi * E::VEC), a.Y, a.m_base, &flag);
 }
 
@@ -217,7 +217,7 @@ bool valu_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_
         if (c.k2_splits < 1 || c.k2_splits > ng) return false;
         const int nchunk = d_model / (dtype == DFK_BF16 ? 8 : 4);
         if (c.k2_col_blocks < 1 || c.k2_col_blocks > nchunk || c.k2_col_blocks > kTicketLevel2) return false;
-        if (!partials_fit(c.k2_splits * c.k2_col_blocks, tokens, M, d_model)) return false;
+        if (!partials_fit(c.k2_splits, tokens, M, d_model)) return false;
         if ((long long)c.k2_splits * c.k2_col_blocks > 65535) return false;
         if ((long long)mt * max_slice_rows(d_ff, c.k2_splits) > kMaxRowsLds * 8) return false;
         if (c.a2_dtype != DFK_BF16 && c.a2_dtype != DFK_FP32) return false;
