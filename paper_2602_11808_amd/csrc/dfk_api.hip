@@ -149,7 +149,7 @@ std::vector<dfk_config_t> candidates(int M, int d_model, int d_ff, dfk_dtype_t d
                 if (nblk < cbw || nblk % cbw) continue;
                 const int k2c = nblk / cbw;
                 for (int grid : {256, 512})
-                    for (int reduce : {DFK_REDUCE_ATOMIC, DFK_REDUCE_TICKET})
+                    for (int reduce : {DFK_REDUCE_TICKET, DFK_REDUCE_ATOMIC})
                         for (int wd : {83, 84, 46, 48})   // wavefronts, ring depth
                             push(make_cfg(DFK_VARIANT_TWO_KERNEL, DFK_PATH_MFMA, clamp_splits(splits, d_ff), wd / 10, wd % 10,
                                           clamp_splits(std::max(1, grid / k2c), d_ff), k2c, DFK_BF16, reduce, 0, 1));
@@ -170,15 +170,23 @@ std::vector<dfk_config_t> candidates(int M, int d_model, int d_ff, dfk_dtype_t d
     return out;
 }
 
-// Untuned default: first valid candidate of the preferred variant for this M.
+// Untuned default.  Measured on MI355X, the two-kernel variant wins at every token count
+// (the fused kernel pays a 256-way sum of full-width partial blocks), its kernel pair
+// for up to 64 tokens first, then the rows-split down kernel, then the rest.
 bool heuristic(int M, int d_model, int d_ff, dfk_dtype_t dtype, int want_variant, dfk_config_t* out) {
     auto cands = candidates(M, d_model, d_ff, dtype);
-    int variant = want_variant;
-    if (variant == DFK_VARIANT_AUTO) variant = M <= 8 ? DFK_VARIANT_FUSED : DFK_VARIANT_TWO_KERNEL;
-    for (const auto& c : cands)
-        if (c.variant == variant) { *out = c; return true; }
-    if (want_variant == DFK_VARIANT_AUTO && !cands.empty()) { *out = cands[0]; return true; }
-    return false;
+    auto rank = [&](const dfk_config_t& c) {
+        if (c.variant == DFK_VARIANT_TWO_KERNEL) return c.kmajor ? 0 : c.k2_rows_by_wave ? 1 : 2;
+        return 3;
+    };
+    const dfk_config_t* best = nullptr;
+    for (const auto& c : cands) {
+        if (want_variant != DFK_VARIANT_AUTO && c.variant != want_variant) continue;
+        if (!best || rank(c) < rank(*best)) best = &c;
+    }
+    if (!best) return false;
+    *out = *best;
+    return true;
 }
 
 // ---------------------------------------------------------------- tuning table
