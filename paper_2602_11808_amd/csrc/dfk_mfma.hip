@@ -1,7 +1,10 @@
-// MFMA path (bf16 inputs, fp32 accumulation) for gfx950.
+// MFMA path (bf16 inputs, fp32 accumulation) for gfx950: the deeply fused single
+// launch, and the first generation of the two-kernel variant (at most 32 tokens
+// per launch; dfk_mfma_km.hip holds the pair for up to 64).
 //
-// One kernel template covers the deeply fused single launch (MODE_FUSED) and
-// the two launches of the two-kernel variant (MODE_GATEUP, MODE_DOWN).
+// k_mfma<NW, TT, MODE> covers the fused launch (MODE_FUSED) and the two launches of
+// the two-kernel variant (MODE_GATEUP, MODE_DOWN); k_down_rows is a second form of
+// the down kernel.
 //
 // Work split ("column-major tiling" of the Method section: a workgroup owns a
 // block of weight rows and reuses it for every token): workgroup s owns the
@@ -17,15 +20,14 @@
 // [w*KW, (w+1)*KW) of d_model.  A tile is 16 weight rows (8 of W_gate, the same
 // 8 of W_up) x 128 k; it is the A operand of v_mfma_f32_16x16x32_bf16 (4 k-steps
 // per tile), X^T (tokens padded to 16 per token tile) is the B operand; the
-// wavefront's whole k-range of X is loaded into registers once, before the
-// stream starts, so that nothing but tile loads sits in the memory queue.  16-byte chunks are XOR-swizzled by row on the
-// way into LDS (by permuting which global chunk each lane fetches), so the
-// operand reads are bank-conflict free.  The wavefronts' k-partial sums meet
-// in an LDS array through ds_add_f32.  In the fused kernel there is no workgroup
-// barrier between the stages: the wavefront that contributes last to a row tile
-// (an LDS counter per row tile tells) applies SiLU(G)*U for it, leaves A_2 in LDS
-// as bf16 [token][j] and raises the row tile's ready flag.  (MODE_GATEUP instead
-// ends with a barrier and writes A_2 to the workspace.)
+// wavefront's whole k-range of X is loaded into registers once.  16-byte chunks
+// are XOR-swizzled by row on the way into LDS (by permuting which global chunk
+// each lane fetches), so the operand reads are bank-conflict free.  The
+// wavefronts' k-partial sums meet in LDS without atomics: each wavefront stores
+// its block and counts its arrival at the row tile; the one that arrives last
+// adds the blocks, applies SiLU(G)*U and hands A_2 on (bf16 [token][j] in LDS and
+// a ready flag in the fused kernel, so there is no workgroup barrier between the
+// stages; the workspace in MODE_GATEUP).
 //
 // Stage two (Y += A_2 W_down over the slice): wavefront w owns 128-column blocks
 // of d_model.  A tile is 4 row-groups of W_down: lane (q, g) fetches 16 bytes
@@ -36,10 +38,10 @@
 // does the slice's first 32 rows for all of the wavefront's column blocks (they
 // need only row tiles whose flags were raised long ago, which absorbs the skew
 // between wavefronts), then finishes and flushes one block after the other.
-// The fp32 block
-// of partial Y is published to the workspace with device-scope stores and combined
-// by the two-level arrival-counter reduction (reduce_store); device-wide float
-// atomics were measured at ~10 G adds/s on MI355X and are not used.
+// The fp32 block of partial Y is published to the workspace with device-scope
+// stores and combined by the two-level arrival-counter reduction (reduce_store),
+// or added into the workspace accumulator with device-wide float atomics, one
+// instruction per 64 consecutive floats (DFK_REDUCE_ATOMIC).
 #include "dfk_mfma_common.h"
 
 namespace dfk {
@@ -167,13 +169,9 @@ struct TileStream {
     // Returns the LDS address of the next tile, landed and readable by this wavefront.
     // Only loads count: with at most 4*(depth-1) operations outstanding, at most that
     // many loads are, and loads complete in issue order, so the wanted tile is in.
-    // LDS_TAIL: LDS instructions this wavefront issued after its last read of a ring slot
-    // (the adds into the gate/up sums); LDS completes a wavefront's instructions in order,
-    // so the refill only has to wait until no more than those are outstanding.
-    template <int LDS_TAIL = 0>
     __device__ __forceinline__ const unsigned char* acquire() {
         // Reads of the slot about to be refilled must have returned before its refill is issued.
-        DFK_WAIT_LGKM(LDS_TAIL);
+        DFK_WAIT_LGKM0();
         asm volatile("" ::: "memory");
         if (issued < T) {
             issue();
@@ -243,7 +241,7 @@ __global__ __launch_bounds__(NW * 64) void k_mfma(MlpArgs a, Geom geo) {
     DFK_STAMP(0);
     ts.start();
 
-    // Everything in LDS that must start from a known value (raw stores: see lds_add_f32_raw).
+    // Everything in LDS that must start from a known value (raw stores: see dfk_mfma_common.h).
     if (MODE != MODE_DOWN) {
         for (int i = tid; i < 2 * geo.sync_cap; i += NTHREADS)
             lds_write_b32_raw(sync_addr + 4u * (unsigned)i, (i >= geo.sync_cap + nt) ? 1u : 0u);

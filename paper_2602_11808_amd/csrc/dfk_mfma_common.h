@@ -23,7 +23,6 @@ constexpr int kAuxNonTemporal = 2;  // cache-policy bit "nt": the weight stream 
 // s_waitcnt with only vmcnt constrained (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4]<<14)
 #define DFK_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | ((((n) >> 4) & 3) << 14))
 #define DFK_WAIT_LGKM0() __builtin_amdgcn_s_waitcnt(0xC07F)
-#define DFK_WAIT_LGKM(n) __builtin_amdgcn_s_waitcnt(0xC07F | (((n) & 15) << 8))
 #define DFK_STAMP(k) do { if (a.trace && tid == 0) a.trace[(size_t)blockIdx.x * 8 + (k)] = wall_clock64(); } while (0)
 
 // Wait until at most `newer_ops` of this wavefront's vector-memory operations
@@ -57,9 +56,6 @@ __device__ __forceinline__ void wait_vm_ops(int newer_ops) {
 // target of tile loads.  Completion is awaited in lds_barrier.
 __device__ __forceinline__ unsigned lds_addr(const void* p) {
     return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
-}
-__device__ __forceinline__ void lds_add_f32_raw(unsigned addr, float v) {
-    asm volatile("ds_add_f32 %0, %1" : : "v"(addr), "v"(v) : "memory");
 }
 __device__ __forceinline__ void lds_write_b16_raw(unsigned addr, unsigned v) {
     asm volatile("ds_write_b16 %0, %1" : : "v"(addr), "v"(v) : "memory");
