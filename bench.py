@@ -51,6 +51,69 @@ def committed_traffic():
         return None, None
 
 
+def decode32(args, torch, di, dfk, dev):
+    """The decode sweep: 32 distinct layers of the headline shape (11.3 GB of weights, far beyond
+    any cache) chained in stream order with a weight-free RMS normalisation between them, the
+    whole pass captured once in a HIP graph and replayed (the method's deployment mode: the
+    scheduler's choice is baked into the graph, no dispatch cost per token).  A layer's time
+    includes its normalisation launch (one small kernel)."""
+    L = 32
+    sweep = (1, 2, 3, 4, 8, 16, 24, 32, 64, 128, 256)
+    layers = [di.mlp_inputs_torch(1, D_MODEL, D_FF, seed=1000, layer=l, device=dev) for l in range(L)]
+    ws = dfk.new_workspace(max(sweep), D_MODEL, D_FF, dev)
+    dfk.dfk_set_workspace(ws)
+    scratch = torch.empty(dfk.dfk_tune_scratch_bytes(max(sweep), D_MODEL, D_FF, dfk.DFK_BF16, 3),
+                          dtype=torch.uint8, device=dev)
+    dfk.dfk_tune(list(sweep), D_MODEL, D_FF, dfk.DFK_BF16, scratch, sets=3, iters=8)
+    torch.cuda.synchronize()
+    del scratch
+    rows = {}
+    for M in sweep:
+        X0 = di.mlp_inputs_torch(M, D_MODEL, D_FF, seed=0, layer=0, device=dev)["X"]
+        bufs = [torch.empty_like(X0) for _ in range(L + 1)]
+        ys = [torch.empty_like(X0) for _ in range(L)]
+
+        def chain(stream=None):
+            for l in range(L):
+                w = layers[l]
+                dfk.dfk_swiglu_mlp(bufs[l], w["Wg"], w["Wu"], w["Wd"], ys[l], stream=stream)
+                dfk.dfk_rms_normalize(ys[l], bufs[l + 1], stream=stream)
+
+        bufs[0].copy_(X0)
+        chain()                                    # eager: kernel attributes get set, result to compare with
+        torch.cuda.synchronize()
+        eager0 = ys[0].clone()
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                chain(stream=side)
+        ok = True
+        for _ in range(3):
+            ys[0].zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            # layer 0 sees the same input every time (later layers amplify the last-bit freedom
+            # of the atomic reduction, so only their finiteness is checked)
+            d0 = float((eager0.float() - ys[0].float()).abs().max() / eager0.float().abs().max())
+            ok = ok and d0 <= 1e-2 and bool(torch.isfinite(bufs[L].float()).all())
+        reps = max(3, args.steps // 20)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            graph.replay()
+        b.record()
+        torch.cuda.synchronize()
+        us_layer = a.elapsed_time(b) * 1e3 / reps / L
+        c, tuned = dfk.dfk_get_choice(M, D_MODEL, D_FF, dfk.DFK_BF16)
+        rows[str(M)] = {"us_per_layer_in_graph": round(us_layer, 2),
+                        "tb_per_s": round(algorithmic_bytes(M, D_MODEL, D_FF) / us_layer / 1e6, 3),
+                        "replays_match_eager_layer0": ok, "pick": dict(c.as_dict(), tuned=tuned)}
+    print(json.dumps({"workload": "decode32: 32 chained llama3-8b-shaped layers, HIP graph replay", "layers": L,
+                      "weights_gb": round(L * 6 * D_MODEL * D_FF / 1e9, 2), "per_M": rows}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -61,6 +124,9 @@ def main():
     ap.add_argument("--tuning-file", default=None,
                     help="load the scheduler table from this file if it exists, else tune and save it there")
     ap.add_argument("--force", choices=["auto", "fused", "unfused"], default="auto")
+    ap.add_argument("--workload", choices=["layer", "decode32"], default="layer",
+                    help="layer (default): the headline workload; decode32: 32 chained distinct layers of the "
+                         "same shape, captured once in a HIP graph and replayed, M swept 1..256")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU by design (one MI355X); run with --gpus 1. "
@@ -75,6 +141,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.workload == "decode32":
+        return decode32(args, torch, di, dfk, dev)
     Mmax = max(M_SET)
 
     # ---- synthetic inputs, resident in HBM

@@ -253,6 +253,11 @@ dfk_status_t dfk_stream_read(const void* src, size_t bytes, void* sink, void* st
 dfk_status_t dfk_fill_synthetic(void* dst, size_t elems, dfk_dtype_t dtype, float scale,
                                 unsigned seed, void* stream);
 
+/* out[m, :] = in[m, :] / rms(in[m, :]) for bf16 [M, d_model] (fp32 arithmetic, no weight; in == out
+ * allowed).  Not part of the block: benchmarks and tests chain random layers with it, which would
+ * otherwise shrink the activations to zero within a few layers.  M <= 65535. */
+dfk_status_t dfk_rms_normalize(const void* in, void* out, int M, int d_model, void* stream);
+
 /* Optional in-kernel timeline for profiling the MFMA kernels: while a device buffer
  * of at least 64 bytes per workgroup of the launch is registered, each workgroup
  * writes up to 8 wall-clock stamps (100 MHz counter): [0] start, [1] first tile

@@ -79,6 +79,7 @@ SIGNATURES = [
     ("dfk_load_tuning", _ci, [ctypes.c_char_p]),
     ("dfk_stream_read", _ci, [_vp, _sz, _vp, _vp]),
     ("dfk_fill_synthetic", _ci, [_vp, _sz, _ci, ctypes.c_float, ctypes.c_uint, _vp]),
+    ("dfk_rms_normalize", _ci, [_vp, _vp, _ci, _ci, _vp]),
     ("dfk_set_trace_buffer", _ci, [_vp, _sz]),
     ("dfk_status_string", ctypes.c_char_p, [_ci]),
     ("dfk_last_hip_error", _ci, []),
@@ -289,6 +290,11 @@ def dfk_stream_read(src, sink, stream=None):
 def dfk_fill_synthetic(dst, scale: float, seed: int, stream=None):
     _check(lib().dfk_fill_synthetic(_ptr(dst), dst.numel(), _dtype_code(dst), scale, seed,
                                     _stream(stream)), "dfk_fill_synthetic")
+
+
+def dfk_rms_normalize(src, dst, stream=None):
+    M, d = src.shape
+    _check(lib().dfk_rms_normalize(_ptr(src), _ptr(dst), M, d, _stream(stream)), "dfk_rms_normalize")
 
 
 def dfk_set_trace_buffer(buf):

@@ -600,6 +600,13 @@ dfk_status_t dfk_load_tuning(const char* path) {
     return DFK_OK;
 }
 
+dfk_status_t dfk_rms_normalize(const void* in, void* out, int M, int d_model, void* stream) {
+    if (!in || !out || M < 1 || d_model < 1) return DFK_ERR_INVALID_ARG;
+    if (M > 65535) return DFK_ERR_UNSUPPORTED_SHAPE;
+    hipError_t e = launch_rms_normalize(in, out, M, d_model, (hipStream_t)stream);
+    return e == hipSuccess ? DFK_OK : hip_fail(e);
+}
+
 dfk_status_t dfk_stream_read(const void* src, size_t bytes, void* sink, void* stream) {
     if (!src || !sink || bytes == 0) return DFK_ERR_INVALID_ARG;
     if (bytes % 16) return DFK_ERR_UNSUPPORTED_SHAPE;

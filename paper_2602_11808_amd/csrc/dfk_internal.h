@@ -117,6 +117,7 @@ int valu_max_tokens_per_launch();
 // utility kernels
 hipError_t launch_zero(void* p, size_t bytes, hipStream_t st);
 hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, hipStream_t st);
+hipError_t launch_rms_normalize(const void* in, void* out, int M, int d_model, hipStream_t st);
 hipError_t launch_fill(void* dst, size_t elems, dfk_dtype_t dtype, float scale, unsigned seed,
                        hipStream_t st);
 

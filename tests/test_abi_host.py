@@ -160,6 +160,13 @@ def test_timing_calls_check_their_arguments_on_the_host():
     assert L.dfk_time_kernels(ctypes.byref(big), 64, D, FF, 0, fake, 1 << 40, 2, 4, None, us) == dfk.DFK_ERR_UNSUPPORTED_SHAPE
 
 
+def test_helper_calls_check_their_arguments_on_the_host():
+    L = dfk.lib()
+    assert L.dfk_rms_normalize(None, 4096, 1, 512, None) == dfk.DFK_ERR_INVALID_ARG
+    assert L.dfk_rms_normalize(4096, 4096, 0, 512, None) == dfk.DFK_ERR_INVALID_ARG
+    assert L.dfk_rms_normalize(4096, 4096, 70000, 512, None) == dfk.DFK_ERR_UNSUPPORTED_SHAPE
+
+
 def test_status_strings():
     for s in range(0, -9, -1):
         assert dfk.dfk_status_string(s) not in ("", "unknown status")

@@ -338,6 +338,17 @@ def test_per_launch_timing_splits_the_two_kernel_variant():
         assert us1 + us2 < 3 * whole + 50      # same order as the whole-call time
 
 
+def test_rms_normalize_helper():
+    # the weight-free normalisation benchmarks chain layers with (not part of the block)
+    for M, d in ((1, 512), (5, 4096), (64, 1000)):
+        x = (torch.randn(M, d, device=DEV, generator=torch.Generator(device=DEV).manual_seed(M)) * 3.0).to(torch.bfloat16)
+        y = torch.empty_like(x)
+        dfk.dfk_rms_normalize(x, y)
+        xf = x.double()
+        want = xf / xf.pow(2).mean(dim=1, keepdim=True).sqrt()
+        assert float((y.double() - want).abs().max()) <= 2.0 ** -7 * float(want.abs().max())
+
+
 def test_calls_can_be_captured_in_a_graph_and_replayed():
     # the deployment mode of the method: the chosen kernels are captured once and replayed;
     # arrival counters reset themselves, so every replay must equal the eager result
