@@ -105,16 +105,18 @@ def test_tiny_config_against_stored_oracle_output():
 
 FULL = [
     # the configurations the benchmark times, at their real sizes
-    ("llama3-8b", 4096, 14336, (1, 2, 4, 8, 16)),
-    ("qwen2.5-32b", 5120, 27648, (1, 8)),
-    ("llama3-70b", 8192, 28672, (1, 16)),
+    ("llama3-8b", 4096, 14336, (1, 2, 4, 8, 16, 64, 256)),
+    ("qwen2.5-32b", 5120, 27648, (1, 8, 32, 64)),
+    ("llama3-70b", 8192, 28672, (1, 16, 64, 128)),
 ]
 
 
 @pytest.mark.parametrize("name,d,ff,Ms", FULL, ids=[f[0] for f in FULL])
 def test_full_size_entry_points_match_oracle(name, d, ff, Ms):
     """Default entry points (scheduler's choice, forced fused, forced two-kernel)
-    at full size, in the launch configuration the benchmark uses."""
+    at full size, in the launch configuration the benchmark uses.  Up to 16 tokens every
+    output is compared; beyond, the rows of a sample of tokens (rows of Y are independent,
+    so the oracle computes exactly those)."""
     Mmax = max(Ms)
     g = di.mlp_inputs_torch(Mmax, d, ff, seed=0, device=DEV)
     host = {k: di.to_numpy(v) for k, v in g.items()}
@@ -123,14 +125,17 @@ def test_full_size_entry_points_match_oracle(name, d, ff, Ms):
     try:
         for M in Ms:
             X = g["X"][:M].contiguous()
-            ref = oracle.swiglu_mlp(host["X"][:M], host["Wg"], host["Wu"], host["Wd"])
+            rows = list(range(M)) if M <= 16 else sorted({0, 1, 15, 16, M // 2, M - 2, M - 1})
+            ref = oracle.swiglu_mlp(host["X"][rows], host["Wg"], host["Wu"], host["Wd"])
             assert 0.05 < np.abs(ref).max() < 50.0
-            for fn in (dfk.dfk_swiglu_mlp, dfk.dfk_swiglu_mlp_fused, dfk.dfk_swiglu_mlp_unfused):
+            fns = (dfk.dfk_swiglu_mlp, dfk.dfk_swiglu_mlp_fused, dfk.dfk_swiglu_mlp_unfused)
+            for fn in (fns if M <= 16 else fns[:1] + fns[2:]):   # the fused kernel is a small-M form
                 print("case", name, "M", M, fn.__name__, flush=True)
                 Y = torch.full_like(X, float("nan"))
                 fn(X, g["Wg"], g["Wu"], g["Wd"], Y)
                 torch.cuda.synchronize()
-                err = rel_err(y64(Y), ref)
+                assert bool(torch.isfinite(Y.float()).all()), (name, M, fn.__name__)
+                err = rel_err(y64(Y)[rows], ref)
                 assert err <= TOL_BF16, (name, M, fn.__name__, err)
                 assert workspace_is_clean(ws, M, d)
     finally:
