@@ -76,7 +76,7 @@ def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
 
 
 def as_f64(a: np.ndarray) -> np.ndarray:
-    """Exact float64 view of a uint16 (bf16 bits) or float32 array."""
+    """Exact float64 view of a uint16 (bf16 bits), float16 or float32 array."""
     if a.dtype == np.uint16:
         return bf16_bits_to_f32(a).astype(np.float64)
     return np.asarray(a, dtype=np.float64)
@@ -89,7 +89,9 @@ def tensor(seed: int, shape, std: float, dtype: str = "bf16") -> np.ndarray:
         return f32_to_bf16_bits(f)
     if dtype == "fp32":
         return f
-    raise ValueError("dtype must be 'bf16' or 'fp32'")
+    if dtype == "fp16":
+        return f.astype(np.float16)      # round-to-nearest-even
+    raise ValueError("dtype must be 'bf16', 'fp16' or 'fp32'")
 
 
 def layer_seeds(seed: int, layer: int):
@@ -112,21 +114,25 @@ def mlp_inputs(M: int, d_model: int, d_ff: int, seed: int = 0, layer: int = 0,
 # ---- torch interchange (imported lazily so numpy-only users need no torch) ----
 
 def to_torch(a: np.ndarray, device="cpu"):
-    """numpy uint16 bf16 bits -> torch.bfloat16; float32 -> torch.float32."""
+    """numpy uint16 bf16 bits -> torch.bfloat16; float16 -> torch.float16; float32 -> torch.float32."""
     import torch
     if a.dtype == np.uint16:
         t = torch.from_numpy(np.ascontiguousarray(a).view(np.int16).copy()).view(torch.bfloat16)
+    elif a.dtype == np.float16:
+        t = torch.from_numpy(np.ascontiguousarray(a).copy())
     else:
         t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32).copy())
     return t.to(device)
 
 
 def to_numpy(t) -> np.ndarray:
-    """torch.bfloat16 -> numpy uint16 bit patterns; torch.float32 -> float32."""
+    """torch.bfloat16 -> numpy uint16 bit patterns; torch.float16 -> float16; torch.float32 -> float32."""
     import torch
     t = t.detach().cpu().contiguous()
     if t.dtype == torch.bfloat16:
         return t.view(torch.int16).numpy().view(np.uint16).copy()
+    if t.dtype == torch.float16:
+        return t.numpy().copy()
     return t.to(torch.float32).numpy().copy()
 
 
@@ -134,7 +140,7 @@ def mlp_inputs_torch(M: int, d_model: int, d_ff: int, seed: int = 0, layer: int 
                      dtype: str = "bf16", device="cuda"):
     """Same recipe from torch's seeded generator on ``device`` (large shapes)."""
     import torch
-    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    tdt = {"bf16": torch.bfloat16, "fp16": torch.float16, "fp32": torch.float32}[dtype]
     s = layer_seeds(seed, layer)
 
     def draw(sd, shape, std):

@@ -8,7 +8,7 @@ which follows the SwiGLU equations of the Background section and the
 two-stage split of the Method section.
 
 Arrays are numpy: bfloat16 tensors are passed as their uint16 bit patterns,
-fp32 tensors as float32.  Layouts: X [M, d_model]; W_gate, W_up, W_down all
+fp32 tensors as float32, IEEE half tensors as float16.  Layouts: X [M, d_model]; W_gate, W_up, W_down all
 [d_ff, d_model] row-major; results are float64.
 """
 from __future__ import annotations
@@ -25,6 +25,7 @@ _LIB = os.path.join(_HERE, "liboracle.so")
 
 BF16 = 0
 FP32 = 1
+FP16 = 2
 
 
 def build(force: bool = False) -> str:
@@ -67,7 +68,9 @@ def _dtype_code(a: np.ndarray) -> int:
         return BF16
     if a.dtype == np.float32:
         return FP32
-    raise TypeError(f"oracle takes uint16 (bf16 bits) or float32 arrays, got {a.dtype}")
+    if a.dtype == np.float16:
+        return FP16
+    raise TypeError(f"oracle takes uint16 (bf16 bits), float16 or float32 arrays, got {a.dtype}")
 
 
 def _prep(a: np.ndarray, shape, code: int) -> np.ndarray:

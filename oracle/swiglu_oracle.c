@@ -25,7 +25,8 @@
  *     W_up   row-major [d_ff, d_model]   (transposed mathematical shape)
  *     W_down row-major [d_ff, d_model]   (the mathematical shape)
  *     Y      row-major [M, d_model], fp64
- * Element types: dtype 0 = bfloat16 bit patterns (uint16_t), 1 = IEEE fp32.
+ * Element types: dtype 0 = bfloat16 bit patterns (uint16_t), 1 = IEEE fp32,
+ * 2 = IEEE binary16 bit patterns (uint16_t).
  *
  * Threads only partition independent output elements (columns of d_ff in
  * stage one, columns of d_model in stage two); each output element is
@@ -40,6 +41,7 @@
 
 #define ORACLE_BF16 0
 #define ORACLE_FP32 1
+#define ORACLE_FP16 2
 
 /* Exact widening of one stored element to fp64. */
 static double widen(const void *base, size_t idx, int dtype)
@@ -49,6 +51,16 @@ static double widen(const void *base, size_t idx, int dtype)
         float f;
         memcpy(&f, &bits, sizeof f);
         return (double)f;
+    }
+    if (dtype == ORACLE_FP16) {
+        /* IEEE binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits */
+        uint16_t h = ((const uint16_t *)base)[idx];
+        int sign = h >> 15, e = (h >> 10) & 31, frac = h & 1023;
+        double v;
+        if (e == 0) v = ldexp((double)frac, -24);                  /* zero and subnormals */
+        else if (e == 31) v = frac ? NAN : INFINITY;
+        else v = ldexp((double)(1024 + frac), e - 25);             /* (1 + frac/1024) * 2^(e-15) */
+        return sign ? -v : v;
     }
     return (double)((const float *)base)[idx];
 }
@@ -136,7 +148,7 @@ int oracle_gate_up_silu(const void *X, const void *Wg, const void *Wu,
                         int M, int d_model, int d_ff, int dtype, int nthreads)
 {
     if (!X || !Wg || !Wu || !A2 || M < 1 || d_model < 1 || d_ff < 1) return -1;
-    if (dtype != ORACLE_BF16 && dtype != ORACLE_FP32) return -1;
+    if (dtype != ORACLE_BF16 && dtype != ORACLE_FP32 && dtype != ORACLE_FP16) return -1;
     job_t p;
     memset(&p, 0, sizeof p);
     p.X = X; p.Wg = Wg; p.Wu = Wu; p.G = G; p.U = U; p.A2 = A2;
@@ -149,7 +161,7 @@ int oracle_down(const double *A2, const void *Wd, double *Y,
                 int M, int d_model, int d_ff, int dtype, int nthreads)
 {
     if (!A2 || !Wd || !Y || M < 1 || d_model < 1 || d_ff < 1) return -1;
-    if (dtype != ORACLE_BF16 && dtype != ORACLE_FP32) return -1;
+    if (dtype != ORACLE_BF16 && dtype != ORACLE_FP32 && dtype != ORACLE_FP16) return -1;
     job_t p;
     memset(&p, 0, sizeof p);
     p.A2 = (double *)A2; p.Wd = Wd; p.Y = Y;

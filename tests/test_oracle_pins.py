@@ -201,7 +201,7 @@ def test_dff_split_identity():
         np.testing.assert_allclose(tot, full, rtol=1e-12, atol=1e-14)
 
 
-@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("dtype", ["fp32", "bf16", "fp16"])
 def test_against_independent_dgemm_on_math_shapes(dtype):
     # Mathematical shapes: W_gate, W_up in R^{d_model x d_ff}, W_down in
     # R^{d_ff x d_model}; numpy's dgemm is an independent contraction.
@@ -244,6 +244,26 @@ def test_bf16_widening_is_exact():
     # bf16 and fp32 inputs holding the same values give the same result bit for bit
     t = di.mlp_inputs(2, 32, 48, seed=81, dtype="bf16")
     t32 = {k: di.bf16_bits_to_f32(v) for k, v in t.items()}
+    np.testing.assert_array_equal(oracle.swiglu_mlp(t["X"], t["Wg"], t["Wu"], t["Wd"]),
+                                  oracle.swiglu_mlp(t32["X"], t32["Wg"], t32["Wu"], t32["Wd"]))
+
+
+def test_fp16_widening_is_exact_for_every_finite_pattern():
+    # Stage two with A_2 = [[1]] returns the row of W_down widened to fp64: all 63488 finite
+    # IEEE half patterns (zeros, subnormals, normals, both signs) against numpy's own conversion,
+    # by hand for a few, and through the fp32 route.
+    bits = np.arange(65536, dtype=np.uint16)
+    finite = bits[(bits & 0x7C00) != 0x7C00]
+    row = finite.view(np.float16).reshape(1, -1)
+    got = oracle.down(np.ones((1, 1)), row)[0]
+    np.testing.assert_array_equal(got, row[0].astype(np.float64))
+    hand = np.array([[0x3C00, 0xC000, 0x0001, 0x03FF, 0x0400, 0x7BFF, 0x8000]], np.uint16).view(np.float16)
+    want = np.array([1.0, -2.0, 2.0 ** -24, 1023 * 2.0 ** -24, 2.0 ** -14, 65504.0, -0.0])
+    got = oracle.down(np.ones((1, 1)), hand)[0]
+    np.testing.assert_array_equal(got, want)
+    assert np.signbit(got[6])
+    t = di.mlp_inputs(2, 32, 48, seed=83, dtype="fp16")
+    t32 = {k: v.astype(np.float32) for k, v in t.items()}
     np.testing.assert_array_equal(oracle.swiglu_mlp(t["X"], t["Wg"], t["Wu"], t["Wd"]),
                                   oracle.swiglu_mlp(t32["X"], t32["Wg"], t32["Wu"], t32["Wd"]))
 
