@@ -17,8 +17,9 @@
  *     W_down [d_ff, d_model]   the mathematical shape
  *     Y      [M,    d_model]   output, fully overwritten (never accumulated into)
  * so that every d_ff slice of each weight matrix is one contiguous block.
- * Element type: bfloat16 (inputs and Y; fp32 accumulation) or, in the fp32
- * test mode, IEEE fp32 for inputs and Y.  Y must not overlap any input.
+ * Element type: bfloat16 or IEEE half (inputs and Y; fp32 accumulation; A_2 is
+ * rounded to the same 16-bit type on the MFMA path) or, in the fp32 test mode,
+ * IEEE fp32 for inputs and Y.  Y must not overlap any input.
  *
  * Ownership and execution: the caller owns every buffer, including the
  * workspace.  No entry point on the call path allocates or frees device
@@ -57,7 +58,7 @@ typedef enum {
     DFK_ERR_NOT_FOUND = -8           /* no tuned entry / no such candidate */
 } dfk_status_t;
 
-typedef enum { DFK_BF16 = 0, DFK_FP32 = 1 } dfk_dtype_t;
+typedef enum { DFK_BF16 = 0, DFK_FP32 = 1, DFK_FP16 = 2 } dfk_dtype_t;   /* FP16 = IEEE binary16 */
 
 /* Fusion depth (Method section; Figure 1 b/c): one launch for the whole block,
  * or two launches cut after A_2. */
@@ -93,7 +94,8 @@ typedef enum { DFK_REDUCE_TICKET = 0, DFK_REDUCE_ATOMIC = 1 } dfk_reduce_t;
  *   k2_col_blocks  two-kernel variant: column blocks of the down projection
  *                  (grid of the second kernel = k2_splits * k2_col_blocks)
  *   a2_dtype       two-kernel variant: type A_2 is stored in between the
- *                  kernels, DFK_BF16 or DFK_FP32
+ *                  kernels: DFK_FP32, or the 16-bit type of the inputs (DFK_BF16 with
+ *                  bf16 inputs; with half inputs DFK_FP16, kmajor pair only)
  *   k2_rows_by_wave  two-kernel variant, MFMA path: 0 = in the down projection each
  *                  wavefront owns 128-column blocks of the workgroup's columns;
  *                  1 = the wavefronts share the workgroup's (at most 4) column blocks

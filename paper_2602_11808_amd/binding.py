@@ -24,7 +24,7 @@ DFK_ERR_HIP = -6
 DFK_ERR_IO = -7
 DFK_ERR_NOT_FOUND = -8
 
-DFK_BF16, DFK_FP32 = 0, 1
+DFK_BF16, DFK_FP32, DFK_FP16 = 0, 1, 2
 DFK_VARIANT_AUTO, DFK_VARIANT_FUSED, DFK_VARIANT_TWO_KERNEL = 0, 1, 2
 DFK_PATH_VALU, DFK_PATH_MFMA = 0, 1
 DFK_REDUCE_TICKET, DFK_REDUCE_ATOMIC = 0, 1
@@ -127,7 +127,9 @@ def _dtype_code(t) -> int:
         return DFK_BF16
     if t.dtype == torch.float32:
         return DFK_FP32
-    raise TypeError(f"dfk takes bfloat16 or float32 tensors, got {t.dtype}")
+    if t.dtype == torch.float16:
+        return DFK_FP16
+    raise TypeError(f"dfk takes bfloat16, float16 or float32 tensors, got {t.dtype}")
 
 
 def _shapes(X, W_gate, W_up, W_down, Y):

@@ -49,7 +49,7 @@ dfk_status_t check(const void* X, const void* Wg, const void* Wu, const void* Wd
                    const void* ws, size_t ws_bytes, bool need_ws) {
     if (!X || !Wg || !Wu || !Wd || !Y) return DFK_ERR_INVALID_ARG;
     if (M < 1 || d_model < 1 || d_ff < 1) return DFK_ERR_INVALID_ARG;
-    if (dtype != DFK_BF16 && dtype != DFK_FP32) return DFK_ERR_INVALID_ARG;
+    if (dtype != DFK_BF16 && dtype != DFK_FP32 && dtype != DFK_FP16) return DFK_ERR_INVALID_ARG;
     if (d_model % 8 || d_ff % 8 || M > DFK_MAX_M || d_model > kMaxDModel) return DFK_ERR_UNSUPPORTED_SHAPE;
     const void* ptrs[5] = {X, Wg, Wu, Wd, Y};
     for (const void* p : ptrs)
@@ -107,8 +107,8 @@ std::vector<dfk_config_t> candidates(int M, int d_model, int d_ff, dfk_dtype_t d
             if (same_cfg(o, c)) return;
         out.push_back(c);
     };
-    const int a2dt = dtype == DFK_FP32 ? DFK_FP32 : DFK_BF16;
-    if (dtype == DFK_BF16) {
+    const int a2dt = dtype == DFK_BF16 ? DFK_BF16 : DFK_FP32;   // VALU pair: fp32 unless the inputs are bf16
+    if (dtype == DFK_BF16 || dtype == DFK_FP16) {   // (the first-generation MFMA kernels validate for bf16 only)
         // MFMA path: d_ff slices ("column-major tiling": each workgroup owns a
         // block of weight rows and reuses it for every token).
         for (int splits : {256, 512})
@@ -152,14 +152,14 @@ std::vector<dfk_config_t> candidates(int M, int d_model, int d_ff, dfk_dtype_t d
                     for (int reduce : {DFK_REDUCE_TICKET, DFK_REDUCE_ATOMIC})
                         for (int wd : {83, 84, 46, 48})   // wavefronts, ring depth
                             push(make_cfg(DFK_VARIANT_TWO_KERNEL, DFK_PATH_MFMA, clamp_splits(splits, d_ff), wd / 10, wd % 10,
-                                          clamp_splits(std::max(1, grid / k2c), d_ff), k2c, DFK_BF16, reduce, 0, 1));
+                                          clamp_splits(std::max(1, grid / k2c), d_ff), k2c, (int)dtype, reduce, 0, 1));
             }
     }
     for (int splits : {256, 512, 1024})
         for (int waves : {4, 8})
             push(make_cfg(DFK_VARIANT_FUSED, DFK_PATH_VALU, clamp_splits(splits, d_ff), waves, 0, 0, 0,
                           a2dt));
-    const int nchunk = d_model / (dtype == DFK_BF16 ? 8 : 4);
+    const int nchunk = d_model / (dtype == DFK_FP32 ? 4 : 8);
     for (int splits : {512, 1024})
         for (int k2s : {8, 16, 32}) {
             const int k2 = clamp_splits(k2s, d_ff);
@@ -237,6 +237,7 @@ dfk_status_t run(const void* X, const void* Wg, const void* Wu, const void* Wd, 
     a.X = X; a.Wg = Wg; a.Wu = Wu; a.Wd = Wd; a.Y = Y;
     a.M = M; a.d_model = d_model; a.d_ff = d_ff;
     a.splits = c.splits; a.k2_splits = c.k2_splits; a.k2_col_blocks = c.k2_col_blocks;
+    a.dtype = (int)dtype;
     a.a2_is_fp32 = c.a2_dtype == DFK_FP32;
     a.tickets = (unsigned*)((char*)ws + l.tickets_off);
     a.reduce_mode = c.reduce;
@@ -586,7 +587,7 @@ dfk_status_t dfk_load_tuning(const char* path) {
                                   &e.cfg.variant, &e.cfg.path, &e.cfg.splits, &e.cfg.waves, &e.cfg.depth,
                                   &e.cfg.reduce, &e.cfg.k2_splits, &e.cfg.k2_col_blocks, &e.cfg.a2_dtype,
                                   &e.cfg.k2_rows_by_wave, &e.cfg.kmajor, &e.usec);
-        if (n != 16 || M < 1 || M > DFK_MAX_M || (dt != DFK_BF16 && dt != DFK_FP32) || dm < 8 ||
+        if (n != 16 || M < 1 || M > DFK_MAX_M || (dt != DFK_BF16 && dt != DFK_FP32 && dt != DFK_FP16) || dm < 8 ||
             df < 8 || dm % 8 || df % 8 || !config_valid(e.cfg, M, dm, df, (dfk_dtype_t)dt)) {
             rc = DFK_ERR_IO;
             break;
@@ -618,7 +619,7 @@ dfk_status_t dfk_stream_read(const void* src, size_t bytes, void* sink, void* st
 dfk_status_t dfk_fill_synthetic(void* dst, size_t elems, dfk_dtype_t dtype, float scale, unsigned seed,
                                 void* stream) {
     if (!dst || elems == 0) return DFK_ERR_INVALID_ARG;
-    if (dtype != DFK_BF16 && dtype != DFK_FP32) return DFK_ERR_INVALID_ARG;
+    if (dtype != DFK_BF16 && dtype != DFK_FP32 && dtype != DFK_FP16) return DFK_ERR_INVALID_ARG;
     if ((uintptr_t)dst % 4) return DFK_ERR_ALIGNMENT;
     hipError_t e = launch_fill(dst, elems, dtype, scale, seed, (hipStream_t)stream);
     return e == hipSuccess ? DFK_OK : hip_fail(e);

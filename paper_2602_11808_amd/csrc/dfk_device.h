@@ -49,11 +49,37 @@ struct BF16 {
     __device__ static __forceinline__ void store(void* Y, size_t i, float v) {
         ((uint16_t*)Y)[i] = (uint16_t)f32_to_bf16_bits(v);
     }
+    __device__ static __forceinline__ uint32_t pack2(float lo, float hi) { return pack_bf16x2(lo, hi); }
     // four consecutive outputs, i a multiple of 4
     __device__ static __forceinline__ void store4(void* Y, size_t i, float a, float b, float c, float d) {
         uint2 v;
         v.x = pack_bf16x2(a, b);
         v.y = pack_bf16x2(c, d);
+        *(uint2*)((uint16_t*)Y + i) = v;
+    }
+};
+// IEEE binary16; conversions are the hardware's (round-to-nearest-even, exact widening).
+struct FP16 {
+    static constexpr int VEC = 8;
+    static constexpr int BYTES = 2;
+    typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+    __device__ static __forceinline__ void widen(const u32x4& v, float (&f)[8]) {
+        union { u32x4 u; h8 h; } c;
+        c.u = v;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) f[i] = (float)c.h[i];
+    }
+    __device__ static __forceinline__ uint32_t bits(float v) {
+        union { _Float16 h; uint16_t u; } c;
+        c.h = (_Float16)v;
+        return c.u;
+    }
+    __device__ static __forceinline__ void store(void* Y, size_t i, float v) { ((uint16_t*)Y)[i] = (uint16_t)bits(v); }
+    __device__ static __forceinline__ uint32_t pack2(float lo, float hi) { return bits(lo) | (bits(hi) << 16); }
+    __device__ static __forceinline__ void store4(void* Y, size_t i, float a, float b, float c, float d) {
+        uint2 v;
+        v.x = pack2(a, b);
+        v.y = pack2(c, d);
         *(uint2*)((uint16_t*)Y + i) = v;
     }
 };

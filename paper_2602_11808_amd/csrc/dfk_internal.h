@@ -70,7 +70,8 @@ struct MlpArgs {
     int m_count;       // tokens this launch handles (<= kMaxTokensPerLaunch)
     int splits;        // d_ff slices (grid of the fused kernel / first kernel)
     int k2_splits, k2_col_blocks;
-    int a2_is_fp32;    // storage type of A_2 in the workspace (two-kernel variant)
+    int dtype;         // dfk_dtype_t of X, the weights and Y
+    int a2_is_fp32;    // storage type of A_2 in the workspace (two-kernel variant): fp32, else the 16-bit input type
     int reduce_mode;   // dfk_reduce_t
     float* yacc;       // [m_count, d_model] fp32 accumulator, zero on entry and on exit (atomic reduction)
     float* P;          // partial sums [slice][m_count][d_model]

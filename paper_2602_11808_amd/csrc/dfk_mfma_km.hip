@@ -32,6 +32,20 @@
 namespace dfk {
 namespace {
 
+// v_mfma_f32_16x16x32 for the element type: operands are the same 16 bytes per lane either way.
+template <typename E>
+__device__ __forceinline__ f32x4 mfma16(const u32x4& a, const u32x4& b, const f32x4& c);
+template <>
+__device__ __forceinline__ f32x4 mfma16<BF16>(const u32x4& a, const u32x4& b, const f32x4& c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a), as_bf16x8(b), c, 0, 0, 0);
+}
+template <>
+__device__ __forceinline__ f32x4 mfma16<FP16>(const u32x4& a, const u32x4& b, const f32x4& c) {
+    union { u32x4 u; FP16::h8 h; } x, y;
+    x.u = a; y.u = b;
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(x.h, y.h, c, 0, 0, 0);
+}
+
 constexpr int kKmMaxRowTiles = 8;   // row tiles per workgroup of the gate/up kernel (accumulators)
 constexpr int kKmTokensPerLaunch = 64;
 
@@ -103,7 +117,7 @@ struct KmStream1 {
     }
 };
 
-template <int NW, int TT>
+template <int NW, int TT, typename E>
 __global__ __launch_bounds__(NW * 64) void k_gateup_km(MlpArgs a, KmGeom geo) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     constexpr int TOK = 16 * TT;
@@ -150,10 +164,9 @@ __global__ __launch_bounds__(NW * 64) void k_gateup_km(MlpArgs a, KmGeom geo) {
                 const unsigned char* slot = ts.acquire();
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
-                    const bf16x8 av = *(const bf16x8*)(slot + (q * 16 + ((4 * c + g) ^ q)) * 16);
+                    const u32x4 av = *(const u32x4*)(slot + (q * 16 + ((4 * c + g) ^ q)) * 16);
 #pragma unroll
-                    for (int tt = 0; tt < TT; ++tt)
-                        acc[rt][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, as_bf16x8(xk[tt][c]), acc[rt][tt], 0, 0, 0);
+                    for (int tt = 0; tt < TT; ++tt) acc[rt][tt] = mfma16<E>(av, xk[tt][c], acc[rt][tt]);
                 }
             }
         }
@@ -190,7 +203,7 @@ __global__ __launch_bounds__(NW * 64) void k_gateup_km(MlpArgs a, KmGeom geo) {
                     g0 += gv.x; g1 += gv.y; u0 += uv.x; u1 += uv.y;
                 }
                 const size_t o = (size_t)(a.m_base + m) * a.d_ff + j0 + (rt0 + r) * 8 + 2 * pr;
-                *(uint32_t*)((uint16_t*)a.a2 + o) = pack_bf16x2(silu_mul_fast(g0, u0), silu_mul_fast(g1, u1));
+                *(uint32_t*)((uint16_t*)a.a2 + o) = E::pack2(silu_mul_fast(g0, u0), silu_mul_fast(g1, u1));
             }
         }
         __syncthreads();
@@ -272,7 +285,7 @@ struct KmStream2 {
 
 __host__ __device__ constexpr int km_col_blocks(int tt) { return tt >= 4 ? 1 : 2; }   // accumulator budget
 
-template <int NW, int TT>
+template <int NW, int TT, typename E>
 __global__ __launch_bounds__(NW * 64) void k_down_km(MlpArgs a, KmGeom geo) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     __shared__ int flag;
@@ -350,7 +363,7 @@ __global__ __launch_bounds__(NW * 64) void k_down_km(MlpArgs a, KmGeom geo) {
                     for (int p = 0; p < 4; ++p) bb[p] = __builtin_amdgcn_perm(w[2 * p + 1][c >> 1], w[2 * p][c >> 1], sel);
 #pragma unroll
                     for (int tt = 0; tt < TT; ++tt)
-                        acc2[b][c][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(av[tt]), as_bf16x8(bb), acc2[b][c][tt], 0, 0, 0);
+                        acc2[b][c][tt] = mfma16<E>(av[tt], bb, acc2[b][c][tt]);
                 }
             }
         }
@@ -410,11 +423,11 @@ __global__ __launch_bounds__(NW * 64) void k_down_km(MlpArgs a, KmGeom geo) {
             const int m = idx / (width / 2), c2 = idx - m * (width / 2);
             float* src = a.yacc + (size_t)m * a.d_model + blk_lo * 128 + 2 * c2;
             const float v0 = acc_take(src), v1 = acc_take(src + 1);
-            *(uint32_t*)((uint16_t*)a.Y + (size_t)(a.m_base + m) * a.d_model + blk_lo * 128 + 2 * c2) = pack_bf16x2(v0, v1);
+            *(uint32_t*)((uint16_t*)a.Y + (size_t)(a.m_base + m) * a.d_model + blk_lo * 128 + 2 * c2) = E::pack2(v0, v1);
         }
         return;
     }
-    reduce_store<BF16>(plan_column_block(a, cb, blk_lo * 128, blk_lo * 128 + width), a.Y, a.m_base, &flag, a.trace);
+    reduce_store<E>(plan_column_block(a, cb, blk_lo * 128, blk_lo * 128 + width), a.Y, a.m_base, &flag, a.trace);
 }
 
 // ---------------------------------------------------------------- host side
@@ -435,18 +448,18 @@ size_t km_lds_down(const dfk_config_t& c, KmGeom* geo) {
     return std::max((size_t)c.waves * c.depth * kTileBytes, (size_t)c.waves * 16 * 128 * 4);
 }
 
-template <int NW, int TT>
-hipError_t launch_km_t(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
+template <int NW, int TT, typename E>
+hipError_t launch_km_te(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
     static size_t configured1 = 0, configured2 = 0;
     if (g_stage_mask & 1) {
         KmGeom geo;
         const size_t lds = km_lds_gateup(c, TT, a.d_ff, &geo);
         if (lds > configured1) {
-            hipError_t e = hipFuncSetAttribute((const void*)k_gateup_km<NW, TT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            hipError_t e = hipFuncSetAttribute((const void*)k_gateup_km<NW, TT, E>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
             configured1 = lds;
         }
-        hipLaunchKernelGGL((k_gateup_km<NW, TT>), dim3(a.splits), dim3(NW * 64), lds, st, a, geo);
+        hipLaunchKernelGGL((k_gateup_km<NW, TT, E>), dim3(a.splits), dim3(NW * 64), lds, st, a, geo);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -454,14 +467,19 @@ hipError_t launch_km_t(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) 
         KmGeom geo;
         const size_t lds = km_lds_down(c, &geo);
         if (lds > configured2) {
-            hipError_t e = hipFuncSetAttribute((const void*)k_down_km<NW, TT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            hipError_t e = hipFuncSetAttribute((const void*)k_down_km<NW, TT, E>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
             configured2 = lds;
         }
-        hipLaunchKernelGGL((k_down_km<NW, TT>), dim3(a.k2_splits * a.k2_col_blocks), dim3(NW * 64), lds, st, a, geo);
+        hipLaunchKernelGGL((k_down_km<NW, TT, E>), dim3(a.k2_splits * a.k2_col_blocks), dim3(NW * 64), lds, st, a, geo);
         return hipGetLastError();
     }
     return hipSuccess;
+}
+
+template <int NW, int TT>
+hipError_t launch_km_t(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
+    return a.dtype == DFK_FP16 ? launch_km_te<NW, TT, FP16>(a, c, st) : launch_km_te<NW, TT, BF16>(a, c, st);
 }
 
 }  // namespace
@@ -469,8 +487,8 @@ hipError_t launch_km_t(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) 
 int mfma_km_tokens_per_launch() { return kKmTokensPerLaunch; }
 
 bool mfma_km_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype) {
-    if (c.path != DFK_PATH_MFMA || dtype != DFK_BF16 || c.variant != DFK_VARIANT_TWO_KERNEL) return false;
-    if (c.kmajor != 1 || c.k2_rows_by_wave != 0 || c.a2_dtype != DFK_BF16) return false;
+    if (c.path != DFK_PATH_MFMA || (dtype != DFK_BF16 && dtype != DFK_FP16) || c.variant != DFK_VARIANT_TWO_KERNEL) return false;
+    if (c.kmajor != 1 || c.k2_rows_by_wave != 0 || c.a2_dtype != (int)dtype) return false;   // A_2 in the inputs' 16-bit type
     if (c.reduce != DFK_REDUCE_TICKET && c.reduce != DFK_REDUCE_ATOMIC) return false;
     if ((c.waves != 4 && c.waves != 8) || c.depth < 2 || c.depth > 16) return false;
     if (M < 1 || d_model < 8 || d_ff < 8 || d_ff % 8 || d_model > kMaxDModel) return false;

@@ -19,12 +19,13 @@ __device__ __forceinline__ uint32_t mix32(uint32_t x) {
     return x;
 }
 
-__global__ void k_fill(void* dst, size_t n, int is_fp32, float scale, uint32_t seed) {
+__global__ void k_fill(void* dst, size_t n, int dtype, float scale, uint32_t seed) {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
         const uint32_t h = mix32((uint32_t)i * 0x9E3779B9u + mix32(seed + (uint32_t)(i >> 32)));
         const float u = ((float)(h >> 8) * (1.0f / 8388608.0f) - 1.0f) * scale;  // (-scale, scale)
-        if (is_fp32) ((float*)dst)[i] = u;
+        if (dtype == DFK_FP32) ((float*)dst)[i] = u;
+        else if (dtype == DFK_FP16) FP16::store(dst, i, u);
         else ((uint16_t*)dst)[i] = (uint16_t)f32_to_bf16_bits(u);
     }
 }
@@ -94,7 +95,7 @@ hipError_t launch_fill(void* dst, size_t elems, dfk_dtype_t dtype, float scale, 
     if (blocks < 1) blocks = 1;
     if (blocks > 8192) blocks = 8192;
     hipLaunchKernelGGL(k_fill, dim3((unsigned)blocks), dim3(256), 0, st, dst, elems,
-                       dtype == DFK_FP32 ? 1 : 0, scale, seed);
+                       (int)dtype, scale, seed);
     return hipGetLastError();
 }
 

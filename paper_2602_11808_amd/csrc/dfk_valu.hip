@@ -197,7 +197,6 @@ hipError_t launch_e(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
 }  // namespace
 
 bool valu_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype) {
-    (void)dtype;
     if (c.path != DFK_PATH_VALU) return false;
     if (c.variant != DFK_VARIANT_FUSED && c.variant != DFK_VARIANT_TWO_KERNEL) return false;
     if (c.kmajor != 0) return false;
@@ -215,12 +214,13 @@ bool valu_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_
     }
     if (c.variant == DFK_VARIANT_TWO_KERNEL) {
         if (c.k2_splits < 1 || c.k2_splits > ng) return false;
-        const int nchunk = d_model / (dtype == DFK_BF16 ? 8 : 4);
+        const int nchunk = d_model / (dtype == DFK_FP32 ? 4 : 8);
         if (c.k2_col_blocks < 1 || c.k2_col_blocks > nchunk || c.k2_col_blocks > kTicketLevel2) return false;
         if (!partials_fit(c.k2_splits, tokens, M, d_model)) return false;
         if ((long long)c.k2_splits * c.k2_col_blocks > 65535) return false;
         if ((long long)mt * max_slice_rows(d_ff, c.k2_splits) > kMaxRowsLds * 8) return false;
-        if (c.a2_dtype != DFK_BF16 && c.a2_dtype != DFK_FP32) return false;
+        // A_2 between the kernels: fp32, or bf16 with bf16 inputs
+        if (c.a2_dtype != DFK_FP32 && !(c.a2_dtype == DFK_BF16 && dtype == DFK_BF16)) return false;
     }
     return true;
 }
@@ -228,7 +228,7 @@ bool valu_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_
 int valu_max_tokens_per_launch() { return 8; }
 
 hipError_t launch_valu(const MlpArgs& a, const dfk_config_t& c, dfk_dtype_t dtype, hipStream_t st) {
-    return dtype == DFK_BF16 ? launch_e<BF16>(a, c, st) : launch_e<FP32>(a, c, st);
+    return dtype == DFK_BF16 ? launch_e<BF16>(a, c, st) : dtype == DFK_FP16 ? launch_e<FP16>(a, c, st) : launch_e<FP32>(a, c, st);
 }
 
 }  // namespace dfk

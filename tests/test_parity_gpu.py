@@ -11,7 +11,7 @@ import torch
 import dfk_inputs as di
 import paper_2602_11808_amd as dfk
 from oracle import oracle
-from tests.helpers import TOL_BF16, TOL_FP32, rel_err
+from tests.helpers import TOL_BF16, TOL_FP16, TOL_FP32, rel_err
 
 pytestmark = pytest.mark.gpu
 
@@ -19,11 +19,11 @@ DEV = "cuda:0"
 
 
 def _dt(dtype):
-    return dfk.DFK_BF16 if dtype == "bf16" else dfk.DFK_FP32
+    return {"bf16": dfk.DFK_BF16, "fp32": dfk.DFK_FP32, "fp16": dfk.DFK_FP16}[dtype]
 
 
 def _tol(dtype):
-    return TOL_BF16 if dtype == "bf16" else TOL_FP32
+    return {"bf16": TOL_BF16, "fp32": TOL_FP32, "fp16": TOL_FP16}[dtype]
 
 
 def gpu_inputs(t):
@@ -65,7 +65,7 @@ SMALL = [
 ]
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+@pytest.mark.parametrize("dtype", ["bf16", "fp32", "fp16"])
 @pytest.mark.parametrize("shape", SMALL, ids=lambda s: "M%d_d%d_ff%d" % s)
 def test_every_candidate_matches_oracle_small(shape, dtype):
     M, d, ff = shape
@@ -183,6 +183,41 @@ def test_kernels_for_up_to_64_tokens_per_launch(shape):
             err = rel_err(y64(Y), ref)
             assert err <= TOL_BF16, (shape, cfg, err)
             assert workspace_is_clean(ws, M, d), (shape, cfg)
+
+
+@pytest.mark.parametrize("shape", [(1, 1024, 2816), (16, 512, 4104), (33, 1024, 2816), (64, 2048, 4104), (70, 1024, 2816),
+                                   (4, 4096, 14336), (64, 4096, 14336)],
+                         ids=lambda s: "M%d_d%d_ff%d" % s)
+def test_half_precision_inputs(shape):
+    """IEEE half inputs and outputs (the precision the paper evaluates in): every candidate,
+    MFMA pair and VALU kernels, against the oracle on the same half bit patterns."""
+    M, d, ff = shape
+    big = d * ff > 1 << 24
+    t = di.mlp_inputs(M, d, ff, seed=13, dtype="fp16") if not big else None
+    if big:
+        g = di.mlp_inputs_torch(M, d, ff, seed=13, dtype="fp16", device=DEV)
+        t = {k: di.to_numpy(v) for k, v in g.items()}
+    else:
+        g = gpu_inputs(t)
+    ref = oracle.swiglu_mlp(t["X"], t["Wg"], t["Wu"], t["Wd"])
+    ws = dfk.new_workspace(M, d, ff, DEV)
+    n = dfk.dfk_num_candidates(M, d, ff, dfk.DFK_FP16)
+    cfgs = [dfk.dfk_get_candidate(M, d, ff, dfk.DFK_FP16, i) for i in range(n)]
+    assert any(c.path == dfk.DFK_PATH_VALU for c in cfgs)
+    assert any(c.path == dfk.DFK_PATH_MFMA and c.kmajor == 1 for c in cfgs)
+    if big:   # the VALU kernels are slow at full size: the MFMA pair and one VALU candidate
+        cfgs = [c for c in cfgs if c.path == dfk.DFK_PATH_MFMA][:4] + [c for c in cfgs if c.path == dfk.DFK_PATH_VALU][:1]
+    for cfg in cfgs:
+        print("case", shape, cfg, flush=True)
+        Y, _ = run_ex(g, cfg, ws)
+        assert Y.dtype == torch.float16
+        err = rel_err(y64(Y), ref)
+        assert err <= TOL_FP16, (shape, cfg, err)
+        assert workspace_is_clean(ws, M, d), (shape, cfg)
+    # scheduler's choice through the explicit entry point
+    Y = torch.empty_like(g["X"])
+    dfk.dfk_swiglu_mlp_ex(g["X"], g["Wg"], g["Wu"], g["Wd"], Y, None, ws)
+    assert rel_err(y64(Y), ref) <= TOL_FP16
 
 
 def test_degenerate_inputs():
