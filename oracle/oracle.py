@@ -53,6 +53,10 @@ def _load():
         lib.oracle_gate_up_silu.argtypes = [vp, vp, vp, dp, dp, dp, ci, ci, ci, ci, ci]
         lib.oracle_down.restype = ci
         lib.oracle_down.argtypes = [dp, vp, dp, ci, ci, ci, ci, ci]
+        lib.oracle_rmsnorm.restype = ci
+        lib.oracle_rmsnorm.argtypes = [vp, vp, dp, ci, ci, ci, ctypes.c_double]
+        lib.oracle_mlp_block.restype = ci
+        lib.oracle_mlp_block.argtypes = [vp, vp, ctypes.c_double, vp, vp, vp, dp, ci, ci, ci, ci, ci]
         lib.oracle_swiglu_mlp.restype = ci
         lib.oracle_swiglu_mlp.argtypes = [vp, vp, vp, vp, dp, ci, ci, ci, ci, ci]
         _lib = lib
@@ -141,4 +145,42 @@ def swiglu_mlp(X, Wg, Wu, Wd, nthreads: int | None = None):
         M, d_model, d_ff, code, nthreads or default_threads())
     if rc != 0:
         raise RuntimeError(f"oracle_swiglu_mlp failed with {rc}")
+    return Y
+
+
+def rmsnorm(H, w=None, eps: float = 0.0):
+    """N = H * w / sqrt(mean_k(H^2) + eps) row by row, float64 [M, d_model] (w None = ones)."""
+    H = np.ascontiguousarray(H)
+    code = _dtype_code(H)
+    M, d_model = H.shape
+    wp = None
+    if w is not None:
+        w = _prep(w, (d_model,), code)
+        wp = w.ctypes.data
+    N = np.empty((M, d_model), np.float64)
+    rc = _load().oracle_rmsnorm(H.ctypes.data, wp, _dptr(N), M, d_model, code, float(eps))
+    if rc != 0:
+        raise RuntimeError(f"oracle_rmsnorm failed with {rc}")
+    return N
+
+
+def mlp_block(H, w, eps, Wg, Wu, Wd, nthreads: int | None = None):
+    """H_out = H + SwiGLU_MLP(RMSNorm(H; w, eps)), float64 [M, d_model]."""
+    H = np.ascontiguousarray(H)
+    code = _dtype_code(H)
+    M, d_model = H.shape
+    d_ff = Wg.shape[0]
+    Wg = _prep(Wg, (d_ff, d_model), code)
+    Wu = _prep(Wu, (d_ff, d_model), code)
+    Wd = _prep(Wd, (d_ff, d_model), code)
+    wp = None
+    if w is not None:
+        w = _prep(w, (d_model,), code)
+        wp = w.ctypes.data
+    Y = np.empty((M, d_model), np.float64)
+    rc = _load().oracle_mlp_block(H.ctypes.data, wp, float(eps), Wg.ctypes.data, Wu.ctypes.data,
+                                  Wd.ctypes.data, _dptr(Y), M, d_model, d_ff, code,
+                                  nthreads or default_threads())
+    if rc != 0:
+        raise RuntimeError(f"oracle_mlp_block failed with {rc}")
     return Y

@@ -42,6 +42,7 @@
 #define ORACLE_BF16 0
 #define ORACLE_FP32 1
 #define ORACLE_FP16 2
+#define ORACLE_FP64 3   /* internal: X already in fp64 (the normalised input of the decoder-layer form) */
 
 /* Exact widening of one stored element to fp64. */
 static double widen(const void *base, size_t idx, int dtype)
@@ -62,6 +63,7 @@ static double widen(const void *base, size_t idx, int dtype)
         else v = ldexp((double)(1024 + frac), e - 25);             /* (1 + frac/1024) * 2^(e-15) */
         return sign ? -v : v;
     }
+    if (dtype == ORACLE_FP64) return ((const double *)base)[idx];
     return (double)((const float *)base)[idx];
 }
 
@@ -75,6 +77,7 @@ typedef struct {
     const void *X, *Wg, *Wu, *Wd;
     double *G, *U, *A2, *Y;
     int M, d_model, d_ff, dtype;
+    int xdtype; /* element type of X (= dtype, or ORACLE_FP64) */
     int lo, hi; /* this thread's range of columns */
 } job_t;
 
@@ -88,7 +91,7 @@ static void *stage_one(void *arg)
         for (int m = 0; m < t->M; ++m) {
             double g = 0.0, u = 0.0;
             for (int k = 0; k < t->d_model; ++k) {
-                double x = widen(t->X, (size_t)m * t->d_model + k, t->dtype);
+                double x = widen(t->X, (size_t)m * t->d_model + k, t->xdtype);
                 g += x * widen(t->Wg, (size_t)j * t->d_model + k, t->dtype);
                 u += x * widen(t->Wu, (size_t)j * t->d_model + k, t->dtype);
             }
@@ -152,7 +155,7 @@ int oracle_gate_up_silu(const void *X, const void *Wg, const void *Wu,
     job_t p;
     memset(&p, 0, sizeof p);
     p.X = X; p.Wg = Wg; p.Wu = Wu; p.G = G; p.U = U; p.A2 = A2;
-    p.M = M; p.d_model = d_model; p.d_ff = d_ff; p.dtype = dtype;
+    p.M = M; p.d_model = d_model; p.d_ff = d_ff; p.dtype = dtype; p.xdtype = dtype;
     return run_partitioned(stage_one, &p, d_ff, nthreads);
 }
 
@@ -179,5 +182,58 @@ int oracle_swiglu_mlp(const void *X, const void *Wg, const void *Wu, const void 
     int rc = oracle_gate_up_silu(X, Wg, Wu, NULL, NULL, A2, M, d_model, d_ff, dtype, nthreads);
     if (rc == 0) rc = oracle_down(A2, Wd, Y, M, d_model, d_ff, dtype, nthreads);
     free(A2);
+    return rc;
+}
+
+/*
+ * Weighted RMS normalisation of every row, in fp64, nothing rounded:
+ *   N[m,k] = H[m,k] * w[k] / sqrt( (1/d_model) sum_k H[m,k]^2 + eps ).
+ * (The pre-normalisation of a decoder layer's MLP sub-block; not part of the
+ * paper's block, which starts at X.  w == NULL means w = 1.)
+ */
+int oracle_rmsnorm(const void *H, const void *w, double *N, int M, int d_model, int dtype, double eps)
+{
+    if (!H || !N || M < 1 || d_model < 1) return -1;
+    if (dtype != ORACLE_BF16 && dtype != ORACLE_FP32 && dtype != ORACLE_FP16) return -1;
+    for (int m = 0; m < M; ++m) {
+        double ss = 0.0;
+        for (int k = 0; k < d_model; ++k) {
+            double h = widen(H, (size_t)m * d_model + k, dtype);
+            ss += h * h;
+        }
+        double r = sqrt(ss / (double)d_model + eps);
+        for (int k = 0; k < d_model; ++k) {
+            double h = widen(H, (size_t)m * d_model + k, dtype);
+            double wk = w ? widen(w, (size_t)k, dtype) : 1.0;
+            N[(size_t)m * d_model + k] = h * wk / r;
+        }
+    }
+    return 0;
+}
+
+/*
+ * The MLP sub-block of a pre-norm decoder layer around the paper's block:
+ *   H_out = H + SwiGLU_MLP( RMSNorm(H; w, eps) ),   H_out in fp64.
+ */
+int oracle_mlp_block(const void *H, const void *w, double eps,
+                     const void *Wg, const void *Wu, const void *Wd,
+                     double *Y, int M, int d_model, int d_ff, int dtype, int nthreads)
+{
+    if (!H || !Wg || !Wu || !Wd || !Y || M < 1 || d_model < 1 || d_ff < 1) return -1;
+    double *N = (double *)malloc(sizeof(double) * (size_t)M * (size_t)d_model);
+    double *A2 = (double *)malloc(sizeof(double) * (size_t)M * (size_t)d_ff);
+    if (!N || !A2) { free(N); free(A2); return -2; }
+    int rc = oracle_rmsnorm(H, w, N, M, d_model, dtype, eps);
+    if (rc == 0) {
+        job_t p;
+        memset(&p, 0, sizeof p);
+        p.X = N; p.Wg = Wg; p.Wu = Wu; p.A2 = A2;
+        p.M = M; p.d_model = d_model; p.d_ff = d_ff; p.dtype = dtype; p.xdtype = ORACLE_FP64;
+        rc = run_partitioned(stage_one, &p, d_ff, nthreads);
+    }
+    if (rc == 0) rc = oracle_down(A2, Wd, Y, M, d_model, d_ff, dtype, nthreads);
+    if (rc == 0)
+        for (size_t i = 0; i < (size_t)M * (size_t)d_model; ++i) Y[i] += widen(H, i, dtype);
+    free(N); free(A2);
     return rc;
 }

@@ -285,3 +285,64 @@ def test_golden_tiny_config_is_reproduced():
     assert want.shape == (512,)
     np.testing.assert_array_equal(got, want)
     assert 0.1 < np.abs(want).max() < 10.0     # well-scaled for the max-normalised metric
+
+
+# ---- the decoder-layer form around the block: H + MLP(RMSNorm(H; w, eps)) ----
+
+def test_rmsnorm_by_hand_and_closed_forms():
+    # 3-4-5: mean square 12.5
+    h = np.array([[3.0, 4.0]], np.float32)
+    np.testing.assert_allclose(oracle.rmsnorm(h), [[3 / math.sqrt(12.5), 4 / math.sqrt(12.5)]], rtol=1e-15)
+    # a constant row normalises to its sign times w; eps shifts the denominator
+    c = np.full((1, 8), -2.5, np.float32)
+    w = np.arange(1, 9, dtype=np.float32)
+    np.testing.assert_allclose(oracle.rmsnorm(c, w), [-w.astype(np.float64)], rtol=1e-15)
+    np.testing.assert_allclose(oracle.rmsnorm(c, w, eps=6.25), [-w.astype(np.float64) * 2.5 / math.sqrt(12.5)], rtol=1e-15)
+    # zero row stays zero with eps > 0
+    np.testing.assert_array_equal(oracle.rmsnorm(np.zeros((2, 4), np.float32), None, eps=1e-6), np.zeros((2, 4)))
+
+
+def test_rmsnorm_invariants_and_numpy_route():
+    t = di.mlp_inputs(5, 96, 8, seed=91, dtype="fp32")
+    H = t["X"]
+    w = di.tensor(92, (96,), 1.0, "fp32")
+    N = oracle.rmsnorm(H, w)
+    H64, w64 = H.astype(np.float64), w.astype(np.float64)
+    np.testing.assert_allclose(N, H64 * w64 / np.sqrt((H64 ** 2).mean(axis=1, keepdims=True)), rtol=1e-13)
+    # unit mean square before the weight; invariance under a positive power-of-two scaling of H
+    np.testing.assert_allclose(((N / w64) ** 2).mean(axis=1), np.ones(5), rtol=1e-13)
+    np.testing.assert_allclose(oracle.rmsnorm(H * np.float32(4.0), w), N, rtol=1e-14)
+    np.testing.assert_allclose(oracle.rmsnorm(-H, w), -N, rtol=1e-15)
+    # rows are independent; w = None is w = 1
+    np.testing.assert_array_equal(oracle.rmsnorm(H[2:3], w), N[2:3])
+    np.testing.assert_array_equal(oracle.rmsnorm(H, None), oracle.rmsnorm(H, np.ones(96, np.float32)))
+    # 16-bit inputs are widened exactly
+    for dt in ("bf16", "fp16"):
+        Hb, wb = di.tensor(93, (3, 40), 1.0, dt), di.tensor(94, (40,), 1.0, dt)
+        np.testing.assert_array_equal(oracle.rmsnorm(Hb, wb, 1e-5),
+                                      oracle.rmsnorm(di.as_f64(Hb).astype(np.float32), di.as_f64(wb).astype(np.float32), 1e-5))
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16", "fp16"])
+def test_mlp_block_is_residual_plus_block_of_normalised_input(dtype):
+    t = di.mlp_inputs(3, 64, 72, seed=95, dtype=dtype)
+    w = di.tensor(96, (64,), 1.0, dtype)
+    eps = 1e-5
+    got = oracle.mlp_block(t["X"], w, eps, t["Wg"], t["Wu"], t["Wd"])
+    # composed by hand from the pinned pieces, through numpy's dgemm
+    H = di.as_f64(t["X"])
+    N = H * di.as_f64(w) / np.sqrt((H ** 2).mean(axis=1, keepdims=True) + eps)
+    G, U = N @ di.as_f64(t["Wg"]).T, N @ di.as_f64(t["Wu"]).T
+    want = H + (U * G / (1.0 + np.exp(-G))) @ di.as_f64(t["Wd"])
+    np.testing.assert_allclose(got, want, rtol=1e-11, atol=1e-13)
+    # W_down = 0: the residual alone, exactly; w = 1, huge H: the block sees unit-scale input
+    zero = np.zeros_like(t["Wd"])
+    np.testing.assert_array_equal(oracle.mlp_block(t["X"], w, eps, t["Wg"], t["Wu"], zero), H)
+    # the normalised input is scale-free: H and 2H differ in the output only by the residual
+    if dtype == "fp32":
+        a = oracle.mlp_block(t["X"], w, 0.0, t["Wg"], t["Wu"], t["Wd"]) - H
+        b = oracle.mlp_block(t["X"] * np.float32(2), w, 0.0, t["Wg"], t["Wu"], t["Wd"]) - 2 * H
+        np.testing.assert_allclose(a, b, rtol=1e-12, atol=1e-14)
+    # thread count does not change a bit
+    np.testing.assert_array_equal(oracle.mlp_block(t["X"], w, eps, t["Wg"], t["Wu"], t["Wd"], nthreads=1),
+                                  oracle.mlp_block(t["X"], w, eps, t["Wg"], t["Wu"], t["Wd"], nthreads=5))
