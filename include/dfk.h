@@ -159,6 +159,34 @@ dfk_status_t dfk_swiglu_mlp_ex(const void* X, const void* W_gate, const void* W_
                                const dfk_config_t* cfg,
                                void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * The block together with its two neighbours in a pre-norm decoder layer.  This goes one
+ * step beyond the paper's operator, which starts at X and ends at Y (Method); in the
+ * Llama-style models of the Experiments section an RMS normalisation produces X and a
+ * residual add consumes Y, each a separate pass over [M, d_model] otherwise:
+ *
+ *     H_out = H + SwiGLU_MLP( RMSNorm(H; norm_weight, eps) )
+ *     RMSNorm(H; w, eps)[m,k] = H[m,k] * w[k] / sqrt( mean_k H[m,k]^2 + eps )
+ *
+ * in the same two launches as the plain block: the gate/up kernel scales its X operand by
+ * norm_weight, sums the squares of the H values it streams anyway and applies the
+ * per-token factor to its fp32 sums; the down kernel adds H at its final store.
+ *
+ * H, H_out [M, d_model], norm_weight [d_model], weights as above; dtype DFK_BF16 or
+ * DFK_FP16 (DFK_FP32: DFK_ERR_UNSUPPORTED_SHAPE).  H_out may be H itself (in place); any
+ * other overlap is DFK_ERR_ALIAS.  eps >= 0; a row of zeros with eps == 0 yields NaN, as
+ * the definition does.  The product H[m,k] * w[k] is rounded once to dtype before the
+ * contraction (with half inputs it must stay finite in half precision).
+ * Runs on the kernel pair for up to 64 tokens per launch only (cfg->kmajor == 1;
+ * cfg == NULL picks the scheduler's choice among those): shapes that pair does not cover
+ * give DFK_ERR_UNSUPPORTED_SHAPE.  Workspace as for dfk_swiglu_mlp_ex.
+ */
+dfk_status_t dfk_mlp_block(const void* H, const void* norm_weight, float eps,
+                           const void* W_gate, const void* W_up, const void* W_down,
+                           void* H_out, int M, int d_model, int d_ff, dfk_dtype_t dtype,
+                           const dfk_config_t* cfg,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
 /* Host-only argument check: exactly the validation the calls above perform,
  * with no HIP call.  cfg may be NULL.  workspace may be NULL only if
  * workspace_bytes is 0, in which case the workspace checks are skipped. */

@@ -61,6 +61,7 @@ SIGNATURES = [
     ("dfk_swiglu_mlp_fused", _ci, [_vp] * 5 + [_ci] * 3 + [_vp]),
     ("dfk_swiglu_mlp_unfused", _ci, [_vp] * 5 + [_ci] * 3 + [_vp]),
     ("dfk_swiglu_mlp_ex", _ci, [_vp] * 5 + [_ci] * 4 + [_cfgp, _vp, _sz, _vp]),
+    ("dfk_mlp_block", _ci, [_vp, _vp, ctypes.c_float] + [_vp] * 4 + [_ci] * 4 + [_cfgp, _vp, _sz, _vp]),
     ("dfk_check_args", _ci, [_vp] * 5 + [_ci] * 4 + [_cfgp, _vp, _sz]),
     ("dfk_workspace_bytes", _sz, [_ci] * 3),
     ("dfk_workspace_init", _ci, [_vp, _sz, _vp]),
@@ -174,6 +175,20 @@ def dfk_swiglu_mlp_ex(X, W_gate, W_up, W_down, Y, cfg: Optional[dfk_config_t], w
     _check(lib().dfk_swiglu_mlp_ex(_ptr(X), _ptr(W_gate), _ptr(W_up), _ptr(W_down), _ptr(Y), M, d, ff,
                                    _dtype_code(X), ctypes.byref(cfg) if cfg is not None else None,
                                    _ptr(workspace), nbytes, _stream(stream)), "dfk_swiglu_mlp_ex")
+
+
+def dfk_mlp_block(H, norm_weight, eps: float, W_gate, W_up, W_down, H_out, cfg: Optional[dfk_config_t], workspace,
+                  stream=None):
+    """H_out = H + SwiGLU_MLP(RMSNorm(H; norm_weight, eps)); H_out may be H itself."""
+    M, d, ff = _shapes(H, W_gate, W_up, W_down, H_out)
+    if not norm_weight.is_cuda or not norm_weight.is_contiguous() or norm_weight.dtype != H.dtype \
+            or tuple(norm_weight.shape) != (d,):
+        raise ValueError("norm_weight must be a dense device vector [d_model] of the inputs' type")
+    nbytes = workspace.numel() * workspace.element_size()
+    _check(lib().dfk_mlp_block(_ptr(H), _ptr(norm_weight), float(eps), _ptr(W_gate), _ptr(W_up), _ptr(W_down),
+                               _ptr(H_out), M, d, ff, _dtype_code(H),
+                               ctypes.byref(cfg) if cfg is not None else None,
+                               _ptr(workspace), nbytes, _stream(stream)), "dfk_mlp_block")
 
 
 def dfk_check_args(X, W_gate, W_up, W_down, Y, M, d_model, d_ff, dtype=DFK_BF16, cfg=None,

@@ -46,7 +46,7 @@ bool config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype
 
 dfk_status_t check(const void* X, const void* Wg, const void* Wu, const void* Wd, const void* Y,
                    int M, int d_model, int d_ff, dfk_dtype_t dtype, const dfk_config_t* cfg,
-                   const void* ws, size_t ws_bytes, bool need_ws) {
+                   const void* ws, size_t ws_bytes, bool need_ws, bool y_may_be_x = false) {
     if (!X || !Wg || !Wu || !Wd || !Y) return DFK_ERR_INVALID_ARG;
     if (M < 1 || d_model < 1 || d_ff < 1) return DFK_ERR_INVALID_ARG;
     if (dtype != DFK_BF16 && dtype != DFK_FP32 && dtype != DFK_FP16) return DFK_ERR_INVALID_ARG;
@@ -56,7 +56,7 @@ dfk_status_t check(const void* X, const void* Wg, const void* Wu, const void* Wd
         if ((uintptr_t)p % 16) return DFK_ERR_ALIGNMENT;
     const size_t eb = elt_bytes(dtype);
     const size_t nx = (size_t)M * d_model * eb, nw = (size_t)d_ff * d_model * eb;
-    if (overlaps(Y, nx, X, nx) || overlaps(Y, nx, Wg, nw) || overlaps(Y, nx, Wu, nw) ||
+    if ((!(y_may_be_x && Y == X) && overlaps(Y, nx, X, nx)) || overlaps(Y, nx, Wg, nw) || overlaps(Y, nx, Wu, nw) ||
         overlaps(Y, nx, Wd, nw))
         return DFK_ERR_ALIAS;
     if (cfg) {
@@ -228,9 +228,11 @@ bool choose(int M, int d_model, int d_ff, dfk_dtype_t dtype, int want_variant, d
 }
 
 // ---------------------------------------------------------------- dispatch
+// norm_w / eps / resid: the pre-norm residual form (kernel pair for up to 64 tokens only,
+// checked by the caller); NULL / 0 / NULL for the plain block.
 dfk_status_t run(const void* X, const void* Wg, const void* Wu, const void* Wd, void* Y, int M,
                  int d_model, int d_ff, dfk_dtype_t dtype, const dfk_config_t& c, void* ws,
-                 hipStream_t st) {
+                 hipStream_t st, const void* norm_w = nullptr, float eps = 0.f, const void* resid = nullptr) {
     const WsLayout l = ws_layout(M, d_model, d_ff);
     MlpArgs a;
     std::memset(&a, 0, sizeof a);
@@ -245,6 +247,7 @@ dfk_status_t run(const void* X, const void* Wg, const void* Wu, const void* Wd, 
     a.P = (float*)((char*)ws + l.p_off);
     a.Q = (float*)((char*)ws + l.q_off);
     a.a2 = (char*)ws + l.a2_off;
+    a.norm_w = norm_w; a.eps = eps; a.resid = resid;
     a.trace = nullptr;
     {
         const size_t grid = (size_t)std::max(c.splits, c.k2_splits * std::max(1, c.k2_col_blocks));
@@ -401,6 +404,35 @@ dfk_status_t dfk_swiglu_mlp_ex(const void* X, const void* Wg, const void* Wu, co
                                void* stream) {
     return call(X, Wg, Wu, Wd, Y, M, d_model, d_ff, dtype, cfg, DFK_VARIANT_AUTO, workspace,
                 workspace_bytes, stream);
+}
+
+dfk_status_t dfk_mlp_block(const void* H, const void* norm_weight, float eps, const void* Wg,
+                           const void* Wu, const void* Wd, void* H_out, int M, int d_model, int d_ff,
+                           dfk_dtype_t dtype, const dfk_config_t* cfg, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+    if (!H || !norm_weight || !H_out) return DFK_ERR_INVALID_ARG;
+    if (!(eps >= 0.f) || !(eps < 1e30f)) return DFK_ERR_INVALID_ARG;
+    if (dtype != DFK_BF16 && dtype != DFK_FP16)
+        return dtype == DFK_FP32 ? DFK_ERR_UNSUPPORTED_SHAPE : DFK_ERR_INVALID_ARG;
+    if ((uintptr_t)norm_weight % 16) return DFK_ERR_ALIGNMENT;
+    // The output may be the input itself (the residual stream updated in place); any other
+    // overlap is refused.
+    dfk_status_t s = check(H, Wg, Wu, Wd, H_out, M, d_model, d_ff, dtype, cfg, workspace, workspace_bytes, true, true);
+    if (s != DFK_OK) return s;
+    {
+        const size_t nx = (size_t)M * d_model * 2, nv = (size_t)d_model * 2;
+        if (overlaps(H_out, nx, norm_weight, nv) || overlaps(workspace, workspace_bytes, norm_weight, nv))
+            return DFK_ERR_ALIAS;
+    }
+    dfk_config_t c;
+    if (cfg) c = *cfg;
+    else {
+        if (!choose(M, d_model, d_ff, dtype, DFK_VARIANT_TWO_KERNEL, &c, nullptr)) return DFK_ERR_UNSUPPORTED_SHAPE;
+        if (!c.kmajor && !heuristic(M, d_model, d_ff, dtype, DFK_VARIANT_TWO_KERNEL, &c)) return DFK_ERR_UNSUPPORTED_SHAPE;
+    }
+    if (c.path != DFK_PATH_MFMA || !c.kmajor || !mfma_km_block_config_valid(c, M, d_model, d_ff, dtype))
+        return DFK_ERR_UNSUPPORTED_SHAPE;
+    return run(H, Wg, Wu, Wd, H_out, M, d_model, d_ff, dtype, c, workspace, (hipStream_t)stream, norm_weight, eps, H);
 }
 
 dfk_status_t dfk_check_args(const void* X, const void* Wg, const void* Wu, const void* Wd,

@@ -21,8 +21,13 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
     if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x0040u;
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
+// Two at once: the hardware's packed conversion (v_cvt_pk_bf16_f32, also round-to-nearest-even).
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-    return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    union { bf16x2_t b; uint32_t u; } c;
+    c.b = __builtin_convertvector(f32x2_t{lo, hi}, bf16x2_t);
+    return c.u;
 }
 
 // SiLU(g) * u  (Background, SwiGLU equations): Sigmoid(g) * g * u.
@@ -50,6 +55,14 @@ struct BF16 {
         ((uint16_t*)Y)[i] = (uint16_t)f32_to_bf16_bits(v);
     }
     __device__ static __forceinline__ uint32_t pack2(float lo, float hi) { return pack_bf16x2(lo, hi); }
+    __device__ static __forceinline__ void widen2(uint32_t packed, float& lo, float& hi) {
+        lo = bf16_lo(packed); hi = bf16_hi(packed);
+    }
+    // four consecutive elements, i a multiple of 4
+    __device__ static __forceinline__ void load4(const void* p, size_t i, float (&f)[4]) {
+        const uint2 v = *(const uint2*)((const uint16_t*)p + i);
+        widen2(v.x, f[0], f[1]); widen2(v.y, f[2], f[3]);
+    }
     // four consecutive outputs, i a multiple of 4
     __device__ static __forceinline__ void store4(void* Y, size_t i, float a, float b, float c, float d) {
         uint2 v;
@@ -76,6 +89,15 @@ struct FP16 {
     }
     __device__ static __forceinline__ void store(void* Y, size_t i, float v) { ((uint16_t*)Y)[i] = (uint16_t)bits(v); }
     __device__ static __forceinline__ uint32_t pack2(float lo, float hi) { return bits(lo) | (bits(hi) << 16); }
+    __device__ static __forceinline__ void widen2(uint32_t packed, float& lo, float& hi) {
+        union { uint32_t u; _Float16 h[2]; } c;
+        c.u = packed;
+        lo = (float)c.h[0]; hi = (float)c.h[1];
+    }
+    __device__ static __forceinline__ void load4(const void* p, size_t i, float (&f)[4]) {
+        const uint2 v = *(const uint2*)((const uint16_t*)p + i);
+        widen2(v.x, f[0], f[1]); widen2(v.y, f[2], f[3]);
+    }
     __device__ static __forceinline__ void store4(void* Y, size_t i, float a, float b, float c, float d) {
         uint2 v;
         v.x = pack2(a, b);
@@ -91,6 +113,10 @@ struct FP32 {
         f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
     }
     __device__ static __forceinline__ void store(void* Y, size_t i, float v) { ((float*)Y)[i] = v; }
+    __device__ static __forceinline__ void load4(const void* p, size_t i, float (&f)[4]) {
+        const float4 v = *(const float4*)((const float*)p + i);
+        f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+    }
     __device__ static __forceinline__ void store4(void* Y, size_t i, float a, float b, float c, float d) {
         *(float4*)((float*)Y + i) = make_float4(a, b, c, d);
     }
@@ -223,9 +249,20 @@ __device__ __forceinline__ void sum_blocks2(const float* base, size_t stride, in
     }
 }
 
+// Final store of four consecutive outputs: the sum, plus the residual input at the same
+// position when there is one (it may be the output buffer itself: each element is read
+// and then written by this one thread).
+template <typename E>
+__device__ __forceinline__ void store4_plus(void* Y, const void* resid, size_t i, const float4& v) {
+    if (!resid) { E::store4(Y, i, v.x, v.y, v.z, v.w); return; }
+    float r[4];
+    E::load4(resid, i, r);
+    E::store4(Y, i, v.x + r[0], v.y + r[1], v.z + r[2], v.w + r[3]);
+}
+
 template <typename E>
 __device__ __forceinline__ void reduce_store(const ReducePlan& r, void* Y, int m_base, int* flag,
-                                             unsigned long long* trace = nullptr) {
+                                             unsigned long long* trace = nullptr, const void* resid = nullptr) {
     const int tid = threadIdx.x, nth = blockDim.x;
     const int w4 = (r.c_hi - r.c_lo) >> 2;
     const size_t blk = (size_t)r.m_count * r.d_model;
@@ -248,7 +285,7 @@ __device__ __forceinline__ void reduce_store(const ReducePlan& r, void* Y, int m
             const int idx = idx0 + u * nth;
             if (idx < r.m_count * w4) {
                 const int m = idx / w4, c4 = idx - m * w4;
-                if (r.n2 == 1) E::store4(Y, (size_t)(m_base + m) * r.d_model + r.c_lo + 4 * c4, s[u].x, s[u].y, s[u].z, s[u].w);
+                if (r.n2 == 1) store4_plus<E>(Y, resid, (size_t)(m_base + m) * r.d_model + r.c_lo + 4 * c4, s[u]);
                 else store4_device(r.Q + (size_t)r.q_slot * blk + off[u], s[u].x, s[u].y, s[u].z, s[u].w);
             }
         }
@@ -270,7 +307,7 @@ __device__ __forceinline__ void reduce_store(const ReducePlan& r, void* Y, int m
             const int idx = idx0 + u * nth;
             if (idx < r.m_count * w4) {
                 const int m = idx / w4, c4 = idx - m * w4;
-                E::store4(Y, (size_t)(m_base + m) * r.d_model + r.c_lo + 4 * c4, s[u].x, s[u].y, s[u].z, s[u].w);
+                store4_plus<E>(Y, resid, (size_t)(m_base + m) * r.d_model + r.c_lo + 4 * c4, s[u]);
             }
         }
     }

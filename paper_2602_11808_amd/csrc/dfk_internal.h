@@ -79,6 +79,10 @@ struct MlpArgs {
     unsigned* tickets; // zero on entry and on exit
     void* a2;          // [M, d_ff] in the workspace
     unsigned long long* trace;  // optional [workgroup][8] wall-clock stamps (NULL = off)
+    // Pre-norm residual form (kernel pair for up to 64 tokens only; all NULL / 0 otherwise):
+    const void* norm_w;  // [d_model] weight of the RMS normalisation applied to X on the way in
+    float eps;           // added to the mean square under the root
+    const void* resid;   // [M, d_model] added to the result at the final store (may be Y itself)
 };
 
 // d_ff is cut into slices at multiples of 8 rows: slice s of S covers the
@@ -112,6 +116,7 @@ int mfma_max_tokens_per_launch(const dfk_config_t& c, int d_model);
 // the pair of kernels for up to 64 tokens per launch (dfk_mfma_km.hip; config field kmajor)
 hipError_t launch_mfma_km(const MlpArgs& a, const dfk_config_t& c, hipStream_t st);
 bool mfma_km_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype);
+bool mfma_km_block_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype);
 int mfma_km_tokens_per_launch();
 int valu_max_tokens_per_launch();
 

@@ -52,6 +52,7 @@ constexpr int kKmTokensPerLaunch = 64;
 struct KmGeom {
     int depth;   // ring slots per wavefront
     int pass;    // gate/up kernel: row tiles whose partial sums LDS holds per pass at the end
+    int norm_off;  // gate/up kernel with the normalisation: byte offset in LDS of the weight slices, past rings and stage
 };
 
 // ---------------------------------------------------------------- gate/up kernel
@@ -117,7 +118,14 @@ struct KmStream1 {
     }
 };
 
-template <int NW, int TT, typename E>
+// NORM: X is the un-normalised residual stream H and the kernel computes the gate/up sums of
+// RMSNorm(H; w, eps) = H (x) w * s_m, s_m = 1/sqrt(mean_k H[m,k]^2 + eps).  The per-token
+// scalar s_m factors out of both sums, so the B operand becomes round16(H[m,k] * w[k])
+// (one rounding to the 16-bit type, as a separate normalisation kernel's store would do),
+// every lane adds up the squares of the H values it holds anyway, and the end scales the
+// summed G and U by s_m in fp32 before the activation.  Each workgroup reads all of X, so
+// it has the whole sum of squares of every token by itself.
+template <int NW, int TT, typename E, bool NORM>
 __global__ __launch_bounds__(NW * 64) void k_gateup_km(MlpArgs a, KmGeom geo) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     constexpr int TOK = 16 * TT;
@@ -144,6 +152,18 @@ __global__ __launch_bounds__(NW * 64) void k_gateup_km(MlpArgs a, KmGeom geo) {
     DFK_STAMP(0);
     ts.start();
 
+    // The wavefront's slice of the normalisation weight goes to LDS behind the first tile
+    // loads (their latency covers these loads; the wait the stores need drains both).
+    unsigned char* wslice = lds + geo.norm_off + (size_t)wave * KW * 2;
+    float* ssq = (float*)(lds + geo.norm_off + (size_t)a.d_model * 2);   // [NW][TOK] sums of squares
+    float ss[TT];
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) ss[tt] = 0.f;
+    if (NORM) {
+        const u32x4* src = (const u32x4*)((const char*)a.norm_w + (size_t)wave * KW * 2);
+        for (int i = lane; i < KW / 8; i += 64) *(u32x4*)(wslice + i * 16) = src[i];
+    }
+
     f32x4 acc[NT][TT];
 #pragma unroll
     for (int rt = 0; rt < NT; ++rt)
@@ -157,6 +177,26 @@ __global__ __launch_bounds__(NW * 64) void k_gateup_km(MlpArgs a, KmGeom geo) {
             const unsigned char* slot = ts.acquire();
 #pragma unroll
             for (int c = 0; c < 4; ++c) xk[tt][c] = *(const u32x4*)(slot + (q * 16 + ((4 * c + g) ^ q)) * 16);
+            if (NORM) {   // one token tile at a time, the weight re-read from LDS: few registers live
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const u32x4 wv = *(const u32x4*)(wslice + ((size_t)kc * kKC + (4 * c + g) * 8) * 2);
+#pragma unroll
+                    for (int p = 0; p < 4; ++p) {
+                        float w0, w1, h0, h1;
+                        E::widen2(wv[p], w0, w1);
+                        E::widen2(xk[tt][c][p], h0, h1);
+                        ss[tt] = fmaf(h0, h0, ss[tt]);
+                        ss[tt] = fmaf(h1, h1, ss[tt]);
+                        uint32_t packed = E::pack2(h0 * w0, h1 * w1);
+                        asm volatile("" : "+v"(packed));
+                        xk[tt][c][p] = packed;
+                    }
+                    // pin the sum here: otherwise the adds sink to the end of the chunk and the
+                    // widened values stay live across all its MFMAs
+                    asm volatile("" : "+v"(ss[tt]));
+                }
+            }
         }
 #pragma unroll
         for (int rt = 0; rt < NT; ++rt) {
@@ -172,6 +212,15 @@ __global__ __launch_bounds__(NW * 64) void k_gateup_km(MlpArgs a, KmGeom geo) {
         }
     }
     DFK_STAMP(2);
+    if (NORM) {   // lanes (q, 0..3) hold the four k groups' shares of token q's squares
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+            float v = ss[tt];
+            v += __shfl_xor(v, 16);
+            v += __shfl_xor(v, 32);
+            if (g == 0) ssq[wave * TOK + tt * 16 + q] = v;
+        }
+    }
 
     // Every wavefront's tile loads have landed (its last acquire waited for all of them), so
     // after this barrier the rings are free.  The wavefronts' k-partial sums meet there,
@@ -201,6 +250,13 @@ __global__ __launch_bounds__(NW * 64) void k_gateup_km(MlpArgs a, KmGeom geo) {
                     const float2 gv = *(const float2*)(src + (size_t)w * TOK * 16);
                     const float2 uv = *(const float2*)(src + (size_t)w * TOK * 16 + 8);
                     g0 += gv.x; g1 += gv.y; u0 += uv.x; u1 += uv.y;
+                }
+                if (NORM) {
+                    float sq = 0.f;
+#pragma unroll
+                    for (int w = 0; w < NW; ++w) sq += ssq[w * TOK + m];
+                    const float sm = __builtin_amdgcn_rsqf(sq / (float)a.d_model + a.eps);
+                    g0 *= sm; g1 *= sm; u0 *= sm; u1 *= sm;
                 }
                 const size_t o = (size_t)(a.m_base + m) * a.d_ff + j0 + (rt0 + r) * 8 + 2 * pr;
                 *(uint32_t*)((uint16_t*)a.a2 + o) = E::pack2(silu_mul_fast(g0, u0), silu_mul_fast(g1, u1));
@@ -422,44 +478,69 @@ __global__ __launch_bounds__(NW * 64) void k_down_km(MlpArgs a, KmGeom geo) {
         for (int idx = tid; idx < a.m_count * (width / 2); idx += NTHREADS) {
             const int m = idx / (width / 2), c2 = idx - m * (width / 2);
             float* src = a.yacc + (size_t)m * a.d_model + blk_lo * 128 + 2 * c2;
-            const float v0 = acc_take(src), v1 = acc_take(src + 1);
-            *(uint32_t*)((uint16_t*)a.Y + (size_t)(a.m_base + m) * a.d_model + blk_lo * 128 + 2 * c2) = E::pack2(v0, v1);
+            float v0 = acc_take(src), v1 = acc_take(src + 1);
+            const size_t o = (size_t)(a.m_base + m) * a.d_model + blk_lo * 128 + 2 * c2;
+            if (a.resid) {
+                float r0, r1;
+                E::widen2(*(const uint32_t*)((const uint16_t*)a.resid + o), r0, r1);
+                v0 += r0; v1 += r1;
+            }
+            *(uint32_t*)((uint16_t*)a.Y + o) = E::pack2(v0, v1);
         }
         return;
     }
-    reduce_store<E>(plan_column_block(a, cb, blk_lo * 128, blk_lo * 128 + width), a.Y, a.m_base, &flag, a.trace);
+    reduce_store<E>(plan_column_block(a, cb, blk_lo * 128, blk_lo * 128 + width), a.Y, a.m_base, &flag, a.trace, a.resid);
 }
 
 // ---------------------------------------------------------------- host side
 int km_token_tiles(int m_count) { return m_count <= 16 ? 1 : m_count <= 32 ? 2 : 4; }
 
-size_t km_lds_gateup(const dfk_config_t& c, int TT, int d_ff, KmGeom* geo) {
+// norm: the kernel also keeps the normalisation weight (d_model 16-bit values) and the
+// wavefronts' sums of squares behind rings and stage.
+size_t km_lds_gateup(const dfk_config_t& c, int TT, int d_model, int d_ff, bool norm, KmGeom* geo) {
     const int nt_max = max_slice_rows(d_ff, c.splits) / 8;
     const size_t ring = (size_t)c.waves * c.depth * kTileBytes;
     const size_t per_tile = (size_t)c.waves * 16 * TT * 16 * 4;   // partial sums of one row tile
-    const int fit = (int)((size_t)kLdsLimit / per_tile);
+    const size_t extra = norm ? (size_t)d_model * 2 + (size_t)c.waves * 16 * TT * 4 : 0;
+    const size_t room = (size_t)kLdsLimit > extra ? (size_t)kLdsLimit - extra : 0;
+    const int fit = (int)(room / per_tile);
     geo->depth = c.depth;
     geo->pass = std::max(1, std::min(nt_max, fit));
-    return std::max(ring, (size_t)geo->pass * per_tile);
+    const size_t base = std::max(ring, (size_t)geo->pass * per_tile);
+    geo->norm_off = (int)base;
+    return base + extra;
 }
 size_t km_lds_down(const dfk_config_t& c, KmGeom* geo) {
     geo->depth = c.depth;
     geo->pass = 0;
+    geo->norm_off = 0;
     return std::max((size_t)c.waves * c.depth * kTileBytes, (size_t)c.waves * 16 * 128 * 4);
 }
 
 template <int NW, int TT, typename E>
 hipError_t launch_km_te(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
-    static size_t configured1 = 0, configured2 = 0;
-    if (g_stage_mask & 1) {
+    static size_t configured1 = 0, configured1n = 0, configured2 = 0;
+    if ((g_stage_mask & 1) && !a.norm_w) {
         KmGeom geo;
-        const size_t lds = km_lds_gateup(c, TT, a.d_ff, &geo);
+        const size_t lds = km_lds_gateup(c, TT, a.d_model, a.d_ff, false, &geo);
         if (lds > configured1) {
-            hipError_t e = hipFuncSetAttribute((const void*)k_gateup_km<NW, TT, E>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            hipError_t e = hipFuncSetAttribute((const void*)k_gateup_km<NW, TT, E, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
             configured1 = lds;
         }
-        hipLaunchKernelGGL((k_gateup_km<NW, TT, E>), dim3(a.splits), dim3(NW * 64), lds, st, a, geo);
+        hipLaunchKernelGGL((k_gateup_km<NW, TT, E, false>), dim3(a.splits), dim3(NW * 64), lds, st, a, geo);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if ((g_stage_mask & 1) && a.norm_w) {
+        KmGeom geo;
+        const size_t lds = km_lds_gateup(c, TT, a.d_model, a.d_ff, true, &geo);
+        if (lds > configured1n) {
+            hipError_t e = hipFuncSetAttribute((const void*)k_gateup_km<NW, TT, E, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            configured1n = lds;
+        }
+        hipLaunchKernelGGL((k_gateup_km<NW, TT, E, true>), dim3(a.splits), dim3(NW * 64), lds, st, a, geo);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -505,7 +586,15 @@ bool mfma_km_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, d
     if (nblk / c.k2_col_blocks > km_col_blocks(TT)) return false;
     if (c.reduce == DFK_REDUCE_TICKET && !partials_fit(c.k2_splits, tokens, M, d_model)) return false;
     KmGeom geo;
-    return km_lds_gateup(c, TT, d_ff, &geo) <= (size_t)kLdsLimit && km_lds_down(c, &geo) <= (size_t)kLdsLimit;
+    return km_lds_gateup(c, TT, d_model, d_ff, false, &geo) <= (size_t)kLdsLimit && km_lds_down(c, &geo) <= (size_t)kLdsLimit;
+}
+
+// The pre-norm residual form runs on this kernel pair only; its gate/up kernel needs a
+// little more LDS (weight of the normalisation, sums of squares).
+bool mfma_km_block_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype) {
+    if (!mfma_km_config_valid(c, M, d_model, d_ff, dtype)) return false;
+    KmGeom geo;
+    return km_lds_gateup(c, km_token_tiles(std::min(M, kKmTokensPerLaunch)), d_model, d_ff, true, &geo) <= (size_t)kLdsLimit;
 }
 
 hipError_t launch_mfma_km(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {

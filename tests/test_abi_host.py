@@ -167,6 +167,38 @@ def test_helper_calls_check_their_arguments_on_the_host():
     assert L.dfk_rms_normalize(4096, 4096, 70000, 512, None) == dfk.DFK_ERR_UNSUPPORTED_SHAPE
 
 
+def test_mlp_block_checks_its_arguments_on_the_host():
+    import ctypes
+    L = dfk.lib()
+    n = dfk.dfk_num_candidates(4, D, FF, dfk.DFK_BF16)
+    cands = [dfk.dfk_get_candidate(4, D, FF, dfk.DFK_BF16, i) for i in range(n)]
+    km = next(c for c in cands if c.kmajor == 1)
+    other = next(c for c in cands if c.kmajor == 0)
+    nx, nw = 4 * D * 2, FF * D * 2
+    A = 1 << 30     # fake device addresses, never dereferenced: every case fails before any HIP call
+    H, Wg, Wu, Wd, Y, w = A, A + (1 << 28), A + (2 << 28), A + (3 << 28), A + (4 << 28), A + (5 << 28)
+    ws, wsb = A + (6 << 28), dfk.dfk_workspace_bytes(4, D, FF)
+
+    def call(H=H, w=w, eps=1e-5, Wg=Wg, Y=Y, M=4, dtype=dfk.DFK_BF16, cfg=km, ws=ws, wsb=wsb):
+        return L.dfk_mlp_block(H, w, eps, Wg, Wu, Wd, Y, M, D, FF, dtype, ctypes.byref(cfg) if cfg else None, ws, wsb, None)
+
+    assert call(H=None) == dfk.DFK_ERR_INVALID_ARG
+    assert call(w=None) == dfk.DFK_ERR_INVALID_ARG
+    assert call(Y=None) == dfk.DFK_ERR_INVALID_ARG
+    assert call(eps=-1.0) == dfk.DFK_ERR_INVALID_ARG
+    assert call(eps=float("nan")) == dfk.DFK_ERR_INVALID_ARG
+    assert call(dtype=7) == dfk.DFK_ERR_INVALID_ARG
+    assert call(dtype=dfk.DFK_FP32) == dfk.DFK_ERR_UNSUPPORTED_SHAPE
+    assert call(w=w + 2) == dfk.DFK_ERR_ALIGNMENT
+    assert call(Y=H + 16) == dfk.DFK_ERR_ALIAS            # partial overlap with the input
+    assert call(Y=Wg) == dfk.DFK_ERR_ALIAS
+    assert call(w=Y + 64) == dfk.DFK_ERR_ALIAS
+    assert call(ws=None) == dfk.DFK_ERR_WORKSPACE
+    assert call(wsb=1024) == dfk.DFK_ERR_WORKSPACE
+    assert call(cfg=other) == dfk.DFK_ERR_UNSUPPORTED_SHAPE   # only the kernel pair for up to 64 tokens carries it
+    assert call(M=0) == dfk.DFK_ERR_INVALID_ARG
+
+
 def test_status_strings():
     for s in range(0, -9, -1):
         assert dfk.dfk_status_string(s) not in ("", "unknown status")

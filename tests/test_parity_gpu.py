@@ -185,6 +185,109 @@ def test_kernels_for_up_to_64_tokens_per_launch(shape):
             assert workspace_is_clean(ws, M, d), (shape, cfg)
 
 
+def _block_case(M, d, ff, dtype, seed):
+    t = di.mlp_inputs(M, d, ff, seed=seed, dtype=dtype)
+    t["w"] = di.tensor(seed + 1000, (d,), 1.0, dtype)
+    return t
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp16"])
+@pytest.mark.parametrize("shape", [(1, 1024, 2816), (5, 512, 1000), (16, 1024, 4104), (17, 1024, 2816), (33, 2048, 4104),
+                                   (64, 1024, 8200), (70, 1024, 2816), (130, 512, 1536)],
+                         ids=lambda s: "M%d_d%d_ff%d" % s)
+def test_mlp_block_with_norm_and_residual(shape, dtype):
+    """H + MLP(RMSNorm(H)) in the two launches of the plain block, against the oracle's
+    composition: every candidate of the kernel pair that carries it, both reductions, one to
+    four token tiles and several launches, out of place and in place."""
+    M, d, ff = shape
+    eps = 1e-5
+    t = _block_case(M, d, ff, dtype, seed=17)
+    ref = oracle.mlp_block(t["X"], t["w"], eps, t["Wg"], t["Wu"], t["Wd"])
+    H64 = di.as_f64(t["X"])
+    g = gpu_inputs(t)
+    ws = dfk.new_workspace(M, d, ff, DEV)
+    n = dfk.dfk_num_candidates(M, d, ff, _dt(dtype))
+    cfgs = [c for c in (dfk.dfk_get_candidate(M, d, ff, _dt(dtype), i) for i in range(n)) if c.kmajor == 1]
+    assert {c.reduce for c in cfgs} == {dfk.DFK_REDUCE_TICKET, dfk.DFK_REDUCE_ATOMIC}
+    tol = _tol(dtype)
+    for cfg in cfgs:
+        print("case", shape, dtype, cfg, flush=True)
+        out = torch.full_like(g["X"], float("nan"))
+        dfk.dfk_mlp_block(g["X"], g["w"], eps, g["Wg"], g["Wu"], g["Wd"], out, cfg, ws)
+        torch.cuda.synchronize()
+        got = y64(out)
+        assert rel_err(got, ref) <= tol, (shape, cfg, rel_err(got, ref))
+        # the block's own share of the result, measured on its own scale
+        assert rel_err(got - H64, ref - H64) <= tol, (shape, cfg, rel_err(got - H64, ref - H64))
+        assert workspace_is_clean(ws, M, d), (shape, cfg)
+        assert torch.equal(g["X"], di.to_torch(t["X"], DEV))          # input untouched
+        # in place: bit-identical to the out-of-place result for the ticket reduction
+        # (fixed summation order); within tolerance for the atomic one
+        h = g["X"].clone()
+        dfk.dfk_mlp_block(h, g["w"], eps, g["Wg"], g["Wu"], g["Wd"], h, cfg, ws)
+        torch.cuda.synchronize()
+        if cfg.reduce == dfk.DFK_REDUCE_TICKET:
+            assert torch.equal(h.view(torch.int16), out.view(torch.int16)), (shape, cfg)
+        else:
+            assert rel_err(y64(h), ref) <= tol, (shape, cfg)
+        assert workspace_is_clean(ws, M, d), (shape, cfg)
+    # scheduler's choice
+    out = torch.empty_like(g["X"])
+    dfk.dfk_mlp_block(g["X"], g["w"], eps, g["Wg"], g["Wu"], g["Wd"], out, None, ws)
+    assert rel_err(y64(out), ref) <= tol
+
+
+def test_mlp_block_special_cases():
+    """W_down = 0 returns H bit for bit; unit weight and a power-of-two scaling of H leave
+    the block's share unchanged (eps = 0); an eps that is not negligible."""
+    M, d, ff = 7, 1024, 2816
+    t = _block_case(M, d, ff, "bf16", seed=19)
+    g = gpu_inputs(t)
+    ws = dfk.new_workspace(M, d, ff, DEV)
+    out = torch.empty_like(g["X"])
+    zero = torch.zeros_like(g["Wd"])
+    dfk.dfk_mlp_block(g["X"], g["w"], 1e-5, g["Wg"], g["Wu"], zero, out, None, ws)
+    assert torch.equal(out.view(torch.int16), g["X"].view(torch.int16))
+    # scaling H by 4 scales nothing but the residual
+    dfk.dfk_mlp_block(g["X"], g["w"], 0.0, g["Wg"], g["Wu"], g["Wd"], out, None, ws)
+    a = y64(out) - y64(g["X"])
+    h4 = (g["X"].float() * 4).to(torch.bfloat16)
+    out4 = torch.empty_like(h4)
+    dfk.dfk_mlp_block(h4, g["w"], 0.0, g["Wg"], g["Wu"], g["Wd"], out4, None, ws)
+    ref4 = oracle.mlp_block(di.to_numpy(h4), t["w"], 0.0, t["Wg"], t["Wu"], t["Wd"])
+    assert rel_err(y64(out4), ref4) <= TOL_BF16
+    ref1 = oracle.mlp_block(t["X"], t["w"], 0.0, t["Wg"], t["Wu"], t["Wd"])
+    np.testing.assert_allclose(ref4 - y64(h4), ref1 - y64(g["X"]), rtol=1e-9, atol=1e-12)   # the oracle agrees it is scale-free
+    assert rel_err(y64(out4) - y64(h4), a) <= 3 * TOL_BF16    # two bf16 results, the second rounded on a 4x coarser grid
+    # eps three times the mean square (about 1 for these inputs): the normalised input is halved
+    eps = 3.0
+    dfk.dfk_mlp_block(g["X"], g["w"], eps, g["Wg"], g["Wu"], g["Wd"], out, None, ws)
+    ref = oracle.mlp_block(t["X"], t["w"], eps, t["Wg"], t["Wu"], t["Wd"])
+    assert rel_err(y64(out), ref) <= TOL_BF16
+    assert rel_err(y64(out) - y64(g["X"]), ref - y64(g["X"])) <= TOL_BF16
+
+
+def test_mlp_block_full_size_sampled_rows():
+    """Headline shape, the launch configuration the scheduler picks: sampled tokens against the oracle."""
+    d, ff = 4096, 14336
+    for M, dtype in ((1, "bf16"), (16, "bf16"), (64, "bf16"), (4, "fp16")):
+        g = di.mlp_inputs_torch(M, d, ff, seed=23, dtype=dtype, device=DEV)
+        w = di.to_torch(di.tensor(1023, (d,), 1.0, dtype), DEV)
+        ws = dfk.new_workspace(M, d, ff, DEV)
+        out = torch.empty_like(g["X"])
+        print("case full", M, dtype, flush=True)
+        dfk.dfk_mlp_block(g["X"], w, 1e-5, g["Wg"], g["Wu"], g["Wd"], out, None, ws)
+        torch.cuda.synchronize()
+        rows = sorted({0, M - 1, M // 2})
+        t = {k: di.to_numpy(v) for k, v in g.items()}
+        ref = oracle.mlp_block(t["X"][rows], di.to_numpy(w), 1e-5, t["Wg"], t["Wu"], t["Wd"])
+        H = di.as_f64(t["X"][rows])
+        got = y64(out)[rows]
+        assert rel_err(got, ref) <= _tol(dtype), (M, dtype)
+        assert rel_err(got - H, ref - H) <= _tol(dtype), (M, dtype)
+        assert workspace_is_clean(ws, M, d)
+
+
 @pytest.mark.parametrize("shape", [(1, 1024, 2816), (16, 512, 4104), (33, 1024, 2816), (64, 2048, 4104), (70, 1024, 2816),
                                    (4, 4096, 14336), (64, 4096, 14336)],
                          ids=lambda s: "M%d_d%d_ff%d" % s)
