@@ -114,6 +114,78 @@ def decode32(args, torch, di, dfk, dev):
                       "weights_gb": round(L * 6 * D_MODEL * D_FF / 1e9, 2), "per_M": rows}))
 
 
+def block32(args, torch, di, dfk, dev):
+    """The block with its neighbours in a pre-norm decoder layer, 32 distinct layers chained and
+    replayed from a HIP graph: H <- H + MLP(RMSNorm(H; w_l)).  Two ways per token count: the one
+    call that folds normalisation and residual add into the block's two launches, and the same
+    arithmetic as separate launches around the plain block (a normalisation kernel without the
+    weight, the block, an elementwise add)."""
+    L = 32
+    sweep = (1, 4, 16, 64)
+    eps = 1e-5
+    layers = [di.mlp_inputs_torch(1, D_MODEL, D_FF, seed=1000, layer=l, device=dev) for l in range(L)]
+    nws = [di.to_torch(di.tensor(5000 + l, (D_MODEL,), 1.0, "bf16"), dev) for l in range(L)]
+    ws = dfk.new_workspace(max(sweep), D_MODEL, D_FF, dev)
+    dfk.dfk_set_workspace(ws)
+    scratch = torch.empty(dfk.dfk_tune_scratch_bytes(max(sweep), D_MODEL, D_FF, dfk.DFK_BF16, 3),
+                          dtype=torch.uint8, device=dev)
+    dfk.dfk_tune(list(sweep), D_MODEL, D_FF, dfk.DFK_BF16, scratch, sets=3, iters=8)
+    torch.cuda.synchronize()
+    del scratch
+    rows = {}
+    for M in sweep:
+        X0 = di.mlp_inputs_torch(M, D_MODEL, D_FF, seed=0, layer=0, device=dev)["X"]
+        bufs = [torch.empty_like(X0) for _ in range(L + 1)]
+        xn, y = torch.empty_like(X0), torch.empty_like(X0)
+
+        def folded(stream=None):
+            for l in range(L):
+                w = layers[l]
+                dfk.dfk_mlp_block(bufs[l], nws[l], eps, w["Wg"], w["Wu"], w["Wd"], bufs[l + 1], None, ws, stream=stream)
+
+        def separate(stream=None):
+            for l in range(L):
+                w = layers[l]
+                dfk.dfk_rms_normalize(bufs[l], xn, stream=stream)
+                dfk.dfk_swiglu_mlp(xn, w["Wg"], w["Wu"], w["Wd"], y, stream=stream)
+                torch.add(bufs[l], y, out=bufs[l + 1])
+
+        row = {}
+        for name, chain in (("folded", folded), ("separate_launches", separate)):
+            bufs[0].copy_(X0)
+            chain()
+            torch.cuda.synchronize()
+            eager1 = bufs[1].clone()
+            side = torch.cuda.Stream()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(graph, stream=side):
+                    chain(stream=side)
+            ok = True
+            for _ in range(3):
+                bufs[1].zero_()
+                torch.cuda.synchronize()
+                graph.replay()
+                torch.cuda.synchronize()
+                d1 = float((eager1.float() - bufs[1].float()).abs().max() / eager1.float().abs().max())
+                ok = ok and d1 <= 1e-2 and bool(torch.isfinite(bufs[L].float()).all())
+            reps = max(3, args.steps // 20)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(reps):
+                graph.replay()
+            b.record()
+            torch.cuda.synchronize()
+            us_layer = a.elapsed_time(b) * 1e3 / reps / L
+            row[name] = {"us_per_layer_in_graph": round(us_layer, 2), "replays_match_eager_layer0": ok}
+            del graph
+        c, tuned = dfk.dfk_get_choice(M, D_MODEL, D_FF, dfk.DFK_BF16)
+        row["pick"] = dict(c.as_dict(), tuned=tuned)
+        rows[str(M)] = row
+    print(json.dumps({"workload": "block32: 32 chained pre-norm MLP sub-blocks H + MLP(RMSNorm(H)), llama3-8b shape, "
+                                  "HIP graph replay", "layers": L, "per_M": rows}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -124,9 +196,11 @@ def main():
     ap.add_argument("--tuning-file", default=None,
                     help="load the scheduler table from this file if it exists, else tune and save it there")
     ap.add_argument("--force", choices=["auto", "fused", "unfused"], default="auto")
-    ap.add_argument("--workload", choices=["layer", "decode32"], default="layer",
+    ap.add_argument("--workload", choices=["layer", "decode32", "block32"], default="layer",
                     help="layer (default): the headline workload; decode32: 32 chained distinct layers of the "
-                         "same shape, captured once in a HIP graph and replayed, M swept 1..256")
+                         "same shape, captured once in a HIP graph and replayed, M swept 1..256; block32: the "
+                         "same chain with RMS normalisation and residual add, folded into the block's launches "
+                         "or as separate launches")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU by design (one MI355X); run with --gpus 1. "
@@ -143,6 +217,8 @@ def main():
     torch.cuda.set_device(0)
     if args.workload == "decode32":
         return decode32(args, torch, di, dfk, dev)
+    if args.workload == "block32":
+        return block32(args, torch, di, dfk, dev)
     Mmax = max(M_SET)
 
     # ---- synthetic inputs, resident in HBM

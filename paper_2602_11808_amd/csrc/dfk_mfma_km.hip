@@ -150,19 +150,23 @@ __global__ __launch_bounds__(NW * 64) void k_gateup_km(MlpArgs a, KmGeom geo) {
     ts.ring = lds + wave * geo.depth * kTileBytes;
     ts.depth = geo.depth;
     DFK_STAMP(0);
-    ts.start();
-
-    // The wavefront's slice of the normalisation weight goes to LDS behind the first tile
-    // loads (their latency covers these loads; the wait the stores need drains both).
-    unsigned char* wslice = lds + geo.norm_off + (size_t)wave * KW * 2;
-    float* ssq = (float*)(lds + geo.norm_off + (size_t)a.d_model * 2);   // [NW][TOK] sums of squares
+    // The wavefront's slice of the normalisation weight travels to LDS by the same asynchronous
+    // loads as the tiles, issued ahead of them: they are the oldest in the queue, so the first
+    // tile's counted wait covers them and no register or extra wait is involved.  Slices sit
+    // 1 KB-aligned (one load instruction writes 1 KB); lanes past a short slice re-read its end.
+    const int wbytes = KW * 2;
+    const int wstride = (wbytes + 1023) & ~1023;
+    unsigned char* wslice = lds + geo.norm_off + (size_t)wave * wstride;
+    float* ssq = (float*)(lds + geo.norm_off + (size_t)NW * wstride);   // [NW][TOK] sums of squares
     float ss[TT];
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) ss[tt] = 0.f;
     if (NORM) {
-        const u32x4* src = (const u32x4*)((const char*)a.norm_w + (size_t)wave * KW * 2);
-        for (int i = lane; i < KW / 8; i += 64) *(u32x4*)(wslice + i * 16) = src[i];
+        const char* src = (const char*)a.norm_w + (size_t)wave * wbytes;
+        for (int o = 0; o < wbytes; o += 1024)
+            __builtin_amdgcn_global_load_lds(src + min(o + lane * 16, wbytes - 16), DFK_LDS_PTR(wslice + o), 16, 0, 0);
     }
+    ts.start();
 
     f32x4 acc[NT][TT];
 #pragma unroll
@@ -495,13 +499,14 @@ __global__ __launch_bounds__(NW * 64) void k_down_km(MlpArgs a, KmGeom geo) {
 // ---------------------------------------------------------------- host side
 int km_token_tiles(int m_count) { return m_count <= 16 ? 1 : m_count <= 32 ? 2 : 4; }
 
-// norm: the kernel also keeps the normalisation weight (d_model 16-bit values) and the
-// wavefronts' sums of squares behind rings and stage.
+// norm: the kernel also keeps the normalisation weight (d_model 16-bit values, a 1 KB-aligned
+// slice per wavefront) and the wavefronts' sums of squares behind rings and stage.
 size_t km_lds_gateup(const dfk_config_t& c, int TT, int d_model, int d_ff, bool norm, KmGeom* geo) {
     const int nt_max = max_slice_rows(d_ff, c.splits) / 8;
     const size_t ring = (size_t)c.waves * c.depth * kTileBytes;
     const size_t per_tile = (size_t)c.waves * 16 * TT * 16 * 4;   // partial sums of one row tile
-    const size_t extra = norm ? (size_t)d_model * 2 + (size_t)c.waves * 16 * TT * 4 : 0;
+    const size_t wstride = ((size_t)d_model / c.waves * 2 + 1023) & ~(size_t)1023;   // a wavefront's weight slice, 1 KB-aligned
+    const size_t extra = norm ? (size_t)c.waves * wstride + (size_t)c.waves * 16 * TT * 4 : 0;
     const size_t room = (size_t)kLdsLimit > extra ? (size_t)kLdsLimit - extra : 0;
     const int fit = (int)(room / per_tile);
     geo->depth = c.depth;
