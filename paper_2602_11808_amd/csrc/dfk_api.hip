@@ -154,6 +154,16 @@ std::vector<dfk_config_t> candidates(int M, int d_model, int d_ff, dfk_dtype_t d
                             push(make_cfg(DFK_VARIANT_TWO_KERNEL, DFK_PATH_MFMA, clamp_splits(splits, d_ff), wd / 10, wd % 10,
                                           clamp_splits(std::max(1, grid / k2c), d_ff), k2c, (int)dtype, reduce, 0, 1));
             }
+        // two-kernel, workgroup-shared weight tiles: up to 256 tokens per launch (offered beyond 64 tokens)
+        if (M > 64) {
+            const int k2c = nblk;
+            for (int splits : {256, 512})
+                for (int grid : {256, 512})
+                    for (int reduce : {DFK_REDUCE_TICKET, DFK_REDUCE_ATOMIC})
+                        for (int depth : {3, 4})
+                            push(make_cfg(DFK_VARIANT_TWO_KERNEL, DFK_PATH_MFMA, clamp_splits(splits, d_ff), 4, depth,
+                                          clamp_splits(std::max(1, grid / k2c), d_ff), k2c, (int)dtype, reduce, 0, 2));
+        }
     }
     for (int splits : {256, 512, 1024})
         for (int waves : {4, 8})
@@ -428,9 +438,14 @@ dfk_status_t dfk_mlp_block(const void* H, const void* norm_weight, float eps, co
     if (cfg) c = *cfg;
     else {
         if (!choose(M, d_model, d_ff, dtype, DFK_VARIANT_TWO_KERNEL, &c, nullptr)) return DFK_ERR_UNSUPPORTED_SHAPE;
-        if (!c.kmajor && !heuristic(M, d_model, d_ff, dtype, DFK_VARIANT_TWO_KERNEL, &c)) return DFK_ERR_UNSUPPORTED_SHAPE;
+        if (c.kmajor != 1) {   // the scheduler's pick is another kernel family: first candidate of the pair that carries this form
+            bool found = false;
+            for (const auto& k : candidates(M, d_model, d_ff, dtype))
+                if (k.kmajor == 1 && mfma_km_block_config_valid(k, M, d_model, d_ff, dtype)) { c = k; found = true; break; }
+            if (!found) return DFK_ERR_UNSUPPORTED_SHAPE;
+        }
     }
-    if (c.path != DFK_PATH_MFMA || !c.kmajor || !mfma_km_block_config_valid(c, M, d_model, d_ff, dtype))
+    if (c.path != DFK_PATH_MFMA || c.kmajor != 1 || !mfma_km_block_config_valid(c, M, d_model, d_ff, dtype))
         return DFK_ERR_UNSUPPORTED_SHAPE;
     return run(H, Wg, Wu, Wd, H_out, M, d_model, d_ff, dtype, c, workspace, (hipStream_t)stream, norm_weight, eps, H);
 }

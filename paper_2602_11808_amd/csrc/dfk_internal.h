@@ -11,7 +11,7 @@ namespace dfk {
 
 // ---------------------------------------------------------------- workspace layout
 // [0, 4096)        arrival counters (unsigned), zero between calls
-// [4096, +8 MiB)   fp32 accumulator of Y for one launch (kMaxTokensPerLaunch x kMaxDModel),
+// [4096, +8 MiB)   fp32 accumulator of Y for one launch ([tokens of the launch][d_model], at most 8 MiB),
 //                  zero between calls (atomic reduction)
 // [.., +P)         fp32 partial sums of Y, one [tokens, d_model] block per workgroup slice
 //                  (counter reduction)
@@ -67,7 +67,7 @@ struct MlpArgs {
     void* Y;
     int M, d_model, d_ff;
     int m_base;        // first token this launch handles (host-side token chunking)
-    int m_count;       // tokens this launch handles (<= kMaxTokensPerLaunch)
+    int m_count;       // tokens this launch handles (at most what the kernels of the configuration take)
     int splits;        // d_ff slices (grid of the fused kernel / first kernel)
     int k2_splits, k2_col_blocks;
     int dtype;         // dfk_dtype_t of X, the weights and Y
@@ -118,6 +118,10 @@ hipError_t launch_mfma_km(const MlpArgs& a, const dfk_config_t& c, hipStream_t s
 bool mfma_km_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype);
 bool mfma_km_block_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype);
 int mfma_km_tokens_per_launch();
+// the pair of kernels for 65..256 tokens per launch (dfk_mfma_big.hip; config field kmajor = 2)
+hipError_t launch_mfma_big(const MlpArgs& a, const dfk_config_t& c, hipStream_t st);
+bool mfma_big_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype);
+int mfma_big_tokens_per_launch();
 int valu_max_tokens_per_launch();
 
 // utility kernels

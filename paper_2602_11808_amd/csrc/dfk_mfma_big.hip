@@ -1,0 +1,581 @@
+// MFMA kernels of the two-kernel variant for 65..256 tokens per launch (gfx950).
+//
+// With more than 64 tokens the block stops being a matrix-vector stream: per weight tile
+// there are 8..16 token tiles of MFMA work, too many accumulators for one wavefront and too
+// much operand traffic if every wavefront fetched its own copy of the weights.  These
+// kernels are the "row-major" end of the Method section's tiling choice carried through:
+// a workgroup of four wavefronts shares every weight tile through LDS, each wavefront owns
+// a quarter of the launch's tokens (2 or 4 token tiles of 16) and keeps the whole
+// reduction for them, so there is no cross-wavefront sum at the end.
+//
+// Data movement is the same asynchronous global->LDS tile load as in the other MFMA kernels,
+// organised as a workgroup pipeline instead of per-wavefront rings:
+//   * shared tiles (weights): 4 KB tiles of the usual layout; wavefront w issues load
+//     instruction w of every tile (1 KB each), so the four wavefronts fill a tile together and
+//     issue the same number of loads.  `nb` buffers of one pipeline step each.
+//   * private tiles (activations of the wavefront's own tokens): loaded and read by one
+//     wavefront only, `pl` buffers per wavefront.
+//   * one LDS-only barrier per step: before it every wavefront waits, by count, for its own
+//     loads of the step (loads complete in issue order; the kernel keeps the running count of
+//     issued loads and the count at which each step's loads were complete); after it the
+//     step's shared tiles are whole and the buffer of the step before is free to refill.
+//
+// Gate/up kernel: workgroup s owns a d_ff slice of at most 8 row tiles (8 rows of W_gate and
+// the same 8 of W_up per tile); a step is one 128-k chunk: the slice's weight tiles (shared)
+// and the wavefront's token tiles of X (private, read into registers as MFMA B operands at
+// the start of the step).  The D tile of a row tile holds gate rows in lanes 0..31 and up
+// rows in lanes 32..63 of the same token: one cross-lane exchange, SiLU(G)*U, store of A_2.
+//
+// Down kernel: workgroup (js, cb) owns one 128-column block over d_ff split js; a step is
+// two 32-row blocks of W_down (shared, regrouped per lane with v_perm_b32 as in the other
+// down kernels) and the wavefront's A_2 tiles for those rows (private).  Each wavefront
+// publishes its finished [tokens x 128] sums itself (partial block of the split, or the
+// fp32 accumulator); the cross-workgroup reduction is that of the other kernels.
+#include <algorithm>
+
+#include "dfk_mfma_common.h"
+
+namespace dfk {
+namespace {
+
+constexpr int kBigWaves = 4;
+constexpr int kBigMaxRowTiles = 8;
+constexpr int kBigTokensPerLaunch = 256;
+constexpr int kBigSB = 2;            // 32-row blocks of W_down per step of the down kernel (the A_2 tile layout assumes 2)
+
+struct BigGeom {
+    int nb;          // buffers of shared tiles (steps)
+    int pl;          // private buffers per wavefront (1 or 2)
+    int shared_step; // bytes of one shared buffer
+    int priv_off;    // byte offset of the private region
+    int priv_step;   // bytes of one private buffer
+};
+
+// s_waitcnt vmcnt(n) for a run-time n (uniform); more than 63 waits for 63.
+__device__ __forceinline__ void wait_vm_exact(int n) {
+#define DFK_VM_CASE(k) case k: DFK_WAIT_VM(k); break;
+#define DFK_VM_CASE8(k) DFK_VM_CASE(k) DFK_VM_CASE(k + 1) DFK_VM_CASE(k + 2) DFK_VM_CASE(k + 3) \
+                        DFK_VM_CASE(k + 4) DFK_VM_CASE(k + 5) DFK_VM_CASE(k + 6) DFK_VM_CASE(k + 7)
+    switch (n) {
+        DFK_VM_CASE8(0) DFK_VM_CASE8(8) DFK_VM_CASE8(16) DFK_VM_CASE8(24)
+        DFK_VM_CASE8(32) DFK_VM_CASE8(40) DFK_VM_CASE8(48)
+        DFK_VM_CASE(56) DFK_VM_CASE(57) DFK_VM_CASE(58) DFK_VM_CASE(59) DFK_VM_CASE(60) DFK_VM_CASE(61) DFK_VM_CASE(62)
+        default: DFK_WAIT_VM(63); break;
+    }
+#undef DFK_VM_CASE8
+#undef DFK_VM_CASE
+    asm volatile("" ::: "memory");
+}
+
+// Bookkeeping of the workgroup pipeline, plain wave-uniform ints in the kernels (kept out of
+// any struct that is passed around: that ended up in scratch memory, whose loads drain the
+// tile loads): `issued` counts this wavefront's tile-load instructions; p_mark<i> / s_mark<i> is
+// that count right after the loads of the private / shared tiles of step (current + i) were
+// issued (0: none issued, nothing to wait for).
+#define DFK_PIPE_DECL() int issued = 0, p_mark0 = 0, p_mark1 = 0, s_mark0 = 0, s_mark1 = 0, s_mark2 = 0
+#define DFK_PIPE_SET_P(ahead) do { if ((ahead) == 0) p_mark0 = issued; else p_mark1 = issued; } while (0)
+#define DFK_PIPE_SET_S(ahead) do { if ((ahead) == 0) s_mark0 = issued; else if ((ahead) == 1) s_mark1 = issued; else s_mark2 = issued; } while (0)
+// Wait for this wavefront's loads of the current step, meet the other wavefronts, move on one step.
+#define DFK_PIPE_ENTER_STEP() do {                                             \
+        wait_vm_exact(issued - max(p_mark0, s_mark0));                          \
+        lds_barrier();                                                          \
+        p_mark0 = p_mark1; p_mark1 = 0;                                         \
+        s_mark0 = s_mark1; s_mark1 = s_mark2; s_mark2 = 0;                      \
+    } while (0)
+
+// ---------------------------------------------------------------- gate/up kernel
+template <int TT>
+struct BigLoads1 {
+    const char* wsrc;          // this lane's address in the slice's first weight tile, chunk 0
+    const char* xsrc[TT][4];   // this lane's addresses in the wavefront's X tiles, chunk 0
+    size_t row_bytes;
+    int nt, wave;
+    unsigned char *lds, *xpriv;
+    int shared_step, priv_step;
+
+    __device__ __forceinline__ int issue_x(int kc, int buf) {
+        unsigned char* dst = xpriv + (size_t)buf * priv_step;
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                __builtin_amdgcn_global_load_lds(xsrc[tt][u] + (size_t)kc * (kKC * 2), DFK_LDS_PTR(dst + tt * kTileBytes + u * 1024), 16, 0, 0);
+        return 4 * TT;
+    }
+    __device__ __forceinline__ int issue_w(int kc, int buf) {
+        unsigned char* dst = lds + (size_t)buf * shared_step + wave * 1024;
+        for (int rt = 0; rt < nt; ++rt)
+            __builtin_amdgcn_global_load_lds(wsrc + (size_t)rt * 8 * row_bytes + (size_t)kc * (kKC * 2), DFK_LDS_PTR(dst + rt * kTileBytes), 16, 0,
+                                             kAuxNonTemporal);
+        return nt;
+    }
+};
+
+// MFMAs of one 128-k chunk for NTC row tiles: the A operands (weight tile rows) are read from
+// LDS one row tile ahead of their use, so that the read latency hides behind the MFMAs of the
+// tile before.  wt points at this lane's row (q) of the chunk's first weight tile.
+template <int NTC, int TT, typename E>
+__device__ __forceinline__ void gateup_chunk(f32x4 (&acc)[NTC][TT], const u32x4 (&xk)[TT][4], const unsigned char* wt, int q, int g,
+                                             bool last_present) {
+    u32x4 av[2][4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) av[0][c] = *(const u32x4*)(wt + (((4 * c + g) ^ q)) * 16);
+#pragma unroll
+    for (int rt = 0; rt < NTC; ++rt) {
+        if (rt + 1 < NTC) {   // (the last tile's buffer exists in every workgroup; its data is used only where present)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) av[(rt + 1) & 1][c] = *(const u32x4*)(wt + (rt + 1) * kTileBytes + (((4 * c + g) ^ q)) * 16);
+        }
+        if (rt + 1 < NTC || last_present) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) acc[rt][tt] = mfma16<E>(av[rt & 1][c], xk[tt][c], acc[rt][tt]);
+        }
+    }
+}
+
+// NTC: the largest row-tile count of a d_ff slice of the launch (a compile-time constant so that
+// the chunk body is straight-line code); every slice has NTC or NTC - 1 row tiles.
+template <int TT, typename E, int NTC>
+__global__ __launch_bounds__(kBigWaves * 64) void k_gateup_big(MlpArgs a, BigGeom geo) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    constexpr int NT = NTC;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int q = lane & 15, g = lane >> 4;
+    int j0, j1;
+    slice_rows(a.d_ff, a.splits, blockIdx.x, j0, j1);
+    const int nt = (j1 - j0) / 8;                  // NTC or NTC - 1 (slices differ by at most one 8-row group)
+    const int nkc = a.d_model / kKC;
+    const size_t row_bytes = (size_t)a.d_model * 2;
+    const int tile0 = wave * TT;                   // this wavefront's first token tile
+
+    BigLoads1<TT> ld;
+    ld.row_bytes = row_bytes; ld.nt = nt; ld.wave = wave; ld.lds = lds;
+    ld.shared_step = geo.shared_step; ld.priv_step = geo.priv_step;
+    // this wavefront's instruction of a weight tile: tile row i = 4*wave + g, 16-byte chunk q ^ i
+    const int iw = 4 * wave + g;
+    ld.wsrc = (const char*)(wave < 2 ? a.Wg : a.Wu) + (size_t)j0 * row_bytes + (size_t)(iw & 7) * row_bytes + ((q ^ iw) * 16);
+    // X tile: instruction u covers tile rows (tokens) 4u + g
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = 4 * u + g;
+            const int token = min((tile0 + tt) * 16 + i, a.m_count - 1);
+            ld.xsrc[tt][u] = (const char*)a.X + (size_t)(a.m_base + token) * row_bytes + ((q ^ i) * 16);
+        }
+    unsigned char* xpriv = lds + geo.priv_off + (size_t)wave * geo.pl * geo.priv_step;
+    ld.xpriv = xpriv;
+
+    DFK_PIPE_DECL();
+    DFK_STAMP(0);
+    // prologue: X of the first pl steps, weights of the first nb - 1, earliest needs first
+    {
+        int xs = 0, ws = 0;
+        for (int s = 0; s < 3; ++s) {
+            if (xs < geo.pl && xs < nkc && xs <= s) { issued += ld.issue_x(xs, xs); DFK_PIPE_SET_P(xs); ++xs; }
+            if (ws < geo.nb - 1 && ws < nkc && ws <= s) { issued += ld.issue_w(ws, ws); DFK_PIPE_SET_S(ws); ++ws; }
+        }
+    }
+
+    f32x4 acc[NT][TT];
+#pragma unroll
+    for (int rt = 0; rt < NT; ++rt)
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) acc[rt][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    int xbuf = 0, wbuf = 0;                        // buffers of the current step
+    int wfree = geo.nb - 1;                        // shared buffer the step nb-1 ahead goes to
+    for (int kc = 0; kc < nkc; ++kc) {
+        DFK_PIPE_ENTER_STEP();
+        u32x4 xk[TT][4];       // B operands of the chunk: token q of each of the wavefront's token tiles
+        {
+            const unsigned char* xs = xpriv + (size_t)xbuf * geo.priv_step;
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) xk[tt][c] = *(const u32x4*)(xs + tt * kTileBytes + (q * 16 + ((4 * c + g) ^ q)) * 16);
+        }
+        DFK_WAIT_LGKM0();      // the X buffer has been read: it may be refilled
+        asm volatile("" ::: "memory");
+        if (kc + geo.pl < nkc) { issued += ld.issue_x(kc + geo.pl, xbuf); DFK_PIPE_SET_P(geo.pl - 1); }
+        if (kc + geo.nb - 1 < nkc) { issued += ld.issue_w(kc + geo.nb - 1, wfree); DFK_PIPE_SET_S(geo.nb - 2); }
+        const unsigned char* wt = lds + (size_t)wbuf * geo.shared_step + (q * 16) * 16;
+        gateup_chunk<NTC, TT, E>(acc, xk, wt, q, g, nt == NTC);
+        if (++xbuf == geo.pl) xbuf = 0;
+        if (++wbuf == geo.nb) wbuf = 0;
+        if (++wfree == geo.nb) wfree = 0;
+    }
+    DFK_STAMP(2);
+
+    // D tile of (row tile, token tile): lane (q, g) holds token q, tile rows 4g .. 4g+3; rows 0..7
+    // are the gate rows, 8..15 the up rows of the same 8 d_ff rows: lanes 32 apart pair up.
+#pragma unroll
+    for (int rt = 0; rt < NT; ++rt) {
+        if (rt < nt) {
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) {
+                const f32x4 v = acc[rt][tt];
+                float o[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) o[i] = __shfl_xor(v[i], 32);
+                const int m = (tile0 + tt) * 16 + q;
+                if (g < 2 && m < a.m_count) {
+                    uint2 pk;
+                    pk.x = E::pack2(silu_mul_fast(v[0], o[0]), silu_mul_fast(v[1], o[1]));
+                    pk.y = E::pack2(silu_mul_fast(v[2], o[2]), silu_mul_fast(v[3], o[3]));
+                    *(uint2*)((uint16_t*)a.a2 + (size_t)(a.m_base + m) * a.d_ff + j0 + rt * 8 + 4 * g) = pk;
+                }
+            }
+        }
+    }
+    DFK_STAMP(1);
+}
+
+// ---------------------------------------------------------------- down kernel
+template <int TT>
+struct BigLoads2 {
+    const char* asrc[TT][2];   // this lane's token rows of A_2 at the split's first row (per load instruction)
+    const char* Wd;
+    size_t row_bytes, colb;
+    int j0, rows, njb, d_ff, wave, q, g, lane;
+    unsigned char *lds, *apriv;
+    int shared_step, priv_step;
+
+    // A_2 of a step (64 rows = 128 contiguous bytes per token), 2 KB per token tile: instruction h
+    // covers tokens 8h .. 8h+7 of the tile, 8 consecutive lanes one token's 128 bytes (a whole
+    // cache line per token); within a token the eight 16-byte chunks sit XOR-swizzled by the
+    // token so that the operand reads below spread over the LDS banks.
+    __device__ __forceinline__ int issue_a(int s, int buf) {
+        unsigned char* dst = apriv + (size_t)buf * priv_step;
+        const int chunk = (lane & 7) ^ ((lane >> 3) & 7);
+        const int j = min(s * 64 + 8 * chunk, rows - 8);   // past the split: any valid address (masked at use)
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+                __builtin_amdgcn_global_load_lds(asrc[tt][h] + (size_t)j * 2, DFK_LDS_PTR(dst + tt * 2048 + h * 1024), 16, 0, 0);
+        return 2 * TT;
+    }
+    // W_down tiles of a 32-row block: tile h (0, 1) holds rows 4h + 8g + u for instruction u; this
+    // wavefront issues instruction u = wave of both
+    __device__ __forceinline__ int issue_w(int s, int buf) {
+        unsigned char* dst = lds + (size_t)buf * shared_step + wave * 1024;
+        int n = 0;
+        for (int b = 0; b < kBigSB; ++b) {
+            const int jb = s * kBigSB + b;
+            if (jb < njb) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int row = min(j0 + jb * 32 + 4 * h + 8 * g + wave, d_ff - 1);   // past d_ff: masked at use
+                    __builtin_amdgcn_global_load_lds(Wd + (size_t)row * row_bytes + colb + 16 * q,
+                                                     DFK_LDS_PTR(dst + (b * 2 + h) * kTileBytes), 16, 0, kAuxNonTemporal);
+                }
+                n += 2;
+            }
+        }
+        return n;
+    }
+};
+
+template <int TT, typename E, int NW>
+__global__ __launch_bounds__(NW * 64) void k_down_big(MlpArgs a, BigGeom geo) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    __shared__ int flag;
+    constexpr int NTHREADS = kBigWaves * 64;
+    constexpr int SB = kBigSB;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int q = lane & 15, g = lane >> 4;
+    const int js = blockIdx.x / a.k2_col_blocks;
+    const int cb = blockIdx.x - js * a.k2_col_blocks;   // one 128-column block per workgroup (checked on the host)
+    int j0, j1;
+    slice_rows(a.d_ff, a.k2_splits, js, j0, j1);
+    const int rows = j1 - j0;
+    const int njb = (rows + 31) / 32;
+    const int nsteps = (njb + SB - 1) / SB;
+    const size_t row_bytes = (size_t)a.d_model * 2;
+    const int tile0 = wave * TT;
+    const size_t colb = (size_t)cb * 256;
+
+    BigLoads2<TT> ld;
+    ld.Wd = (const char*)a.Wd; ld.row_bytes = row_bytes; ld.colb = colb;
+    ld.j0 = j0; ld.rows = rows; ld.njb = njb; ld.d_ff = a.d_ff; ld.wave = wave; ld.q = q; ld.g = g;
+    ld.lds = lds; ld.shared_step = geo.shared_step; ld.priv_step = geo.priv_step;
+    ld.lane = lane;
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int token = min((tile0 + tt) * 16 + 8 * h + (lane >> 3), a.m_count - 1);
+            ld.asrc[tt][h] = (const char*)a.a2 + ((size_t)(a.m_base + token) * a.d_ff + j0) * 2;
+        }
+    unsigned char* apriv = lds + geo.priv_off + (size_t)wave * geo.pl * geo.priv_step;
+    ld.apriv = apriv;
+
+    DFK_PIPE_DECL();
+    DFK_STAMP(3);
+    {
+        int as = 0, ws = 0;
+        for (int s = 0; s < 3; ++s) {
+            if (as < geo.pl && as < nsteps && as <= s) { issued += ld.issue_a(as, as); DFK_PIPE_SET_P(as); ++as; }
+            if (ws < geo.nb - 1 && ws < nsteps && ws <= s) { issued += ld.issue_w(ws, ws); DFK_PIPE_SET_S(ws); ++ws; }
+        }
+    }
+
+    f32x4 acc2[8][TT];
+#pragma unroll
+    for (int c = 0; c < 8; ++c)
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) acc2[c][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    int abuf = 0, wbuf = 0, wfree = geo.nb - 1;
+    for (int s = 0; s < nsteps; ++s) {
+        DFK_PIPE_ENTER_STEP();
+        u32x4 av[SB][TT];      // A operands: A_2[token q of tile tt][rows 8g .. 8g+7 of block b]
+        {
+            // token q of the tile sits in instruction q / 8 at lanes 8 (q % 8) .. +7, chunk k at (k ^ (q % 8))
+            const unsigned char* as = apriv + (size_t)abuf * geo.priv_step + (q >> 3) * 1024 + (q & 7) * 128;
+#pragma unroll
+            for (int b = 0; b < SB; ++b) {
+                const bool past = (s * SB + b) * 32 + 8 * g >= rows;
+                const int k = 4 * b + g;
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) {
+                    const u32x4 v = *(const u32x4*)(as + tt * 2048 + ((k ^ (q & 7)) * 16));
+                    av[b][tt] = past ? u32x4{0, 0, 0, 0} : v;
+                }
+            }
+        }
+        DFK_WAIT_LGKM0();
+        asm volatile("" ::: "memory");
+        if (s + geo.pl < nsteps) { issued += ld.issue_a(s + geo.pl, abuf); DFK_PIPE_SET_P(geo.pl - 1); }
+        if (s + geo.nb - 1 < nsteps) { issued += ld.issue_w(s + geo.nb - 1, wfree); DFK_PIPE_SET_S(geo.nb - 2); }
+        // Both blocks of the step are read and multiplied unconditionally: a block past the split
+        // has every row masked to zero below and its A operands zeroed above.
+        const unsigned char* wt = lds + (size_t)wbuf * geo.shared_step + lane * 16;
+        u32x4 w[SB][8];
+#pragma unroll
+        for (int b = 0; b < SB; ++b)
+#pragma unroll
+            for (int r = 0; r < 8; ++r) w[b][r] = *(const u32x4*)(wt + (b * 2 + (r >> 2)) * kTileBytes + (r & 3) * 1024);
+#pragma unroll
+        for (int b = 0; b < SB; ++b) {
+            const int jb = s * SB + b;
+            if (jb * 32 + 32 > rows) {   // rows past the split contribute nothing
+#pragma unroll
+                for (int r = 0; r < 8; ++r)
+                    if (jb * 32 + 8 * g + r >= rows) w[b][r] = u32x4{0, 0, 0, 0};
+            }
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
+                u32x4 bb;
+#pragma unroll
+                for (int p = 0; p < 4; ++p) bb[p] = __builtin_amdgcn_perm(w[b][2 * p + 1][c >> 1], w[b][2 * p][c >> 1], sel);
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) acc2[c][tt] = mfma16<E>(av[b][tt], bb, acc2[c][tt]);
+            }
+        }
+        if (++abuf == geo.pl) abuf = 0;
+        if (++wbuf == geo.nb) wbuf = 0;
+        if (++wfree == geo.nb) wfree = 0;
+    }
+    DFK_STAMP(4);
+
+    // D tile (column tile c, token tile tt): lane (q, g) holds tokens 4g .. 4g+3 of the tile, column
+    // 8q + c of the block: the lane's 8 column tiles are 8 consecutive columns.
+    const bool atomic_mode = a.reduce_mode == DFK_REDUCE_ATOMIC;
+    const int nb0 = cb * 128;
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int m = (tile0 + tt) * 16 + 4 * g + i;
+            if (m < a.m_count) {
+                if (atomic_mode) {
+                    float* dst = a.yacc + (size_t)m * a.d_model + nb0 + 8 * q;
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) acc_add(dst + c, acc2[c][tt][i]);
+                } else {       // partial block of the split: plain stores, summed by the launch that follows
+                    float* dst = a.P + ((size_t)js * a.m_count + m) * a.d_model + nb0 + 8 * q;
+                    *(f32x4*)dst = f32x4{acc2[0][tt][i], acc2[1][tt][i], acc2[2][tt][i], acc2[3][tt][i]};
+                    *(f32x4*)(dst + 4) = f32x4{acc2[4][tt][i], acc2[5][tt][i], acc2[6][tt][i], acc2[7][tt][i]};
+                }
+            }
+        }
+    }
+    if (atomic_mode) {
+        drain_own_memory_ops();
+        __syncthreads();
+        if (tid == 0) flag = arrive_last(a.tickets + cb, (unsigned)a.k2_splits) ? 1 : 0;
+        __syncthreads();
+        if (!flag) return;
+        for (int idx = tid; idx < a.m_count * 64; idx += NTHREADS) {
+            const int m = idx >> 6, c2 = idx & 63;
+            float* src = a.yacc + (size_t)m * a.d_model + nb0 + 2 * c2;
+            float v0 = acc_take(src), v1 = acc_take(src + 1);
+            const size_t o = (size_t)(a.m_base + m) * a.d_model + nb0 + 2 * c2;
+            if (a.resid) {
+                float r0, r1;
+                E::widen2(*(const uint32_t*)((const uint16_t*)a.resid + o), r0, r1);
+                v0 += r0; v1 += r1;
+            }
+            *(uint32_t*)((uint16_t*)a.Y + o) = E::pack2(v0, v1);
+        }
+    }
+}
+
+// Sum of the splits' partial blocks (counter reduction mode of the down kernel above): with
+// hundreds of tokens the blocks are tens of MB, too much for the last workgroup of a column
+// block to add up alone, so a launch of its own spreads the sum over the whole chip.  Fixed
+// order (split 0, 1, ...): bitwise reproducible.  One thread per four consecutive outputs.
+template <typename E>
+__global__ __launch_bounds__(256) void k_sum_partials_big(MlpArgs a) {
+    const int w4 = a.d_model >> 2;
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (size_t)a.m_count * w4) return;
+    const int m = (int)(idx / w4), c4 = (int)(idx - (size_t)m * w4);
+    const size_t blk = (size_t)a.m_count * a.d_model;
+    const float* src = a.P + (size_t)m * a.d_model + 4 * c4;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int js0 = 0; js0 < a.k2_splits; js0 += 8) {
+        float4 t[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            t[k] = js0 + k < a.k2_splits ? *(const float4*)(src + (size_t)(js0 + k) * blk) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) { v.x += t[k].x; v.y += t[k].y; v.z += t[k].z; v.w += t[k].w; }
+    }
+    store4_plus<E>(a.Y, a.resid, (size_t)(a.m_base + m) * a.d_model + 4 * c4, v);
+}
+
+// Every instantiation the launcher uses, spelled out (the host pass otherwise emitted the launch
+// stub of only one element type per token-tile count).
+#define DFK_INST_GATEUP(NTC)                                                     \
+    template __global__ void k_gateup_big<2, BF16, NTC>(MlpArgs, BigGeom);       \
+    template __global__ void k_gateup_big<2, FP16, NTC>(MlpArgs, BigGeom);       \
+    template __global__ void k_gateup_big<4, BF16, NTC>(MlpArgs, BigGeom);       \
+    template __global__ void k_gateup_big<4, FP16, NTC>(MlpArgs, BigGeom);
+DFK_INST_GATEUP(1) DFK_INST_GATEUP(2) DFK_INST_GATEUP(3) DFK_INST_GATEUP(4)
+DFK_INST_GATEUP(5) DFK_INST_GATEUP(6) DFK_INST_GATEUP(7) DFK_INST_GATEUP(8)
+#undef DFK_INST_GATEUP
+template __global__ void k_sum_partials_big<BF16>(MlpArgs);
+template __global__ void k_sum_partials_big<FP16>(MlpArgs);
+template __global__ void k_down_big<2, BF16, kBigWaves>(MlpArgs, BigGeom);
+template __global__ void k_down_big<2, FP16, kBigWaves>(MlpArgs, BigGeom);
+template __global__ void k_down_big<4, BF16, kBigWaves>(MlpArgs, BigGeom);
+template __global__ void k_down_big<4, FP16, kBigWaves>(MlpArgs, BigGeom);
+
+// ---------------------------------------------------------------- host side
+int big_token_tiles(int m_count) { return m_count <= 128 ? 2 : 4; }   // per wavefront
+
+// LDS of the gate/up kernel: nb shared buffers of the slice's weight tiles, then pl X buffers per wavefront.
+size_t big_lds_gateup(const dfk_config_t& c, int TT, int d_ff, BigGeom* geo) {
+    const int nt_max = max_slice_rows(d_ff, c.splits) / 8;
+    geo->nb = c.depth;
+    geo->shared_step = nt_max * kTileBytes;
+    geo->priv_off = geo->nb * geo->shared_step;
+    geo->priv_step = TT * kTileBytes;
+    const size_t one = (size_t)kBigWaves * geo->priv_step;
+    geo->pl = (size_t)geo->priv_off + 2 * one <= (size_t)kLdsLimit ? 2 : 1;
+    return (size_t)geo->priv_off + geo->pl * one;
+}
+size_t big_lds_down(const dfk_config_t& c, BigGeom* geo) {
+    geo->nb = c.depth;
+    geo->shared_step = kBigSB * 2 * kTileBytes;
+    geo->priv_off = geo->nb * geo->shared_step;
+    geo->priv_step = 4 * 2048;                 // 2 KB per token tile of the wavefront (up to 4)
+    const size_t one = (size_t)kBigWaves * geo->priv_step;
+    geo->pl = (size_t)geo->priv_off + 2 * one <= (size_t)kLdsLimit ? 2 : 1;
+    return (size_t)geo->priv_off + geo->pl * one;
+}
+
+template <int TT, typename E, int NTC>
+hipError_t launch_big_gateup(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
+    static size_t configured = 0;
+    BigGeom geo;
+    const size_t lds = big_lds_gateup(c, TT, a.d_ff, &geo);
+    if (lds > configured) {
+        hipError_t e = hipFuncSetAttribute((const void*)k_gateup_big<TT, E, NTC>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        configured = lds;
+    }
+    hipLaunchKernelGGL((k_gateup_big<TT, E, NTC>), dim3(a.splits), dim3(kBigWaves * 64), lds, st, a, geo);
+    return hipGetLastError();
+}
+
+template <int TT, typename E>
+hipError_t launch_big_te(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
+    static size_t configured2 = 0;
+    if (g_stage_mask & 1) {
+        hipError_t e;
+        switch (max_slice_rows(a.d_ff, c.splits) / 8) {
+            case 1: e = launch_big_gateup<TT, E, 1>(a, c, st); break;
+            case 2: e = launch_big_gateup<TT, E, 2>(a, c, st); break;
+            case 3: e = launch_big_gateup<TT, E, 3>(a, c, st); break;
+            case 4: e = launch_big_gateup<TT, E, 4>(a, c, st); break;
+            case 5: e = launch_big_gateup<TT, E, 5>(a, c, st); break;
+            case 6: e = launch_big_gateup<TT, E, 6>(a, c, st); break;
+            case 7: e = launch_big_gateup<TT, E, 7>(a, c, st); break;
+            case 8: e = launch_big_gateup<TT, E, 8>(a, c, st); break;
+            default: e = hipErrorInvalidValue; break;
+        }
+        if (e != hipSuccess) return e;
+    }
+    if (g_stage_mask & 2) {
+        BigGeom geo;
+        const size_t lds = big_lds_down(c, &geo);
+        if (lds > configured2) {
+            hipError_t e = hipFuncSetAttribute((const void*)k_down_big<TT, E, kBigWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            configured2 = lds;
+        }
+        hipLaunchKernelGGL((k_down_big<TT, E, kBigWaves>), dim3(a.k2_splits * a.k2_col_blocks), dim3(kBigWaves * 64), lds, st, a, geo);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess || a.reduce_mode == DFK_REDUCE_ATOMIC) return e;
+        const size_t n4 = (size_t)a.m_count * (a.d_model / 4);
+        hipLaunchKernelGGL((k_sum_partials_big<E>), dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, a);
+        return hipGetLastError();
+    }
+    return hipSuccess;
+}
+
+template <int TT>
+hipError_t launch_big_t(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
+    return a.dtype == DFK_FP16 ? launch_big_te<TT, FP16>(a, c, st) : launch_big_te<TT, BF16>(a, c, st);
+}
+
+}  // namespace
+
+int mfma_big_tokens_per_launch() { return kBigTokensPerLaunch; }
+
+bool mfma_big_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype) {
+    if (c.path != DFK_PATH_MFMA || (dtype != DFK_BF16 && dtype != DFK_FP16) || c.variant != DFK_VARIANT_TWO_KERNEL) return false;
+    if (c.kmajor != 2 || c.k2_rows_by_wave != 0 || c.a2_dtype != (int)dtype) return false;
+    if (c.reduce != DFK_REDUCE_TICKET && c.reduce != DFK_REDUCE_ATOMIC) return false;
+    if (c.waves != kBigWaves || c.depth < 3 || c.depth > 4) return false;      // depth = buffers of shared tiles
+    if (M < 1 || d_model < 128 || d_ff < 8 || d_ff % 8 || d_model % kKC || d_model > kMaxDModel) return false;
+    const int ng = d_ff / 8;
+    if (c.splits < 1 || c.splits > ng || c.splits > 65535) return false;
+    if (max_slice_rows(d_ff, c.splits) / 8 > kBigMaxRowTiles) return false;
+    if (c.k2_splits < 1 || c.k2_splits > ng) return false;
+    if (c.k2_col_blocks != d_model / 128) return false;                        // one 128-column block per workgroup
+    if ((long long)c.k2_splits * c.k2_col_blocks > 65535 || c.k2_col_blocks > kTicketLevel2) return false;
+    const int tokens = std::min(M, kBigTokensPerLaunch);
+    if ((size_t)tokens * d_model * 4 > kYaccBytes) return false;               // fp32 accumulator of one launch
+    if (c.reduce == DFK_REDUCE_TICKET && !partials_fit(c.k2_splits, tokens, M, d_model)) return false;
+    BigGeom geo;
+    return big_lds_gateup(c, big_token_tiles(tokens), d_ff, &geo) <= (size_t)kLdsLimit && big_lds_down(c, &geo) <= (size_t)kLdsLimit;
+}
+
+hipError_t launch_mfma_big(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
+    if (a.norm_w) return hipErrorInvalidValue;   // the normalisation is folded into the 64-token pair only
+    return big_token_tiles(a.m_count) == 2 ? launch_big_t<2>(a, c, st) : launch_big_t<4>(a, c, st);
+}
+
+}  // namespace dfk

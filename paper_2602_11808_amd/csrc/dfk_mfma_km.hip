@@ -32,20 +32,6 @@
 namespace dfk {
 namespace {
 
-// v_mfma_f32_16x16x32 for the element type: operands are the same 16 bytes per lane either way.
-template <typename E>
-__device__ __forceinline__ f32x4 mfma16(const u32x4& a, const u32x4& b, const f32x4& c);
-template <>
-__device__ __forceinline__ f32x4 mfma16<BF16>(const u32x4& a, const u32x4& b, const f32x4& c) {
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a), as_bf16x8(b), c, 0, 0, 0);
-}
-template <>
-__device__ __forceinline__ f32x4 mfma16<FP16>(const u32x4& a, const u32x4& b, const f32x4& c) {
-    union { u32x4 u; FP16::h8 h; } x, y;
-    x.u = a; y.u = b;
-    return __builtin_amdgcn_mfma_f32_16x16x32_f16(x.h, y.h, c, 0, 0, 0);
-}
-
 constexpr int kKmMaxRowTiles = 8;   // row tiles per workgroup of the gate/up kernel (accumulators)
 constexpr int kKmTokensPerLaunch = 64;
 

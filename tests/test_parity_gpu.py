@@ -185,6 +185,54 @@ def test_kernels_for_up_to_64_tokens_per_launch(shape):
             assert workspace_is_clean(ws, M, d), (shape, cfg)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "fp16"])
+@pytest.mark.parametrize("shape", [(65, 1024, 2816), (100, 512, 1000), (128, 1024, 4104), (129, 2048, 4104),
+                                   (200, 512, 1536), (256, 1024, 4104)],
+                         ids=lambda s: "M%d_d%d_ff%d" % s)
+def test_kernels_for_up_to_256_tokens_per_launch(shape, dtype):
+    """Every candidate of the pair of kernels whose workgroups share the weight tiles (config
+    field kmajor = 2): two and four token tiles per wavefront, token tiles that are partly or
+    wholly empty, ragged d_ff, both reductions, up to the largest token count a call accepts."""
+    M, d, ff = shape
+    t = di.mlp_inputs(M, d, ff, seed=29, dtype=dtype)
+    ref = oracle.swiglu_mlp(t["X"], t["Wg"], t["Wu"], t["Wd"])
+    g = gpu_inputs(t)
+    ws = dfk.new_workspace(M, d, ff, DEV)
+    n = dfk.dfk_num_candidates(M, d, ff, _dt(dtype))
+    cfgs = [c for c in (dfk.dfk_get_candidate(M, d, ff, _dt(dtype), i) for i in range(n)) if c.kmajor == 2]
+    assert cfgs
+    assert {c.reduce for c in cfgs} == {dfk.DFK_REDUCE_TICKET, dfk.DFK_REDUCE_ATOMIC}
+    for cfg in cfgs:
+        print("case", shape, dtype, cfg, flush=True)
+        for _ in range(2):
+            Y, _ = run_ex(g, cfg, ws)
+            err = rel_err(y64(Y), ref)
+            assert err <= _tol(dtype), (shape, cfg, err)
+            assert workspace_is_clean(ws, M, d), (shape, cfg)
+
+
+def test_kernels_for_up_to_256_tokens_full_size_sampled_rows():
+    """Headline shape at 128 and 256 tokens in one launch: a sample of tokens against the oracle."""
+    d, ff = 4096, 14336
+    g = di.mlp_inputs_torch(256, d, ff, seed=31, device=DEV)
+    host = {k: di.to_numpy(v) for k, v in g.items()}
+    ws = dfk.new_workspace(256, d, ff, DEV)
+    for M in (128, 256):
+        X = g["X"][:M].contiguous()
+        rows = sorted({0, 17, 63, 64, M // 2 + 5, M - 16, M - 1})
+        ref = oracle.swiglu_mlp(host["X"][rows], host["Wg"], host["Wu"], host["Wd"])
+        cfgs = [c for c in _cfgs(M, d, ff, lambda c: c.kmajor == 2)]
+        picked = [next(c for c in cfgs if c.reduce == r) for r in (dfk.DFK_REDUCE_TICKET, dfk.DFK_REDUCE_ATOMIC)]
+        for cfg in picked:
+            print("case full", M, cfg, flush=True)
+            Y = torch.full_like(X, float("nan"))
+            dfk.dfk_swiglu_mlp_ex(X, g["Wg"], g["Wu"], g["Wd"], Y, cfg, ws)
+            torch.cuda.synchronize()
+            assert bool(torch.isfinite(Y.float()).all()), (M, cfg)
+            assert rel_err(y64(Y)[rows], ref) <= TOL_BF16, (M, cfg)
+            assert workspace_is_clean(ws, M, d)
+
+
 def _block_case(M, d, ff, dtype, seed):
     t = di.mlp_inputs(M, d, ff, seed=seed, dtype=dtype)
     t["w"] = di.tensor(seed + 1000, (d,), 1.0, dtype)
