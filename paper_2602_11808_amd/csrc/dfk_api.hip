@@ -181,12 +181,16 @@ std::vector<dfk_config_t> candidates(int M, int d_model, int d_ff, dfk_dtype_t d
 }
 
 // Untuned default.  Measured on MI355X, the two-kernel variant wins at every token count
-// (the fused kernel pays a 256-way sum of full-width partial blocks), its kernel pair
-// for up to 64 tokens first, then the rows-split down kernel, then the rest.
+// (the fused kernel pays a 256-way sum of full-width partial blocks): beyond 64 tokens the
+// kernel pair that takes up to 256 per launch, else the pair for up to 64 tokens, then the
+// rows-split down kernel, then the rest.
 bool heuristic(int M, int d_model, int d_ff, dfk_dtype_t dtype, int want_variant, dfk_config_t* out) {
     auto cands = candidates(M, d_model, d_ff, dtype);
     auto rank = [&](const dfk_config_t& c) {
-        if (c.variant == DFK_VARIANT_TWO_KERNEL) return c.kmajor ? 0 : c.k2_rows_by_wave ? 1 : 2;
+        if (c.variant == DFK_VARIANT_TWO_KERNEL) {
+            if (c.kmajor == 2) return M > 64 ? -1 : 1;     // one launch for up to 256 tokens beats several of 64
+            return c.kmajor ? 0 : c.k2_rows_by_wave ? 1 : 2;
+        }
         return 3;
     };
     const dfk_config_t* best = nullptr;

@@ -342,12 +342,17 @@ __global__ __launch_bounds__(NW * 64) void k_down_big(MlpArgs a, BigGeom geo) {
             const unsigned char* as = apriv + (size_t)abuf * geo.priv_step + (q >> 3) * 1024 + (q & 7) * 128;
 #pragma unroll
             for (int b = 0; b < SB; ++b) {
-                const bool past = (s * SB + b) * 32 + 8 * g >= rows;
                 const int k = 4 * b + g;
 #pragma unroll
-                for (int tt = 0; tt < TT; ++tt) {
-                    const u32x4 v = *(const u32x4*)(as + tt * 2048 + ((k ^ (q & 7)) * 16));
-                    av[b][tt] = past ? u32x4{0, 0, 0, 0} : v;
+                for (int tt = 0; tt < TT; ++tt) av[b][tt] = *(const u32x4*)(as + tt * 2048 + ((k ^ (q & 7)) * 16));
+            }
+            if ((s + 1) * SB * 32 > rows) {   // only the last step can reach past the split
+#pragma unroll
+                for (int b = 0; b < SB; ++b) {
+                    const bool past = (s * SB + b) * 32 + 8 * g >= rows;
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt)
+                        if (past) av[b][tt] = u32x4{0, 0, 0, 0};
                 }
             }
         }
