@@ -126,12 +126,16 @@ __device__ __forceinline__ void gateup_chunk(f32x4 (&acc)[NTC][TT], const u32x4 
 #pragma unroll
             for (int c = 0; c < 4; ++c) av[(rt + 1) & 1][c] = *(const u32x4*)(wt + (rt + 1) * kTileBytes + (((4 * c + g) ^ q)) * 16);
         }
+        // keep the four reads above ahead of this tile's MFMAs (the scheduler otherwise moves each
+        // read next to its use, two MFMAs before a full LDS wait)
+        __builtin_amdgcn_sched_barrier(0);
         if (rt + 1 < NTC || last_present) {
 #pragma unroll
             for (int c = 0; c < 4; ++c)
 #pragma unroll
                 for (int tt = 0; tt < TT; ++tt) acc[rt][tt] = mfma16<E>(av[rt & 1][c], xk[tt][c], acc[rt][tt]);
         }
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
@@ -172,12 +176,16 @@ __global__ __launch_bounds__(kBigWaves * 64) void k_gateup_big(MlpArgs a, BigGeo
 
     DFK_PIPE_DECL();
     DFK_STAMP(0);
+    // Every workgroup walks the k chunks in its own rotation: all of them read the same X, and in
+    // lock-step they would ask the same few L2 channels for the same lines at the same moment.
+    const int rot = (int)((blockIdx.x * 7u) % (unsigned)nkc);
+#define DFK_KC(step) (((step) + rot) < nkc ? (step) + rot : (step) + rot - nkc)
     // prologue: X of the first pl steps, weights of the first nb - 1, earliest needs first
     {
         int xs = 0, ws = 0;
         for (int s = 0; s < 3; ++s) {
-            if (xs < geo.pl && xs < nkc && xs <= s) { issued += ld.issue_x(xs, xs); DFK_PIPE_SET_P(xs); ++xs; }
-            if (ws < geo.nb - 1 && ws < nkc && ws <= s) { issued += ld.issue_w(ws, ws); DFK_PIPE_SET_S(ws); ++ws; }
+            if (xs < geo.pl && xs < nkc && xs <= s) { issued += ld.issue_x(DFK_KC(xs), xs); DFK_PIPE_SET_P(xs); ++xs; }
+            if (ws < geo.nb - 1 && ws < nkc && ws <= s) { issued += ld.issue_w(DFK_KC(ws), ws); DFK_PIPE_SET_S(ws); ++ws; }
         }
     }
 
@@ -201,14 +209,15 @@ __global__ __launch_bounds__(kBigWaves * 64) void k_gateup_big(MlpArgs a, BigGeo
         }
         DFK_WAIT_LGKM0();      // the X buffer has been read: it may be refilled
         asm volatile("" ::: "memory");
-        if (kc + geo.pl < nkc) { issued += ld.issue_x(kc + geo.pl, xbuf); DFK_PIPE_SET_P(geo.pl - 1); }
-        if (kc + geo.nb - 1 < nkc) { issued += ld.issue_w(kc + geo.nb - 1, wfree); DFK_PIPE_SET_S(geo.nb - 2); }
+        if (kc + geo.pl < nkc) { issued += ld.issue_x(DFK_KC(kc + geo.pl), xbuf); DFK_PIPE_SET_P(geo.pl - 1); }
+        if (kc + geo.nb - 1 < nkc) { issued += ld.issue_w(DFK_KC(kc + geo.nb - 1), wfree); DFK_PIPE_SET_S(geo.nb - 2); }
         const unsigned char* wt = lds + (size_t)wbuf * geo.shared_step + (q * 16) * 16;
         gateup_chunk<NTC, TT, E>(acc, xk, wt, q, g, nt == NTC);
         if (++xbuf == geo.pl) xbuf = 0;
         if (++wbuf == geo.nb) wbuf = 0;
         if (++wfree == geo.nb) wfree = 0;
     }
+#undef DFK_KC
     DFK_STAMP(2);
 
     // D tile of (row tile, token tile): lane (q, g) holds token q, tile rows 4g .. 4g+3; rows 0..7
@@ -319,11 +328,14 @@ __global__ __launch_bounds__(NW * 64) void k_down_big(MlpArgs a, BigGeom geo) {
 
     DFK_PIPE_DECL();
     DFK_STAMP(3);
+    // The workgroups of one split read the same A_2 rows: each walks the steps in its own rotation.
+    const int rot = (int)((cb * 5u) % (unsigned)nsteps);
+#define DFK_ST(step) (((step) + rot) < nsteps ? (step) + rot : (step) + rot - nsteps)
     {
         int as = 0, ws = 0;
         for (int s = 0; s < 3; ++s) {
-            if (as < geo.pl && as < nsteps && as <= s) { issued += ld.issue_a(as, as); DFK_PIPE_SET_P(as); ++as; }
-            if (ws < geo.nb - 1 && ws < nsteps && ws <= s) { issued += ld.issue_w(ws, ws); DFK_PIPE_SET_S(ws); ++ws; }
+            if (as < geo.pl && as < nsteps && as <= s) { issued += ld.issue_a(DFK_ST(as), as); DFK_PIPE_SET_P(as); ++as; }
+            if (ws < geo.nb - 1 && ws < nsteps && ws <= s) { issued += ld.issue_w(DFK_ST(ws), ws); DFK_PIPE_SET_S(ws); ++ws; }
         }
     }
 
@@ -335,6 +347,7 @@ __global__ __launch_bounds__(NW * 64) void k_down_big(MlpArgs a, BigGeom geo) {
 
     int abuf = 0, wbuf = 0, wfree = geo.nb - 1;
     for (int s = 0; s < nsteps; ++s) {
+        const int se = DFK_ST(s);   // the rows this step covers: 64 se .. 64 se + 63 of the split
         DFK_PIPE_ENTER_STEP();
         u32x4 av[SB][TT];      // A operands: A_2[token q of tile tt][rows 8g .. 8g+7 of block b]
         {
@@ -346,10 +359,10 @@ __global__ __launch_bounds__(NW * 64) void k_down_big(MlpArgs a, BigGeom geo) {
 #pragma unroll
                 for (int tt = 0; tt < TT; ++tt) av[b][tt] = *(const u32x4*)(as + tt * 2048 + ((k ^ (q & 7)) * 16));
             }
-            if ((s + 1) * SB * 32 > rows) {   // only the last step can reach past the split
+            if ((se + 1) * SB * 32 > rows) {   // only the split's last 64 rows can reach past it
 #pragma unroll
                 for (int b = 0; b < SB; ++b) {
-                    const bool past = (s * SB + b) * 32 + 8 * g >= rows;
+                    const bool past = (se * SB + b) * 32 + 8 * g >= rows;
 #pragma unroll
                     for (int tt = 0; tt < TT; ++tt)
                         if (past) av[b][tt] = u32x4{0, 0, 0, 0};
@@ -358,8 +371,8 @@ __global__ __launch_bounds__(NW * 64) void k_down_big(MlpArgs a, BigGeom geo) {
         }
         DFK_WAIT_LGKM0();
         asm volatile("" ::: "memory");
-        if (s + geo.pl < nsteps) { issued += ld.issue_a(s + geo.pl, abuf); DFK_PIPE_SET_P(geo.pl - 1); }
-        if (s + geo.nb - 1 < nsteps) { issued += ld.issue_w(s + geo.nb - 1, wfree); DFK_PIPE_SET_S(geo.nb - 2); }
+        if (s + geo.pl < nsteps) { issued += ld.issue_a(DFK_ST(s + geo.pl), abuf); DFK_PIPE_SET_P(geo.pl - 1); }
+        if (s + geo.nb - 1 < nsteps) { issued += ld.issue_w(DFK_ST(s + geo.nb - 1), wfree); DFK_PIPE_SET_S(geo.nb - 2); }
         // Both blocks of the step are read and multiplied unconditionally: a block past the split
         // has every row masked to zero below and its A operands zeroed above.
         const unsigned char* wt = lds + (size_t)wbuf * geo.shared_step + lane * 16;
@@ -370,7 +383,7 @@ __global__ __launch_bounds__(NW * 64) void k_down_big(MlpArgs a, BigGeom geo) {
             for (int r = 0; r < 8; ++r) w[b][r] = *(const u32x4*)(wt + (b * 2 + (r >> 2)) * kTileBytes + (r & 3) * 1024);
 #pragma unroll
         for (int b = 0; b < SB; ++b) {
-            const int jb = s * SB + b;
+            const int jb = se * SB + b;
             if (jb * 32 + 32 > rows) {   // rows past the split contribute nothing
 #pragma unroll
                 for (int r = 0; r < 8; ++r)
@@ -390,6 +403,7 @@ __global__ __launch_bounds__(NW * 64) void k_down_big(MlpArgs a, BigGeom geo) {
         if (++wbuf == geo.nb) wbuf = 0;
         if (++wfree == geo.nb) wfree = 0;
     }
+#undef DFK_ST
     DFK_STAMP(4);
 
     // D tile (column tile c, token tile tt): lane (q, g) holds tokens 4g .. 4g+3 of the tile, column
