@@ -295,6 +295,29 @@ def main():
         per_m[str(M)] = {"us_per_call": round(us, 2),
                          "tb_per_s": round(algorithmic_bytes(M, D_MODEL, D_FF) / us / 1e6, 3)}
 
+    # ---- beyond the headline set (reported beside it, not part of `value`): larger token counts in
+    # one call each, scheduler's untuned default, same rotating weight sets
+    extended = {}
+    ws_ext = dfk.new_workspace(256, D_MODEL, D_FF, dev)
+    for M in (32, 64, 128, 256):
+        Xe = di.mlp_inputs_torch(M, D_MODEL, D_FF, seed=0, layer=0, device=dev)["X"]
+        Ye = torch.empty_like(Xe)
+        n = max(20, args.steps // 4)
+        for it in range(-3, n):
+            if it == 0:
+                torch.cuda.synchronize()
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+            w = layers[it % WEIGHT_SETS]
+            dfk.dfk_swiglu_mlp_ex(Xe, w["Wg"], w["Wu"], w["Wd"], Ye, None, ws_ext)
+        b.record()
+        torch.cuda.synchronize()
+        us = a.elapsed_time(b) * 1e3 / n
+        c, _ = dfk.dfk_get_choice(M, D_MODEL, D_FF, dfk.DFK_BF16)
+        extended[str(M)] = {"us_per_call": round(us, 2), "tb_per_s": round(algorithmic_bytes(M, D_MODEL, D_FF) / us / 1e6, 3),
+                            "kernel_family": {0: "first", 1: "64-token pair", 2: "256-token pair"}[c.kmajor]}
+    del ws_ext
+
     # ---- read-stream ceiling of this machine (plain 128-bit streaming read of 1.4 GB), and one
     # write-only kernel of known size; both also calibrate the FETCH_SIZE / WRITE_SIZE counters
     sink = torch.zeros(2, dtype=torch.int32, device=dev)
@@ -391,7 +414,7 @@ def main():
                                "M in {1,2,4,8,16}, one call per M per step, 4 rotating weight sets",
                    "entry": args.force, "calls_per_step": calls_per_step},
         "achieved_tb_per_s": round(achieved / 1e3, 3),
-        "per_M": per_m, "per_M_launches": kernels, "scheduler_picks": picks, "tune_seconds": round(tune_s, 2),
+        "per_M": per_m, "per_M_beyond_headline": extended, "per_M_launches": kernels, "scheduler_picks": picks, "tune_seconds": round(tune_s, 2),
         "roofline": roofline, "cpu_baseline": cpu, "parity": parity,
     }
     print(json.dumps(out))
