@@ -110,6 +110,37 @@ def test_config_validation():
     assert dfk.dfk_num_candidates(4, 4100, FF, dfk.DFK_BF16) == 0
 
 
+def test_kernel_families_by_token_count():
+    """The 64-token pair is offered at every token count, the 256-token pair beyond 64 tokens only; the
+    untuned default follows; the limits of the 256-token pair are enforced on the host."""
+    import copy
+    for dt in (dfk.DFK_BF16, dfk.DFK_FP16):
+        for M, want2 in ((1, False), (64, False), (65, True), (128, True), (256, True)):
+            cands = [dfk.dfk_get_candidate(M, D, FF, dt, i) for i in range(dfk.dfk_num_candidates(M, D, FF, dt))]
+            assert any(c.kmajor == 1 for c in cands)
+            assert any(c.kmajor == 2 for c in cands) == want2
+            for c in cands:
+                assert dfk.dfk_config_valid(c, M, D, FF, dt), (M, c)
+            pick, tuned = dfk.dfk_get_choice(M, D, FF, dt)
+            assert not tuned and pick.kmajor == (2 if want2 else 1)
+    assert dfk.dfk_num_candidates(128, D, FF, dfk.DFK_FP32) > 0          # fp32 test mode: VALU kernels only
+    assert all(dfk.dfk_get_candidate(128, D, FF, dfk.DFK_FP32, i).path == dfk.DFK_PATH_VALU
+               for i in range(dfk.dfk_num_candidates(128, D, FF, dfk.DFK_FP32)))
+    big = next(c for c in (dfk.dfk_get_candidate(256, D, FF, dfk.DFK_BF16, i)
+                         for i in range(dfk.dfk_num_candidates(256, D, FF, dfk.DFK_BF16))) if c.kmajor == 2)
+    for field, bad in (("waves", 8), ("depth", 2), ("depth", 5), ("k2_col_blocks", 16), ("splits", 128),
+                       ("a2_dtype", dfk.DFK_FP32), ("k2_rows_by_wave", 1), ("variant", dfk.DFK_VARIANT_FUSED)):
+        c = copy.copy(big)
+        setattr(c, field, bad)
+        assert not dfk.dfk_config_valid(c, 256, D, FF, dfk.DFK_BF16), (field, bad)
+    # the fp32 accumulator of one launch holds 8 MiB: 256 tokens x d_model 16384 do not fit
+    wide = copy.copy(big)
+    wide.k2_col_blocks = 16384 // 128
+    wide.k2_splits = 2
+    assert not dfk.dfk_config_valid(wide, 256, 16384, FF, dfk.DFK_BF16)
+    assert dfk.dfk_config_valid(wide, 128, 16384, FF, dfk.DFK_BF16)
+
+
 def test_scheduler_table_roundtrip(tmp_path):
     dfk.dfk_clear_tuning()
     c0, tuned = dfk.dfk_get_choice(2, D, FF, dfk.DFK_BF16)
