@@ -4,15 +4,16 @@
 // there are 8..16 token tiles of MFMA work, too many accumulators for one wavefront and too
 // much operand traffic if every wavefront fetched its own copy of the weights.  These
 // kernels are the "row-major" end of the Method section's tiling choice carried through:
-// a workgroup of four wavefronts shares every weight tile through LDS, each wavefront owns
-// a quarter of the launch's tokens (2 or 4 token tiles of 16) and keeps the whole
-// reduction for them, so there is no cross-wavefront sum at the end.
+// the wavefronts of a workgroup (four in the gate/up kernel, eight in the down kernel) share
+// every weight tile through LDS, each wavefront owns its share of the launch's tokens (1, 2
+// or 4 token tiles of 16) and keeps the whole reduction for them, so there is no
+// cross-wavefront sum at the end.
 //
 // Data movement is the same asynchronous global->LDS tile load as in the other MFMA kernels,
 // organised as a workgroup pipeline instead of per-wavefront rings:
-//   * shared tiles (weights): 4 KB tiles of the usual layout; wavefront w issues load
-//     instruction w of every tile (1 KB each), so the four wavefronts fill a tile together and
-//     issue the same number of loads.  `nb` buffers of one pipeline step each.
+//   * shared tiles (weights): 4 KB tiles of the usual layout; the 1 KB load instructions of a
+//     step's tiles are dealt out evenly, so the wavefronts fill the tiles together and issue
+//     the same number of loads.  `nb` buffers of one pipeline step each.
 //   * private tiles (activations of the wavefront's own tokens): loaded and read by one
 //     wavefront only, `pl` buffers per wavefront.
 //   * one LDS-only barrier per step: before it every wavefront waits, by count, for its own
@@ -38,7 +39,9 @@
 namespace dfk {
 namespace {
 
-constexpr int kBigWaves = 4;
+constexpr int kBigWaves = 4;          // gate/up kernel
+constexpr int kBigDownWaves = 8;      // down kernel: two wavefronts per SIMD, so that one's operand shuffles
+                                      // (v_perm_b32) run under the other's MFMAs
 constexpr int kBigMaxRowTiles = 8;
 constexpr int kBigTokensPerLaunch = 256;
 constexpr int kBigSB = 2;            // 32-row blocks of W_down per step of the down kernel (the A_2 tile layout assumes 2)
@@ -245,7 +248,7 @@ __global__ __launch_bounds__(kBigWaves * 64) void k_gateup_big(MlpArgs a, BigGeo
 }
 
 // ---------------------------------------------------------------- down kernel
-template <int TT>
+template <int TT, int NW>
 struct BigLoads2 {
     const char* asrc[TT][2];   // this lane's token rows of A_2 at the split's first row (per load instruction)
     const char* Wd;
@@ -269,21 +272,24 @@ struct BigLoads2 {
                 __builtin_amdgcn_global_load_lds(asrc[tt][h] + (size_t)j * 2, DFK_LDS_PTR(dst + tt * 2048 + h * 1024), 16, 0, 0);
         return 2 * TT;
     }
-    // W_down tiles of a 32-row block: tile h (0, 1) holds rows 4h + 8g + u for instruction u; this
-    // wavefront issues instruction u = wave of both
+    // W_down tiles of a 32-row block: tile h (0, 1) holds rows 4h + 8g + u for instruction u.  The
+    // 8 instructions of a block are dealt out evenly: with 4 wavefronts each issues instruction
+    // u = wave of both tiles, with 8 wavefronts instruction wave % 4 of tile wave / 4.
     __device__ __forceinline__ int issue_w(int s, int buf) {
-        unsigned char* dst = lds + (size_t)buf * shared_step + wave * 1024;
+        const int u = wave & 3;
+        unsigned char* dst = lds + (size_t)buf * shared_step + u * 1024;
         int n = 0;
         for (int b = 0; b < kBigSB; ++b) {
             const int jb = s * kBigSB + b;
             if (jb < njb) {
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const int row = min(j0 + jb * 32 + 4 * h + 8 * g + wave, d_ff - 1);   // past d_ff: masked at use
+                for (int hh = 0; hh < (NW == 8 ? 1 : 2); ++hh) {
+                    const int h = NW == 8 ? (wave >> 2) : hh;
+                    const int row = min(j0 + jb * 32 + 4 * h + 8 * g + u, d_ff - 1);   // past d_ff: masked at use
                     __builtin_amdgcn_global_load_lds(Wd + (size_t)row * row_bytes + colb + 16 * q,
                                                      DFK_LDS_PTR(dst + (b * 2 + h) * kTileBytes), 16, 0, kAuxNonTemporal);
                 }
-                n += 2;
+                n += NW == 8 ? 1 : 2;
             }
         }
         return n;
@@ -294,7 +300,8 @@ template <int TT, typename E, int NW>
 __global__ __launch_bounds__(NW * 64) void k_down_big(MlpArgs a, BigGeom geo) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     __shared__ int flag;
-    constexpr int NTHREADS = kBigWaves * 64;
+    static_assert(NW == 4 || NW == 8, "shared tiles are dealt out to 4 or 8 wavefronts");
+    constexpr int NTHREADS = NW * 64;
     constexpr int SB = kBigSB;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -311,7 +318,7 @@ __global__ __launch_bounds__(NW * 64) void k_down_big(MlpArgs a, BigGeom geo) {
     const int tile0 = wave * TT;
     const size_t colb = (size_t)cb * 256;
 
-    BigLoads2<TT> ld;
+    BigLoads2<TT, NW> ld;
     ld.Wd = (const char*)a.Wd; ld.row_bytes = row_bytes; ld.colb = colb;
     ld.j0 = j0; ld.rows = rows; ld.njb = njb; ld.d_ff = a.d_ff; ld.wave = wave; ld.q = q; ld.g = g;
     ld.lds = lds; ld.shared_step = geo.shared_step; ld.priv_step = geo.priv_step;
@@ -485,10 +492,10 @@ DFK_INST_GATEUP(5) DFK_INST_GATEUP(6) DFK_INST_GATEUP(7) DFK_INST_GATEUP(8)
 #undef DFK_INST_GATEUP
 template __global__ void k_sum_partials_big<BF16>(MlpArgs);
 template __global__ void k_sum_partials_big<FP16>(MlpArgs);
-template __global__ void k_down_big<2, BF16, kBigWaves>(MlpArgs, BigGeom);
-template __global__ void k_down_big<2, FP16, kBigWaves>(MlpArgs, BigGeom);
-template __global__ void k_down_big<4, BF16, kBigWaves>(MlpArgs, BigGeom);
-template __global__ void k_down_big<4, FP16, kBigWaves>(MlpArgs, BigGeom);
+template __global__ void k_down_big<1, BF16, kBigDownWaves>(MlpArgs, BigGeom);
+template __global__ void k_down_big<1, FP16, kBigDownWaves>(MlpArgs, BigGeom);
+template __global__ void k_down_big<2, BF16, kBigDownWaves>(MlpArgs, BigGeom);
+template __global__ void k_down_big<2, FP16, kBigDownWaves>(MlpArgs, BigGeom);
 
 // ---------------------------------------------------------------- host side
 int big_token_tiles(int m_count) { return m_count <= 128 ? 2 : 4; }   // per wavefront
@@ -508,8 +515,8 @@ size_t big_lds_down(const dfk_config_t& c, BigGeom* geo) {
     geo->nb = c.depth;
     geo->shared_step = kBigSB * 2 * kTileBytes;
     geo->priv_off = geo->nb * geo->shared_step;
-    geo->priv_step = 4 * 2048;                 // 2 KB per token tile of the wavefront (up to 4)
-    const size_t one = (size_t)kBigWaves * geo->priv_step;
+    geo->priv_step = 2 * 2048;                 // 2 KB per token tile of the wavefront (up to 2)
+    const size_t one = (size_t)kBigDownWaves * geo->priv_step;
     geo->pl = (size_t)geo->priv_off + 2 * one <= (size_t)kLdsLimit ? 2 : 1;
     return (size_t)geo->priv_off + geo->pl * one;
 }
@@ -550,11 +557,12 @@ hipError_t launch_big_te(const MlpArgs& a, const dfk_config_t& c, hipStream_t st
         BigGeom geo;
         const size_t lds = big_lds_down(c, &geo);
         if (lds > configured2) {
-            hipError_t e = hipFuncSetAttribute((const void*)k_down_big<TT, E, kBigWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            hipError_t e = hipFuncSetAttribute((const void*)k_down_big<TT / 2, E, kBigDownWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
             configured2 = lds;
         }
-        hipLaunchKernelGGL((k_down_big<TT, E, kBigWaves>), dim3(a.k2_splits * a.k2_col_blocks), dim3(kBigWaves * 64), lds, st, a, geo);
+        // (TT token tiles per wavefront of the 4-wavefront gate/up kernel are TT / 2 in the 8 of this one)
+        hipLaunchKernelGGL((k_down_big<TT / 2, E, kBigDownWaves>), dim3(a.k2_splits * a.k2_col_blocks), dim3(kBigDownWaves * 64), lds, st, a, geo);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess || a.reduce_mode == DFK_REDUCE_ATOMIC) return e;
         const size_t n4 = (size_t)a.m_count * (a.d_model / 4);
