@@ -107,10 +107,11 @@ typedef enum { DFK_REDUCE_TICKET = 0, DFK_REDUCE_ATOMIC = 1 } dfk_reduce_t;
  *                  k-major with all its row tiles accumulating in registers); needs
  *                  k2_rows_by_wave = 0; 0 = the kernels above;
  *                  2 = the pair that takes up to 256 tokens per launch (offered beyond 64
- *                  tokens): four wavefronts share every weight tile through LDS and own a
- *                  quarter of the tokens each; waves = 4, depth = 3 or 4 (buffers of shared
- *                  tiles), k2_col_blocks = d_model / 128; with DFK_REDUCE_TICKET the splits'
- *                  partial sums are added by a third, small launch
+ *                  tokens): the wavefronts share every weight tile through LDS and own a
+ *                  share of the tokens each; waves = 4 or 8 (wavefronts of the gate/up kernel;
+ *                  the down kernel always runs 8), depth = 3 or 4 (buffers of shared tiles),
+ *                  k2_col_blocks = d_model / 128; with DFK_REDUCE_TICKET the splits' partial
+ *                  sums are added by a third, small launch
  */
 typedef struct dfk_config_t {
     int variant;

@@ -161,8 +161,9 @@ std::vector<dfk_config_t> candidates(int M, int d_model, int d_ff, dfk_dtype_t d
                 for (int grid : {256, 512})
                     for (int reduce : {DFK_REDUCE_TICKET, DFK_REDUCE_ATOMIC})
                         for (int depth : {3, 4})
-                            push(make_cfg(DFK_VARIANT_TWO_KERNEL, DFK_PATH_MFMA, clamp_splits(splits, d_ff), 4, depth,
-                                          clamp_splits(std::max(1, grid / k2c), d_ff), k2c, (int)dtype, reduce, 0, 2));
+                            for (int waves : {8, 4})   // of the gate/up kernel
+                                push(make_cfg(DFK_VARIANT_TWO_KERNEL, DFK_PATH_MFMA, clamp_splits(splits, d_ff), waves, depth,
+                                              clamp_splits(std::max(1, grid / k2c), d_ff), k2c, (int)dtype, reduce, 0, 2));
         }
     }
     for (int splits : {256, 512, 1024})

@@ -4,7 +4,7 @@
 // there are 8..16 token tiles of MFMA work, too many accumulators for one wavefront and too
 // much operand traffic if every wavefront fetched its own copy of the weights.  These
 // kernels are the "row-major" end of the Method section's tiling choice carried through:
-// the wavefronts of a workgroup (four in the gate/up kernel, eight in the down kernel) share
+// the wavefronts of a workgroup (four or eight in the gate/up kernel, eight in the down kernel) share
 // every weight tile through LDS, each wavefront owns its share of the launch's tokens (1, 2
 // or 4 token tiles of 16) and keeps the whole reduction for them, so there is no
 // cross-wavefront sum at the end.
@@ -39,7 +39,7 @@
 namespace dfk {
 namespace {
 
-constexpr int kBigWaves = 4;          // gate/up kernel
+constexpr int kBigWaves = 4;          // gate/up kernel: 4 or 8; token tiles per wavefront are counted for 4
 constexpr int kBigDownWaves = 8;      // down kernel: two wavefronts per SIMD, so that one's operand shuffles
                                       // (v_perm_b32) run under the other's MFMAs
 constexpr int kBigMaxRowTiles = 8;
@@ -87,7 +87,7 @@ __device__ __forceinline__ void wait_vm_exact(int n) {
     } while (0)
 
 // ---------------------------------------------------------------- gate/up kernel
-template <int TT>
+template <int TT, int NW>
 struct BigLoads1 {
     const char* wsrc;          // this lane's address in the slice's first weight tile, chunk 0
     const char* xsrc[TT][4];   // this lane's addresses in the wavefront's X tiles, chunk 0
@@ -105,12 +105,17 @@ struct BigLoads1 {
                 __builtin_amdgcn_global_load_lds(xsrc[tt][u] + (size_t)kc * (kKC * 2), DFK_LDS_PTR(dst + tt * kTileBytes + u * 1024), 16, 0, 0);
         return 4 * TT;
     }
+    // 4 wavefronts: each issues its instruction (wave) of every tile; 8: instruction wave % 4 of
+    // the tiles of parity wave / 4
     __device__ __forceinline__ int issue_w(int kc, int buf) {
-        unsigned char* dst = lds + (size_t)buf * shared_step + wave * 1024;
-        for (int rt = 0; rt < nt; ++rt)
+        unsigned char* dst = lds + (size_t)buf * shared_step + (wave & 3) * 1024;
+        int n = 0;
+        for (int rt = NW == 8 ? (wave >> 2) : 0; rt < nt; rt += NW == 8 ? 2 : 1) {
             __builtin_amdgcn_global_load_lds(wsrc + (size_t)rt * 8 * row_bytes + (size_t)kc * (kKC * 2), DFK_LDS_PTR(dst + rt * kTileBytes), 16, 0,
                                              kAuxNonTemporal);
-        return nt;
+            ++n;
+        }
+        return n;
     }
 };
 
@@ -144,8 +149,8 @@ __device__ __forceinline__ void gateup_chunk(f32x4 (&acc)[NTC][TT], const u32x4 
 
 // NTC: the largest row-tile count of a d_ff slice of the launch (a compile-time constant so that
 // the chunk body is straight-line code); every slice has NTC or NTC - 1 row tiles.
-template <int TT, typename E, int NTC>
-__global__ __launch_bounds__(kBigWaves * 64) void k_gateup_big(MlpArgs a, BigGeom geo) {
+template <int TT, typename E, int NTC, int NW>
+__global__ __launch_bounds__(NW * 64) void k_gateup_big(MlpArgs a, BigGeom geo) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     constexpr int NT = NTC;
     const int tid = threadIdx.x;
@@ -159,12 +164,12 @@ __global__ __launch_bounds__(kBigWaves * 64) void k_gateup_big(MlpArgs a, BigGeo
     const size_t row_bytes = (size_t)a.d_model * 2;
     const int tile0 = wave * TT;                   // this wavefront's first token tile
 
-    BigLoads1<TT> ld;
+    BigLoads1<TT, NW> ld;
     ld.row_bytes = row_bytes; ld.nt = nt; ld.wave = wave; ld.lds = lds;
     ld.shared_step = geo.shared_step; ld.priv_step = geo.priv_step;
     // this wavefront's instruction of a weight tile: tile row i = 4*wave + g, 16-byte chunk q ^ i
-    const int iw = 4 * wave + g;
-    ld.wsrc = (const char*)(wave < 2 ? a.Wg : a.Wu) + (size_t)j0 * row_bytes + (size_t)(iw & 7) * row_bytes + ((q ^ iw) * 16);
+    const int iw = 4 * (wave & 3) + g;
+    ld.wsrc = (const char*)((wave & 3) < 2 ? a.Wg : a.Wu) + (size_t)j0 * row_bytes + (size_t)(iw & 7) * row_bytes + ((q ^ iw) * 16);
     // X tile: instruction u covers tile rows (tokens) 4u + g
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt)
@@ -483,10 +488,14 @@ __global__ __launch_bounds__(256) void k_sum_partials_big(MlpArgs a) {
 // Every instantiation the launcher uses, spelled out (the host pass otherwise emitted the launch
 // stub of only one element type per token-tile count).
 #define DFK_INST_GATEUP(NTC)                                                     \
-    template __global__ void k_gateup_big<2, BF16, NTC>(MlpArgs, BigGeom);       \
-    template __global__ void k_gateup_big<2, FP16, NTC>(MlpArgs, BigGeom);       \
-    template __global__ void k_gateup_big<4, BF16, NTC>(MlpArgs, BigGeom);       \
-    template __global__ void k_gateup_big<4, FP16, NTC>(MlpArgs, BigGeom);
+    template __global__ void k_gateup_big<1, BF16, NTC, 8>(MlpArgs, BigGeom);    \
+    template __global__ void k_gateup_big<1, FP16, NTC, 8>(MlpArgs, BigGeom);    \
+    template __global__ void k_gateup_big<2, BF16, NTC, 8>(MlpArgs, BigGeom);    \
+    template __global__ void k_gateup_big<2, FP16, NTC, 8>(MlpArgs, BigGeom);    \
+    template __global__ void k_gateup_big<2, BF16, NTC, 4>(MlpArgs, BigGeom);    \
+    template __global__ void k_gateup_big<2, FP16, NTC, 4>(MlpArgs, BigGeom);    \
+    template __global__ void k_gateup_big<4, BF16, NTC, 4>(MlpArgs, BigGeom);    \
+    template __global__ void k_gateup_big<4, FP16, NTC, 4>(MlpArgs, BigGeom);
 DFK_INST_GATEUP(1) DFK_INST_GATEUP(2) DFK_INST_GATEUP(3) DFK_INST_GATEUP(4)
 DFK_INST_GATEUP(5) DFK_INST_GATEUP(6) DFK_INST_GATEUP(7) DFK_INST_GATEUP(8)
 #undef DFK_INST_GATEUP
@@ -506,8 +515,8 @@ size_t big_lds_gateup(const dfk_config_t& c, int TT, int d_ff, BigGeom* geo) {
     geo->nb = c.depth;
     geo->shared_step = nt_max * kTileBytes;
     geo->priv_off = geo->nb * geo->shared_step;
-    geo->priv_step = TT * kTileBytes;
-    const size_t one = (size_t)kBigWaves * geo->priv_step;
+    geo->priv_step = TT * kTileBytes * kBigWaves / c.waves;   // TT counts token tiles per wavefront of the 4-wavefront form
+    const size_t one = (size_t)c.waves * geo->priv_step;
     geo->pl = (size_t)geo->priv_off + 2 * one <= (size_t)kLdsLimit ? 2 : 1;
     return (size_t)geo->priv_off + geo->pl * one;
 }
@@ -527,11 +536,15 @@ hipError_t launch_big_gateup(const MlpArgs& a, const dfk_config_t& c, hipStream_
     BigGeom geo;
     const size_t lds = big_lds_gateup(c, TT, a.d_ff, &geo);
     if (lds > configured) {
-        hipError_t e = hipFuncSetAttribute((const void*)k_gateup_big<TT, E, NTC>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = hipFuncSetAttribute((const void*)k_gateup_big<TT, E, NTC, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_gateup_big<TT / 2, E, NTC, 8>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         configured = lds;
     }
-    hipLaunchKernelGGL((k_gateup_big<TT, E, NTC>), dim3(a.splits), dim3(kBigWaves * 64), lds, st, a, geo);
+    if (c.waves == 8)
+        hipLaunchKernelGGL((k_gateup_big<TT / 2, E, NTC, 8>), dim3(a.splits), dim3(512), lds, st, a, geo);
+    else
+        hipLaunchKernelGGL((k_gateup_big<TT, E, NTC, 4>), dim3(a.splits), dim3(256), lds, st, a, geo);
     return hipGetLastError();
 }
 
@@ -585,7 +598,7 @@ bool mfma_big_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, 
     if (c.path != DFK_PATH_MFMA || (dtype != DFK_BF16 && dtype != DFK_FP16) || c.variant != DFK_VARIANT_TWO_KERNEL) return false;
     if (c.kmajor != 2 || c.k2_rows_by_wave != 0 || c.a2_dtype != (int)dtype) return false;
     if (c.reduce != DFK_REDUCE_TICKET && c.reduce != DFK_REDUCE_ATOMIC) return false;
-    if (c.waves != kBigWaves || c.depth < 3 || c.depth > 4) return false;      // depth = buffers of shared tiles
+    if ((c.waves != 4 && c.waves != 8) || c.depth < 3 || c.depth > 4) return false;   // depth = buffers of shared tiles
     if (M < 1 || d_model < 128 || d_ff < 8 || d_ff % 8 || d_model % kKC || d_model > kMaxDModel) return false;
     const int ng = d_ff / 8;
     if (c.splits < 1 || c.splits > ng || c.splits > 65535) return false;

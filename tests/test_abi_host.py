@@ -128,7 +128,7 @@ def test_kernel_families_by_token_count():
                for i in range(dfk.dfk_num_candidates(128, D, FF, dfk.DFK_FP32)))
     big = next(c for c in (dfk.dfk_get_candidate(256, D, FF, dfk.DFK_BF16, i)
                          for i in range(dfk.dfk_num_candidates(256, D, FF, dfk.DFK_BF16))) if c.kmajor == 2)
-    for field, bad in (("waves", 8), ("depth", 2), ("depth", 5), ("k2_col_blocks", 16), ("splits", 128),
+    for field, bad in (("waves", 2), ("waves", 16), ("depth", 2), ("depth", 5), ("k2_col_blocks", 16), ("splits", 128),
                        ("a2_dtype", dfk.DFK_FP32), ("k2_rows_by_wave", 1), ("variant", dfk.DFK_VARIANT_FUSED)):
         c = copy.copy(big)
         setattr(c, field, bad)
