@@ -211,13 +211,14 @@ def test_kernels_for_up_to_256_tokens_per_launch(shape, dtype):
             assert workspace_is_clean(ws, M, d), (shape, cfg)
 
 
-def test_kernels_for_up_to_256_tokens_full_size_sampled_rows():
-    """Headline shape at 128 and 256 tokens in one launch: a sample of tokens against the oracle."""
-    d, ff = 4096, 14336
-    g = di.mlp_inputs_torch(256, d, ff, seed=31, device=DEV)
+@pytest.mark.parametrize("d,ff,Ms", [(4096, 14336, (128, 256)), (5120, 27648, (128,))], ids=["llama3_8b", "qwen2.5_32b"])
+def test_kernels_for_up_to_256_tokens_full_size_sampled_rows(d, ff, Ms):
+    """Full-size layers at 128 and 256 tokens in one launch: a sample of tokens against the oracle
+    (the second shape has 40 column blocks and d_ff slices of 6 and 7 row tiles)."""
+    g = di.mlp_inputs_torch(max(Ms), d, ff, seed=31, device=DEV)
     host = {k: di.to_numpy(v) for k, v in g.items()}
-    ws = dfk.new_workspace(256, d, ff, DEV)
-    for M in (128, 256):
+    ws = dfk.new_workspace(max(Ms), d, ff, DEV)
+    for M in Ms:
         X = g["X"][:M].contiguous()
         rows = sorted({0, 17, 63, 64, M // 2 + 5, M - 16, M - 1})
         ref = oracle.swiglu_mlp(host["X"][rows], host["Wg"], host["Wu"], host["Wd"])
