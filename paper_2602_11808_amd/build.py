@@ -27,22 +27,28 @@ FLAGS = [
 ]
 
 
+def _compile(hipcc: str, s: str, verbose: bool) -> str:
+    src = os.path.join(CSRC, s)
+    obj = os.path.join(CSRC, s.replace(".hip", ".o"))
+    cmd = [hipcc, *[f for f in FLAGS if f != "-shared"], "-c", src, "-o", obj]
+    if verbose:
+        print("[dfk build]", " ".join(cmd), flush=True)
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    out = "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l)
+    if out.strip() and verbose:
+        print(out)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed on {s}:\n{out}")
+    return obj
+
+
 def build(verbose: bool = True) -> str:
+    """Compiles every source (a few at a time: the kernel files take about half a minute each) and links."""
+    from concurrent.futures import ThreadPoolExecutor
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    objs = []
-    for s in SOURCES:
-        src = os.path.join(CSRC, s)
-        obj = os.path.join(CSRC, s.replace(".hip", ".o"))
-        cmd = [hipcc, *[f for f in FLAGS if f != "-shared"], "-c", src, "-o", obj]
-        if verbose:
-            print("[dfk build]", " ".join(cmd), flush=True)
-        r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-        out = "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l)
-        if out.strip() and verbose:
-            print(out)
-        if r.returncode != 0:
-            raise RuntimeError(f"hipcc failed on {s}:\n{out}")
-        objs.append(obj)
+    jobs = max(1, min(4, len(os.sched_getaffinity(0))))
+    with ThreadPoolExecutor(max_workers=jobs) as pool:
+        objs = list(pool.map(lambda s: _compile(hipcc, s, verbose), SOURCES))
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     if verbose:
         print("[dfk build]", " ".join(cmd), flush=True)
