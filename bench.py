@@ -295,6 +295,28 @@ def main():
         per_m[str(M)] = {"us_per_call": round(us, 2),
                          "tb_per_s": round(algorithmic_bytes(M, D_MODEL, D_FF) / us / 1e6, 3)}
 
+    # ---- each variant at each M: 4 repeats x 50 launches (the paper's protocol is 4 repeats), mean +- std
+    # and median of the repeats' per-call times
+    per_variant = {}
+    for name, fn in (("scheduler", dfk.dfk_swiglu_mlp), ("fused", dfk.dfk_swiglu_mlp_fused),
+                     ("two_kernel", dfk.dfk_swiglu_mlp_unfused)):
+        rows = {}
+        for M in M_SET:
+            reps = []
+            for rep in range(-1, 4):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                for i in range(50):
+                    w = layers[(rep + i) % WEIGHT_SETS]
+                    fn(X[M], w["Wg"], w["Wu"], w["Wd"], Y[M])
+                b.record()
+                torch.cuda.synchronize()
+                if rep >= 0:
+                    reps.append(a.elapsed_time(b) * 1e3 / 50)
+            rows[str(M)] = {"mean_us": round(float(np.mean(reps)), 2), "std_us": round(float(np.std(reps)), 2),
+                            "median_us": round(float(np.median(reps)), 2)}
+        per_variant[name] = rows
+
     # ---- beyond the headline set (reported beside it, not part of `value`): larger token counts in
     # one call each, scheduler's untuned default, same rotating weight sets
     extended = {}
@@ -414,7 +436,7 @@ def main():
                                "M in {1,2,4,8,16}, one call per M per step, 4 rotating weight sets",
                    "entry": args.force, "calls_per_step": calls_per_step},
         "achieved_tb_per_s": round(achieved / 1e3, 3),
-        "per_M": per_m, "per_M_beyond_headline": extended, "per_M_launches": kernels, "scheduler_picks": picks, "tune_seconds": round(tune_s, 2),
+        "per_M": per_m, "per_variant_4x50": per_variant, "per_M_beyond_headline": extended, "per_M_launches": kernels, "scheduler_picks": picks, "tune_seconds": round(tune_s, 2),
         "roofline": roofline, "cpu_baseline": cpu, "parity": parity,
     }
     print(json.dumps(out))
