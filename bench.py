@@ -121,7 +121,7 @@ def block32(args, torch, di, dfk, dev):
     arithmetic as separate launches around the plain block (a normalisation kernel without the
     weight, the block, an elementwise add)."""
     L = 32
-    sweep = (1, 4, 16, 64)
+    sweep = (1, 4, 16, 64, 256)
     eps = 1e-5
     layers = [di.mlp_inputs_torch(1, D_MODEL, D_FF, seed=1000, layer=l, device=dev) for l in range(L)]
     nws = [di.to_torch(di.tensor(5000 + l, (D_MODEL,), 1.0, "bf16"), dev) for l in range(L)]

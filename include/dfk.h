@@ -183,9 +183,13 @@ dfk_status_t dfk_swiglu_mlp_ex(const void* X, const void* W_gate, const void* W_
  * other overlap is DFK_ERR_ALIAS.  eps >= 0; a row of zeros with eps == 0 yields NaN, as
  * the definition does.  The product H[m,k] * w[k] is rounded once to dtype before the
  * contraction (with half inputs it must stay finite in half precision).
- * Runs on the kernel pair for up to 64 tokens per launch only (cfg->kmajor == 1;
- * cfg == NULL picks the scheduler's choice among those): shapes that pair does not cover
- * give DFK_ERR_UNSUPPORTED_SHAPE.  Workspace as for dfk_swiglu_mlp_ex.
+ * Runs on the kernel pairs that take the activations through LDS: cfg->kmajor == 1 (up to 64
+ * tokens per launch, everything folded into the two launches as described), or
+ * cfg->kmajor == 2 (up to 256 tokens; there the normalisation is one small launch of its own
+ * ahead of the pair, into the workspace: that pair is paced by its arithmetic, and scaling X
+ * inside every workgroup measured slower; the residual add stays in the final store).
+ * cfg == NULL picks the scheduler's choice among those.  Any other configuration, and shapes
+ * those pairs do not cover, give DFK_ERR_UNSUPPORTED_SHAPE.  Workspace as for dfk_swiglu_mlp_ex.
  */
 dfk_status_t dfk_mlp_block(const void* H, const void* norm_weight, float eps,
                            const void* W_gate, const void* W_up, const void* W_down,

@@ -263,6 +263,15 @@ dfk_status_t run(const void* X, const void* Wg, const void* Wu, const void* Wd, 
     a.Q = (float*)((char*)ws + l.q_off);
     a.a2 = (char*)ws + l.a2_off;
     a.norm_w = norm_w; a.eps = eps; a.resid = resid;
+    if (norm_w && c.kmajor == 2) {
+        // The 256-token pair is paced by its MFMA and LDS work, so scaling X inside every workgroup
+        // costs more there than one small launch that writes the normalised input once.
+        void* xn = (char*)ws + l.xn_off;
+        hipError_t e = launch_rmsnorm_weighted(X, norm_w, xn, M, d_model, eps, dtype, st);
+        if (e != hipSuccess) return hip_fail(e);
+        a.X = xn;
+        a.norm_w = nullptr;
+    }
     a.trace = nullptr;
     {
         const size_t grid = (size_t)std::max(c.splits, c.k2_splits * std::max(1, c.k2_col_blocks));
@@ -439,19 +448,23 @@ dfk_status_t dfk_mlp_block(const void* H, const void* norm_weight, float eps, co
         if (overlaps(H_out, nx, norm_weight, nv) || overlaps(workspace, workspace_bytes, norm_weight, nv))
             return DFK_ERR_ALIAS;
     }
+    auto carries = [&](const dfk_config_t& k) {
+        return k.path == DFK_PATH_MFMA &&
+               ((k.kmajor == 1 && mfma_km_block_config_valid(k, M, d_model, d_ff, dtype)) ||
+                (k.kmajor == 2 && mfma_big_config_valid(k, M, d_model, d_ff, dtype)));
+    };
     dfk_config_t c;
     if (cfg) c = *cfg;
     else {
         if (!choose(M, d_model, d_ff, dtype, DFK_VARIANT_TWO_KERNEL, &c, nullptr)) return DFK_ERR_UNSUPPORTED_SHAPE;
-        if (c.kmajor != 1) {   // the scheduler's pick is another kernel family: first candidate of the pair that carries this form
+        if (!carries(c)) {   // the scheduler's pick is another kernel family: first candidate that carries this form
             bool found = false;
             for (const auto& k : candidates(M, d_model, d_ff, dtype))
-                if (k.kmajor == 1 && mfma_km_block_config_valid(k, M, d_model, d_ff, dtype)) { c = k; found = true; break; }
+                if (k.variant == DFK_VARIANT_TWO_KERNEL && carries(k)) { c = k; found = true; break; }
             if (!found) return DFK_ERR_UNSUPPORTED_SHAPE;
         }
     }
-    if (c.path != DFK_PATH_MFMA || c.kmajor != 1 || !mfma_km_block_config_valid(c, M, d_model, d_ff, dtype))
-        return DFK_ERR_UNSUPPORTED_SHAPE;
+    if (!carries(c)) return DFK_ERR_UNSUPPORTED_SHAPE;
     return run(H, Wg, Wu, Wd, H_out, M, d_model, d_ff, dtype, c, workspace, (hipStream_t)stream, norm_weight, eps, H);
 }
 

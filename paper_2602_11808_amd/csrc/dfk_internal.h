@@ -17,6 +17,7 @@ namespace dfk {
 //                  (counter reduction)
 // [.., +Q)         fp32 group sums (second level of the counter reduction)
 // [.., +M*d_ff*4)  A_2 between the two launches of the two-kernel variant
+// [.., +M*d_model*2) the normalised input of dfk_mlp_block where the normalisation is a launch of its own
 // The part that has to be zero between calls comes first and has a fixed size, so
 // calls of different shapes on one workspace never put scratch where another call
 // expects zeros.
@@ -37,7 +38,7 @@ inline size_t partial_bytes(int M, int d_model) {
 }
 
 struct WsLayout {
-    size_t tickets_off, yacc_off, p_off, q_off, a2_off, total;
+    size_t tickets_off, yacc_off, p_off, q_off, a2_off, xn_off, total;
 };
 
 inline WsLayout ws_layout(int M, int d_model, int d_ff) {
@@ -47,7 +48,8 @@ inline WsLayout ws_layout(int M, int d_model, int d_ff) {
     l.p_off = l.yacc_off + kYaccBytes;
     l.q_off = l.p_off + align_up(partial_bytes(M, d_model), 256);
     l.a2_off = l.q_off + align_up(partial_bytes(M, d_model) / 8, 256);
-    l.total = l.a2_off + align_up((size_t)M * d_ff * 4, 256);
+    l.xn_off = l.a2_off + align_up((size_t)M * d_ff * 4, 256);
+    l.total = l.xn_off + align_up((size_t)M * d_model * 2, 256);
     return l;
 }
 
@@ -128,6 +130,8 @@ int valu_max_tokens_per_launch();
 hipError_t launch_zero(void* p, size_t bytes, hipStream_t st);
 hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, hipStream_t st);
 hipError_t launch_rms_normalize(const void* in, void* out, int M, int d_model, hipStream_t st);
+hipError_t launch_rmsnorm_weighted(const void* in, const void* w, void* out, int M, int d_model, float eps, dfk_dtype_t dtype,
+                                   hipStream_t st);
 hipError_t launch_fill(void* dst, size_t elems, dfk_dtype_t dtype, float scale, unsigned seed,
                        hipStream_t st);
 

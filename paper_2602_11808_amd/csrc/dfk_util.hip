@@ -77,7 +77,49 @@ __global__ __launch_bounds__(256) void k_rms_normalize(const uint16_t* __restric
         y[i] = (uint16_t)f32_to_bf16_bits(__uint_as_float((uint32_t)x[i] << 16) * scale);
 }
 
+// out[m,:] = round16(in[m,:] * w * rsqrt(mean(in[m,:]^2) + eps)), 16-bit element type E, fp32 arithmetic;
+// one workgroup per token, 16-byte accesses.  The normalisation ahead of the 256-token kernel pair in
+// dfk_mlp_block (there the in-kernel form costs more than this pass).
+template <typename E>
+__global__ __launch_bounds__(256) void k_rmsnorm_weighted(const void* __restrict__ in, const void* __restrict__ w,
+                                                          void* __restrict__ out, int d_model, float eps) {
+    __shared__ float part[4];
+    const u32x4* x = (const u32x4*)((const uint16_t*)in + (size_t)blockIdx.x * d_model);
+    const u32x4* wv = (const u32x4*)w;
+    u32x4* y = (u32x4*)((uint16_t*)out + (size_t)blockIdx.x * d_model);
+    const int nv = d_model / 8;
+    float s = 0.f;
+    for (int i = threadIdx.x; i < nv; i += 256) {
+        float f[8];
+        E::widen(x[i], f);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) s = fmaf(f[k], f[k], s);
+    }
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = s;
+    __syncthreads();
+    const float scale = __builtin_amdgcn_rsqf((part[0] + part[1] + part[2] + part[3]) / (float)d_model + eps);
+    for (int i = threadIdx.x; i < nv; i += 256) {
+        float f[8], g[8];
+        E::widen(x[i], f);
+        E::widen(wv[i], g);
+        u32x4 o;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) o[k] = E::pack2(f[2 * k] * g[2 * k] * scale, f[2 * k + 1] * g[2 * k + 1] * scale);
+        y[i] = o;
+    }
+}
+
 }  // namespace
+
+hipError_t launch_rmsnorm_weighted(const void* in, const void* w, void* out, int M, int d_model, float eps, dfk_dtype_t dtype,
+                                   hipStream_t st) {
+    if (dtype == DFK_FP16)
+        hipLaunchKernelGGL(k_rmsnorm_weighted<FP16>, dim3((unsigned)M), dim3(256), 0, st, in, w, out, d_model, eps);
+    else
+        hipLaunchKernelGGL(k_rmsnorm_weighted<BF16>, dim3((unsigned)M), dim3(256), 0, st, in, w, out, d_model, eps);
+    return hipGetLastError();
+}
 
 hipError_t launch_zero(void* p, size_t bytes, hipStream_t st) {
     const size_t n16 = bytes / 16, ntail = bytes % 16;

@@ -242,7 +242,7 @@ def _block_case(M, d, ff, dtype, seed):
 
 @pytest.mark.parametrize("dtype", ["bf16", "fp16"])
 @pytest.mark.parametrize("shape", [(1, 1024, 2816), (5, 512, 1000), (16, 1024, 4104), (17, 1024, 2816), (33, 2048, 4104),
-                                   (64, 1024, 8200), (70, 1024, 2816), (130, 512, 1536)],
+                                   (64, 1024, 8200), (70, 1024, 2816), (130, 512, 1536), (256, 1024, 2816)],
                          ids=lambda s: "M%d_d%d_ff%d" % s)
 def test_mlp_block_with_norm_and_residual(shape, dtype):
     """H + MLP(RMSNorm(H)) in the two launches of the plain block, against the oracle's
@@ -256,8 +256,16 @@ def test_mlp_block_with_norm_and_residual(shape, dtype):
     g = gpu_inputs(t)
     ws = dfk.new_workspace(M, d, ff, DEV)
     n = dfk.dfk_num_candidates(M, d, ff, _dt(dtype))
-    cfgs = [c for c in (dfk.dfk_get_candidate(M, d, ff, _dt(dtype), i) for i in range(n)) if c.kmajor == 1]
+    every = [dfk.dfk_get_candidate(M, d, ff, _dt(dtype), i) for i in range(n)]
+    # the two kernel pairs that carry this form (the 256-token pair with the normalisation as a launch of its
+    # own ahead of it); anything else is refused
+    cfgs = [c for c in every if c.kmajor in (1, 2)]
     assert {c.reduce for c in cfgs} == {dfk.DFK_REDUCE_TICKET, dfk.DFK_REDUCE_ATOMIC}
+    assert any(c.kmajor == 2 for c in cfgs) == (M > 64)
+    for c in [c for c in every if c not in cfgs][:3]:
+        with pytest.raises(dfk.DfkError) as ei:
+            dfk.dfk_mlp_block(g["X"], g["w"], eps, g["Wg"], g["Wu"], g["Wd"], torch.empty_like(g["X"]), c, ws)
+        assert ei.value.status == dfk.DFK_ERR_UNSUPPORTED_SHAPE
     tol = _tol(dtype)
     for cfg in cfgs:
         print("case", shape, dtype, cfg, flush=True)
@@ -319,7 +327,7 @@ def test_mlp_block_special_cases():
 def test_mlp_block_full_size_sampled_rows():
     """Headline shape, the launch configuration the scheduler picks: sampled tokens against the oracle."""
     d, ff = 4096, 14336
-    for M, dtype in ((1, "bf16"), (16, "bf16"), (64, "bf16"), (4, "fp16")):
+    for M, dtype in ((1, "bf16"), (16, "bf16"), (64, "bf16"), (4, "fp16"), (128, "bf16"), (256, "bf16")):
         g = di.mlp_inputs_torch(M, d, ff, seed=23, dtype=dtype, device=DEV)
         w = di.to_torch(di.tensor(1023, (d,), 1.0, dtype), DEV)
         ws = dfk.new_workspace(M, d, ff, DEV)
