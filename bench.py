@@ -186,6 +186,44 @@ def block32(args, torch, di, dfk, dev):
                                   "HIP graph replay", "layers": L, "per_M": rows}))
 
 
+def shapes(args, torch, di, dfk, dev):
+    """The other layer shapes of the workload list (parity-test configurations, timed here for the record):
+    scheduler tuned per shape, one call per M on three rotating weight sets."""
+    out = {}
+    for name, d, ff, Ms in (("qwen2.5-32b-shaped", 5120, 27648, (1, 8, 32, 64)),
+                            ("llama3-70b-shaped", 8192, 28672, (1, 16, 64, 128)),
+                            ("llama3-70b tp4 shard", 8192, 7168, (1, 16, 64))):
+        sets = [di.mlp_inputs_torch(1, d, ff, seed=2000, layer=l, device=dev) for l in range(3)]
+        ws = dfk.new_workspace(max(Ms), d, ff, dev)
+        scratch = torch.empty(dfk.dfk_tune_scratch_bytes(max(Ms), d, ff, dfk.DFK_BF16, 3), dtype=torch.uint8, device=dev)
+        dfk.dfk_tune(list(Ms), d, ff, dfk.DFK_BF16, scratch, sets=3, iters=6)
+        torch.cuda.synchronize()
+        del scratch
+        rows = {}
+        for M in Ms:
+            X = di.mlp_inputs_torch(M, d, ff, seed=0, layer=0, device=dev)["X"]
+            Y = torch.empty_like(X)
+            n = max(20, args.steps // 5)
+            for it in range(-3, n):
+                if it == 0:
+                    torch.cuda.synchronize()
+                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record()
+                w = sets[it % 3]
+                dfk.dfk_swiglu_mlp_ex(X, w["Wg"], w["Wu"], w["Wd"], Y, None, ws)
+            b.record()
+            torch.cuda.synchronize()
+            us = a.elapsed_time(b) * 1e3 / n
+            c, tuned = dfk.dfk_get_choice(M, d, ff, dfk.DFK_BF16)
+            rows[str(M)] = {"us_per_call": round(us, 2), "tb_per_s": round(algorithmic_bytes(M, d, ff) / us / 1e6, 3),
+                            "frac_of_8tbs": round(algorithmic_bytes(M, d, ff) / us / 1e6 / 8.0, 4),
+                            "pick": dict(c.as_dict(), tuned=tuned)}
+        out[name] = {"d_model": d, "d_ff": ff, "per_M": rows}
+        del sets, ws
+        torch.cuda.empty_cache()
+    print(json.dumps({"workload": "shapes: other decode-shaped layers, bf16, scheduler tuned per shape", "shapes": out}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -196,11 +234,11 @@ def main():
     ap.add_argument("--tuning-file", default=None,
                     help="load the scheduler table from this file if it exists, else tune and save it there")
     ap.add_argument("--force", choices=["auto", "fused", "unfused"], default="auto")
-    ap.add_argument("--workload", choices=["layer", "decode32", "block32"], default="layer",
+    ap.add_argument("--workload", choices=["layer", "decode32", "block32", "shapes"], default="layer",
                     help="layer (default): the headline workload; decode32: 32 chained distinct layers of the "
                          "same shape, captured once in a HIP graph and replayed, M swept 1..256; block32: the "
                          "same chain with RMS normalisation and residual add, folded into the block's launches "
-                         "or as separate launches")
+                         "or as separate launches; shapes: the other layer shapes of the workload list")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU by design (one MI355X); run with --gpus 1. "
@@ -219,6 +257,8 @@ def main():
         return decode32(args, torch, di, dfk, dev)
     if args.workload == "block32":
         return block32(args, torch, di, dfk, dev)
+    if args.workload == "shapes":
+        return shapes(args, torch, di, dfk, dev)
     Mmax = max(M_SET)
 
     # ---- synthetic inputs, resident in HBM
