@@ -258,8 +258,9 @@ dfk_status_t dfk_time_config(const dfk_config_t* cfg, int M, int d_model, int d_
  * of the first kernel back to back between two HIP events on `stream`, then the same
  * for the second.  usec_out[0] = the fused kernel, or the gate/up kernel of the
  * two-kernel variant; usec_out[1] = its down-projection kernel (0 for the fused
- * variant).  M must fit one launch of the configuration (16, 32 or 64 tokens on the MFMA
- * path, 8 on the VALU path), else DFK_ERR_UNSUPPORTED_SHAPE; iters <= 1024. */
+ * variant; with kmajor = 2 and DFK_REDUCE_TICKET it includes the small launch that adds the
+ * partial sums).  M must fit one launch of the configuration (16, 32, 64 or 256 tokens on the
+ * MFMA path, 8 on the VALU path), else DFK_ERR_UNSUPPORTED_SHAPE; iters <= 1024. */
 dfk_status_t dfk_time_kernels(const dfk_config_t* cfg, int M, int d_model, int d_ff,
                               dfk_dtype_t dtype, void* scratch, size_t scratch_bytes,
                               int sets, int iters, void* stream, double* usec_out);

@@ -520,6 +520,57 @@ def test_counter_reduction_is_bitwise_reproducible_on_the_mfma_path():
                 assert torch.equal(first.view(torch.int16), again.view(torch.int16)), c
 
 
+def test_scheduler_tunes_picks_and_reloads(tmp_path):
+    """The profile-driven scheduler (Method: a short pre-inference profiling step picks the kernel):
+    tune a few token counts on a small shape, check that the picks are valid candidates, that calls
+    use them and still match the oracle, that token counts without an entry fall back to the built-in
+    default, and that the table survives a save / clear / load."""
+    d, ff = 1024, 2816
+    Ms = [1, 5, 70]
+    dfk.dfk_clear_tuning()
+    scratch = torch.empty(dfk.dfk_tune_scratch_bytes(max(Ms), d, ff, dfk.DFK_BF16, 3), dtype=torch.uint8, device=DEV)
+    dfk.dfk_tune(Ms, d, ff, dfk.DFK_BF16, scratch, sets=3, iters=3)
+    torch.cuda.synchronize()
+    picks = {}
+    for M in Ms:
+        c, tuned = dfk.dfk_get_choice(M, d, ff, dfk.DFK_BF16)
+        assert tuned, M
+        assert dfk.dfk_config_valid(c, M, d, ff, dfk.DFK_BF16)
+        cands = [dfk.dfk_get_candidate(M, d, ff, dfk.DFK_BF16, i).as_dict()
+                 for i in range(dfk.dfk_num_candidates(M, d, ff, dfk.DFK_BF16))]
+        assert c.as_dict() in cands
+        us = dfk.dfk_time_config(c, M, d, ff, dfk.DFK_BF16, scratch, sets=3, iters=3)
+        assert 0.5 < us < 5000.0, (M, us)
+        picks[M] = c.as_dict()
+    assert not dfk.dfk_get_choice(200, d, ff, dfk.DFK_BF16)[1]          # no entry for 200 or its bucket 256
+    assert not dfk.dfk_get_choice(1, d, ff, dfk.DFK_FP16)[1]            # another element type
+    assert not dfk.dfk_get_choice(1, d, ff + 8, dfk.DFK_BF16)[1]        # another shape
+    del scratch
+    # calls through the scheduler's choice match the oracle
+    ws = dfk.new_workspace(max(Ms), d, ff, DEV)
+    dfk.dfk_set_workspace(ws)
+    try:
+        for M in Ms:
+            t = di.mlp_inputs(M, d, ff, seed=37)
+            g = gpu_inputs(t)
+            Y = torch.empty_like(g["X"])
+            dfk.dfk_swiglu_mlp(g["X"], g["Wg"], g["Wu"], g["Wd"], Y)
+            torch.cuda.synchronize()
+            assert rel_err(y64(Y), oracle.swiglu_mlp(t["X"], t["Wg"], t["Wu"], t["Wd"])) <= TOL_BF16, M
+            assert workspace_is_clean(ws, M, d)
+    finally:
+        dfk.dfk_set_workspace(None)
+    path = str(tmp_path / "table.txt")
+    dfk.dfk_save_tuning(path)
+    dfk.dfk_clear_tuning()
+    assert not dfk.dfk_get_choice(5, d, ff, dfk.DFK_BF16)[1]
+    dfk.dfk_load_tuning(path)
+    for M in Ms:
+        c, tuned = dfk.dfk_get_choice(M, d, ff, dfk.DFK_BF16)
+        assert tuned and c.as_dict() == picks[M]
+    dfk.dfk_clear_tuning()
+
+
 def test_trace_buffer_records_a_monotone_timeline():
     M, d, ff = 1, 1024, 2816
     g = gpu_inputs(di.mlp_inputs(M, d, ff, seed=31))
