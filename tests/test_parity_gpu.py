@@ -187,12 +187,13 @@ def test_kernels_for_up_to_64_tokens_per_launch(shape):
 
 @pytest.mark.parametrize("dtype", ["bf16", "fp16"])
 @pytest.mark.parametrize("shape", [(65, 1024, 2816), (100, 512, 1000), (128, 1024, 4104), (129, 2048, 4104),
-                                   (200, 512, 1536), (256, 1024, 4104)],
+                                   (200, 512, 1536), (256, 1024, 4104), (130, 128, 264), (256, 256, 520)],
                          ids=lambda s: "M%d_d%d_ff%d" % s)
 def test_kernels_for_up_to_256_tokens_per_launch(shape, dtype):
     """Every candidate of the pair of kernels whose workgroups share the weight tiles (config
     field kmajor = 2): two and four token tiles per wavefront, token tiles that are partly or
-    wholly empty, ragged d_ff, both reductions, up to the largest token count a call accepts."""
+    wholly empty, ragged d_ff, both reductions, up to the largest token count a call accepts; the
+    last two shapes have fewer pipeline steps than buffers (one or two k chunks, 8-row d_ff splits)."""
     M, d, ff = shape
     t = di.mlp_inputs(M, d, ff, seed=29, dtype=dtype)
     ref = oracle.swiglu_mlp(t["X"], t["Wg"], t["Wu"], t["Wd"])
