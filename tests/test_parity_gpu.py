@@ -619,10 +619,12 @@ def test_rms_normalize_helper():
         assert float((y.double() - want).abs().max()) <= 2.0 ** -7 * float(want.abs().max())
 
 
-def test_calls_can_be_captured_in_a_graph_and_replayed():
+@pytest.mark.parametrize("M", [4, 150])
+def test_calls_can_be_captured_in_a_graph_and_replayed(M):
     # the deployment mode of the method: the chosen kernels are captured once and replayed;
     # arrival counters reset themselves, so every replay must equal the eager result
-    M, d, ff = 4, 1024, 2816
+    # (150 tokens: the 256-token pair with its third launch, and several launches of the fused kernel)
+    d, ff = 1024, 2816
     t = di.mlp_inputs(M, d, ff, seed=37)
     ref = oracle.swiglu_mlp(t["X"], t["Wg"], t["Wu"], t["Wd"])
     g = gpu_inputs(t)
@@ -650,8 +652,32 @@ def test_calls_can_be_captured_in_a_graph_and_replayed():
                 fn(g["X"], g["Wg"], g["Wu"], g["Wd"], torch.empty_like(Y))
                 torch.cuda.synchronize()
                 assert workspace_is_clean(ws, M, d)
+        # the block with its neighbours, in place, captured the same way (each replay advances H by one layer)
+        w = di.to_torch(di.tensor(1037, (d,), 1.0, "bf16"), DEV)
+        h = g["X"].clone()
+        dfk.dfk_mlp_block(h, w, 1e-5, g["Wg"], g["Wu"], g["Wd"], h, None, ws)
+        torch.cuda.synchronize()
+        h.copy_(g["X"])
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                dfk.dfk_mlp_block(h, w, 1e-5, g["Wg"], g["Wu"], g["Wd"], h, None, ws, stream=side)
+        cur = di.to_numpy(g["X"])
+        for rep in range(3):
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            want = oracle.mlp_block(cur, t_w(w), 1e-5, t["Wg"], t["Wu"], t["Wd"])
+            assert rel_err(y64(h), want) <= TOL_BF16, rep
+            cur = di.to_numpy(h)                 # teacher forcing: the next layer starts from the GPU's bf16 state
+            assert workspace_is_clean(ws, M, d)
     finally:
         dfk.dfk_set_workspace(None)
+
+
+def t_w(w):
+    return di.to_numpy(w)
 
 
 def test_chained_layers_teacher_forced():
