@@ -155,7 +155,7 @@ std::vector<dfk_config_t> candidates(int M, int d_model, int d_ff, dfk_dtype_t d
                                           clamp_splits(std::max(1, grid / k2c), d_ff), k2c, (int)dtype, reduce, 0, 1));
             }
         // two-kernel, workgroup-shared weight tiles: up to 256 tokens per launch (offered beyond 64 tokens)
-        if (M > 64) {
+        if (M > 64 && nblk >= 1) {
             const int k2c = nblk;
             for (int splits : {256, 512})
                 for (int grid : {256, 512})

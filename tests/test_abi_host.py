@@ -141,6 +141,40 @@ def test_kernel_families_by_token_count():
     assert dfk.dfk_config_valid(wide, 128, 16384, FF, dfk.DFK_BF16)
 
 
+def test_candidates_and_workspace_over_random_shapes():
+    """Host logic over a seeded sample of shapes: every candidate the scheduler lists is valid for its
+    problem and passes the argument check with a workspace of the advertised size; there is always at
+    least one; the workspace size is monotone in M; the untuned choice is one of the candidates."""
+    import random
+    rng = random.Random(20240611)
+    fake = 1 << 30
+    for _ in range(60):
+        d = 8 * rng.choice([1, 2, 16, 33, 64, 128, 160, 512, 640, 1024])
+        ff = 8 * rng.choice([1, 3, 33, 125, 352, 513, 1792, 3456, 3584])
+        M = rng.choice([1, 2, 3, 7, 16, 17, 33, 64, 65, 100, 128, 200, 256])
+        for dt in (dfk.DFK_BF16, dfk.DFK_FP16, dfk.DFK_FP32):
+            n = dfk.dfk_num_candidates(M, d, ff, dt)
+            assert n > 0, (M, d, ff, dt)
+            wsb = dfk.dfk_workspace_bytes(M, d, ff)
+            assert wsb >= dfk.dfk_workspace_bytes(max(1, M - 1), d, ff) > 0
+            eb = 4 if dt == dfk.DFK_FP32 else 2
+            nx, nw = M * d * eb, ff * d * eb
+            al = lambda v: (v + 255) // 256 * 256
+            Xp = fake; Wg = Xp + al(nx); Wu = Wg + al(nw); Wd = Wu + al(nw); Yp = Wd + al(nw); ws = Yp + al(nx)
+            cands = []
+            for i in range(n):
+                c = dfk.dfk_get_candidate(M, d, ff, dt, i)
+                cands.append(c.as_dict())
+                assert dfk.dfk_config_valid(c, M, d, ff, dt), (M, d, ff, dt, c)
+                assert dfk.dfk_check_args(Xp, Wg, Wu, Wd, Yp, M, d, ff, dt, c, ws, wsb) == dfk.DFK_OK, (M, d, ff, dt, c)
+                if c.kmajor == 2:
+                    assert M > 64 and c.k2_col_blocks * 128 == d
+                if c.path == dfk.DFK_PATH_MFMA:
+                    assert dt != dfk.DFK_FP32
+            pick, tuned = dfk.dfk_get_choice(M, d, ff, dt)
+            assert not tuned and pick.as_dict() in cands
+
+
 def test_scheduler_table_roundtrip(tmp_path):
     dfk.dfk_clear_tuning()
     c0, tuned = dfk.dfk_get_choice(2, D, FF, dfk.DFK_BF16)
