@@ -521,6 +521,32 @@ def test_counter_reduction_is_bitwise_reproducible_on_the_mfma_path():
                 assert torch.equal(first.view(torch.int16), again.view(torch.int16)), c
 
 
+def test_seeded_random_shapes_and_candidates():
+    """A seeded sample of shapes off the beaten path (d_model and d_ff any multiple of 8, token counts on
+    and off tile boundaries): the scheduler's default and a few randomly drawn candidates each, bf16 and
+    half, against the oracle."""
+    import random
+    rng = random.Random(815)
+    for case in range(14):
+        d = 8 * rng.choice([5, 16, 33, 48, 64, 96, 128, 160, 192])
+        ff = 8 * rng.choice([2, 9, 33, 70, 125, 257, 352])
+        M = rng.choice([1, 3, 15, 16, 17, 31, 33, 48, 63, 64, 65, 97, 129, 255, 256])
+        dtype = rng.choice(["bf16", "fp16"])
+        t = di.mlp_inputs(M, d, ff, seed=900 + case, dtype=dtype)
+        ref = oracle.swiglu_mlp(t["X"], t["Wg"], t["Wu"], t["Wd"])
+        g = gpu_inputs(t)
+        ws = dfk.new_workspace(M, d, ff, DEV)
+        n = dfk.dfk_num_candidates(M, d, ff, _dt(dtype))
+        cands = [dfk.dfk_get_candidate(M, d, ff, _dt(dtype), i) for i in range(n)]
+        chosen = [None] + rng.sample(cands, min(4, n))
+        for cfg in chosen:
+            print("case", case, (M, d, ff), dtype, cfg, flush=True)
+            Y, _ = run_ex(g, cfg, ws)
+            err = rel_err(y64(Y), ref)
+            assert err <= _tol(dtype), (case, (M, d, ff), dtype, cfg, err)
+            assert workspace_is_clean(ws, M, d), (case, cfg)
+
+
 def test_scheduler_tunes_picks_and_reloads(tmp_path):
     """The profile-driven scheduler (Method: a short pre-inference profiling step picks the kernel):
     tune a few token counts on a small shape, check that the picks are valid candidates, that calls
