@@ -42,6 +42,7 @@
 // stores and combined by the two-level arrival-counter reduction (reduce_store),
 // or added into the workspace accumulator with device-wide float atomics, one
 // instruction per 64 consecutive floats (DFK_REDUCE_ATOMIC).
+#include <atomic>
 #include "dfk_mfma_common.h"
 
 namespace dfk {
@@ -746,7 +747,7 @@ Sizes sizes(const dfk_config_t& c, int mode, int TT, int d_ff, int d_model) {
 
 template <int NW, int TT, int MODE>
 hipError_t launch_one(const MlpArgs& a, const dfk_config_t& c, int grid, hipStream_t st) {
-    static size_t configured = 0;   // largest dynamic LDS size this instantiation was allowed so far
+    static std::atomic<size_t> configured{0};   // largest dynamic LDS size this instantiation was allowed so far (callers may be concurrent)
     const Sizes s = sizes(c, MODE, TT, a.d_ff, a.d_model);
     const void* fn = MODE == MODE_DOWN_ROWS ? (const void*)k_down_rows<NW, TT> : (const void*)k_mfma<NW, TT, MODE == MODE_DOWN_ROWS ? MODE_DOWN : MODE>;
     if (s.lds > configured) {

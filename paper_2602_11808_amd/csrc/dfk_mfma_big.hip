@@ -32,6 +32,7 @@
 // down kernels) and the wavefront's A_2 tiles for those rows (private).  Each wavefront
 // publishes its finished [tokens x 128] sums itself (partial block of the split, or the
 // fp32 accumulator); the cross-workgroup reduction is that of the other kernels.
+#include <atomic>
 #include <algorithm>
 
 #include "dfk_mfma_common.h"
@@ -532,7 +533,7 @@ size_t big_lds_down(const dfk_config_t& c, BigGeom* geo) {
 
 template <int TT, typename E, int NTC>
 hipError_t launch_big_gateup(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
-    static size_t configured = 0;
+    static std::atomic<size_t> configured{0};
     BigGeom geo;
     const size_t lds = big_lds_gateup(c, TT, a.d_ff, &geo);
     if (lds > configured) {
@@ -550,7 +551,7 @@ hipError_t launch_big_gateup(const MlpArgs& a, const dfk_config_t& c, hipStream_
 
 template <int TT, typename E>
 hipError_t launch_big_te(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
-    static size_t configured2 = 0;
+    static std::atomic<size_t> configured2{0};
     if (g_stage_mask & 1) {
         hipError_t e;
         switch (max_slice_rows(a.d_ff, c.splits) / 8) {

@@ -27,6 +27,7 @@
 //
 // Rows of X / A_2 past the launch's tokens are fetched from the last real token:
 // they only feed output rows that are never stored.
+#include <atomic>
 #include "dfk_mfma_common.h"
 
 namespace dfk {
@@ -510,7 +511,7 @@ size_t km_lds_down(const dfk_config_t& c, KmGeom* geo) {
 
 template <int NW, int TT, typename E>
 hipError_t launch_km_te(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
-    static size_t configured1 = 0, configured1n = 0, configured2 = 0;
+    static std::atomic<size_t> configured1{0}, configured1n{0}, configured2{0};
     if ((g_stage_mask & 1) && !a.norm_w) {
         KmGeom geo;
         const size_t lds = km_lds_gateup(c, TT, a.d_model, a.d_ff, false, &geo);
