@@ -11,7 +11,7 @@ import torch
 import dfk_inputs as di
 import paper_2602_11808_amd as dfk
 from oracle import oracle
-from tests.helpers import TOL_BF16, TOL_FP16, TOL_FP32, rel_err
+from tests.helpers import TOL_BF16, TOL_FP16, TOL_FP32, assert_parity, rel_err
 
 pytestmark = pytest.mark.gpu
 
@@ -80,8 +80,7 @@ def test_every_candidate_matches_oracle_small(shape, dtype):
         cfg = dfk.dfk_get_candidate(M, d, ff, _dt(dtype), i)
         print("case", shape, dtype, cfg, flush=True)
         Y, ws = run_ex(g, cfg, ws)
-        err = rel_err(y64(Y), ref)
-        assert err <= _tol(dtype), (shape, dtype, cfg, err)
+        assert_parity(y64(Y), ref, dtype, (shape, dtype, cfg))
         assert workspace_is_clean(ws, M, d), (shape, dtype, cfg)
         seen.add((cfg.variant, cfg.path))
     assert any(v == dfk.DFK_VARIANT_FUSED for v, _ in seen)
@@ -135,8 +134,7 @@ def test_full_size_entry_points_match_oracle(name, d, ff, Ms):
                 fn(X, g["Wg"], g["Wu"], g["Wd"], Y)
                 torch.cuda.synchronize()
                 assert bool(torch.isfinite(Y.float()).all()), (name, M, fn.__name__)
-                err = rel_err(y64(Y)[rows], ref)
-                assert err <= TOL_BF16, (name, M, fn.__name__, err)
+                assert_parity(y64(Y)[rows], ref, "bf16", (name, M, fn.__name__))
                 assert workspace_is_clean(ws, M, d)
     finally:
         dfk.dfk_set_workspace(None)
@@ -156,7 +154,7 @@ def test_large_token_counts(M):
                 continue
             print("case M", M, cfg, flush=True)
             Y, _ = run_ex(g, cfg, ws)
-            assert rel_err(y64(Y), ref) <= TOL_BF16, (M, cfg)
+            assert_parity(y64(Y), ref, "bf16", (M, cfg))
             assert workspace_is_clean(ws, M, d)
             break
 
@@ -180,8 +178,7 @@ def test_kernels_for_up_to_64_tokens_per_launch(shape):
         print("case", shape, cfg, flush=True)
         for _ in range(2):
             Y, _ = run_ex(g, cfg, ws)
-            err = rel_err(y64(Y), ref)
-            assert err <= TOL_BF16, (shape, cfg, err)
+            assert_parity(y64(Y), ref, "bf16", (shape, cfg))
             assert workspace_is_clean(ws, M, d), (shape, cfg)
 
 
@@ -207,8 +204,7 @@ def test_kernels_for_up_to_256_tokens_per_launch(shape, dtype):
         print("case", shape, dtype, cfg, flush=True)
         for _ in range(2):
             Y, _ = run_ex(g, cfg, ws)
-            err = rel_err(y64(Y), ref)
-            assert err <= _tol(dtype), (shape, cfg, err)
+            assert_parity(y64(Y), ref, dtype, (shape, cfg))
             assert workspace_is_clean(ws, M, d), (shape, cfg)
 
 
@@ -231,7 +227,7 @@ def test_kernels_for_up_to_256_tokens_full_size_sampled_rows(d, ff, Ms):
             dfk.dfk_swiglu_mlp_ex(X, g["Wg"], g["Wu"], g["Wd"], Y, cfg, ws)
             torch.cuda.synchronize()
             assert bool(torch.isfinite(Y.float()).all()), (M, cfg)
-            assert rel_err(y64(Y)[rows], ref) <= TOL_BF16, (M, cfg)
+            assert_parity(y64(Y)[rows], ref, "bf16", (M, cfg))
             assert workspace_is_clean(ws, M, d)
 
 
@@ -274,7 +270,7 @@ def test_mlp_block_with_norm_and_residual(shape, dtype):
         dfk.dfk_mlp_block(g["X"], g["w"], eps, g["Wg"], g["Wu"], g["Wd"], out, cfg, ws)
         torch.cuda.synchronize()
         got = y64(out)
-        assert rel_err(got, ref) <= tol, (shape, cfg, rel_err(got, ref))
+        assert_parity(got, ref, dtype, (shape, cfg))
         # the block's own share of the result, measured on its own scale
         assert rel_err(got - H64, ref - H64) <= tol, (shape, cfg, rel_err(got - H64, ref - H64))
         assert workspace_is_clean(ws, M, d), (shape, cfg)
@@ -341,7 +337,7 @@ def test_mlp_block_full_size_sampled_rows():
         ref = oracle.mlp_block(t["X"][rows], di.to_numpy(w), 1e-5, t["Wg"], t["Wu"], t["Wd"])
         H = di.as_f64(t["X"][rows])
         got = y64(out)[rows]
-        assert rel_err(got, ref) <= _tol(dtype), (M, dtype)
+        assert_parity(got, ref, dtype, (M, dtype))
         assert rel_err(got - H, ref - H) <= _tol(dtype), (M, dtype)
         assert workspace_is_clean(ws, M, d)
 
@@ -372,8 +368,7 @@ def test_half_precision_inputs(shape):
         print("case", shape, cfg, flush=True)
         Y, _ = run_ex(g, cfg, ws)
         assert Y.dtype == torch.float16
-        err = rel_err(y64(Y), ref)
-        assert err <= TOL_FP16, (shape, cfg, err)
+        assert_parity(y64(Y), ref, "fp16", (shape, cfg))
         assert workspace_is_clean(ws, M, d), (shape, cfg)
     # scheduler's choice through the explicit entry point
     Y = torch.empty_like(g["X"])
@@ -542,8 +537,7 @@ def test_seeded_random_shapes_and_candidates():
         for cfg in chosen:
             print("case", case, (M, d, ff), dtype, cfg, flush=True)
             Y, _ = run_ex(g, cfg, ws)
-            err = rel_err(y64(Y), ref)
-            assert err <= _tol(dtype), (case, (M, d, ff), dtype, cfg, err)
+            assert_parity(y64(Y), ref, dtype, (case, (M, d, ff), dtype, cfg))
             assert workspace_is_clean(ws, M, d), (case, cfg)
 
 
