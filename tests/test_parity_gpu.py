@@ -442,6 +442,61 @@ def test_one_workspace_serves_calls_of_different_token_counts():
         dfk.dfk_set_workspace(None)
 
 
+def test_two_host_threads_on_their_own_streams_and_workspaces():
+    """Calls from two host threads at once, each on its own stream with its own workspace and its own
+    problem (different shapes, kernel families and entry points): the library keeps no state that such
+    callers share except the tuning table.  With the counter reduction a result does not depend on what
+    else runs, so every call must reproduce, bit for bit, the result the same call gave alone."""
+    import threading
+    jobs = []
+    for k, (M, d, ff, kmajor) in enumerate([(4, 512, 1536, 1), (100, 512, 1000, 2)]):
+        t = _block_case(M, d, ff, "bf16", seed=50 + k)
+        g = gpu_inputs(t)
+        n = dfk.dfk_num_candidates(M, d, ff, dfk.DFK_BF16)
+        cfg = next(c for c in (dfk.dfk_get_candidate(M, d, ff, dfk.DFK_BF16, i) for i in range(n))
+                   if c.kmajor == kmajor and c.reduce == dfk.DFK_REDUCE_TICKET)
+        ws = dfk.new_workspace(M, d, ff, DEV)
+        alone_y, _ = run_ex(g, cfg, ws)
+        alone_b = torch.empty_like(g["X"])
+        dfk.dfk_mlp_block(g["X"], g["w"], 1e-5, g["Wg"], g["Wu"], g["Wd"], alone_b, cfg, ws)
+        torch.cuda.synchronize()
+        assert_parity(y64(alone_y), oracle.swiglu_mlp(t["X"], t["Wg"], t["Wu"], t["Wd"]), "bf16", (M, d, ff))
+        assert_parity(y64(alone_b), oracle.mlp_block(t["X"], t["w"], 1e-5, t["Wg"], t["Wu"], t["Wd"]), "bf16", (M, d, ff))
+        jobs.append(dict(g=g, cfg=cfg, ws=ws, alone_y=alone_y, alone_b=alone_b, stream=torch.cuda.Stream(), shape=(M, d, ff)))
+    torch.cuda.synchronize()
+    failures = []
+    start = threading.Barrier(len(jobs))
+
+    def worker(j):
+        try:
+            g, cfg, ws, st = j["g"], j["cfg"], j["ws"], j["stream"]
+            ys = [torch.empty_like(g["X"]) for _ in range(60)]
+            start.wait()
+            for i, y in enumerate(ys):
+                if i % 2 == 0:
+                    dfk.dfk_swiglu_mlp_ex(g["X"], g["Wg"], g["Wu"], g["Wd"], y, cfg, ws, stream=st)
+                else:
+                    dfk.dfk_mlp_block(g["X"], g["w"], 1e-5, g["Wg"], g["Wu"], g["Wd"], y, cfg, ws, stream=st)
+            st.synchronize()
+            for i, y in enumerate(ys):
+                want = j["alone_y"] if i % 2 == 0 else j["alone_b"]
+                if not torch.equal(y.view(torch.int16), want.view(torch.int16)):
+                    failures.append((j["shape"], i))
+        except Exception as e:   # reported by the main thread
+            failures.append((j["shape"], repr(e)))
+
+    threads = [threading.Thread(target=worker, args=(j,)) for j in jobs]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join(timeout=120)
+    assert not any(th.is_alive() for th in threads)
+    assert not failures, failures[:5]
+    for j in jobs:
+        M, d, _ = j["shape"]
+        assert workspace_is_clean(j["ws"], M, d)
+
+
 def test_split_identity_on_gpu():
     # Appendix A.1 algebra through the GPU path: d_ff shards' outputs sum to the whole.
     M, d, ff = 2, 512, 2048
