@@ -361,11 +361,18 @@ def main():
     # one call each, scheduler's untuned default, same rotating weight sets
     extended = {}
     ws_ext = dfk.new_workspace(256, D_MODEL, D_FF, dev)
+    if not args.no_tune and not (args.tuning_file and os.path.exists(args.tuning_file)):
+        scratch = torch.empty(dfk.dfk_tune_scratch_bytes(256, D_MODEL, D_FF, dfk.DFK_BF16, 3), dtype=torch.uint8, device=dev)
+        dfk.dfk_tune([32, 64, 128, 256], D_MODEL, D_FF, dfk.DFK_BF16, scratch, sets=3, iters=8)
+        torch.cuda.synchronize()
+        del scratch
+        if args.tuning_file:
+            dfk.dfk_save_tuning(args.tuning_file)
     for M in (32, 64, 128, 256):
         Xe = di.mlp_inputs_torch(M, D_MODEL, D_FF, seed=0, layer=0, device=dev)["X"]
         Ye = torch.empty_like(Xe)
-        n = max(20, args.steps // 4)
-        for it in range(-3, n):
+        n = max(60, args.steps // 2)
+        for it in range(-20, n):   # 20 untimed calls first: a few ms of work, so the clocks are up
             if it == 0:
                 torch.cuda.synchronize()
                 a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -375,9 +382,10 @@ def main():
         b.record()
         torch.cuda.synchronize()
         us = a.elapsed_time(b) * 1e3 / n
-        c, _ = dfk.dfk_get_choice(M, D_MODEL, D_FF, dfk.DFK_BF16)
+        c, tuned = dfk.dfk_get_choice(M, D_MODEL, D_FF, dfk.DFK_BF16)
         extended[str(M)] = {"us_per_call": round(us, 2), "tb_per_s": round(algorithmic_bytes(M, D_MODEL, D_FF) / us / 1e6, 3),
-                            "kernel_family": {0: "first", 1: "64-token pair", 2: "256-token pair"}[c.kmajor]}
+                            "kernel_family": {0: "first", 1: "64-token pair", 2: "256-token pair"}[c.kmajor],
+                            "pick": dict(c.as_dict(), tuned=tuned)}
     del ws_ext
 
     # ---- read-stream ceiling of this machine (plain 128-bit streaming read of 1.4 GB), and one
