@@ -4,6 +4,7 @@ scheduler table (set / get / save / load / clear)."""
 import ctypes
 import os
 import re
+import subprocess
 
 import pytest
 
@@ -29,6 +30,48 @@ def test_library_exports_every_declared_symbol():
         if name.startswith("dfk_") and name not in ("dfk_config_t",):
             assert hasattr(dfk, name), f"binding lacks {name}"
     assert "gfx950" in dfk.dfk_version()
+
+
+def test_header_is_plain_c_and_a_c_program_can_call_the_library(tmp_path):
+    """The boundary is a C ABI: the header compiles as strict C99 and as C++, a C program links
+    against the library and calls its host-only entry points, and the configuration struct has
+    the layout the Python binding assumes."""
+    inc = os.path.join(ROOT, "include")
+    src = tmp_path / "use_dfk.c"
+    src.write_text(r"""
+#include <stddef.h>
+#include <stdio.h>
+#include "dfk.h"
+int main(void) {
+    dfk_config_t c;
+    int n = dfk_num_candidates(4, 4096, 14336, DFK_BF16);
+    if (n < 1 || dfk_get_candidate(4, 4096, 14336, DFK_BF16, 0, &c) != DFK_OK) return 2;
+    if (!dfk_config_valid(&c, 4, 4096, 14336, DFK_BF16)) return 3;
+    if (dfk_check_args((const void*)0x10000000, (const void*)0x20000000, (const void*)0x30000000,
+                       (const void*)0x40000000, (const void*)0x50000000, 4, 4096, 14336, DFK_BF16, &c, NULL, 0) != DFK_OK) return 4;
+    if (dfk_check_args(NULL, NULL, NULL, NULL, NULL, 4, 4096, 14336, DFK_BF16, NULL, NULL, 0) == DFK_OK) return 5;
+    printf("%d %d %d %d %d %s\n", (int)sizeof(dfk_config_t), (int)offsetof(dfk_config_t, variant),
+           (int)offsetof(dfk_config_t, k2_splits), (int)offsetof(dfk_config_t, kmajor), n, dfk_version());
+    return 0;
+}
+""")
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", inc, "-fsyntax-only", str(src)])
+    cxx = tmp_path / "use_dfk.cpp"
+    cxx.write_text('#include "dfk.h"\nint main() { return dfk_status_string(DFK_OK) ? 0 : 1; }\n')
+    subprocess.check_call(["g++", "-std=c++11", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", inc, "-fsyntax-only", str(cxx)])
+    exe = tmp_path / "use_dfk"
+    libdir = os.path.dirname(dfk.LIB_PATH)
+    subprocess.check_call(["gcc", "-std=c99", "-I", inc, "-o", str(exe), str(src), "-L", libdir, "-ldfk",
+                           "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib"])
+    out = subprocess.run([str(exe)], stdout=subprocess.PIPE, text=True, timeout=120)
+    assert out.returncode == 0, out.returncode
+    size, o_variant, o_k2s, o_kmajor, n, version = out.stdout.split(None, 5)
+    assert int(size) == ctypes.sizeof(dfk.dfk_config_t)
+    assert int(o_variant) == dfk.dfk_config_t.variant.offset
+    assert int(o_k2s) == dfk.dfk_config_t.k2_splits.offset
+    assert int(o_kmajor) == dfk.dfk_config_t.kmajor.offset
+    assert int(n) == dfk.dfk_num_candidates(4, 4096, 14336, dfk.DFK_BF16)
+    assert "gfx950" in version
 
 
 def chk(**kw):
