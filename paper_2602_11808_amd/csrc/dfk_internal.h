@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -105,6 +106,38 @@ inline int max_slice_rows(int d_ff, int S) {
 // (fused kernel, or gate/up kernel), bit 1 the second (down kernel).  3 except inside
 // dfk_time_kernels, which times each launch on its own, back to back.
 extern thread_local int g_stage_mask;
+
+// ---------------------------------------------------------------- dynamic-LDS allowance of a kernel
+// hipFuncSetAttribute(MaxDynamicSharedMemorySize) applies to a function on one device.  Each launcher
+// keeps one of these per kernel instantiation (a function-local static, so zero to begin with) and
+// remembers, per device, the largest size it has set; callers may be concurrent.
+struct LdsAllowance {
+    static constexpr int kDevices = 32;
+    std::atomic<size_t> set_[kDevices];
+    // true if `bytes` are already allowed on the current device; *dev is that device, or -1 if it
+    // cannot be tracked (then the attribute is simply set again on every launch)
+    bool covers(size_t bytes, int* dev) const {
+        if (hipGetDevice(dev) != hipSuccess || *dev < 0 || *dev >= kDevices) {
+            *dev = -1;
+            return false;
+        }
+        return bytes <= set_[*dev].load(std::memory_order_relaxed);
+    }
+    void record(int dev, size_t bytes) {
+        if (dev < 0) return;
+        size_t cur = set_[dev].load(std::memory_order_relaxed);
+        while (cur < bytes && !set_[dev].compare_exchange_weak(cur, bytes, std::memory_order_relaxed)) {}
+    }
+};
+
+// Raises the allowance of `fn` on the current device to `bytes` if it is lower.
+inline hipError_t allow_lds(LdsAllowance& known, const void* fn, size_t bytes) {
+    int dev;
+    if (known.covers(bytes, &dev)) return hipSuccess;
+    const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess) known.record(dev, bytes);
+    return e;
+}
 
 // ---------------------------------------------------------------- launchers (defined per path)
 // Each returns hipSuccess or the launch error.  No allocation, no sync.

@@ -747,14 +747,10 @@ Sizes sizes(const dfk_config_t& c, int mode, int TT, int d_ff, int d_model) {
 
 template <int NW, int TT, int MODE>
 hipError_t launch_one(const MlpArgs& a, const dfk_config_t& c, int grid, hipStream_t st) {
-    static std::atomic<size_t> configured{0};   // largest dynamic LDS size this instantiation was allowed so far (callers may be concurrent)
+    static LdsAllowance allowed;   // of this instantiation, per device
     const Sizes s = sizes(c, MODE, TT, a.d_ff, a.d_model);
     const void* fn = MODE == MODE_DOWN_ROWS ? (const void*)k_down_rows<NW, TT> : (const void*)k_mfma<NW, TT, MODE == MODE_DOWN_ROWS ? MODE_DOWN : MODE>;
-    if (s.lds > configured) {
-        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s.lds);
-        if (e != hipSuccess) return e;
-        configured = s.lds;
-    }
+    if (hipError_t e = allow_lds(allowed, fn, s.lds); e != hipSuccess) return e;
     if (MODE == MODE_DOWN_ROWS)
         hipLaunchKernelGGL((k_down_rows<NW, TT>), dim3(grid), dim3(NW * 64), s.lds, st, a, s.geo);
     else

@@ -533,25 +533,22 @@ size_t big_lds_down(const dfk_config_t& c, BigGeom* geo) {
 
 template <int TT, typename E, int NTC>
 hipError_t launch_big_gateup(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
-    static std::atomic<size_t> configured{0};
+    static LdsAllowance allowed4, allowed8;   // of the two kernels of this instantiation, per device
     BigGeom geo;
     const size_t lds = big_lds_gateup(c, TT, a.d_ff, &geo);
-    if (lds > configured) {
-        hipError_t e = hipFuncSetAttribute((const void*)k_gateup_big<TT, E, NTC, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_gateup_big<TT / 2, E, NTC, 8>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        configured = lds;
-    }
-    if (c.waves == 8)
+    if (c.waves == 8) {
+        if (hipError_t e = allow_lds(allowed8, (const void*)k_gateup_big<TT / 2, E, NTC, 8>, lds); e != hipSuccess) return e;
         hipLaunchKernelGGL((k_gateup_big<TT / 2, E, NTC, 8>), dim3(a.splits), dim3(512), lds, st, a, geo);
-    else
+    } else {
+        if (hipError_t e = allow_lds(allowed4, (const void*)k_gateup_big<TT, E, NTC, 4>, lds); e != hipSuccess) return e;
         hipLaunchKernelGGL((k_gateup_big<TT, E, NTC, 4>), dim3(a.splits), dim3(256), lds, st, a, geo);
+    }
     return hipGetLastError();
 }
 
 template <int TT, typename E>
 hipError_t launch_big_te(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
-    static std::atomic<size_t> configured2{0};
+    static LdsAllowance allowed2;   // of the down kernel of this instantiation, per device
     if (g_stage_mask & 1) {
         hipError_t e;
         switch (max_slice_rows(a.d_ff, c.splits) / 8) {
@@ -570,11 +567,7 @@ hipError_t launch_big_te(const MlpArgs& a, const dfk_config_t& c, hipStream_t st
     if (g_stage_mask & 2) {
         BigGeom geo;
         const size_t lds = big_lds_down(c, &geo);
-        if (lds > configured2) {
-            hipError_t e = hipFuncSetAttribute((const void*)k_down_big<TT / 2, E, kBigDownWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-            configured2 = lds;
-        }
+        if (hipError_t e = allow_lds(allowed2, (const void*)k_down_big<TT / 2, E, kBigDownWaves>, lds); e != hipSuccess) return e;
         // (TT token tiles per wavefront of the 4-wavefront gate/up kernel are TT / 2 in the 8 of this one)
         hipLaunchKernelGGL((k_down_big<TT / 2, E, kBigDownWaves>), dim3(a.k2_splits * a.k2_col_blocks), dim3(kBigDownWaves * 64), lds, st, a, geo);
         hipError_t e = hipGetLastError();

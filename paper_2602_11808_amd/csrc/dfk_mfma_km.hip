@@ -511,15 +511,11 @@ size_t km_lds_down(const dfk_config_t& c, KmGeom* geo) {
 
 template <int NW, int TT, typename E>
 hipError_t launch_km_te(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
-    static std::atomic<size_t> configured1{0}, configured1n{0}, configured2{0};
+    static LdsAllowance allowed1, allowed1n, allowed2;   // of the three kernels of this instantiation, per device
     if ((g_stage_mask & 1) && !a.norm_w) {
         KmGeom geo;
         const size_t lds = km_lds_gateup(c, TT, a.d_model, a.d_ff, false, &geo);
-        if (lds > configured1) {
-            hipError_t e = hipFuncSetAttribute((const void*)k_gateup_km<NW, TT, E, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-            configured1 = lds;
-        }
+        if (hipError_t e = allow_lds(allowed1, (const void*)k_gateup_km<NW, TT, E, false>, lds); e != hipSuccess) return e;
         hipLaunchKernelGGL((k_gateup_km<NW, TT, E, false>), dim3(a.splits), dim3(NW * 64), lds, st, a, geo);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -527,11 +523,7 @@ hipError_t launch_km_te(const MlpArgs& a, const dfk_config_t& c, hipStream_t st)
     if ((g_stage_mask & 1) && a.norm_w) {
         KmGeom geo;
         const size_t lds = km_lds_gateup(c, TT, a.d_model, a.d_ff, true, &geo);
-        if (lds > configured1n) {
-            hipError_t e = hipFuncSetAttribute((const void*)k_gateup_km<NW, TT, E, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-            configured1n = lds;
-        }
+        if (hipError_t e = allow_lds(allowed1n, (const void*)k_gateup_km<NW, TT, E, true>, lds); e != hipSuccess) return e;
         hipLaunchKernelGGL((k_gateup_km<NW, TT, E, true>), dim3(a.splits), dim3(NW * 64), lds, st, a, geo);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -539,11 +531,7 @@ hipError_t launch_km_te(const MlpArgs& a, const dfk_config_t& c, hipStream_t st)
     if (g_stage_mask & 2) {
         KmGeom geo;
         const size_t lds = km_lds_down(c, &geo);
-        if (lds > configured2) {
-            hipError_t e = hipFuncSetAttribute((const void*)k_down_km<NW, TT, E>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-            configured2 = lds;
-        }
+        if (hipError_t e = allow_lds(allowed2, (const void*)k_down_km<NW, TT, E>, lds); e != hipSuccess) return e;
         hipLaunchKernelGGL((k_down_km<NW, TT, E>), dim3(a.k2_splits * a.k2_col_blocks), dim3(NW * 64), lds, st, a, geo);
         return hipGetLastError();
     }
