@@ -47,12 +47,15 @@ constexpr int kBigMaxRowTiles = 8;
 constexpr int kBigTokensPerLaunch = 256;
 constexpr int kBigSB = 2;            // 32-row blocks of W_down per step of the down kernel (the A_2 tile layout assumes 2)
 
+constexpr size_t kL2BytesPerXcd = (size_t)4 << 20;
+
 struct BigGeom {
     int nb;          // buffers of shared tiles (steps)
     int pl;          // private buffers per wavefront (1 or 2)
     int shared_step; // bytes of one shared buffer
     int priv_off;    // byte offset of the private region
     int priv_step;   // bytes of one private buffer
+    int by_xcd;      // down kernel: place the workgroups of a d_ff split on one XCD (see down_tile_of)
 };
 
 // s_waitcnt vmcnt(n) for a run-time n (uniform); more than 63 waits for 63.
@@ -302,6 +305,31 @@ struct BigLoads2 {
     }
 };
 
+// Which (d_ff split, column block) a workgroup of the down kernel takes.  Workgroups are handed to
+// the 8 XCDs in turn (workgroup b runs on XCD b % 8) and each XCD has its own L2; all column blocks
+// of a split read the same A_2 rows, so a split's workgroups are placed on one XCD (or, with fewer
+// than 8 splits, on 8 / splits of them) and those rows are fetched into that L2 once.  Any other
+// split count keeps the plain order, and so does a launch whose whole A_2 fits one L2 (the host
+// decides: there the plain order already shares it, and measured 2 us faster at 128 tokens of the
+// 8B shape, against 4 to 20 us slower at 256 tokens and on the 70B shape).  A bijection from
+// [0, S * C) onto S x C in every case.
+__device__ __forceinline__ void down_tile_of(int b, int S, int C, bool by_xcd, int& js, int& cb) {
+    const int x = b & 7, r = b >> 3;
+    if (!by_xcd) {
+        js = b / C;
+        cb = b - js * C;
+    } else if ((S & 7) == 0) {
+        js = x + 8 * (r / C);
+        cb = r % C;
+    } else if ((S == 1 || S == 2 || S == 4) && ((C * S) & 7) == 0) {
+        js = x % S;
+        cb = (x / S) * (C * S / 8) + r;
+    } else {
+        js = b / C;
+        cb = b - js * C;
+    }
+}
+
 template <int TT, typename E, int NW>
 __global__ __launch_bounds__(NW * 64) void k_down_big(MlpArgs a, BigGeom geo) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -313,8 +341,8 @@ __global__ __launch_bounds__(NW * 64) void k_down_big(MlpArgs a, BigGeom geo) {
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int q = lane & 15, g = lane >> 4;
-    const int js = blockIdx.x / a.k2_col_blocks;
-    const int cb = blockIdx.x - js * a.k2_col_blocks;   // one 128-column block per workgroup (checked on the host)
+    int js, cb;   // d_ff split and 128-column block of this workgroup (one column block each: checked on the host)
+    down_tile_of((int)blockIdx.x, a.k2_splits, a.k2_col_blocks, geo.by_xcd != 0, js, cb);
     int j0, j1;
     slice_rows(a.d_ff, a.k2_splits, js, j0, j1);
     const int rows = j1 - j0;
@@ -534,7 +562,7 @@ size_t big_lds_down(const dfk_config_t& c, BigGeom* geo) {
 template <int TT, typename E, int NTC>
 hipError_t launch_big_gateup(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
     static LdsAllowance allowed4, allowed8;   // of the two kernels of this instantiation, per device
-    BigGeom geo;
+    BigGeom geo{};
     const size_t lds = big_lds_gateup(c, TT, a.d_ff, &geo);
     if (c.waves == 8) {
         if (hipError_t e = allow_lds(allowed8, (const void*)k_gateup_big<TT / 2, E, NTC, 8>, lds); e != hipSuccess) return e;
@@ -565,8 +593,9 @@ hipError_t launch_big_te(const MlpArgs& a, const dfk_config_t& c, hipStream_t st
         if (e != hipSuccess) return e;
     }
     if (g_stage_mask & 2) {
-        BigGeom geo;
+        BigGeom geo{};
         const size_t lds = big_lds_down(c, &geo);
+        geo.by_xcd = (size_t)a.m_count * a.d_ff * 2 > kL2BytesPerXcd;
         if (hipError_t e = allow_lds(allowed2, (const void*)k_down_big<TT / 2, E, kBigDownWaves>, lds); e != hipSuccess) return e;
         // (TT token tiles per wavefront of the 4-wavefront gate/up kernel are TT / 2 in the 8 of this one)
         hipLaunchKernelGGL((k_down_big<TT / 2, E, kBigDownWaves>), dim3(a.k2_splits * a.k2_col_blocks), dim3(kBigDownWaves * 64), lds, st, a, geo);
@@ -603,7 +632,7 @@ bool mfma_big_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, 
     const int tokens = std::min(M, kBigTokensPerLaunch);
     if ((size_t)tokens * d_model * 4 > kYaccBytes) return false;               // fp32 accumulator of one launch
     if (c.reduce == DFK_REDUCE_TICKET && !partials_fit(c.k2_splits, tokens, M, d_model)) return false;
-    BigGeom geo;
+    BigGeom geo{};
     return big_lds_gateup(c, big_token_tiles(tokens), d_ff, &geo) <= (size_t)kLdsLimit && big_lds_down(c, &geo) <= (size_t)kLdsLimit;
 }
 
