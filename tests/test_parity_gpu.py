@@ -184,13 +184,14 @@ def test_kernels_for_up_to_64_tokens_per_launch(shape):
 
 @pytest.mark.parametrize("dtype", ["bf16", "fp16"])
 @pytest.mark.parametrize("shape", [(65, 1024, 2816), (100, 512, 1000), (128, 1024, 4104), (129, 2048, 4104),
-                                   (200, 512, 1536), (256, 1024, 4104), (130, 128, 264), (256, 256, 520)],
+                                   (200, 512, 1536), (256, 1024, 4104), (130, 128, 264), (256, 256, 520), (256, 512, 8200)],
                          ids=lambda s: "M%d_d%d_ff%d" % s)
 def test_kernels_for_up_to_256_tokens_per_launch(shape, dtype):
     """Every candidate of the pair of kernels whose workgroups share the weight tiles (config
     field kmajor = 2): two and four token tiles per wavefront, token tiles that are partly or
     wholly empty, ragged d_ff, both reductions, up to the largest token count a call accepts; the
-    last two shapes have fewer pipeline steps than buffers (one or two k chunks, 8-row d_ff splits)."""
+    two shapes before the last have fewer pipeline steps than buffers (one or two k chunks, 8-row d_ff splits);
+    in the last A_2 is larger than one L2, where the down kernel places the workgroups of a split on one XCD."""
     M, d, ff = shape
     t = di.mlp_inputs(M, d, ff, seed=29, dtype=dtype)
     ref = oracle.swiglu_mlp(t["X"], t["Wg"], t["Wu"], t["Wd"])
@@ -208,10 +209,14 @@ def test_kernels_for_up_to_256_tokens_per_launch(shape, dtype):
             assert workspace_is_clean(ws, M, d), (shape, cfg)
 
 
-@pytest.mark.parametrize("d,ff,Ms", [(4096, 14336, (128, 256)), (5120, 27648, (128,))], ids=["llama3_8b", "qwen2.5_32b"])
+@pytest.mark.parametrize("d,ff,Ms", [(4096, 14336, (128, 256)), (5120, 27648, (128,)), (8192, 8200, (256,))],
+                         ids=["llama3_8b", "qwen2.5_32b", "wide_d8192"])
 def test_kernels_for_up_to_256_tokens_full_size_sampled_rows(d, ff, Ms):
     """Full-size layers at 128 and 256 tokens in one launch: a sample of tokens against the oracle
-    (the second shape has 40 column blocks and d_ff slices of 6 and 7 row tiles)."""
+    (the second shape has 40 column blocks and d_ff slices of 6 and 7 row tiles; the third 64 column blocks,
+    so the down kernel runs with 4 and 8 d_ff splits).  Between them the three ways the down kernel maps
+    workgroups to (split, column block) when A_2 exceeds one L2: splits a multiple of 8, splits dividing 8,
+    and the plain order for anything else (6 and 12 splits)."""
     g = di.mlp_inputs_torch(max(Ms), d, ff, seed=31, device=DEV)
     host = {k: di.to_numpy(v) for k, v in g.items()}
     ws = dfk.new_workspace(max(Ms), d, ff, DEV)
@@ -220,7 +225,11 @@ def test_kernels_for_up_to_256_tokens_full_size_sampled_rows(d, ff, Ms):
         rows = sorted({0, 17, 63, 64, M // 2 + 5, M - 16, M - 1})
         ref = oracle.swiglu_mlp(host["X"][rows], host["Wg"], host["Wu"], host["Wd"])
         cfgs = [c for c in _cfgs(M, d, ff, lambda c: c.kmajor == 2)]
-        picked = [next(c for c in cfgs if c.reduce == r) for r in (dfk.DFK_REDUCE_TICKET, dfk.DFK_REDUCE_ATOMIC)]
+        picked = {}   # the first candidate of each (reduction, number of d_ff splits of the down kernel)
+        for c in cfgs:
+            picked.setdefault((c.reduce, c.k2_splits), c)
+        assert {r for r, _ in picked} == {dfk.DFK_REDUCE_TICKET, dfk.DFK_REDUCE_ATOMIC}
+        picked = list(picked.values())
         for cfg in picked:
             print("case full", M, cfg, flush=True)
             Y = torch.full_like(X, float("nan"))
