@@ -38,7 +38,13 @@ bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
     return a0 < b0 + nb && b0 < a0 + na;
 }
 
+// The shapes a call accepts: every query below and the argument check agree on it.
+bool shape_supported(int M, int d_model, int d_ff) {
+    return M >= 1 && M <= DFK_MAX_M && d_model >= 8 && d_model <= kMaxDModel && d_ff >= 8 && d_model % 8 == 0 && d_ff % 8 == 0;
+}
+
 bool config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype) {
+    if (!shape_supported(M, d_model, d_ff)) return false;
     if (c.path == DFK_PATH_VALU) return valu_config_valid(c, M, d_model, d_ff, dtype);
     if (c.path == DFK_PATH_MFMA) return mfma_config_valid(c, M, d_model, d_ff, dtype);
     return false;
@@ -50,7 +56,7 @@ dfk_status_t check(const void* X, const void* Wg, const void* Wu, const void* Wd
     if (!X || !Wg || !Wu || !Wd || !Y) return DFK_ERR_INVALID_ARG;
     if (M < 1 || d_model < 1 || d_ff < 1) return DFK_ERR_INVALID_ARG;
     if (dtype != DFK_BF16 && dtype != DFK_FP32 && dtype != DFK_FP16) return DFK_ERR_INVALID_ARG;
-    if (d_model % 8 || d_ff % 8 || M > DFK_MAX_M || d_model > kMaxDModel) return DFK_ERR_UNSUPPORTED_SHAPE;
+    if (!shape_supported(M, d_model, d_ff)) return DFK_ERR_UNSUPPORTED_SHAPE;
     const void* ptrs[5] = {X, Wg, Wu, Wd, Y};
     for (const void* p : ptrs)
         if ((uintptr_t)p % 16) return DFK_ERR_ALIGNMENT;
@@ -475,7 +481,7 @@ dfk_status_t dfk_check_args(const void* X, const void* Wg, const void* Wu, const
 }
 
 size_t dfk_workspace_bytes(int M_max, int d_model, int d_ff) {
-    if (M_max < 1 || M_max > DFK_MAX_M || d_model < 1 || d_ff < 1) return 0;
+    if (!shape_supported(M_max, d_model, d_ff)) return 0;
     return ws_layout(M_max, d_model, d_ff).total;
 }
 
@@ -504,15 +510,14 @@ dfk_status_t dfk_set_trace_buffer(void* buffer, size_t bytes) {
 }
 
 int dfk_num_candidates(int M, int d_model, int d_ff, dfk_dtype_t dtype) {
-    if (M < 1 || M > DFK_MAX_M || d_model < 8 || d_ff < 8 || d_model % 8 || d_ff % 8) return 0;
+    if (!shape_supported(M, d_model, d_ff)) return 0;
     return (int)candidates(M, d_model, d_ff, dtype).size();
 }
 
 dfk_status_t dfk_get_candidate(int M, int d_model, int d_ff, dfk_dtype_t dtype, int i,
                                dfk_config_t* out) {
     if (!out) return DFK_ERR_INVALID_ARG;
-    if (M < 1 || M > DFK_MAX_M || d_model < 8 || d_ff < 8 || d_model % 8 || d_ff % 8)
-        return DFK_ERR_UNSUPPORTED_SHAPE;
+    if (!shape_supported(M, d_model, d_ff)) return DFK_ERR_UNSUPPORTED_SHAPE;
     auto c = candidates(M, d_model, d_ff, dtype);
     if (i < 0 || i >= (int)c.size()) return DFK_ERR_NOT_FOUND;
     *out = c[i];
@@ -520,12 +525,12 @@ dfk_status_t dfk_get_candidate(int M, int d_model, int d_ff, dfk_dtype_t dtype, 
 }
 
 int dfk_config_valid(const dfk_config_t* cfg, int M, int d_model, int d_ff, dfk_dtype_t dtype) {
-    if (!cfg || M < 1 || M > DFK_MAX_M) return 0;
+    if (!cfg) return 0;
     return config_valid(*cfg, M, d_model, d_ff, dtype) ? 1 : 0;
 }
 
 size_t dfk_tune_scratch_bytes(int M_max, int d_model, int d_ff, dfk_dtype_t dtype, int sets) {
-    if (M_max < 1 || M_max > DFK_MAX_M || d_model < 1 || d_ff < 1 || sets < 1) return 0;
+    if (!shape_supported(M_max, d_model, d_ff) || sets < 1) return 0;
     return scratch_layout(M_max, d_model, d_ff, dtype, sets).total;
 }
 
@@ -534,7 +539,7 @@ dfk_status_t dfk_time_config(const dfk_config_t* cfg, int M, int d_model, int d_
                              double* usec_out) {
     if (!cfg || !scratch || !usec_out || sets < 1 || iters < 1) return DFK_ERR_INVALID_ARG;
     if (M < 1 || d_model < 1 || d_ff < 1) return DFK_ERR_INVALID_ARG;
-    if (M > DFK_MAX_M || d_model % 8 || d_ff % 8) return DFK_ERR_UNSUPPORTED_SHAPE;
+    if (!shape_supported(M, d_model, d_ff)) return DFK_ERR_UNSUPPORTED_SHAPE;
     if (!config_valid(*cfg, M, d_model, d_ff, dtype)) return DFK_ERR_UNSUPPORTED_SHAPE;
     if ((uintptr_t)scratch % 256) return DFK_ERR_ALIGNMENT;
     if (scratch_bytes < scratch_layout(M, d_model, d_ff, dtype, sets).total) return DFK_ERR_WORKSPACE;
@@ -547,7 +552,7 @@ dfk_status_t dfk_time_kernels(const dfk_config_t* cfg, int M, int d_model, int d
                               double* usec_out) {
     if (!cfg || !scratch || !usec_out || sets < 1 || iters < 1 || iters > 1024) return DFK_ERR_INVALID_ARG;
     if (M < 1 || d_model < 1 || d_ff < 1) return DFK_ERR_INVALID_ARG;
-    if (M > DFK_MAX_M || d_model % 8 || d_ff % 8) return DFK_ERR_UNSUPPORTED_SHAPE;
+    if (!shape_supported(M, d_model, d_ff)) return DFK_ERR_UNSUPPORTED_SHAPE;
     if (!config_valid(*cfg, M, d_model, d_ff, dtype)) return DFK_ERR_UNSUPPORTED_SHAPE;
     const int per = cfg->path == DFK_PATH_MFMA ? mfma_max_tokens_per_launch(*cfg, d_model) : valu_max_tokens_per_launch();
     if (M > per) return DFK_ERR_UNSUPPORTED_SHAPE;   // one set of launches per call only
@@ -560,7 +565,7 @@ dfk_status_t dfk_tune(const int* M_list, int nM, int d_model, int d_ff, dfk_dtyp
                       void* scratch, size_t scratch_bytes, int sets, int iters, void* stream) {
     if (!M_list || nM < 1 || !scratch || sets < 1 || iters < 1) return DFK_ERR_INVALID_ARG;
     if (d_model < 1 || d_ff < 1) return DFK_ERR_INVALID_ARG;
-    if (d_model % 8 || d_ff % 8) return DFK_ERR_UNSUPPORTED_SHAPE;
+    if (!shape_supported(1, d_model, d_ff)) return DFK_ERR_UNSUPPORTED_SHAPE;
     if ((uintptr_t)scratch % 256) return DFK_ERR_ALIGNMENT;
     for (int i = 0; i < nM; ++i) {
         if (M_list[i] < 1) return DFK_ERR_INVALID_ARG;
@@ -593,7 +598,7 @@ dfk_status_t dfk_get_choice(int M, int d_model, int d_ff, dfk_dtype_t dtype, dfk
                             int* tuned_out) {
     if (!out) return DFK_ERR_INVALID_ARG;
     if (M < 1 || d_model < 1 || d_ff < 1) return DFK_ERR_INVALID_ARG;
-    if (M > DFK_MAX_M || d_model % 8 || d_ff % 8) return DFK_ERR_UNSUPPORTED_SHAPE;
+    if (!shape_supported(M, d_model, d_ff)) return DFK_ERR_UNSUPPORTED_SHAPE;
     return choose(M, d_model, d_ff, dtype, DFK_VARIANT_AUTO, out, tuned_out) ? DFK_OK
                                                                              : DFK_ERR_UNSUPPORTED_SHAPE;
 }
@@ -601,7 +606,7 @@ dfk_status_t dfk_get_choice(int M, int d_model, int d_ff, dfk_dtype_t dtype, dfk
 dfk_status_t dfk_set_choice(int M, int d_model, int d_ff, dfk_dtype_t dtype, const dfk_config_t* cfg,
                             double usec) {
     if (!cfg || M < 1 || d_model < 1 || d_ff < 1) return DFK_ERR_INVALID_ARG;
-    if (M > DFK_MAX_M || d_model % 8 || d_ff % 8) return DFK_ERR_UNSUPPORTED_SHAPE;
+    if (!shape_supported(M, d_model, d_ff)) return DFK_ERR_UNSUPPORTED_SHAPE;
     if (!config_valid(*cfg, M, d_model, d_ff, dtype)) return DFK_ERR_UNSUPPORTED_SHAPE;
     std::lock_guard<std::mutex> lk(g_mu);
     Entry e;

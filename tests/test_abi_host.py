@@ -218,6 +218,33 @@ def test_candidates_and_workspace_over_random_shapes():
             assert not tuned and pick.as_dict() in cands
 
 
+def test_every_query_agrees_on_which_shapes_are_supported():
+    """One token more than DFK_MAX_M, one step beyond the largest d_model, sizes that are not multiples
+    of 8 or below 8: no candidates, no workspace or scratch size, no valid configuration, and the
+    argument check says unsupported; at the limits themselves everything answers."""
+    ok = dfk.dfk_get_candidate(4, 512, 512, dfk.DFK_BF16, 0)
+    for dt in (dfk.DFK_BF16, dfk.DFK_FP16, dfk.DFK_FP32):
+        for M, d, ff in ((dfk.DFK_MAX_M + 1, 512, 512), (4, 32768 + 8, 512), (4, 516, 512), (4, 512, 516), (4, 4, 512), (4, 512, 4)):
+            assert dfk.dfk_num_candidates(M, d, ff, dt) == 0, (M, d, ff)
+            assert dfk.dfk_workspace_bytes(M, d, ff) == 0, (M, d, ff)
+            assert dfk.dfk_tune_scratch_bytes(M, d, ff, dt, 3) == 0, (M, d, ff)
+            assert not dfk.dfk_config_valid(ok, M, d, ff, dt), (M, d, ff)
+            with pytest.raises(dfk.DfkError) as ei:
+                dfk.dfk_get_candidate(M, d, ff, dt, 0)
+            assert ei.value.status == dfk.DFK_ERR_UNSUPPORTED_SHAPE
+            with pytest.raises(dfk.DfkError) as ei:
+                dfk.dfk_get_choice(M, d, ff, dt)
+            assert ei.value.status == dfk.DFK_ERR_UNSUPPORTED_SHAPE
+            assert dfk.dfk_check_args(X=X, W_gate=WG, W_up=WU, W_down=WD, Y=Y, M=M, d_model=d, d_ff=ff, dtype=dt) == dfk.DFK_ERR_UNSUPPORTED_SHAPE
+        for M, d, ff in ((dfk.DFK_MAX_M, 32768, 8), (1, 8, 8), (dfk.DFK_MAX_M, 8, 262144)):
+            n = dfk.dfk_num_candidates(M, d, ff, dt)
+            assert n > 0, (M, d, ff)
+            assert dfk.dfk_workspace_bytes(M, d, ff) > 0 and dfk.dfk_tune_scratch_bytes(M, d, ff, dt, 3) > 0
+            c, _ = dfk.dfk_get_choice(M, d, ff, dt)
+            assert dfk.dfk_config_valid(c, M, d, ff, dt)
+            assert all(dfk.dfk_config_valid(dfk.dfk_get_candidate(M, d, ff, dt, i), M, d, ff, dt) for i in range(n))
+
+
 def test_scheduler_table_roundtrip(tmp_path):
     dfk.dfk_clear_tuning()
     c0, tuned = dfk.dfk_get_choice(2, D, FF, dfk.DFK_BF16)

@@ -409,6 +409,30 @@ def test_degenerate_inputs():
         assert rel_err(y64(Y), ref) <= TOL_BF16, cfg
 
 
+@pytest.mark.parametrize("shape,dtype", [((3, 32768, 264), "bf16"), ((64, 32768, 264), "bf16"), ((256, 32768, 72), "bf16"),
+                                         ((16, 16384, 1024), "fp16"), ((2, 8, 262144), "bf16"), ((2, 8, 262144), "fp32"),
+                                         ((256, 8, 8), "fp32"), ((3, 32768, 264), "fp32")],
+                         ids=lambda v: v if isinstance(v, str) else "M%d_d%d_ff%d" % v)
+def test_sizes_at_the_limits(shape, dtype):
+    """The largest d_model and token count a call accepts (together: four launches of 64 tokens with the
+    accumulator area filled to its last byte), a very long and a minimal d_ff, the smallest d_model:
+    every candidate the scheduler offers there, against the oracle."""
+    M, d, ff = shape
+    t = di.mlp_inputs(M, d, ff, seed=77, dtype=dtype)
+    ref = oracle.swiglu_mlp(t["X"], t["Wg"], t["Wu"], t["Wd"])
+    g = gpu_inputs(t)
+    ws = dfk.new_workspace(M, d, ff, DEV)
+    n = dfk.dfk_num_candidates(M, d, ff, _dt(dtype))
+    assert n > 0
+    for i in range(n):
+        cfg = dfk.dfk_get_candidate(M, d, ff, _dt(dtype), i)
+        assert dfk.dfk_config_valid(cfg, M, d, ff, _dt(dtype))
+        print("case", shape, dtype, cfg, flush=True)
+        Y, _ = run_ex(g, cfg, ws)
+        assert_parity(y64(Y), ref, dtype, (shape, cfg))
+        assert workspace_is_clean(ws, M, d), (shape, cfg)
+
+
 def test_repeated_calls_share_a_workspace_and_stay_correct():
     M, d, ff = 4, 1024, 4096
     t = di.mlp_inputs(M, d, ff, seed=9)
