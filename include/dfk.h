@@ -184,7 +184,9 @@ dfk_status_t dfk_swiglu_mlp_ex(const void* X, const void* W_gate, const void* W_
  * the definition does.  The product H[m,k] * w[k] is rounded once to dtype before the
  * contraction (with half inputs it must stay finite in half precision).
  * Runs on the kernel pairs that take the activations through LDS: cfg->kmajor == 1 (up to 64
- * tokens per launch, everything folded into the two launches as described), or
+ * tokens per launch, everything folded into the two launches as described; where d_model is
+ * so wide that the normalisation weight does not fit that kernel's LDS beside its rings, the
+ * normalisation becomes one small launch of its own, as below), or
  * cfg->kmajor == 2 (up to 256 tokens; there the normalisation is one small launch of its own
  * ahead of the pair, into the workspace: that pair is paced by its arithmetic, and scaling X
  * inside every workgroup measured slower; the residual add stays in the final store).

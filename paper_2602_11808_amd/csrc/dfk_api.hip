@@ -269,9 +269,12 @@ dfk_status_t run(const void* X, const void* Wg, const void* Wu, const void* Wd, 
     a.Q = (float*)((char*)ws + l.q_off);
     a.a2 = (char*)ws + l.a2_off;
     a.norm_w = norm_w; a.eps = eps; a.resid = resid;
-    if (norm_w && c.kmajor == 2) {
+    if (norm_w && (c.kmajor == 2 || !mfma_km_block_config_valid(c, M, d_model, d_ff, dtype))) {
         // The 256-token pair is paced by its MFMA and LDS work, so scaling X inside every workgroup
-        // costs more there than one small launch that writes the normalised input once.
+        // costs more there than one small launch that writes the normalised input once.  The
+        // 64-token pair folds the normalisation into its gate/up kernel unless the slices of the
+        // normalisation weight do not fit its LDS beside the rings (very wide d_model): then it
+        // takes the same small launch.
         void* xn = (char*)ws + l.xn_off;
         hipError_t e = launch_rmsnorm_weighted(X, norm_w, xn, M, d_model, eps, dtype, st);
         if (e != hipSuccess) return hip_fail(e);
@@ -456,7 +459,7 @@ dfk_status_t dfk_mlp_block(const void* H, const void* norm_weight, float eps, co
     }
     auto carries = [&](const dfk_config_t& k) {
         return k.path == DFK_PATH_MFMA &&
-               ((k.kmajor == 1 && mfma_km_block_config_valid(k, M, d_model, d_ff, dtype)) ||
+               ((k.kmajor == 1 && mfma_km_config_valid(k, M, d_model, d_ff, dtype)) ||
                 (k.kmajor == 2 && mfma_big_config_valid(k, M, d_model, d_ff, dtype)));
     };
     dfk_config_t c;

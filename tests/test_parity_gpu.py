@@ -431,6 +431,16 @@ def test_sizes_at_the_limits(shape, dtype):
         Y, _ = run_ex(g, cfg, ws)
         assert_parity(y64(Y), ref, dtype, (shape, cfg))
         assert workspace_is_clean(ws, M, d), (shape, cfg)
+    if dtype != "fp32" and d >= 1024:
+        # the block with its neighbours, scheduler's choice, in place
+        t["w"] = di.tensor(1077, (d,), 1.0, dtype)
+        refb = oracle.mlp_block(t["X"], t["w"], 1e-5, t["Wg"], t["Wu"], t["Wd"])
+        h = g["X"].clone()
+        print("case block", shape, dtype, flush=True)
+        dfk.dfk_mlp_block(h, di.to_torch(t["w"], DEV), 1e-5, g["Wg"], g["Wu"], g["Wd"], h, None, ws)
+        torch.cuda.synchronize()
+        assert_parity(y64(h), refb, dtype, (shape, "block"))
+        assert workspace_is_clean(ws, M, d), shape
 
 
 def test_repeated_calls_share_a_workspace_and_stay_correct():
