@@ -278,6 +278,49 @@ def test_scheduler_table_roundtrip(tmp_path):
     dfk.dfk_clear_tuning()
 
 
+def test_table_loader_survives_damaged_files(tmp_path):
+    """Seeded damage to a saved table (fields replaced by huge, negative or non-numeric values, lines cut
+    or doubled, binary bytes): loading either succeeds or reports an I/O error, and whatever the table
+    then holds, the choice for a shape is a configuration that is valid for it."""
+    import random
+    rng = random.Random(99)
+    dfk.dfk_clear_tuning()
+    shapes = [(M, D, FF, dfk.DFK_BF16) for M in (1, 4, 64, 200)] + [(3, 512, 1000, dfk.DFK_FP32)]
+    for M, d, ff, dt in shapes:
+        n = dfk.dfk_num_candidates(M, d, ff, dt)
+        dfk.dfk_set_choice(M, d, ff, dt, dfk.dfk_get_candidate(M, d, ff, dt, rng.randrange(n)), 50.0)
+    good = str(tmp_path / "good.txt")
+    dfk.dfk_save_tuning(good)
+    lines = open(good).read().splitlines()
+    junk = ["-1", "0", "7", "99999999999999999999", "2147483647", "-2147483648", "nan", "x", "", "1e9", "256", "3"]
+    for case in range(300):
+        out = []
+        for ln in lines:
+            r = rng.random()
+            if ln.startswith("#") or r < 0.5:
+                out.append(ln)
+            elif r < 0.8:
+                f = ln.split()
+                f[rng.randrange(len(f))] = rng.choice(junk)
+                out.append(" ".join(f))
+            elif r < 0.9:
+                out.append(ln[:rng.randrange(len(ln))])
+            else:
+                out.append(ln + " " + ln)
+        path = str(tmp_path / "damaged.txt")
+        with open(path, "wb") as f:
+            f.write("\n".join(out).encode() + (bytes(rng.randrange(256) for _ in range(40)) if case % 7 == 0 else b"\n"))
+        dfk.dfk_clear_tuning()
+        try:
+            dfk.dfk_load_tuning(path)
+        except dfk.DfkError as e:
+            assert e.status == dfk.DFK_ERR_IO
+        for M, d, ff, dt in shapes:
+            c, _ = dfk.dfk_get_choice(M, d, ff, dt)
+            assert dfk.dfk_config_valid(c, M, d, ff, dt), (case, M, c)
+    dfk.dfk_clear_tuning()
+
+
 def test_timing_calls_check_their_arguments_on_the_host():
     import ctypes
     c = dfk.dfk_get_candidate(4, D, FF, dfk.DFK_BF16, 0)
