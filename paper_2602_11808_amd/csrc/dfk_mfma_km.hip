@@ -5,7 +5,7 @@
 // 32 tokens; more tokens mean further launches that stream the weights again.  Here
 // the activations ride the same per-wavefront LDS ring as the weight tiles, 4 KB
 // tiles fetched by the same asynchronous global->LDS loads in one in-order stream,
-// so their register cost is one tile at a time and a launch takes 4 token tiles of
+// so their register cost is one tile at a time and a launch takes up to 4 token tiles of
 // 16 ("row-major" end of the Method section's tiling choice: X stays local while
 // more of it is reused per weight tile).
 //
@@ -330,7 +330,7 @@ struct KmStream2 {
     }
 };
 
-__host__ __device__ constexpr int km_col_blocks(int tt) { return tt >= 4 ? 1 : 2; }   // accumulator budget
+__host__ __device__ constexpr int km_col_blocks(int tt) { return tt >= 3 ? 1 : 2; }   // accumulator budget
 
 template <int NW, int TT, typename E>
 __global__ __launch_bounds__(NW * 64) void k_down_km(MlpArgs a, KmGeom geo) {
@@ -484,7 +484,7 @@ __global__ __launch_bounds__(NW * 64) void k_down_km(MlpArgs a, KmGeom geo) {
 }
 
 // ---------------------------------------------------------------- host side
-int km_token_tiles(int m_count) { return m_count <= 16 ? 1 : m_count <= 32 ? 2 : 4; }
+int km_token_tiles(int m_count) { return m_count <= 16 ? 1 : m_count <= 32 ? 2 : m_count <= 48 ? 3 : 4; }
 
 // norm: the kernel also keeps the normalisation weight (d_model 16-bit values, a 1 KB-aligned
 // slice per wavefront) and the wavefronts' sums of squares behind rings and stage.
@@ -581,9 +581,11 @@ hipError_t launch_mfma_km(const MlpArgs& a, const dfk_config_t& c, hipStream_t s
     switch (c.waves * 10 + km_token_tiles(a.m_count)) {
         case 41: return launch_km_t<4, 1>(a, c, st);
         case 42: return launch_km_t<4, 2>(a, c, st);
+        case 43: return launch_km_t<4, 3>(a, c, st);
         case 44: return launch_km_t<4, 4>(a, c, st);
         case 81: return launch_km_t<8, 1>(a, c, st);
         case 82: return launch_km_t<8, 2>(a, c, st);
+        case 83: return launch_km_t<8, 3>(a, c, st);
         case 84: return launch_km_t<8, 4>(a, c, st);
         default: return hipErrorInvalidValue;
     }

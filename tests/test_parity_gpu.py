@@ -164,7 +164,7 @@ def test_large_token_counts(M):
                          ids=lambda s: "M%d_d%d_ff%d" % s)
 def test_kernels_for_up_to_64_tokens_per_launch(shape):
     """Every candidate of the pair of kernels whose activations travel through the tile
-    rings (config field kmajor): one, two and four token tiles, ragged d_ff, both reductions,
+    rings (config field kmajor): one to four token tiles, ragged d_ff, both reductions,
     and a token count that needs two launches."""
     M, d, ff = shape
     t = di.mlp_inputs(M, d, ff, seed=11)
