@@ -310,8 +310,9 @@ struct BigLoads2 {
 // of a split read the same A_2 rows, so a split's workgroups are placed on one XCD (or, with fewer
 // than 8 splits, on 8 / splits of them) and those rows are fetched into that L2 once.  Any other
 // split count keeps the plain order, and so does a launch whose whole A_2 fits one L2 (the host
-// decides: there the plain order already shares it, and measured 2 us faster at 128 tokens of the
-// 8B shape, against 4 to 20 us slower at 256 tokens and on the 70B shape).  A bijection from
+// decides: there the plain order measured 2 us faster, at 128 tokens of the 8B shape; beyond,
+// the placement gains 1 to 4 us of 60 at 256 tokens of that shape and 13 of 200 on the 70B
+// shape).  A bijection from
 // [0, S * C) onto S x C in every case.
 __device__ __forceinline__ void down_tile_of(int b, int S, int C, bool by_xcd, int& js, int& cb) {
     const int x = b & 7, r = b >> 3;
