@@ -417,6 +417,19 @@ def main():
     torch.cuda.synchronize()
     read_gbs = reps * sum(s.numel() * 2 for s in both) / (a.elapsed_time(b) * 1e-3) / 1e9
     del both
+    # the gate/up kernel's own memory pattern without its work (same slices, wavefronts, pieces and order)
+    pat_waves = max(set(p["waves"] for p in picks.values() if p.get("kmajor") == 1), default=8)
+    pat_splits = max(set(p["splits"] for p in picks.values() if p.get("kmajor") == 1), default=256)
+    for l in layers:
+        dfk.dfk_read_gateup_pattern(l["Wg"], l["Wu"], pat_splits, pat_waves, sink)
+    torch.cuda.synchronize()
+    a.record()
+    for _ in range(reps):
+        for l in layers:
+            dfk.dfk_read_gateup_pattern(l["Wg"], l["Wu"], pat_splits, pat_waves, sink)
+    b.record()
+    torch.cuda.synchronize()
+    pattern_us = a.elapsed_time(b) * 1e3 / (reps * len(layers))
     fill_target = torch.empty(64 << 20, dtype=torch.bfloat16, device=dev)     # 128 MiB written once
     dfk.dfk_fill_synthetic(fill_target, 1.0, 1)
     torch.cuda.synchronize()
@@ -458,6 +471,9 @@ def main():
                 "read_stream_ceiling_gbs": round(read_gbs, 1),
                 "read_stream_one_matrix_gbs": round(read_small_gbs, 1),
                 "kernel_frac_of_read_stream_ceiling": round(k_achieved / read_gbs, 4),
+                # a read-only kernel with the gate/up kernel's slices, wavefronts, 256-byte pieces and tile order
+                "gateup_pattern_read_us": round(pattern_us, 2),
+                "gateup_pattern_read_gbs": round(4 * D_MODEL * D_FF / pattern_us / 1e3, 1),
                 "frac_of_read_stream_ceiling": round(achieved / read_gbs, 4)}
 
     # ---- the fp64 oracle on the host cores: whole steps of the same workload until ~12 s of CPU

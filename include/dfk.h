@@ -291,6 +291,17 @@ dfk_status_t dfk_load_tuning(const char* path);
  * the block's bandwidth is compared with.  bytes must be a multiple of 16. */
 dfk_status_t dfk_stream_read(const void* src, size_t bytes, void* sink, void* stream);
 
+/* Read-only kernel that fetches W_gate and W_up [d_ff, d_model] (16-bit elements) exactly as the
+ * gate/up kernel of the two-kernel variant for up to 64 tokens does (Method: the first stage is
+ * where the weights dominate): `splits` workgroups, one d_ff slice each, `waves` (4 or 8)
+ * wavefronts that divide every row's k range, 4 rows x 256 bytes per load instruction, the same
+ * tile order, 16 instructions in flight per wavefront; and nothing else (no X, no MFMA, no LDS,
+ * no stores).  Its duration is what that kernel's memory pattern costs on its own.
+ * d_model must be a multiple of 128 * waves, d_ff of 8, 1 <= splits <= min(d_ff / 8, 65535);
+ * sink as for dfk_stream_read.  Errors as for the other calls (arguments are checked on the host). */
+dfk_status_t dfk_read_gateup_pattern(const void* W_gate, const void* W_up, int d_model, int d_ff,
+                                     int splits, int waves, void* sink, void* stream);
+
 /* Fill a device buffer with synthetic bf16 (or fp32) values in (-scale, scale),
  * a cheap hash of the element index and seed.  Used by dfk_tune and by benchmarks. */
 dfk_status_t dfk_fill_synthetic(void* dst, size_t elems, dfk_dtype_t dtype, float scale,

@@ -79,6 +79,7 @@ SIGNATURES = [
     ("dfk_save_tuning", _ci, [ctypes.c_char_p]),
     ("dfk_load_tuning", _ci, [ctypes.c_char_p]),
     ("dfk_stream_read", _ci, [_vp, _sz, _vp, _vp]),
+    ("dfk_read_gateup_pattern", _ci, [_vp, _vp, _ci, _ci, _ci, _ci, _vp, _vp]),
     ("dfk_fill_synthetic", _ci, [_vp, _sz, _ci, ctypes.c_float, ctypes.c_uint, _vp]),
     ("dfk_rms_normalize", _ci, [_vp, _vp, _ci, _ci, _vp]),
     ("dfk_set_trace_buffer", _ci, [_vp, _sz]),
@@ -302,6 +303,16 @@ def dfk_load_tuning(path: str):
 def dfk_stream_read(src, sink, stream=None):
     _check(lib().dfk_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink),
                                  _stream(stream)), "dfk_stream_read")
+
+
+def dfk_read_gateup_pattern(W_gate, W_up, splits: int, waves: int, sink, stream=None):
+    """Reads W_gate and W_up [d_ff, d_model] in the gate/up kernel's access pattern, and nothing else."""
+    if W_gate.shape != W_up.shape or W_gate.dim() != 2 or W_gate.element_size() != 2 \
+            or not W_gate.is_contiguous() or not W_up.is_contiguous():
+        raise ValueError("W_gate and W_up must be dense [d_ff, d_model] tensors of a 16-bit type")
+    d_ff, d_model = W_gate.shape
+    _check(lib().dfk_read_gateup_pattern(_ptr(W_gate), _ptr(W_up), d_model, d_ff, splits, waves, _ptr(sink),
+                                         _stream(stream)), "dfk_read_gateup_pattern")
 
 
 def dfk_fill_synthetic(dst, scale: float, seed: int, stream=None):

@@ -689,6 +689,17 @@ dfk_status_t dfk_stream_read(const void* src, size_t bytes, void* sink, void* st
     return e == hipSuccess ? DFK_OK : hip_fail(e);
 }
 
+dfk_status_t dfk_read_gateup_pattern(const void* Wg, const void* Wu, int d_model, int d_ff, int splits, int waves,
+                                     void* sink, void* stream) {
+    if (!Wg || !Wu || !sink || d_model < 1 || d_ff < 1 || splits < 1) return DFK_ERR_INVALID_ARG;
+    if (waves != 4 && waves != 8) return DFK_ERR_INVALID_ARG;
+    if (d_ff % 8 || d_model % (128 * waves) || d_model > kMaxDModel || splits > d_ff / 8 || splits > 65535)
+        return DFK_ERR_UNSUPPORTED_SHAPE;
+    if ((uintptr_t)Wg % 16 || (uintptr_t)Wu % 16 || (uintptr_t)sink % 8) return DFK_ERR_ALIGNMENT;
+    hipError_t e = launch_read_gateup_pattern(Wg, Wu, d_model, d_ff, splits, waves, sink, (hipStream_t)stream);
+    return e == hipSuccess ? DFK_OK : hip_fail(e);
+}
+
 dfk_status_t dfk_fill_synthetic(void* dst, size_t elems, dfk_dtype_t dtype, float scale, unsigned seed,
                                 void* stream) {
     if (!dst || elems == 0) return DFK_ERR_INVALID_ARG;

@@ -162,6 +162,8 @@ int valu_max_tokens_per_launch();
 // utility kernels
 hipError_t launch_zero(void* p, size_t bytes, hipStream_t st);
 hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, hipStream_t st);
+hipError_t launch_read_gateup_pattern(const void* Wg, const void* Wu, int d_model, int d_ff, int splits, int waves,
+                                      void* sink, hipStream_t st);
 hipError_t launch_rms_normalize(const void* in, void* out, int M, int d_model, hipStream_t st);
 hipError_t launch_rmsnorm_weighted(const void* in, const void* w, void* out, int M, int d_model, float eps, dfk_dtype_t dtype,
                                    hipStream_t st);

@@ -146,6 +146,60 @@ hipError_t launch_rms_normalize(const void* in, void* out, int M, int d_model, h
     return hipGetLastError();
 }
 
+// Reads W_gate and W_up the way the gate/up kernel for up to 64 tokens does, and nothing else:
+// workgroup s takes the d_ff slice s of both matrices, wavefront w the k range w of every row,
+// a load instruction covers 4 rows x 256 bytes (one quarter of a 16-row x 128-k tile; rows 0..7
+// of a tile from W_gate, 8..15 the same rows of W_up), the tiles are walked k chunk by k chunk
+// over all row tiles of the slice, 16 instructions (4 tiles) in flight per wavefront.  No X, no
+// MFMA, no LDS, no stores: what is left is the memory pattern's own time.
+template <int NW>
+__global__ __launch_bounds__(NW * 64) void k_read_gateup_pattern(const char* __restrict__ Wg, const char* __restrict__ Wu,
+                                                                  int d_model, int d_ff, int splits, unsigned* sink) {
+    constexpr int kInFlight = 16;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int j0, j1;
+    slice_rows(d_ff, splits, blockIdx.x, j0, j1);
+    const int nt = (j1 - j0) / 8;                       // row tiles of 8 rows of each matrix
+    const size_t row_bytes = (size_t)d_model * 2;
+    const int kw_bytes = d_model * 2 / NW;              // this wavefront's bytes of every row
+    const int nkc = kw_bytes / 256;
+    const size_t base = (size_t)j0 * row_bytes + (size_t)wave * kw_bytes + (size_t)(lane & 15) * 16;
+    const int tiles = nkc * nt;                         // 16-row x 128-k tiles of this wavefront, k chunk by k chunk
+    const char* gl = Wg + base + (size_t)(lane >> 4) * row_bytes;   // this lane in rows 0..3 of the slice
+    const char* ul = Wu + base + (size_t)(lane >> 4) * row_bytes;
+    u32x4 acc = {0, 0, 0, 0};
+    int kc = 0, rt = 0;                                 // (wave-uniform counters: no division per load)
+    for (int t0 = 0; t0 < tiles; t0 += kInFlight / 4) {
+        u32x4 v[kInFlight];
+#pragma unroll
+        for (int t = 0; t < kInFlight / 4; ++t) {
+            const size_t off = (size_t)rt * 8 * row_bytes + (size_t)kc * 256;
+            v[4 * t + 0] = __builtin_nontemporal_load((const u32x4*)(gl + off));
+            v[4 * t + 1] = __builtin_nontemporal_load((const u32x4*)(gl + off + 4 * row_bytes));
+            v[4 * t + 2] = __builtin_nontemporal_load((const u32x4*)(ul + off));
+            v[4 * t + 3] = __builtin_nontemporal_load((const u32x4*)(ul + off + 4 * row_bytes));
+            if (t0 + t + 1 < tiles) {                   // past the last tile: it is read again
+                if (++rt == nt) { rt = 0; ++kc; }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kInFlight; ++u) acc ^= v[u];
+    }
+    const unsigned a = acc.x ^ acc.z, b = acc.y ^ acc.w;
+    if (a == 0x9E3779B9u && b == 0x7F4A7C15u) sink[0] = 1u;
+}
+
+hipError_t launch_read_gateup_pattern(const void* Wg, const void* Wu, int d_model, int d_ff, int splits, int waves,
+                                      void* sink, hipStream_t st) {
+    if (waves == 8)
+        hipLaunchKernelGGL(k_read_gateup_pattern<8>, dim3(splits), dim3(512), 0, st, (const char*)Wg, (const char*)Wu,
+                           d_model, d_ff, splits, (unsigned*)sink);
+    else
+        hipLaunchKernelGGL(k_read_gateup_pattern<4>, dim3(splits), dim3(256), 0, st, (const char*)Wg, (const char*)Wu,
+                           d_model, d_ff, splits, (unsigned*)sink);
+    return hipGetLastError();
+}
+
 hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, hipStream_t st) {
     const size_t n16 = bytes / 16;
     const size_t tile = (size_t)kReadThreads * kReadUnroll;

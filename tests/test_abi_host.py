@@ -343,6 +343,17 @@ def test_helper_calls_check_their_arguments_on_the_host():
     assert L.dfk_rms_normalize(None, 4096, 1, 512, None) == dfk.DFK_ERR_INVALID_ARG
     assert L.dfk_rms_normalize(4096, 4096, 0, 512, None) == dfk.DFK_ERR_INVALID_ARG
     assert L.dfk_rms_normalize(4096, 4096, 70000, 512, None) == dfk.DFK_ERR_UNSUPPORTED_SHAPE
+    # the read-only kernel with the gate/up kernel's access pattern
+    rp = L.dfk_read_gateup_pattern
+    assert rp(None, WU, D, FF, 256, 8, WS, None) == dfk.DFK_ERR_INVALID_ARG
+    assert rp(WG, WU, D, FF, 256, 8, None, None) == dfk.DFK_ERR_INVALID_ARG
+    assert rp(WG, WU, D, FF, 256, 6, WS, None) == dfk.DFK_ERR_INVALID_ARG            # 4 or 8 wavefronts
+    assert rp(WG, WU, D, FF, 0, 8, WS, None) == dfk.DFK_ERR_INVALID_ARG
+    assert rp(WG, WU, D, FF, FF // 8 + 1, 8, WS, None) == dfk.DFK_ERR_UNSUPPORTED_SHAPE   # more slices than 8-row groups
+    assert rp(WG, WU, D + 128, FF, 256, 8, WS, None) == dfk.DFK_ERR_UNSUPPORTED_SHAPE     # k range not whole 128-k chunks per wavefront
+    assert rp(WG, WU, D, FF + 4, 256, 8, WS, None) == dfk.DFK_ERR_UNSUPPORTED_SHAPE
+    assert rp(WG + 8, WU, D, FF, 256, 8, WS, None) == dfk.DFK_ERR_ALIGNMENT
+    assert rp(WG, WU, D, FF, 256, 8, WS + 4, None) == dfk.DFK_ERR_ALIGNMENT
 
 
 def test_mlp_block_checks_its_arguments_on_the_host():

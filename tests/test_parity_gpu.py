@@ -726,6 +726,28 @@ def test_per_launch_timing_splits_the_two_kernel_variant():
         assert us1 + us2 < 3 * whole + 50      # same order as the whole-call time
 
 
+def test_read_only_kernel_with_the_gateup_access_pattern():
+    """The measurement helper runs on ragged slices and both wavefront counts, leaves the sink alone and
+    takes about as long as a streaming read of the same bytes (it reads every byte of both matrices once)."""
+    sink = torch.zeros(2, dtype=torch.int32, device=DEV)
+    for d, ff, splits in ((1024, 2056, 33), (4096, 14336, 256)):
+        w = di.mlp_inputs_torch(1, d, ff, seed=3, device=DEV)
+        for waves in (4, 8):
+            for _ in range(3):
+                dfk.dfk_read_gateup_pattern(w["Wg"], w["Wu"], splits, waves, sink)
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(10):
+                dfk.dfk_read_gateup_pattern(w["Wg"], w["Wu"], splits, waves, sink)
+            b.record()
+            torch.cuda.synchronize()
+            us = a.elapsed_time(b) * 100.0
+            assert int(sink.abs().sum().item()) == 0
+            if d == 4096:     # 234.9 MB: between the 8 TB/s peak and a quarter of it (the weights partly sit in the memory-side cache here)
+                assert 234.9e6 / 8e12 * 1e6 * 0.5 < us < 120.0, us
+
+
 def test_rms_normalize_helper():
     # the weight-free normalisation benchmarks chain layers with (not part of the block)
     for M, d in ((1, 512), (5, 4096), (64, 1000)):
