@@ -83,8 +83,9 @@ typedef enum { DFK_REDUCE_TICKET = 0, DFK_REDUCE_ATOMIC = 1 } dfk_reduce_t;
  * One candidate kernel configuration (Method section: tiling / loop-order
  * variants and tile sizes; the scheduler chooses among these).
  *   variant        DFK_VARIANT_FUSED or DFK_VARIANT_TWO_KERNEL
- *   path           DFK_PATH_VALU (any supported shape, both dtypes) or
- *                  DFK_PATH_MFMA (bf16 only, shape constraints, see dfk_config_valid)
+ *   path           DFK_PATH_VALU (any supported shape, all three element types) or
+ *                  DFK_PATH_MFMA (bf16, and IEEE half with the kmajor pairs; shape
+ *                  constraints, see dfk_config_valid)
  *   splits         number of d_ff slices = workgroups of the fused kernel, or of
  *                  the first kernel of the two-kernel variant
  *   waves          wavefronts (64 lanes) per workgroup
@@ -153,8 +154,8 @@ dfk_status_t dfk_swiglu_mlp_unfused(const void* X, const void* W_gate, const voi
                                     int M, int d_model, int d_ff, void* stream);
 
 /*
- * Fully explicit form.  dtype selects bf16 or the fp32 test mode (all five
- * tensors in that type).  cfg == NULL means "scheduler's choice"; otherwise
+ * Fully explicit form.  dtype selects bf16, IEEE half (the precision of the paper's
+ * Experiments section) or the fp32 test mode (all five tensors in that type).  cfg == NULL means "scheduler's choice"; otherwise
  * cfg must satisfy dfk_config_valid for the shape.  workspace is a device
  * buffer of at least dfk_workspace_bytes(M, d_model, d_ff) bytes, 256-byte
  * aligned, initialised once with dfk_workspace_init.
@@ -211,7 +212,8 @@ dfk_status_t dfk_check_args(const void* X, const void* W_gate, const void* W_up,
 /* ---------------------------------------------------------------- workspace */
 
 /* Upper bound, over every configuration the library can pick, of the workspace
- * a call with M <= M_max needs.  Returns 0 for invalid arguments. */
+ * a call with M <= M_max needs.  Returns 0 for invalid arguments and for shapes no
+ * call accepts (the conditions of DFK_ERR_UNSUPPORTED_SHAPE). */
 size_t dfk_workspace_bytes(int M_max, int d_model, int d_ff);
 
 /* Enqueue the zero-initialisation of a workspace (a fill kernel; capturable). */
@@ -237,7 +239,8 @@ int dfk_config_valid(const dfk_config_t* cfg, int M, int d_model, int d_ff, dfk_
 
 /* Bytes of device scratch dfk_tune needs: `sets` rotating copies of the three
  * weight matrices (so timed launches stream from HBM, not from cache) plus X,
- * Y and a workspace for the largest M in the list. */
+ * Y and a workspace for the largest M in the list.  0 for invalid arguments and
+ * unsupported shapes. */
 size_t dfk_tune_scratch_bytes(int M_max, int d_model, int d_ff, dfk_dtype_t dtype, int sets);
 
 /*
