@@ -106,9 +106,10 @@ typedef enum { DFK_REDUCE_TICKET = 0, DFK_REDUCE_ATOMIC = 1 } dfk_reduce_t;
  *                  tokens per launch (the activations travel through the same LDS rings
  *                  as the weight tiles instead of sitting in registers; gate/up kernel
  *                  k-major with all its row tiles accumulating in registers); needs
- *                  k2_rows_by_wave = 0; 0 = the kernels above;
+ *                  k2_rows_by_wave = 0 and d_model a multiple of 128 with at least `waves`
+ *                  128-k chunks (512 and up); 0 = the kernels above;
  *                  2 = the pair that takes up to 256 tokens per launch (offered beyond 64
- *                  tokens): the wavefronts share every weight tile through LDS and own a
+ *                  tokens, and at any token count where d_model rules out the pair above): the wavefronts share every weight tile through LDS and own a
  *                  share of the tokens each; waves = 4 or 8 (wavefronts of the gate/up kernel;
  *                  the down kernel always runs 8), depth = 3 or 4 (buffers of shared tiles),
  *                  k2_col_blocks = d_model / 128; with DFK_REDUCE_TICKET the splits' partial

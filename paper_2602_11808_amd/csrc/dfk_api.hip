@@ -160,8 +160,12 @@ std::vector<dfk_config_t> candidates(int M, int d_model, int d_ff, dfk_dtype_t d
                             push(make_cfg(DFK_VARIANT_TWO_KERNEL, DFK_PATH_MFMA, clamp_splits(splits, d_ff), wd / 10, wd % 10,
                                           clamp_splits(std::max(1, grid / k2c), d_ff), k2c, (int)dtype, reduce, 0, 1));
             }
-        // two-kernel, workgroup-shared weight tiles: up to 256 tokens per launch (offered beyond 64 tokens)
-        if (M > 64 && nblk >= 1) {
+        // two-kernel, workgroup-shared weight tiles: up to 256 tokens per launch.  Offered beyond 64 tokens,
+        // and below where d_model rules out the pair above (it needs whole 128-k chunks per wavefront,
+        // this one only d_model % 128 == 0)
+        bool have_km = false;
+        for (const auto& o : out) have_km = have_km || o.kmajor == 1;
+        if ((M > 64 || !have_km) && nblk >= 1) {
             const int k2c = nblk;
             for (int splits : {256, 512})
                 for (int grid : {256, 512})

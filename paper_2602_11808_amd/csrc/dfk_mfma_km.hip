@@ -10,8 +10,8 @@
 // more of it is reused per weight tile).
 //
 // Gate/up kernel (A_2 = (X W_up) (x) SiLU(X W_gate), same split as before: workgroup s
-// owns a d_ff slice of at most 8 row tiles of 8 rows, wavefront w the k range
-// [w*KW, (w+1)*KW)).  The stream is k-major: for every 128-k chunk first the X tiles
+// owns a d_ff slice of at most 8 row tiles of 8 rows, wavefront w a contiguous run of the
+// 128-k chunks of every row).  The stream is k-major: for every 128-k chunk first the X tiles
 // (16 tokens x 128 k each, same shape and swizzle as a weight tile; they become the
 // MFMA B operand registers of the chunk), then the weight tile of every row tile.
 // All row tiles accumulate in registers until the stream ends; the wavefronts' sums
@@ -41,6 +41,13 @@ struct KmGeom {
     int pass;    // gate/up kernel: row tiles whose partial sums LDS holds per pass at the end
     int norm_off;  // gate/up kernel with the normalisation: byte offset in LDS of the weight slices, past rings and stage
 };
+
+// Bytes between the wavefronts' slices of the normalisation weight in LDS: the longest run of
+// chunks a wavefront can own, 1 KB-aligned (one load instruction writes 1 KB).
+__host__ __device__ inline int km_norm_stride(int d_model, int waves) {
+    const int nchunks = d_model / kKC;
+    return (((nchunks + waves - 1) / waves) * (kKC * 2) + 1023) & ~1023;
+}
 
 // ---------------------------------------------------------------- gate/up kernel
 template <int NW, int TT>
@@ -125,14 +132,18 @@ __global__ __launch_bounds__(NW * 64) void k_gateup_km(MlpArgs a, KmGeom geo) {
     int j0, j1;
     slice_rows(a.d_ff, a.splits, blockIdx.x, j0, j1);
     const int nt = (j1 - j0) / 8;                 // <= NT, checked on the host
-    const int KW = a.d_model / NW;
+    // The 128-k chunks of a row are dealt out to the wavefronts in contiguous runs, as evenly as
+    // their number allows (equal runs when d_model is a multiple of 128 * NW).
+    const int nchunks = a.d_model / kKC;
+    const int c0 = wave * nchunks / NW, c1 = (wave + 1) * nchunks / NW;
+    const size_t kbase = (size_t)c0 * (kKC * 2);          // bytes into a row
 
     KmStream1<NW, TT> ts;
     ts.Wg = (const char*)a.Wg; ts.Wu = (const char*)a.Wu; ts.X = (const char*)a.X;
     ts.row_bytes = (size_t)a.d_model * 2;
-    ts.w_base = (size_t)j0 * ts.row_bytes + (size_t)wave * KW * 2;
-    ts.x_base = (size_t)a.m_base * ts.row_bytes + (size_t)wave * KW * 2;
-    ts.nt = nt; ts.nkc = KW / kKC; ts.m_count = a.m_count;
+    ts.w_base = (size_t)j0 * ts.row_bytes + kbase;
+    ts.x_base = (size_t)a.m_base * ts.row_bytes + kbase;
+    ts.nt = nt; ts.nkc = c1 - c0; ts.m_count = a.m_count;
     ts.q = q; ts.g = g;
     ts.ring = lds + wave * geo.depth * kTileBytes;
     ts.depth = geo.depth;
@@ -141,15 +152,15 @@ __global__ __launch_bounds__(NW * 64) void k_gateup_km(MlpArgs a, KmGeom geo) {
     // loads as the tiles, issued ahead of them: they are the oldest in the queue, so the first
     // tile's counted wait covers them and no register or extra wait is involved.  Slices sit
     // 1 KB-aligned (one load instruction writes 1 KB); lanes past a short slice re-read its end.
-    const int wbytes = KW * 2;
-    const int wstride = (wbytes + 1023) & ~1023;
+    const int wbytes = ts.nkc * (kKC * 2);
+    const int wstride = km_norm_stride(a.d_model, NW);
     unsigned char* wslice = lds + geo.norm_off + (size_t)wave * wstride;
     float* ssq = (float*)(lds + geo.norm_off + (size_t)NW * wstride);   // [NW][TOK] sums of squares
     float ss[TT];
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) ss[tt] = 0.f;
     if (NORM) {
-        const char* src = (const char*)a.norm_w + (size_t)wave * wbytes;
+        const char* src = (const char*)a.norm_w + kbase;
         for (int o = 0; o < wbytes; o += 1024)
             __builtin_amdgcn_global_load_lds(src + min(o + lane * 16, wbytes - 16), DFK_LDS_PTR(wslice + o), 16, 0, 0);
     }
@@ -492,7 +503,7 @@ size_t km_lds_gateup(const dfk_config_t& c, int TT, int d_model, int d_ff, bool 
     const int nt_max = max_slice_rows(d_ff, c.splits) / 8;
     const size_t ring = (size_t)c.waves * c.depth * kTileBytes;
     const size_t per_tile = (size_t)c.waves * 16 * TT * 16 * 4;   // partial sums of one row tile
-    const size_t wstride = ((size_t)d_model / c.waves * 2 + 1023) & ~(size_t)1023;   // a wavefront's weight slice, 1 KB-aligned
+    const size_t wstride = (size_t)km_norm_stride(d_model, c.waves);
     const size_t extra = norm ? (size_t)c.waves * wstride + (size_t)c.waves * 16 * TT * 4 : 0;
     const size_t room = (size_t)kLdsLimit > extra ? (size_t)kLdsLimit - extra : 0;
     const int fit = (int)(room / per_tile);
@@ -553,7 +564,7 @@ bool mfma_km_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, d
     if (c.reduce != DFK_REDUCE_TICKET && c.reduce != DFK_REDUCE_ATOMIC) return false;
     if ((c.waves != 4 && c.waves != 8) || c.depth < 2 || c.depth > 16) return false;
     if (M < 1 || d_model < 8 || d_ff < 8 || d_ff % 8 || d_model > kMaxDModel) return false;
-    if (d_model % (kKC * c.waves)) return false;          // each wavefront owns whole 128-k chunks
+    if (d_model % kKC || d_model / kKC < c.waves) return false;   // each wavefront owns whole 128-k chunks, at least one
     const int ng = d_ff / 8;
     if (c.splits < 1 || c.splits > ng || c.splits > 65535) return false;
     if (max_slice_rows(d_ff, c.splits) / 8 > kKmMaxRowTiles) return false;   // accumulators of the row tiles

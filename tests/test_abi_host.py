@@ -210,8 +210,9 @@ def test_candidates_and_workspace_over_random_shapes():
                 cands.append(c.as_dict())
                 assert dfk.dfk_config_valid(c, M, d, ff, dt), (M, d, ff, dt, c)
                 assert dfk.dfk_check_args(Xp, Wg, Wu, Wd, Yp, M, d, ff, dt, c, ws, wsb) == dfk.DFK_OK, (M, d, ff, dt, c)
-                if c.kmajor == 2:
-                    assert M > 64 and c.k2_col_blocks * 128 == d
+                if c.kmajor == 2:   # beyond 64 tokens, or where d_model rules the 64-token pair out
+                    assert c.k2_col_blocks * 128 == d
+                    assert M > 64 or d < 512
                 if c.path == dfk.DFK_PATH_MFMA:
                     assert dt != dfk.DFK_FP32
             pick, tuned = dfk.dfk_get_choice(M, d, ff, dt)

@@ -160,12 +160,14 @@ def test_large_token_counts(M):
 
 
 @pytest.mark.parametrize("shape", [(1, 1024, 2816), (16, 1024, 4104), (17, 1024, 2816), (33, 2048, 4104),
-                                   (48, 1024, 2816), (64, 1024, 8200), (100, 1024, 2816)],
+                                   (48, 1024, 2816), (64, 1024, 8200), (100, 1024, 2816),
+                                   (3, 768, 1000), (40, 1280, 2056), (64, 2304, 1536), (16, 896, 1000), (33, 640, 520)],
                          ids=lambda s: "M%d_d%d_ff%d" % s)
 def test_kernels_for_up_to_64_tokens_per_launch(shape):
     """Every candidate of the pair of kernels whose activations travel through the tile
     rings (config field kmajor): one to four token tiles, ragged d_ff, both reductions,
-    and a token count that needs two launches."""
+    and a token count that needs two launches; the last five shapes have a d_model whose 128-k chunks do not
+    divide evenly among the wavefronts (6, 10, 18, 7 and 5 chunks for 4 or 8 wavefronts)."""
     M, d, ff = shape
     t = di.mlp_inputs(M, d, ff, seed=11)
     ref = oracle.swiglu_mlp(t["X"], t["Wg"], t["Wu"], t["Wd"])
@@ -184,14 +186,17 @@ def test_kernels_for_up_to_64_tokens_per_launch(shape):
 
 @pytest.mark.parametrize("dtype", ["bf16", "fp16"])
 @pytest.mark.parametrize("shape", [(65, 1024, 2816), (100, 512, 1000), (128, 1024, 4104), (129, 2048, 4104),
-                                   (200, 512, 1536), (256, 1024, 4104), (130, 128, 264), (256, 256, 520), (256, 512, 8200)],
+                                   (200, 512, 1536), (256, 1024, 4104), (130, 128, 264), (256, 256, 520), (256, 512, 8200),
+                                   (3, 384, 1000), (40, 256, 2056), (64, 384, 1536)],
                          ids=lambda s: "M%d_d%d_ff%d" % s)
 def test_kernels_for_up_to_256_tokens_per_launch(shape, dtype):
     """Every candidate of the pair of kernels whose workgroups share the weight tiles (config
     field kmajor = 2): two and four token tiles per wavefront, token tiles that are partly or
     wholly empty, ragged d_ff, both reductions, up to the largest token count a call accepts; the
     two shapes before the last have fewer pipeline steps than buffers (one or two k chunks, 8-row d_ff splits);
-    in the last A_2 is larger than one L2, where the down kernel places the workgroups of a split on one XCD."""
+    in (256, 512, 8200) A_2 is larger than one L2, where the down kernel places the workgroups of a split on one
+    XCD; the last three are token counts of 64 and below at a d_model the 64-token pair cannot take (fewer
+    128-k chunks than wavefronts), where this pair is offered instead."""
     M, d, ff = shape
     t = di.mlp_inputs(M, d, ff, seed=29, dtype=dtype)
     ref = oracle.swiglu_mlp(t["X"], t["Wg"], t["Wu"], t["Wd"])
@@ -248,7 +253,7 @@ def _block_case(M, d, ff, dtype, seed):
 
 @pytest.mark.parametrize("dtype", ["bf16", "fp16"])
 @pytest.mark.parametrize("shape", [(1, 1024, 2816), (5, 512, 1000), (16, 1024, 4104), (17, 1024, 2816), (33, 2048, 4104),
-                                   (64, 1024, 8200), (70, 1024, 2816), (130, 512, 1536), (256, 1024, 2816)],
+                                   (64, 1024, 8200), (70, 1024, 2816), (130, 512, 1536), (256, 1024, 2816), (9, 768, 1000), (20, 384, 520)],
                          ids=lambda s: "M%d_d%d_ff%d" % s)
 def test_mlp_block_with_norm_and_residual(shape, dtype):
     """H + MLP(RMSNorm(H)) in the two launches of the plain block, against the oracle's
@@ -267,7 +272,7 @@ def test_mlp_block_with_norm_and_residual(shape, dtype):
     # own ahead of it); anything else is refused
     cfgs = [c for c in every if c.kmajor in (1, 2)]
     assert {c.reduce for c in cfgs} == {dfk.DFK_REDUCE_TICKET, dfk.DFK_REDUCE_ATOMIC}
-    assert any(c.kmajor == 2 for c in cfgs) == (M > 64)
+    assert any(c.kmajor == 2 for c in cfgs) == (M > 64 or d < 512)
     for c in [c for c in every if c not in cfgs][:3]:
         with pytest.raises(dfk.DfkError) as ei:
             dfk.dfk_mlp_block(g["X"], g["w"], eps, g["Wg"], g["Wu"], g["Wd"], torch.empty_like(g["X"]), c, ws)
