@@ -149,8 +149,11 @@ std::vector<dfk_config_t> candidates(int M, int d_model, int d_ff, dfk_dtype_t d
                             push(make_cfg(DFK_VARIANT_TWO_KERNEL, DFK_PATH_MFMA, clamp_splits(256, d_ff), waves, depth,
                                           clamp_splits(std::max(1, grid / k2c), d_ff), k2c, DFK_BF16, reduce, 1));
             }
-        // two-kernel, activations through the tile rings: up to 64 tokens per launch
-        for (int splits : {256, 512})
+        // two-kernel, activations through the tile rings: up to 64 tokens per launch.  A slice of the
+        // gate/up kernels of this pair and of the next holds at most 64 rows, so a d_ff beyond
+        // 512 * 64 needs more slices: the next multiple of 256 that is enough.
+        const int more_splits = d_ff > 512 * 64 ? ((d_ff + 63) / 64 + 255) / 256 * 256 : 512;
+        for (int splits : {256, 512, more_splits})
             for (int cbw : {1, 2}) {
                 if (nblk < cbw || nblk % cbw) continue;
                 const int k2c = nblk / cbw;
@@ -167,7 +170,7 @@ std::vector<dfk_config_t> candidates(int M, int d_model, int d_ff, dfk_dtype_t d
         for (const auto& o : out) have_km = have_km || o.kmajor == 1;
         if ((M > 64 || !have_km) && nblk >= 1) {
             const int k2c = nblk;
-            for (int splits : {256, 512})
+            for (int splits : {256, 512, more_splits})
                 for (int grid : {256, 512})
                     for (int reduce : {DFK_REDUCE_TICKET, DFK_REDUCE_ATOMIC})
                         for (int depth : {3, 4})

@@ -161,13 +161,15 @@ def test_large_token_counts(M):
 
 @pytest.mark.parametrize("shape", [(1, 1024, 2816), (16, 1024, 4104), (17, 1024, 2816), (33, 2048, 4104),
                                    (48, 1024, 2816), (64, 1024, 8200), (100, 1024, 2816),
-                                   (3, 768, 1000), (40, 1280, 2056), (64, 2304, 1536), (16, 896, 1000), (33, 640, 520)],
+                                   (3, 768, 1000), (40, 1280, 2056), (64, 2304, 1536), (16, 896, 1000), (33, 640, 520),
+                                   (5, 512, 40968)],
                          ids=lambda s: "M%d_d%d_ff%d" % s)
 def test_kernels_for_up_to_64_tokens_per_launch(shape):
     """Every candidate of the pair of kernels whose activations travel through the tile
     rings (config field kmajor): one to four token tiles, ragged d_ff, both reductions,
     and a token count that needs two launches; the last five shapes have a d_model whose 128-k chunks do not
-    divide evenly among the wavefronts (6, 10, 18, 7 and 5 chunks for 4 or 8 wavefronts)."""
+    divide evenly among the wavefronts (6, 10, 18, 7 and 5 chunks for 4 or 8 wavefronts); the last one a d_ff
+    beyond 512 slices of 64 rows, which runs with more slices."""
     M, d, ff = shape
     t = di.mlp_inputs(M, d, ff, seed=11)
     ref = oracle.swiglu_mlp(t["X"], t["Wg"], t["Wu"], t["Wd"])
@@ -187,7 +189,7 @@ def test_kernels_for_up_to_64_tokens_per_launch(shape):
 @pytest.mark.parametrize("dtype", ["bf16", "fp16"])
 @pytest.mark.parametrize("shape", [(65, 1024, 2816), (100, 512, 1000), (128, 1024, 4104), (129, 2048, 4104),
                                    (200, 512, 1536), (256, 1024, 4104), (130, 128, 264), (256, 256, 520), (256, 512, 8200),
-                                   (3, 384, 1000), (40, 256, 2056), (64, 384, 1536)],
+                                   (3, 384, 1000), (40, 256, 2056), (64, 384, 1536), (70, 512, 33000)],
                          ids=lambda s: "M%d_d%d_ff%d" % s)
 def test_kernels_for_up_to_256_tokens_per_launch(shape, dtype):
     """Every candidate of the pair of kernels whose workgroups share the weight tiles (config
@@ -196,7 +198,8 @@ def test_kernels_for_up_to_256_tokens_per_launch(shape, dtype):
     two shapes before the last have fewer pipeline steps than buffers (one or two k chunks, 8-row d_ff splits);
     in (256, 512, 8200) A_2 is larger than one L2, where the down kernel places the workgroups of a split on one
     XCD; the last three are token counts of 64 and below at a d_model the 64-token pair cannot take (fewer
-    128-k chunks than wavefronts), where this pair is offered instead."""
+    128-k chunks than wavefronts), where this pair is offered instead; the last one a d_ff beyond 512 slices of
+    64 rows."""
     M, d, ff = shape
     t = di.mlp_inputs(M, d, ff, seed=29, dtype=dtype)
     ref = oracle.swiglu_mlp(t["X"], t["Wg"], t["Wu"], t["Wd"])
