@@ -631,8 +631,9 @@ bool mfma_big_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, 
     if (c.k2_col_blocks != d_model / 128) return false;                        // one 128-column block per workgroup
     if ((long long)c.k2_splits * c.k2_col_blocks > 65535 || c.k2_col_blocks > kTicketLevel2) return false;
     const int tokens = std::min(M, kBigTokensPerLaunch);
-    if ((size_t)tokens * d_model * 4 > kYaccBytes) return false;               // fp32 accumulator of one launch
-    if (c.reduce == DFK_REDUCE_TICKET && !partials_fit(c.k2_splits, tokens, M, d_model)) return false;
+    if (c.reduce == DFK_REDUCE_ATOMIC && (size_t)tokens * d_model * 4 > kYaccBytes) return false;   // fp32 accumulator of one launch
+    // (this pair's counter mode keeps one partial block per split and no group sums)
+    if (c.reduce == DFK_REDUCE_TICKET && (size_t)c.k2_splits * tokens * d_model * 4 > partial_bytes(M, d_model)) return false;
     BigGeom geo{};
     return big_lds_gateup(c, big_token_tiles(tokens), d_ff, &geo) <= (size_t)kLdsLimit && big_lds_down(c, &geo) <= (size_t)kLdsLimit;
 }

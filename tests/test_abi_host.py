@@ -176,10 +176,16 @@ def test_kernel_families_by_token_count():
         c = copy.copy(big)
         setattr(c, field, bad)
         assert not dfk.dfk_config_valid(c, 256, D, FF, dfk.DFK_BF16), (field, bad)
-    # the fp32 accumulator of one launch holds 8 MiB: 256 tokens x d_model 16384 do not fit
+    # the fp32 accumulator of one launch holds 8 MiB: 256 tokens x d_model 16384 do not fit it, which
+    # rules out the atomic mode there; the counter mode keeps its partial blocks elsewhere and runs
     wide = copy.copy(big)
     wide.k2_col_blocks = 16384 // 128
     wide.k2_splits = 2
+    wide.reduce = dfk.DFK_REDUCE_ATOMIC
+    assert not dfk.dfk_config_valid(wide, 256, 16384, FF, dfk.DFK_BF16)
+    wide.reduce = dfk.DFK_REDUCE_TICKET
+    assert dfk.dfk_config_valid(wide, 256, 16384, FF, dfk.DFK_BF16)
+    wide.k2_splits = 16        # 16 blocks of 256 x 16384 fp32 exceed the partial-sum area (128 MiB)
     assert not dfk.dfk_config_valid(wide, 256, 16384, FF, dfk.DFK_BF16)
     assert dfk.dfk_config_valid(wide, 128, 16384, FF, dfk.DFK_BF16)
 

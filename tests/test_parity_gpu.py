@@ -418,6 +418,7 @@ def test_degenerate_inputs():
 
 
 @pytest.mark.parametrize("shape,dtype", [((3, 32768, 264), "bf16"), ((64, 32768, 264), "bf16"), ((256, 32768, 72), "bf16"),
+                                         ((130, 16384, 264), "bf16"),
                                          ((16, 16384, 1024), "fp16"), ((2, 8, 262144), "bf16"), ((2, 8, 262144), "fp32"),
                                          ((256, 8, 8), "fp32"), ((3, 32768, 264), "fp32")],
                          ids=lambda v: v if isinstance(v, str) else "M%d_d%d_ff%d" % v)
