@@ -192,7 +192,12 @@ def shapes(args, torch, di, dfk, dev):
     out = {}
     for name, d, ff, Ms in (("qwen2.5-32b-shaped", 5120, 27648, (1, 8, 32, 64)),
                             ("llama3-70b-shaped", 8192, 28672, (1, 16, 64, 128)),
-                            ("llama3-70b tp4 shard", 8192, 7168, (1, 16, 64))):
+                            ("llama3-70b tp4 shard", 8192, 7168, (1, 16, 64)),
+                            # widths whose 128-k chunks do not divide evenly among the wavefronts
+                            ("2304x9216 (gemma-2b-sized)", 2304, 9216, (1, 16, 64)),
+                            ("3584x18944 (qwen2.5-7b-sized)", 3584, 18944, (1, 16, 64)),
+                            # d_ff beyond 512 slices of 64 rows; 5.2 GB of weights per set
+                            ("16384x53248 (405b-class)", 16384, 53248, (1, 16, 64, 128))):
         sets = [di.mlp_inputs_torch(1, d, ff, seed=2000, layer=l, device=dev) for l in range(3)]
         ws = dfk.new_workspace(max(Ms), d, ff, dev)
         scratch = torch.empty(dfk.dfk_tune_scratch_bytes(max(Ms), d, ff, dfk.DFK_BF16, 3), dtype=torch.uint8, device=dev)
@@ -204,7 +209,7 @@ def shapes(args, torch, di, dfk, dev):
             X = di.mlp_inputs_torch(M, d, ff, seed=0, layer=0, device=dev)["X"]
             Y = torch.empty_like(X)
             n = max(20, args.steps // 5)
-            for it in range(-3, n):
+            for it in range(-10, n):
                 if it == 0:
                     torch.cuda.synchronize()
                     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
