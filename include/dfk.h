@@ -255,6 +255,12 @@ size_t dfk_tune_scratch_bytes(int M_max, int d_model, int d_ff, dfk_dtype_t dtyp
 dfk_status_t dfk_tune(const int* M_list, int nM, int d_model, int d_ff, dfk_dtype_t dtype,
                       void* scratch, size_t scratch_bytes, int sets, int iters, void* stream);
 
+/* dfk_tune leaves out a candidate whose timing fails (a launch error, say) and goes on with the
+ * others; it fails only where every candidate of a token count failed, with that status.  This
+ * returns how many candidates the last dfk_tune call on the calling thread left out, and the status
+ * of the last one in *last_status_out (may be NULL; DFK_OK if none).  Host-only. */
+int dfk_tune_skipped(dfk_status_t* last_status_out);
+
 /* Time one configuration the same way; writes mean microseconds per call. */
 dfk_status_t dfk_time_config(const dfk_config_t* cfg, int M, int d_model, int d_ff,
                              dfk_dtype_t dtype, void* scratch, size_t scratch_bytes,

@@ -71,6 +71,7 @@ SIGNATURES = [
     ("dfk_config_valid", _ci, [_cfgp] + [_ci] * 4),
     ("dfk_tune_scratch_bytes", _sz, [_ci] * 5),
     ("dfk_tune", _ci, [ctypes.POINTER(_ci), _ci, _ci, _ci, _ci, _vp, _sz, _ci, _ci, _vp]),
+    ("dfk_tune_skipped", _ci, [ctypes.POINTER(_ci)]),
     ("dfk_time_config", _ci, [_cfgp] + [_ci] * 4 + [_vp, _sz, _ci, _ci, _vp, ctypes.POINTER(ctypes.c_double)]),
     ("dfk_time_kernels", _ci, [_cfgp] + [_ci] * 4 + [_vp, _sz, _ci, _ci, _vp, ctypes.POINTER(ctypes.c_double)]),
     ("dfk_get_choice", _ci, [_ci] * 4 + [_cfgp, ctypes.POINTER(_ci)]),
@@ -255,6 +256,13 @@ def dfk_tune(M_list: Sequence[int], d_model, d_ff, dtype, scratch, sets=4, iters
     _check(lib().dfk_tune(arr, len(M_list), d_model, d_ff, dtype, _ptr(scratch),
                           scratch.numel() * scratch.element_size(), sets, iters, _stream(stream)),
            "dfk_tune")
+
+
+def dfk_tune_skipped():
+    """(count, status of the last one) of the candidates the last dfk_tune on this thread left out."""
+    st = ctypes.c_int(0)
+    n = int(lib().dfk_tune_skipped(ctypes.byref(st)))
+    return n, int(st.value)
 
 
 def dfk_time_config(cfg, M, d_model, d_ff, dtype, scratch, sets=4, iters=20, stream=None) -> float:

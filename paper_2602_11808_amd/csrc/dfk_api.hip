@@ -16,6 +16,8 @@ thread_local int g_stage_mask = 3;
 namespace {
 
 thread_local int g_last_hip_error = 0;
+thread_local int g_tune_skipped = 0;                  // candidates the last dfk_tune on this thread left out
+thread_local dfk_status_t g_tune_skip_status = DFK_OK;  // status of the last one
 
 dfk_status_t hip_fail(hipError_t e) {
     g_last_hip_error = (int)e;
@@ -29,6 +31,12 @@ struct Registered {
 Registered g_ws;
 Registered g_trace;
 std::mutex g_mu;
+
+// A consistent copy of a registered buffer: the setters write under the same lock.
+Registered snapshot(const Registered& r) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    return r;
+}
 
 // ---------------------------------------------------------------- validation
 size_t elt_bytes(dfk_dtype_t d) { return d == DFK_FP32 ? 4 : 2; }
@@ -258,10 +266,9 @@ bool choose(int M, int d_model, int d_ff, dfk_dtype_t dtype, int want_variant, d
 // ---------------------------------------------------------------- dispatch
 // norm_w / eps / resid: the pre-norm residual form (kernel pair for up to 64 tokens only,
 // checked by the caller); NULL / 0 / NULL for the plain block.
-dfk_status_t run(const void* X, const void* Wg, const void* Wu, const void* Wd, void* Y, int M,
-                 int d_model, int d_ff, dfk_dtype_t dtype, const dfk_config_t& c, void* ws,
-                 hipStream_t st, const void* norm_w = nullptr, float eps = 0.f, const void* resid = nullptr) {
-    const WsLayout l = ws_layout(M, d_model, d_ff);
+dfk_status_t run_in(const WsLayout& l, const void* X, const void* Wg, const void* Wu, const void* Wd, void* Y, int M,
+                    int d_model, int d_ff, dfk_dtype_t dtype, const dfk_config_t& c, void* ws,
+                    hipStream_t st, const void* norm_w = nullptr, float eps = 0.f, const void* resid = nullptr) {
     MlpArgs a;
     std::memset(&a, 0, sizeof a);
     a.X = X; a.Wg = Wg; a.Wu = Wu; a.Wd = Wd; a.Y = Y;
@@ -291,8 +298,9 @@ dfk_status_t run(const void* X, const void* Wg, const void* Wu, const void* Wd, 
     a.trace = nullptr;
     {
         const size_t grid = (size_t)std::max(c.splits, c.k2_splits * std::max(1, c.k2_col_blocks));
-        if (g_trace.ptr && g_trace.bytes >= grid * 8 * sizeof(unsigned long long))
-            a.trace = (unsigned long long*)g_trace.ptr;
+        const Registered tr = snapshot(g_trace);
+        if (tr.ptr && tr.bytes >= grid * 8 * sizeof(unsigned long long))
+            a.trace = (unsigned long long*)tr.ptr;
     }
     // Token chunking on the host: a launch handles at most `per` tokens; further
     // chunks are further launches on the same stream (they re-stream the weights).
@@ -304,6 +312,12 @@ dfk_status_t run(const void* X, const void* Wg, const void* Wu, const void* Wd, 
         if (e != hipSuccess) return hip_fail(e);
     }
     return DFK_OK;
+}
+
+dfk_status_t run(const void* X, const void* Wg, const void* Wu, const void* Wd, void* Y, int M,
+                 int d_model, int d_ff, dfk_dtype_t dtype, const dfk_config_t& c, void* ws,
+                 hipStream_t st, const void* norm_w = nullptr, float eps = 0.f, const void* resid = nullptr) {
+    return run_in(ws_layout(M, d_model, d_ff), X, Wg, Wu, Wd, Y, M, d_model, d_ff, dtype, c, ws, st, norm_w, eps, resid);
 }
 
 dfk_status_t call(const void* X, const void* Wg, const void* Wu, const void* Wd, void* Y, int M,
@@ -422,20 +436,20 @@ extern "C" {
 
 dfk_status_t dfk_swiglu_mlp(const void* X, const void* Wg, const void* Wu, const void* Wd, void* Y,
                             int M, int d_model, int d_ff, void* stream) {
-    return call(X, Wg, Wu, Wd, Y, M, d_model, d_ff, DFK_BF16, nullptr, DFK_VARIANT_AUTO, g_ws.ptr,
-                g_ws.bytes, stream);
+    const Registered ws = snapshot(g_ws);
+    return call(X, Wg, Wu, Wd, Y, M, d_model, d_ff, DFK_BF16, nullptr, DFK_VARIANT_AUTO, ws.ptr, ws.bytes, stream);
 }
 
 dfk_status_t dfk_swiglu_mlp_fused(const void* X, const void* Wg, const void* Wu, const void* Wd,
                                   void* Y, int M, int d_model, int d_ff, void* stream) {
-    return call(X, Wg, Wu, Wd, Y, M, d_model, d_ff, DFK_BF16, nullptr, DFK_VARIANT_FUSED, g_ws.ptr,
-                g_ws.bytes, stream);
+    const Registered ws = snapshot(g_ws);
+    return call(X, Wg, Wu, Wd, Y, M, d_model, d_ff, DFK_BF16, nullptr, DFK_VARIANT_FUSED, ws.ptr, ws.bytes, stream);
 }
 
 dfk_status_t dfk_swiglu_mlp_unfused(const void* X, const void* Wg, const void* Wu, const void* Wd,
                                     void* Y, int M, int d_model, int d_ff, void* stream) {
-    return call(X, Wg, Wu, Wd, Y, M, d_model, d_ff, DFK_BF16, nullptr, DFK_VARIANT_TWO_KERNEL,
-                g_ws.ptr, g_ws.bytes, stream);
+    const Registered ws = snapshot(g_ws);
+    return call(X, Wg, Wu, Wd, Y, M, d_model, d_ff, DFK_BF16, nullptr, DFK_VARIANT_TWO_KERNEL, ws.ptr, ws.bytes, stream);
 }
 
 dfk_status_t dfk_swiglu_mlp_ex(const void* X, const void* Wg, const void* Wu, const void* Wd, void* Y,
@@ -583,25 +597,37 @@ dfk_status_t dfk_tune(const int* M_list, int nM, int d_model, int d_ff, dfk_dtyp
         if (scratch_bytes < scratch_layout(M_list[i], d_model, d_ff, dtype, sets).total)
             return DFK_ERR_WORKSPACE;
     }
+    g_tune_skipped = 0;
+    g_tune_skip_status = DFK_OK;
     for (int i = 0; i < nM; ++i) {
         const int M = M_list[i];
         auto cands = candidates(M, d_model, d_ff, dtype);
         if (cands.empty()) return DFK_ERR_UNSUPPORTED_SHAPE;
         Entry best;
         best.usec = -1.0;
-        bool fill = true;  // scratch layout depends on M: refill once per M
+        bool fill = true;  // scratch layout depends on M: refill once per M (until a candidate has run)
         for (const auto& c : cands) {
             double us = 0.0;
             dfk_status_t s = time_config(c, M, d_model, d_ff, dtype, scratch, sets, iters,
                                          (hipStream_t)stream, fill, &us);
+            if (s != DFK_OK) {   // a candidate that cannot be timed is left out, not the whole tune
+                ++g_tune_skipped;
+                g_tune_skip_status = s;
+                continue;
+            }
             fill = false;
-            if (s != DFK_OK) return s;
             if (best.usec < 0.0 || us < best.usec) { best.cfg = c; best.usec = us; }
         }
+        if (best.usec < 0.0) return g_tune_skip_status;   // every candidate of this M failed
         std::lock_guard<std::mutex> lk(g_mu);
         g_table[Key(M, d_model, d_ff, (int)dtype)] = best;
     }
     return DFK_OK;
+}
+
+int dfk_tune_skipped(dfk_status_t* last_status_out) {
+    if (last_status_out) *last_status_out = g_tune_skip_status;
+    return g_tune_skipped;
 }
 
 dfk_status_t dfk_get_choice(int M, int d_model, int d_ff, dfk_dtype_t dtype, dfk_config_t* out,

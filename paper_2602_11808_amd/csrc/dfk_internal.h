@@ -25,16 +25,16 @@ namespace dfk {
 constexpr size_t kWsHeaderBytes = 4096;
 constexpr int kMaxTickets = 1024;
 constexpr int kTicketLevel2 = 512;          // counters [0,512): level 1 / column blocks, [512,1024): level 2
-constexpr int kMaxTokensPerLaunch = 64;     // a launch handles at most this many tokens
+constexpr int kYaccTokens = 64;             // rows of the fp32 accumulator at the widest d_model (its size is fixed, see above)
 constexpr int kMaxDModel = 32768;
-constexpr size_t kYaccBytes = (size_t)kMaxTokensPerLaunch * kMaxDModel * 4;
+constexpr size_t kYaccBytes = (size_t)kYaccTokens * kMaxDModel * 4;
 constexpr size_t kPartialCapBytes = (size_t)128 << 20;
 constexpr int kGroupSize = 16;              // workgroup partials summed per first-level group
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 inline size_t partial_bytes(int M, int d_model) {
-    const size_t want = (size_t)1024 * (M < kMaxTokensPerLaunch ? M : kMaxTokensPerLaunch) * d_model * 4;
+    const size_t want = (size_t)1024 * (M < kYaccTokens ? M : kYaccTokens) * d_model * 4;
     return want < kPartialCapBytes ? want : kPartialCapBytes;
 }
 

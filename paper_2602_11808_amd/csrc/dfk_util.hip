@@ -59,8 +59,8 @@ __global__ __launch_bounds__(kReadThreads) void k_stream_read(const u32x4* __res
 
 // out[m,:] = in[m,:] / rms(in[m,:]) in bf16 (fp32 arithmetic), one workgroup per token.
 // Keeps chained random layers from shrinking the activations to zero in benchmarks.
-__global__ __launch_bounds__(256) void k_rms_normalize(const uint16_t* __restrict__ in, uint16_t* __restrict__ out,
-                                                       int d_model) {
+// in and out may be the same buffer (no restrict): each element is read twice, then written, by one thread.
+__global__ __launch_bounds__(256) void k_rms_normalize(const uint16_t* in, uint16_t* out, int d_model) {
     __shared__ float part[4];
     const uint16_t* x = in + (size_t)blockIdx.x * d_model;
     uint16_t* y = out + (size_t)blockIdx.x * d_model;

@@ -16,7 +16,9 @@
 namespace dfk {
 namespace {
 
-constexpr int kMaxRowsLds = 2048;  // MT * slice rows held in LDS as fp32 must stay <= 64 KB
+// MT * slice rows are held in LDS as fp32: dynamic LDS, which the launchers leave at the default 64 KiB
+// allowance; the kernels add a static word (the reducer's flag), so the bound stays a little below it.
+constexpr int kMaxLdsFloats = (64 * 1024 - 256) / 4;
 
 template <typename E, int MT>
 __device__ __forceinline__ void stage1_valu(const MlpArgs& a, int j0, int rows, int m0, int mt,
@@ -207,7 +209,7 @@ bool valu_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_
     if (c.splits < 1 || c.splits > ng) return false;
     const int mt = pick_mt(M);
     const int tokens = M < 8 ? M : 8;
-    if ((long long)mt * max_slice_rows(d_ff, c.splits) > kMaxRowsLds * 8) return false;
+    if ((long long)mt * max_slice_rows(d_ff, c.splits) > kMaxLdsFloats) return false;
     if (c.variant == DFK_VARIANT_FUSED) {
         if ((c.splits + kGroupSize - 1) / kGroupSize > kTicketLevel2) return false;
         if (!partials_fit(c.splits, tokens, M, d_model)) return false;
@@ -218,7 +220,7 @@ bool valu_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_
         if (c.k2_col_blocks < 1 || c.k2_col_blocks > nchunk || c.k2_col_blocks > kTicketLevel2) return false;
         if (!partials_fit(c.k2_splits, tokens, M, d_model)) return false;
         if ((long long)c.k2_splits * c.k2_col_blocks > 65535) return false;
-        if ((long long)mt * max_slice_rows(d_ff, c.k2_splits) > kMaxRowsLds * 8) return false;
+        if ((long long)mt * max_slice_rows(d_ff, c.k2_splits) > kMaxLdsFloats) return false;
         // A_2 between the kernels: fp32, or bf16 with bf16 inputs
         if (c.a2_dtype != DFK_FP32 && !(c.a2_dtype == DFK_BF16 && dtype == DFK_BF16)) return false;
     }

@@ -399,3 +399,20 @@ def test_status_strings():
     for s in range(0, -9, -1):
         assert dfk.dfk_status_string(s) not in ("", "unknown status")
     assert dfk.dfk_status_string(-99) == "unknown status"
+
+
+def test_valu_configuration_at_the_lds_boundary_is_refused_on_the_host():
+    """The VALU kernels keep MT x slice rows of fp32 in dynamic LDS under the default 64 KiB allowance,
+    next to a static word: a configuration that needs the full 64 KiB must fail the host check, not the launch."""
+    c = dfk.dfk_get_candidate(8, 512, 16384, dfk.DFK_BF16, 0)
+    c.variant, c.path, c.kmajor, c.k2_rows_by_wave, c.reduce = dfk.DFK_VARIANT_FUSED, dfk.DFK_PATH_VALU, 0, 0, dfk.DFK_REDUCE_TICKET
+    c.waves, c.depth, c.k2_splits, c.k2_col_blocks = 8, 0, 0, 0
+    c.splits = 8                       # 8 tokens x 2048 rows = 16384 floats = 64 KiB exactly
+    assert not dfk.dfk_config_valid(c, 8, 512, 16384, dfk.DFK_BF16)
+    c.splits = 16                      # 8 x 1024 floats = 32 KiB
+    assert dfk.dfk_config_valid(c, 8, 512, 16384, dfk.DFK_BF16)
+
+
+def test_tune_skip_report_starts_empty():
+    n, status = dfk.dfk_tune_skipped()
+    assert n == 0 and status == dfk.DFK_OK

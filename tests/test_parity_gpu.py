@@ -128,7 +128,7 @@ def test_full_size_entry_points_match_oracle(name, d, ff, Ms):
             ref = oracle.swiglu_mlp(host["X"][rows], host["Wg"], host["Wu"], host["Wd"])
             assert 0.05 < np.abs(ref).max() < 50.0
             fns = (dfk.dfk_swiglu_mlp, dfk.dfk_swiglu_mlp_fused, dfk.dfk_swiglu_mlp_unfused)
-            for fn in (fns if M <= 16 else fns[:1] + fns[2:]):   # the fused kernel is a small-M form
+            for fn in fns:   # beyond its tokens per launch the fused form runs as several launches
                 print("case", name, "M", M, fn.__name__, flush=True)
                 Y = torch.full_like(X, float("nan"))
                 fn(X, g["Wg"], g["Wu"], g["Wd"], Y)
