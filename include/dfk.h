@@ -168,6 +168,25 @@ dfk_status_t dfk_swiglu_mlp_ex(const void* X, const void* W_gate, const void* W_
                                void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * dfk_swiglu_mlp_ex for callers that cannot allocate device memory and therefore have no workspace
+ * to pass: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * The same kernels run with their scratch (arrival counters, fp32 accumulator, partial sums, A_2)
+ * in an array that is part of the library's code object: 48 MiB per device, held from the moment
+ * the library is loaded on that device until the process ends.  No call allocates or frees anything.
+ * Arguments as dfk_swiglu_mlp_ex without the workspace; cfg == NULL takes the scheduler's choice, or,
+ * if its partial sums do not fit the array, the first candidate that fits.
+ * Limits: M * d_ff * 4 (A_2) at most 16 MiB, and the partial-sum blocks of the configuration within
+ * what is left (about 21 MiB; the atomic reduction needs none).  Beyond them: DFK_ERR_WORKSPACE,
+ * before any launch.  The first call on a device resolves the array's address and enqueues a fill
+ * kernel that zeroes its counters; make that call outside a graph capture.  All calls on one device
+ * share the array: calls that overlap in time on one device race (one stream, or ordered streams).
+ */
+dfk_status_t dfk_swiglu_mlp_static(const void* X, const void* W_gate, const void* W_up,
+                                   const void* W_down, void* Y,
+                                   int M, int d_model, int d_ff, dfk_dtype_t dtype,
+                                   const dfk_config_t* cfg, void* stream);
+
+/*
  * The block together with its two neighbours in a pre-norm decoder layer.  This goes one
  * step beyond the paper's operator, which starts at X and ends at Y (Method); in the
  * Llama-style models of the Experiments section an RMS normalisation produces X and a

@@ -61,6 +61,7 @@ SIGNATURES = [
     ("dfk_swiglu_mlp_fused", _ci, [_vp] * 5 + [_ci] * 3 + [_vp]),
     ("dfk_swiglu_mlp_unfused", _ci, [_vp] * 5 + [_ci] * 3 + [_vp]),
     ("dfk_swiglu_mlp_ex", _ci, [_vp] * 5 + [_ci] * 4 + [_cfgp, _vp, _sz, _vp]),
+    ("dfk_swiglu_mlp_static", _ci, [_vp] * 5 + [_ci] * 4 + [_cfgp, _vp]),
     ("dfk_mlp_block", _ci, [_vp, _vp, ctypes.c_float] + [_vp] * 4 + [_ci] * 4 + [_cfgp, _vp, _sz, _vp]),
     ("dfk_check_args", _ci, [_vp] * 5 + [_ci] * 4 + [_cfgp, _vp, _sz]),
     ("dfk_workspace_bytes", _sz, [_ci] * 3),
@@ -177,6 +178,14 @@ def dfk_swiglu_mlp_ex(X, W_gate, W_up, W_down, Y, cfg: Optional[dfk_config_t], w
     _check(lib().dfk_swiglu_mlp_ex(_ptr(X), _ptr(W_gate), _ptr(W_up), _ptr(W_down), _ptr(Y), M, d, ff,
                                    _dtype_code(X), ctypes.byref(cfg) if cfg is not None else None,
                                    _ptr(workspace), nbytes, _stream(stream)), "dfk_swiglu_mlp_ex")
+
+
+def dfk_swiglu_mlp_static(X, W_gate, W_up, W_down, Y, cfg: Optional[dfk_config_t] = None, stream=None):
+    """The block on the library's own scratch array: no workspace argument, nothing allocated."""
+    M, d, ff = _shapes(X, W_gate, W_up, W_down, Y)
+    _check(lib().dfk_swiglu_mlp_static(_ptr(X), _ptr(W_gate), _ptr(W_up), _ptr(W_down), _ptr(Y), M, d, ff,
+                                       _dtype_code(X), ctypes.byref(cfg) if cfg is not None else None,
+                                       _stream(stream)), "dfk_swiglu_mlp_static")
 
 
 def dfk_mlp_block(H, norm_weight, eps: float, W_gate, W_up, W_down, H_out, cfg: Optional[dfk_config_t], workspace,

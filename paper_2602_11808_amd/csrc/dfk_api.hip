@@ -331,6 +331,74 @@ dfk_status_t call(const void* X, const void* Wg, const void* Wu, const void* Wd,
     return run(X, Wg, Wu, Wd, Y, M, d_model, d_ff, dtype, c, ws, (hipStream_t)stream);
 }
 
+// ---------------------------------------------------------------- library-owned scratch (dfk_swiglu_mlp_static)
+// One array per device, part of the code object, held until the process ends.  In host code its
+// name is only a stand-in: the device address comes from hipGetSymbolAddress, once per device, and
+// everything below uses that pointer.
+constexpr size_t kStaticScratchBytes = (size_t)48 << 20;
+constexpr size_t kStaticA2MaxBytes = (size_t)16 << 20;
+}  // namespace
+}  // namespace dfk
+
+static __device__ __align__(256) unsigned char scratch[dfk::kStaticScratchBytes];
+
+namespace dfk {
+namespace {
+
+constexpr int kStaticDevices = 32;
+void* g_static_ptr[kStaticDevices];        // device address of `scratch` on each device, NULL until resolved
+bool g_static_cleared[kStaticDevices];     // its counter / accumulator part has been zeroed once on that device
+
+// The array's address on the current device (resolved at the first call on that device, with
+// that device current), or an error.  *first is set where the caller must enqueue the one-time
+// clearing of the part that has to be zero between calls.
+hipError_t static_scratch(void** ptr, bool* first) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kStaticDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (!g_static_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p || (uintptr_t)p % 256) return hipErrorInvalidSymbol;
+        g_static_ptr[dev] = p;
+    }
+    *ptr = g_static_ptr[dev];
+    *first = !g_static_cleared[dev];
+    g_static_cleared[dev] = true;
+    return hipSuccess;
+}
+
+// Layout inside the array: counters and accumulator first, as in a caller's workspace; then A_2
+// at its exact size; what is left is divided 8 : 1 between the partial sums and the group sums.
+bool static_layout(int M, int d_ff, WsLayout* l, size_t* p_bytes, size_t* q_bytes) {
+    const size_t a2 = align_up((size_t)M * d_ff * 4, 256);
+    if (a2 > kStaticA2MaxBytes) return false;
+    l->tickets_off = 0;
+    l->yacc_off = kWsHeaderBytes;
+    l->a2_off = l->yacc_off + kYaccBytes;
+    l->p_off = l->a2_off + a2;
+    const size_t rest = kStaticScratchBytes - l->p_off;
+    *q_bytes = rest / 9 / 256 * 256;
+    *p_bytes = (rest - *q_bytes) / 256 * 256;
+    l->q_off = l->p_off + *p_bytes;
+    l->xn_off = l->total = kStaticScratchBytes;   // no normalised input: this entry point is the plain block
+    return true;
+}
+
+// The partial-sum blocks a configuration writes in one launch fit p_bytes / q_bytes.
+bool partials_fit_static(const dfk_config_t& c, int M, int d_model, size_t p_bytes, size_t q_bytes) {
+    if (c.reduce == DFK_REDUCE_ATOMIC) return true;   // accumulator only, already checked against its fixed size
+    const int per = c.path == DFK_PATH_MFMA ? mfma_max_tokens_per_launch(c, d_model) : valu_max_tokens_per_launch();
+    const size_t tokens = (size_t)std::min(M, per);
+    const bool fused = c.variant == DFK_VARIANT_FUSED;
+    const size_t blocks = fused ? (size_t)c.splits : (size_t)c.k2_splits;
+    const size_t groups = fused ? (blocks + kGroupSize - 1) / kGroupSize : 0;
+    return blocks * tokens * d_model * 4 <= p_bytes && groups * tokens * d_model * 4 <= q_bytes;
+}
+
 // ---------------------------------------------------------------- tuning scratch
 struct Scratch {
     size_t w_bytes, x_bytes, ws_bytes, set_bytes, total;
@@ -458,6 +526,41 @@ dfk_status_t dfk_swiglu_mlp_ex(const void* X, const void* Wg, const void* Wu, co
                                void* stream) {
     return call(X, Wg, Wu, Wd, Y, M, d_model, d_ff, dtype, cfg, DFK_VARIANT_AUTO, workspace,
                 workspace_bytes, stream);
+}
+
+dfk_status_t dfk_swiglu_mlp_static(const void* X, const void* Wg, const void* Wu, const void* Wd, void* Y,
+                                   int M, int d_model, int d_ff, dfk_dtype_t dtype, const dfk_config_t* cfg,
+                                   void* stream) {
+    dfk_status_t s = check(X, Wg, Wu, Wd, Y, M, d_model, d_ff, dtype, cfg, nullptr, 0, false);
+    if (s != DFK_OK) return s;
+    WsLayout l;
+    size_t p_bytes = 0, q_bytes = 0;
+    if (!static_layout(M, d_ff, &l, &p_bytes, &q_bytes)) return DFK_ERR_WORKSPACE;   // A_2 beyond the array's share
+    dfk_config_t c;
+    if (cfg) {
+        c = *cfg;
+        if (!partials_fit_static(c, M, d_model, p_bytes, q_bytes)) return DFK_ERR_WORKSPACE;
+    } else {
+        if (!choose(M, d_model, d_ff, dtype, DFK_VARIANT_AUTO, &c, nullptr)) return DFK_ERR_UNSUPPORTED_SHAPE;
+        if (!partials_fit_static(c, M, d_model, p_bytes, q_bytes)) {   // the first candidate that fits instead
+            bool found = false;
+            for (const auto& k : candidates(M, d_model, d_ff, dtype))
+                if (partials_fit_static(k, M, d_model, p_bytes, q_bytes)) { c = k; found = true; break; }
+            if (!found) return DFK_ERR_WORKSPACE;
+        }
+    }
+    void* ws = nullptr;
+    bool first = false;
+    if (hipError_t e = static_scratch(&ws, &first); e != hipSuccess) return hip_fail(e);
+    const size_t nx = (size_t)M * d_model * elt_bytes(dtype), nw = (size_t)d_ff * d_model * elt_bytes(dtype);
+    if (overlaps(ws, kStaticScratchBytes, Y, nx) || overlaps(ws, kStaticScratchBytes, X, nx) ||
+        overlaps(ws, kStaticScratchBytes, Wg, nw) || overlaps(ws, kStaticScratchBytes, Wu, nw) ||
+        overlaps(ws, kStaticScratchBytes, Wd, nw))
+        return DFK_ERR_ALIAS;
+    if (first) {   // counters and accumulator start from zero (a fill kernel on the caller's stream); calls keep them zero
+        if (hipError_t e = launch_zero(ws, kWsHeaderBytes + kYaccBytes, (hipStream_t)stream); e != hipSuccess) return hip_fail(e);
+    }
+    return run_in(l, X, Wg, Wu, Wd, Y, M, d_model, d_ff, dtype, c, ws, (hipStream_t)stream);
 }
 
 dfk_status_t dfk_mlp_block(const void* H, const void* norm_weight, float eps, const void* Wg,

@@ -401,6 +401,27 @@ def test_status_strings():
     assert dfk.dfk_status_string(-99) == "unknown status"
 
 
+def test_static_scratch_entry_point_rejects_on_the_host():
+    """dfk_swiglu_mlp_static checks its arguments and its size limits before any HIP call."""
+    l = dfk.lib()
+    call = lambda M, d, ff, x=X, cfg=None: l.dfk_swiglu_mlp_static(x, WG, WU, WD, Y, M, d, ff, dfk.DFK_BF16, cfg, None)
+    assert call(1, D, FF, x=0) == dfk.DFK_ERR_INVALID_ARG
+    assert call(0, D, FF) == dfk.DFK_ERR_INVALID_ARG
+    assert call(1, 4100, FF) == dfk.DFK_ERR_UNSUPPORTED_SHAPE
+    assert call(1, D, FF, x=X + 8) == dfk.DFK_ERR_ALIGNMENT
+    # A_2 of M x d_ff fp32 beyond its 16 MiB share of the array
+    assert call(256, 512, 16392) == dfk.DFK_ERR_WORKSPACE
+    assert call(16, 8, 262152) == dfk.DFK_ERR_WORKSPACE
+    # an explicit configuration whose partial sums do not fit what is left (512 slices x 8 tokens x 8192 columns of fp32: 128 MiB)
+    big = None
+    for i in range(dfk.dfk_num_candidates(8, 8192, 8192, dfk.DFK_BF16)):
+        c = dfk.dfk_get_candidate(8, 8192, 8192, dfk.DFK_BF16, i)
+        if c.variant == dfk.DFK_VARIANT_FUSED and c.path == dfk.DFK_PATH_VALU and c.splits == 512:
+            big = c
+    assert big is not None
+    assert call(8, 8192, 8192, cfg=ctypes.byref(big)) == dfk.DFK_ERR_WORKSPACE
+
+
 def test_valu_configuration_at_the_lds_boundary_is_refused_on_the_host():
     """The VALU kernels keep MT x slice rows of fp32 in dynamic LDS under the default 64 KiB allowance,
     next to a static word: a configuration that needs the full 64 KiB must fail the host check, not the launch."""
