@@ -15,7 +15,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libdfk.so")
-SOURCES = ["dfk_api.hip", "dfk_valu.hip", "dfk_mfma.hip", "dfk_mfma_km.hip", "dfk_mfma_big.hip", "dfk_util.hip"]
+SOURCES = ["dfk_api.hip", "dfk_valu.hip", "dfk_mfma.hip", "dfk_mfma_km.hip", "dfk_mfma_fused.hip", "dfk_mfma_big.hip", "dfk_util.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

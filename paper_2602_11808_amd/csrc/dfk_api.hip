@@ -131,9 +131,15 @@ std::vector<dfk_config_t> candidates(int M, int d_model, int d_ff, dfk_dtype_t d
                     for (int reduce : {DFK_REDUCE_ATOMIC, DFK_REDUCE_TICKET})
                         push(make_cfg(DFK_VARIANT_FUSED, DFK_PATH_MFMA, clamp_splits(splits, d_ff), waves,
                                       depth, 0, 0, a2dt, reduce));
+        const int nblk = d_model / 128;
+        // the single launch on the k-major stage one of the 64-token pair (a slice of at most 64 rows per workgroup)
+        for (int splits : {256, 512, d_ff > 512 * 64 ? ((d_ff + 63) / 64 + 255) / 256 * 256 : 512})
+            for (int reduce : {DFK_REDUCE_ATOMIC, DFK_REDUCE_TICKET})
+                for (int wd : {83, 84, 46, 48})   // wavefronts, ring depth
+                    push(make_cfg(DFK_VARIANT_FUSED, DFK_PATH_MFMA, clamp_splits(splits, d_ff), wd / 10, wd % 10, 0, 0, (int)dtype,
+                                  reduce, 0, 1));
         // two-kernel: the down projection is tiled (d_ff splits) x (column blocks of
         // waves*128 or 2*waves*128 columns), about one or two workgroups per CU
-        const int nblk = d_model / 128;
         for (int splits : {256, 512})
             for (int waves : {4, 8})
                 for (int per_wave : {1, 2}) {
@@ -202,10 +208,10 @@ std::vector<dfk_config_t> candidates(int M, int d_model, int d_ff, dfk_dtype_t d
     return out;
 }
 
-// Untuned default.  Measured on MI355X, the two-kernel variant wins at every token count
-// (the fused kernel pays a 256-way sum of full-width partial blocks): beyond 64 tokens the
-// kernel pair that takes up to 256 per launch, else the pair for up to 64 tokens, then the
-// rows-split down kernel, then the rest.
+// Untuned default, from measurements on MI355X.  One token: the single launch on the k-major stage one with
+// the atomic reduction (it saves the boundary between two kernels, and its 256 full-width partial sums are
+// still cheap).  From two tokens on the two-kernel variant: beyond 64 tokens the kernel pair that takes up to
+// 256 per launch, else the pair for up to 64 tokens, then the rows-split down kernel, then the rest.
 bool heuristic(int M, int d_model, int d_ff, dfk_dtype_t dtype, int want_variant, dfk_config_t* out) {
     auto cands = candidates(M, d_model, d_ff, dtype);
     auto rank = [&](const dfk_config_t& c) {
@@ -213,7 +219,9 @@ bool heuristic(int M, int d_model, int d_ff, dfk_dtype_t dtype, int want_variant
             if (c.kmajor == 2) return M > 64 ? -1 : 1;     // one launch for up to 256 tokens beats several of 64
             return c.kmajor ? 0 : c.k2_rows_by_wave ? 1 : 2;
         }
-        return 3;
+        if (c.path == DFK_PATH_MFMA && c.kmajor == 1)      // of the single-launch forms, the one built on the 64-token pair first
+            return c.reduce == DFK_REDUCE_ATOMIC && c.waves == 8 ? (M == 1 ? -2 : 3) : 4;
+        return 5;
     };
     const dfk_config_t* best = nullptr;
     for (const auto& c : cands) {

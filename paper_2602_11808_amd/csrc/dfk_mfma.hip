@@ -775,11 +775,13 @@ hipError_t launch_nt(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
 
 int mfma_max_tokens_per_launch(const dfk_config_t& c, int d_model) {
     if (c.kmajor == 2) return mfma_big_tokens_per_launch();
+    if (c.kmajor == 1 && c.variant == DFK_VARIANT_FUSED) return mfma_fused_km_tokens_per_launch();
     return c.kmajor ? mfma_km_tokens_per_launch() : 16 * max_token_tiles(c, d_model);
 }
 
 bool mfma_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype) {
     if (c.kmajor == 2) return mfma_big_config_valid(c, M, d_model, d_ff, dtype);
+    if (c.kmajor == 1 && c.variant == DFK_VARIANT_FUSED) return mfma_fused_km_config_valid(c, M, d_model, d_ff, dtype);
     if (c.kmajor) return mfma_km_config_valid(c, M, d_model, d_ff, dtype);
     if (c.path != DFK_PATH_MFMA || dtype != DFK_BF16) return false;
     if (c.variant != DFK_VARIANT_FUSED && c.variant != DFK_VARIANT_TWO_KERNEL) return false;
@@ -819,6 +821,7 @@ bool mfma_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_
 
 hipError_t launch_mfma(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
     if (c.kmajor == 2) return launch_mfma_big(a, c, st);
+    if (c.kmajor == 1 && c.variant == DFK_VARIANT_FUSED) return launch_mfma_fused_km(a, c, st);
     if (c.kmajor) return launch_mfma_km(a, c, st);
     const int TT = token_tiles(c, a.m_count);
     switch (c.waves * 10 + TT) {

@@ -368,7 +368,7 @@ def test_mlp_block_checks_its_arguments_on_the_host():
     L = dfk.lib()
     n = dfk.dfk_num_candidates(4, D, FF, dfk.DFK_BF16)
     cands = [dfk.dfk_get_candidate(4, D, FF, dfk.DFK_BF16, i) for i in range(n)]
-    km = next(c for c in cands if c.kmajor == 1)
+    km = next(c for c in cands if c.kmajor == 1 and c.variant == dfk.DFK_VARIANT_TWO_KERNEL)
     other = next(c for c in cands if c.kmajor == 0)
     nx, nw = 4 * D * 2, FF * D * 2
     A = 1 << 30     # fake device addresses, never dereferenced: every case fails before any HIP call

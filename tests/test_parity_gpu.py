@@ -165,8 +165,8 @@ def test_large_token_counts(M):
                                    (5, 512, 40968)],
                          ids=lambda s: "M%d_d%d_ff%d" % s)
 def test_kernels_for_up_to_64_tokens_per_launch(shape):
-    """Every candidate of the pair of kernels whose activations travel through the tile
-    rings (config field kmajor): one to four token tiles, ragged d_ff, both reductions,
+    """Every candidate of the kernels whose activations travel through the tile rings (config field
+    kmajor = 1: the pair for up to 64 tokens per launch, and the single launch built on its stage one): one to four token tiles, ragged d_ff, both reductions,
     and a token count that needs two launches; the last five shapes have a d_model whose 128-k chunks do not
     divide evenly among the wavefronts (6, 10, 18, 7 and 5 chunks for 4 or 8 wavefronts); the last one a d_ff
     beyond 512 slices of 64 rows, which runs with more slices."""
@@ -273,7 +273,7 @@ def test_mlp_block_with_norm_and_residual(shape, dtype):
     every = [dfk.dfk_get_candidate(M, d, ff, _dt(dtype), i) for i in range(n)]
     # the two kernel pairs that carry this form (the 256-token pair with the normalisation as a launch of its
     # own ahead of it); anything else is refused
-    cfgs = [c for c in every if c.kmajor in (1, 2)]
+    cfgs = [c for c in every if c.kmajor in (1, 2) and c.variant == dfk.DFK_VARIANT_TWO_KERNEL]
     assert {c.reduce for c in cfgs} == {dfk.DFK_REDUCE_TICKET, dfk.DFK_REDUCE_ATOMIC}
     assert any(c.kmajor == 2 for c in cfgs) == (M > 64 or d < 512)
     for c in [c for c in every if c not in cfgs][:3]:
@@ -506,7 +506,7 @@ def test_two_host_threads_on_their_own_streams_and_workspaces():
         g = gpu_inputs(t)
         n = dfk.dfk_num_candidates(M, d, ff, dfk.DFK_BF16)
         cfg = next(c for c in (dfk.dfk_get_candidate(M, d, ff, dfk.DFK_BF16, i) for i in range(n))
-                   if c.kmajor == kmajor and c.reduce == dfk.DFK_REDUCE_TICKET)
+                   if c.kmajor == kmajor and c.reduce == dfk.DFK_REDUCE_TICKET and c.variant == dfk.DFK_VARIANT_TWO_KERNEL)
         ws = dfk.new_workspace(M, d, ff, DEV)
         alone_y, _ = run_ex(g, cfg, ws)
         alone_b = torch.empty_like(g["X"])
