@@ -1,5 +1,5 @@
 #!/usr/bin/env python3
-"""Benchmark of the fused SwiGLU MLP hot path on one MI355X.
+"""Benchmark of the SwiGLU MLP hot path on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W]
 
@@ -11,13 +11,20 @@ the next of several distinct weight sets (so weights stream from HBM, never
 from the 256 MB last-level cache).  Inputs are seeded synthetic tensors,
 resident in HBM before the timed region.  Before timing, the profile-driven
 scheduler tunes the (variant, tile) choice per M - the pre-inference step of
-the method - and its picks are reported.
+the method - and its picks (single launch or two kernels, per M) are named in
+`metric` and `config`.
 
 Prints ONE JSON line: value = mean microseconds per call over the step's
-calls; roofline = algorithmic HBM bytes per launch of the dominant kernel (the
-first launch of a call) / its duration measured with HIP events around each
-launch, against the 8 TB/s peak, with the whole-call figure beside it;
-cpu_baseline = the fp64 oracle on the host cores over steps of the same workload.
+calls.  roofline = algorithmic HBM bytes per call / the duration of the call's
+launches, against the 8 TB/s peak: `frac` is the whole call (what the target is
+stated on); the call's dominant launch (the whole block where the single launch
+is picked, else the gate/up kernel, two of the three matrices) is in
+`roofline.dominant_kernel`, timed with HIP events around back-to-back launches
+of that kernel alone.  Beside the headline: the same statistics (4 repeats x 50
+launches) for every M up to 64 and a second mean over M = 1..64, 128 and 256
+tokens, the other layer shapes of the workload list, and the 32-layer decode
+pass replayed from a HIP graph.  cpu_baseline = the fp64 oracle on the host
+cores over steps of the same workload.
 """
 import argparse
 import json
@@ -40,33 +47,57 @@ def algorithmic_bytes(M, d_model, d_ff):
 
 
 def committed_traffic():
-    """HBM bytes per launch of the gate/up kernel from the committed rocprofv3 counter summary
-    (FETCH_SIZE + WRITE_SIZE runs of this script; counters cannot be read from inside it)."""
-    path = os.path.join(ROOT, "profiles", "k_mfma_llama3_8b_hbm_traffic.md")
+    """HBM bytes per call (fetched + written, every launch of the call) from the committed rocprofv3 counter
+    summary (FETCH_SIZE + WRITE_SIZE runs of this script; counters cannot be read from inside it): the mean over
+    the headline token counts, and the dominant launch's share."""
+    path = os.path.join(ROOT, "profiles", "dfk_llama3_8b_hbm_traffic.md")
     try:
         import re
-        m = re.search(r"gateup_hbm_bytes_per_launch\s*=\s*(\d+)", open(path).read())
-        return (int(m.group(1)), "profiles/k_mfma_llama3_8b_hbm_traffic.md") if m else (None, None)
+        txt = open(path).read()
+        call = re.search(r"hbm_bytes_per_call\s*=\s*(\d+)", txt)
+        dom = re.search(r"dominant_kernel_hbm_bytes_per_launch\s*=\s*(\d+)", txt)
+        return (int(call.group(1)) if call else None, int(dom.group(1)) if dom else None,
+                "profiles/dfk_llama3_8b_hbm_traffic.md")
     except OSError:
-        return None, None
+        return None, None, None
 
 
-def decode32(args, torch, di, dfk, dev):
+VARIANT_NAME = {1: "single launch (fused)", 2: "two kernels"}
+
+
+def stats_4x50(torch, np, fn, n_sets):
+    """The paper's protocol: 4 repeats (after one untimed) of 50 launches, HIP events on the launch stream."""
+    reps = []
+    for rep in range(-1, 4):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for i in range(50):
+            fn((rep + i) % n_sets)
+        b.record()
+        torch.cuda.synchronize()
+        if rep >= 0:
+            reps.append(a.elapsed_time(b) * 1e3 / 50)
+    return {"mean_us": round(float(np.mean(reps)), 2), "std_us": round(float(np.std(reps)), 2),
+            "median_us": round(float(np.median(reps)), 2)}
+
+
+def decode32(args, torch, di, dfk, dev, compact=False):
     """The decode sweep: 32 distinct layers of the headline shape (11.3 GB of weights, far beyond
     any cache) chained in stream order with a weight-free RMS normalisation between them, the
     whole pass captured once in a HIP graph and replayed (the method's deployment mode: the
     scheduler's choice is baked into the graph, no dispatch cost per token).  A layer's time
     includes its normalisation launch (one small kernel)."""
     L = 32
-    sweep = (1, 2, 3, 4, 8, 16, 24, 32, 64, 128, 256)
+    sweep = (1, 4, 16, 64, 256) if compact else (1, 2, 3, 4, 8, 16, 24, 32, 64, 128, 256)
     layers = [di.mlp_inputs_torch(1, D_MODEL, D_FF, seed=1000, layer=l, device=dev) for l in range(L)]
     ws = dfk.new_workspace(max(sweep), D_MODEL, D_FF, dev)
     dfk.dfk_set_workspace(ws)
-    scratch = torch.empty(dfk.dfk_tune_scratch_bytes(max(sweep), D_MODEL, D_FF, dfk.DFK_BF16, 3),
-                          dtype=torch.uint8, device=dev)
-    dfk.dfk_tune(list(sweep), D_MODEL, D_FF, dfk.DFK_BF16, scratch, sets=3, iters=8)
-    torch.cuda.synchronize()
-    del scratch
+    if not compact:      # (the compact form runs on the table the headline workload has tuned)
+        scratch = torch.empty(dfk.dfk_tune_scratch_bytes(max(sweep), D_MODEL, D_FF, dfk.DFK_BF16, 3),
+                              dtype=torch.uint8, device=dev)
+        dfk.dfk_tune(list(sweep), D_MODEL, D_FF, dfk.DFK_BF16, scratch, sets=3, iters=8)
+        torch.cuda.synchronize()
+        del scratch
     rows = {}
     for M in sweep:
         X0 = di.mlp_inputs_torch(M, D_MODEL, D_FF, seed=0, layer=0, device=dev)["X"]
@@ -109,9 +140,18 @@ def decode32(args, torch, di, dfk, dev):
         c, tuned = dfk.dfk_get_choice(M, D_MODEL, D_FF, dfk.DFK_BF16)
         rows[str(M)] = {"us_per_layer_in_graph": round(us_layer, 2),
                         "tb_per_s": round(algorithmic_bytes(M, D_MODEL, D_FF) / us_layer / 1e6, 3),
-                        "replays_match_eager_layer0": ok, "pick": dict(c.as_dict(), tuned=tuned)}
-    print(json.dumps({"workload": "decode32: 32 chained llama3-8b-shaped layers, HIP graph replay", "layers": L,
-                      "weights_gb": round(L * 6 * D_MODEL * D_FF / 1e9, 2), "per_M": rows}))
+                        "replays_match_eager_layer0": ok, "variant": VARIANT_NAME[c.variant],
+                        "pick": dict(c.as_dict(), tuned=tuned)}
+        del graph
+    out = {"workload": "decode32: 32 chained llama3-8b-shaped layers, HIP graph replay; a layer's time includes "
+                       "the weight-free normalisation launch between layers", "layers": L,
+           "weights_gb": round(L * 6 * D_MODEL * D_FF / 1e9, 2), "per_M": rows}
+    dfk.dfk_set_workspace(None)
+    del layers, ws
+    torch.cuda.empty_cache()
+    if compact:
+        return out
+    print(json.dumps(out))
 
 
 def block32(args, torch, di, dfk, dev):
@@ -186,18 +226,20 @@ def block32(args, torch, di, dfk, dev):
                                   "HIP graph replay", "layers": L, "per_M": rows}))
 
 
-def shapes(args, torch, di, dfk, dev):
+def shapes(args, torch, di, dfk, dev, compact=False):
     """The other layer shapes of the workload list (parity-test configurations, timed here for the record):
     scheduler tuned per shape, one call per M on three rotating weight sets."""
     out = {}
-    for name, d, ff, Ms in (("qwen2.5-32b-shaped", 5120, 27648, (1, 8, 32, 64)),
-                            ("llama3-70b-shaped", 8192, 28672, (1, 16, 64, 128)),
-                            ("llama3-70b tp4 shard", 8192, 7168, (1, 16, 64)),
-                            # widths whose 128-k chunks do not divide evenly among the wavefronts
-                            ("2304x9216 (gemma-2b-sized)", 2304, 9216, (1, 16, 64)),
-                            ("3584x18944 (qwen2.5-7b-sized)", 3584, 18944, (1, 16, 64)),
-                            # d_ff beyond 512 slices of 64 rows; 5.2 GB of weights per set
-                            ("16384x53248 (405b-class)", 16384, 53248, (1, 16, 64, 128))):
+    table = [("qwen2.5-32b-shaped", 5120, 27648, (1, 8, 32, 64)),
+             ("llama3-70b-shaped", 8192, 28672, (1, 16, 64, 128)),
+             ("llama3-70b tp4 shard", 8192, 7168, (1, 16, 64))]
+    if not compact:
+        table += [# widths whose 128-k chunks do not divide evenly among the wavefronts
+                  ("2304x9216 (gemma-2b-sized)", 2304, 9216, (1, 16, 64)),
+                  ("3584x18944 (qwen2.5-7b-sized)", 3584, 18944, (1, 16, 64)),
+                  # d_ff beyond 512 slices of 64 rows; 5.2 GB of weights per set
+                  ("16384x53248 (405b-class)", 16384, 53248, (1, 16, 64, 128))]
+    for name, d, ff, Ms in table:
         sets = [di.mlp_inputs_torch(1, d, ff, seed=2000, layer=l, device=dev) for l in range(3)]
         ws = dfk.new_workspace(max(Ms), d, ff, dev)
         scratch = torch.empty(dfk.dfk_tune_scratch_bytes(max(Ms), d, ff, dfk.DFK_BF16, 3), dtype=torch.uint8, device=dev)
@@ -222,11 +264,15 @@ def shapes(args, torch, di, dfk, dev):
             c, tuned = dfk.dfk_get_choice(M, d, ff, dfk.DFK_BF16)
             rows[str(M)] = {"us_per_call": round(us, 2), "tb_per_s": round(algorithmic_bytes(M, d, ff) / us / 1e6, 3),
                             "frac_of_8tbs": round(algorithmic_bytes(M, d, ff) / us / 1e6 / 8.0, 4),
-                            "pick": dict(c.as_dict(), tuned=tuned)}
+                            "variant": VARIANT_NAME[c.variant], "pick": dict(c.as_dict(), tuned=tuned)}
         out[name] = {"d_model": d, "d_ff": ff, "per_M": rows}
         del sets, ws
         torch.cuda.empty_cache()
-    print(json.dumps({"workload": "shapes: other decode-shaped layers, bf16, scheduler tuned per shape", "shapes": out}))
+    res = {"workload": "shapes: other decode-shaped layers, bf16, scheduler tuned per shape, one call per M on "
+                       "three rotating weight sets", "shapes": out}
+    if compact:
+        return res
+    print(json.dumps(res))
 
 
 def main():
@@ -236,6 +282,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-tune", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="leave out the blocks beside the headline (other shapes, the 32-layer decode pass)")
     ap.add_argument("--tuning-file", default=None,
                     help="load the scheduler table from this file if it exists, else tune and save it there")
     ap.add_argument("--force", choices=["auto", "fused", "unfused"], default="auto")
@@ -264,18 +312,21 @@ def main():
         return block32(args, torch, di, dfk, dev)
     if args.workload == "shapes":
         return shapes(args, torch, di, dfk, dev)
-    Mmax = max(M_SET)
+    M_WIDE = M_SET + (32, 64)            # the metric is quoted on M = 1..64; the target on M = 1..16
+    M_ALL = M_WIDE + (128, 256)
+    Mmax = max(M_ALL)
 
     # ---- synthetic inputs, resident in HBM
     layers = [di.mlp_inputs_torch(Mmax, D_MODEL, D_FF, seed=0, layer=l, device=dev)
               for l in range(WEIGHT_SETS)]
-    X = {M: layers[0]["X"][:M].contiguous() for M in M_SET}
-    Y = {M: torch.empty_like(X[M]) for M in M_SET}
+    X = {M: layers[0]["X"][:M].contiguous() for M in M_ALL}
+    Y = {M: torch.empty_like(X[M]) for M in M_ALL}
     ws = dfk.new_workspace(Mmax, D_MODEL, D_FF, dev)
     dfk.dfk_set_workspace(ws)
 
     # ---- pre-inference scheduler step (not timed)
     tune_s = 0.0
+    skipped = 0
     if args.tuning_file and os.path.exists(args.tuning_file):
         dfk.dfk_load_tuning(args.tuning_file)
     elif not args.no_tune:
@@ -283,13 +334,16 @@ def main():
         scratch = torch.empty(dfk.dfk_tune_scratch_bytes(Mmax, D_MODEL, D_FF, dfk.DFK_BF16, 3),
                               dtype=torch.uint8, device=dev)
         dfk.dfk_tune(list(M_SET), D_MODEL, D_FF, dfk.DFK_BF16, scratch, sets=3, iters=12)
+        skipped += dfk.dfk_tune_skipped()[0]
+        dfk.dfk_tune([32, 64, 128, 256], D_MODEL, D_FF, dfk.DFK_BF16, scratch, sets=3, iters=8)
+        skipped += dfk.dfk_tune_skipped()[0]
         torch.cuda.synchronize()
         del scratch
         tune_s = time.perf_counter() - t0
         if args.tuning_file:
             dfk.dfk_save_tuning(args.tuning_file)
     picks = {}
-    for M in M_SET:
+    for M in M_ALL:
         c, tuned = dfk.dfk_get_choice(M, D_MODEL, D_FF, dfk.DFK_BF16)
         picks[str(M)] = dict(c.as_dict(), tuned=tuned)
 
@@ -323,78 +377,28 @@ def main():
     calls_per_step = len(M_SET)
     us_per_call = ms_per_step * 1e3 / calls_per_step
 
-    # ---- per-M breakdown with HIP events on the launch stream
+    # ---- per M (1..64 the same way, 128 and 256 beside them): 4 repeats x 50 launches, mean +- std and median;
+    # which variant ran; fraction of the 8 TB/s peak
     per_m = {}
-    for M in M_SET:
+    for M in M_ALL:
         for _ in range(5):
             one_call(M)
         torch.cuda.synchronize()
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        n = max(50, args.steps)
-        a.record()
-        for _ in range(n):
-            one_call(M)
-        b.record()
-        torch.cuda.synchronize()
-        us = a.elapsed_time(b) * 1e3 / n
-        per_m[str(M)] = {"us_per_call": round(us, 2),
-                         "tb_per_s": round(algorithmic_bytes(M, D_MODEL, D_FF) / us / 1e6, 3)}
+        st = stats_4x50(torch, np, lambda i, M=M: call(X[M], layers[i]["Wg"], layers[i]["Wu"], layers[i]["Wd"], Y[M]), WEIGHT_SETS)
+        b = algorithmic_bytes(M, D_MODEL, D_FF)
+        per_m[str(M)] = dict(st, tb_per_s=round(b / st["mean_us"] / 1e6, 3), frac_of_peak=round(b / st["mean_us"] / 1e3 / HBM_PEAK_GBS, 4),
+                             variant=VARIANT_NAME[picks[str(M)]["variant"]] if args.force == "auto" else args.force)
+    mean_wide = float(np.mean([per_m[str(M)]["mean_us"] for M in M_WIDE]))
+    frac_wide = float(np.mean([per_m[str(M)]["frac_of_peak"] for M in M_WIDE]))
 
-    # ---- each variant at each M: 4 repeats x 50 launches (the paper's protocol is 4 repeats), mean +- std
-    # and median of the repeats' per-call times
+    # ---- each variant forced, at the headline token counts: the fused <-> two-kernel crossover
     per_variant = {}
-    for name, fn in (("scheduler", dfk.dfk_swiglu_mlp), ("fused", dfk.dfk_swiglu_mlp_fused),
-                     ("two_kernel", dfk.dfk_swiglu_mlp_unfused)):
-        rows = {}
-        for M in M_SET:
-            reps = []
-            for rep in range(-1, 4):
-                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a.record()
-                for i in range(50):
-                    w = layers[(rep + i) % WEIGHT_SETS]
-                    fn(X[M], w["Wg"], w["Wu"], w["Wd"], Y[M])
-                b.record()
-                torch.cuda.synchronize()
-                if rep >= 0:
-                    reps.append(a.elapsed_time(b) * 1e3 / 50)
-            rows[str(M)] = {"mean_us": round(float(np.mean(reps)), 2), "std_us": round(float(np.std(reps)), 2),
-                            "median_us": round(float(np.median(reps)), 2)}
-        per_variant[name] = rows
+    for name, fn in (("fused", dfk.dfk_swiglu_mlp_fused), ("two_kernel", dfk.dfk_swiglu_mlp_unfused)):
+        per_variant[name] = {str(M): stats_4x50(torch, np, lambda i, M=M, fn=fn: fn(X[M], layers[i]["Wg"], layers[i]["Wu"], layers[i]["Wd"], Y[M]),
+                                                WEIGHT_SETS) for M in M_SET}
 
-    # ---- beyond the headline set (reported beside it, not part of `value`): larger token counts in
-    # one call each, scheduler's untuned default, same rotating weight sets
-    extended = {}
-    ws_ext = dfk.new_workspace(256, D_MODEL, D_FF, dev)
-    if not args.no_tune and not (args.tuning_file and os.path.exists(args.tuning_file)):
-        scratch = torch.empty(dfk.dfk_tune_scratch_bytes(256, D_MODEL, D_FF, dfk.DFK_BF16, 3), dtype=torch.uint8, device=dev)
-        dfk.dfk_tune([32, 64, 128, 256], D_MODEL, D_FF, dfk.DFK_BF16, scratch, sets=3, iters=8)
-        torch.cuda.synchronize()
-        del scratch
-        if args.tuning_file:
-            dfk.dfk_save_tuning(args.tuning_file)
-    for M in (32, 64, 128, 256):
-        Xe = di.mlp_inputs_torch(M, D_MODEL, D_FF, seed=0, layer=0, device=dev)["X"]
-        Ye = torch.empty_like(Xe)
-        n = max(60, args.steps // 2)
-        for it in range(-20, n):   # 20 untimed calls first: a few ms of work, so the clocks are up
-            if it == 0:
-                torch.cuda.synchronize()
-                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a.record()
-            w = layers[it % WEIGHT_SETS]
-            dfk.dfk_swiglu_mlp_ex(Xe, w["Wg"], w["Wu"], w["Wd"], Ye, None, ws_ext)
-        b.record()
-        torch.cuda.synchronize()
-        us = a.elapsed_time(b) * 1e3 / n
-        c, tuned = dfk.dfk_get_choice(M, D_MODEL, D_FF, dfk.DFK_BF16)
-        extended[str(M)] = {"us_per_call": round(us, 2), "tb_per_s": round(algorithmic_bytes(M, D_MODEL, D_FF) / us / 1e6, 3),
-                            "kernel_family": {0: "first", 1: "64-token pair", 2: "256-token pair"}[c.kmajor],
-                            "pick": dict(c.as_dict(), tuned=tuned)}
-    del ws_ext
-
-    # ---- read-stream ceiling of this machine (plain 128-bit streaming read of 1.4 GB), and one
-    # write-only kernel of known size; both also calibrate the FETCH_SIZE / WRITE_SIZE counters
+    # ---- read-stream ceiling of this machine (plain 128-bit streaming reads), and one write-only kernel of known
+    # size; both also calibrate the FETCH_SIZE / WRITE_SIZE counters
     sink = torch.zeros(2, dtype=torch.int32, device=dev)
     srcs = [l[k] for l in layers for k in ("Wg", "Wu", "Wd")]
     for s in srcs[:3]:
@@ -407,24 +411,24 @@ def main():
     b.record()
     torch.cuda.synchronize()
     read_small_gbs = sum(s.numel() * 2 for s in srcs) / (a.elapsed_time(b) * 1e-3) / 1e9
-    # the ceiling proper: launches that read as many bytes as the dominant kernel does (W_gate and W_up of a
-    # layer, copied into one buffer), rotating over the weight sets, back to back
-    both = [torch.cat([l["Wg"].reshape(-1), l["Wu"].reshape(-1)]) for l in layers]
-    for s in both:
+    # launches that read as many bytes as a whole call does (the three matrices of a layer in one buffer),
+    # rotating over the weight sets, back to back
+    whole = [torch.cat([l["Wg"].reshape(-1), l["Wu"].reshape(-1), l["Wd"].reshape(-1)]) for l in layers]
+    for s in whole:
         dfk.dfk_stream_read(s, sink)
     torch.cuda.synchronize()
     reps = 4
     a.record()
     for _ in range(reps):
-        for s in both:
+        for s in whole:
             dfk.dfk_stream_read(s, sink)
     b.record()
     torch.cuda.synchronize()
-    read_gbs = reps * sum(s.numel() * 2 for s in both) / (a.elapsed_time(b) * 1e-3) / 1e9
-    del both
+    read_gbs = reps * sum(s.numel() * 2 for s in whole) / (a.elapsed_time(b) * 1e-3) / 1e9
+    del whole
     # the gate/up kernel's own memory pattern without its work (same slices, wavefronts, pieces and order)
     pat_waves = max(set(p["waves"] for p in picks.values() if p.get("kmajor") == 1), default=8)
-    pat_splits = max(set(p["splits"] for p in picks.values() if p.get("kmajor") == 1), default=256)
+    pat_splits = 256
     for l in layers:
         dfk.dfk_read_gateup_pattern(l["Wg"], l["Wu"], pat_splits, pat_waves, sink)
     torch.cuda.synchronize()
@@ -441,45 +445,47 @@ def main():
     del fill_target
 
     # ---- per-launch durations of the scheduler's picks, HIP events on the launch stream around
-    # each launch (weights rotating over 3 synthetic sets in a scratch buffer)
-    scratch = torch.empty(dfk.dfk_tune_scratch_bytes(Mmax, D_MODEL, D_FF, dfk.DFK_BF16, 3),
+    # back-to-back launches of each kernel alone (weights rotating over 3 synthetic sets in a scratch buffer)
+    scratch = torch.empty(dfk.dfk_tune_scratch_bytes(max(M_WIDE), D_MODEL, D_FF, dfk.DFK_BF16, 3),
                           dtype=torch.uint8, device=dev)
     kernels = {}
-    for M in M_SET:
+    for M in M_WIDE:
         c, _ = dfk.dfk_get_choice(M, D_MODEL, D_FF, dfk.DFK_BF16)
         us1, us2 = dfk.dfk_time_kernels(c, M, D_MODEL, D_FF, dfk.DFK_BF16, scratch, sets=3, iters=max(30, args.steps // 4))
-        kernels[str(M)] = {"first_launch_us": round(us1, 2), "second_launch_us": round(us2, 2)}
+        kernels[str(M)] = {"first_launch_us": round(us1, 2), "second_launch_us": round(us2, 2),
+                           "variant": VARIANT_NAME[c.variant]}
     del scratch
 
-    # ---- roofline.  Dominant kernel: the first launch of a call - the whole block in the fused
-    # variant, else the gate/up kernel, which reads two of the three weight matrices.  Its
-    # algorithmic bytes per launch: W_gate + W_up (+ W_down when fused) + X (+ Y when fused).
+    # ---- roofline.  The bound is HBM.  `frac` is the whole call: algorithmic bytes of a call (three matrices
+    # once + X + Y) / the time of all its launches, from the contract's timed region.  The dominant launch of a
+    # call (the whole block where the single launch is picked, else the gate/up kernel, which reads two of the
+    # three matrices) is reported beside it from back-to-back launches of that kernel alone.
     def first_launch_bytes(M):
         fused = picks[str(M)]["variant"] == dfk.DFK_VARIANT_FUSED
         return (6 if fused else 4) * D_MODEL * D_FF + (4 if fused else 2) * M * D_MODEL
     k_bytes = sum(first_launch_bytes(M) for M in M_SET) / calls_per_step
     k_us = sum(kernels[str(M)]["first_launch_us"] for M in M_SET) / calls_per_step
     k_achieved = k_bytes / k_us / 1e3   # GB/s
-    # the whole call (every launch of the path, gaps included), from the contract's timed region
     mean_bytes = sum(algorithmic_bytes(M, D_MODEL, D_FF) for M in M_SET) / calls_per_step
     ev_us_per_call = ev_ms * 1e3 / (args.steps * calls_per_step)
     achieved = mean_bytes / ev_us_per_call / 1e3   # GB/s
-    traffic, traffic_src = committed_traffic()
-    roofline = {"bound": "hbm", "kernel": "first launch of the call (gate/up kernel; the whole block if fused)",
-                "achieved": round(k_achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(k_achieved / HBM_PEAK_GBS, 4),
-                "algorithmic_bytes_per_launch": int(k_bytes), "us_per_launch": round(k_us, 2),
-                "traffic": traffic, "traffic_source": traffic_src,
-                "whole_call": {"achieved": round(achieved, 1), "frac": round(achieved / HBM_PEAK_GBS, 4),
-                               "algorithmic_bytes_per_call": int(mean_bytes), "us_per_call": round(ev_us_per_call, 2)},
-                # plain streaming reads on the same box: launches of the dominant kernel's size / of one matrix
+    traffic_call, traffic_dom, traffic_src = committed_traffic()
+    roofline = {"bound": "hbm", "kernel": "every launch of a call (the scheduler's pick per M, see config.variant_per_M)",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "algorithmic_bytes_per_call": int(mean_bytes), "us_per_call": round(ev_us_per_call, 2),
+                "traffic": traffic_call, "traffic_source": traffic_src,
+                "dominant_kernel": {"kernel": "first launch of the call: the whole block where the single launch is picked, "
+                                              "else the gate/up kernel", "achieved": round(k_achieved, 1),
+                                    "frac": round(k_achieved / HBM_PEAK_GBS, 4), "algorithmic_bytes_per_launch": int(k_bytes),
+                                    "us_per_launch": round(k_us, 2), "traffic": traffic_dom},
+                # plain streaming reads on the same box: launches of a whole call's size / of one matrix
                 "read_stream_ceiling_gbs": round(read_gbs, 1),
                 "read_stream_one_matrix_gbs": round(read_small_gbs, 1),
-                "kernel_frac_of_read_stream_ceiling": round(k_achieved / read_gbs, 4),
+                "frac_of_read_stream_ceiling": round(achieved / read_gbs, 4),
                 # a read-only kernel with the gate/up kernel's slices, wavefronts, 256-byte pieces and tile order
                 "gateup_pattern_read_us": round(pattern_us, 2),
-                "gateup_pattern_read_gbs": round(4 * D_MODEL * D_FF / pattern_us / 1e3, 1),
-                "frac_of_read_stream_ceiling": round(achieved / read_gbs, 4)}
+                "gateup_pattern_read_gbs": round(4 * D_MODEL * D_FF / pattern_us / 1e3, 1)}
 
     # ---- the fp64 oracle on the host cores: whole steps of the same workload until ~12 s of CPU
     # work have been done (+ parity of the GPU path on every call of the first of those steps)
@@ -512,20 +518,39 @@ def main():
                          f"rotating), {calls} calls, {cpu_s:.1f} s of fp64 CPU work"}
         parity = {"max_rel_err_vs_oracle": worst, "tolerance": 2e-2,
                   "checked": f"every call of the first {min(step_i, WEIGHT_SETS)} steps, all outputs"}
+        del hosts
 
+    # ---- beside the headline (not part of `value`): the other layer shapes and the 32-layer decode pass
+    extras = {}
+    if not args.no_extras:
+        dfk.dfk_set_workspace(None)
+        del layers, X, Y, ws, srcs
+        torch.cuda.empty_cache()
+        extras["shapes"] = shapes(args, torch, di, dfk, dev, compact=True)
+        extras["decode32"] = decode32(args, torch, di, dfk, dev, compact=True)
+
+    variant_per_m = {str(M): (VARIANT_NAME[picks[str(M)]["variant"]] if args.force == "auto" else args.force) for M in M_SET}
+    names = sorted(set(variant_per_m.values()))
     out = {
-        "metric": "fused SwiGLU us/call, d=4096 ff=14336 bf16, mean over M in {1,2,4,8,16}",
+        "metric": "SwiGLU MLP us/call (" + ("scheduler's pick per M: " + ", ".join(
+            f"{v} at M={'/'.join(m for m in variant_per_m if variant_per_m[m] == v)}" for v in names)) +
+                  "), d=4096 ff=14336 bf16, mean over M in {1,2,4,8,16}",
         "value": round(us_per_call, 2), "unit": "us/call",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "llama3-8b-shaped SwiGLU MLP layer, d_model=4096 d_ff=14336, "
                                "M in {1,2,4,8,16}, one call per M per step, 4 rotating weight sets",
-                   "entry": args.force, "calls_per_step": calls_per_step},
+                   "entry": args.force, "calls_per_step": calls_per_step, "variant_per_M": variant_per_m},
+        "whole_call_frac_of_peak": round(achieved / HBM_PEAK_GBS, 4),
         "achieved_tb_per_s": round(achieved / 1e3, 3),
-        "per_M": per_m, "per_variant_4x50": per_variant, "per_M_beyond_headline": extended, "per_M_launches": kernels, "scheduler_picks": picks, "tune_seconds": round(tune_s, 2),
+        "second_headline_M_1_to_64": {"mean_us_per_call": round(mean_wide, 2), "mean_frac_of_peak": round(frac_wide, 4),
+                                      "token_counts": list(M_WIDE), "protocol": "4 repeats x 50 launches per M"},
+        "per_M_4x50": per_m, "per_variant_4x50": per_variant, "per_M_launches": kernels, "scheduler_picks": picks,
+        "tune_seconds": round(tune_s, 2), "tune_candidates_skipped": skipped,
         "roofline": roofline, "cpu_baseline": cpu, "parity": parity,
     }
+    out.update(extras)
     print(json.dumps(out))
 
 
