@@ -84,8 +84,8 @@ typedef enum { DFK_REDUCE_TICKET = 0, DFK_REDUCE_ATOMIC = 1 } dfk_reduce_t;
  * variants and tile sizes; the scheduler chooses among these).
  *   variant        DFK_VARIANT_FUSED or DFK_VARIANT_TWO_KERNEL
  *   path           DFK_PATH_VALU (any supported shape, all three element types) or
- *                  DFK_PATH_MFMA (bf16, and IEEE half with the kmajor pairs; shape
- *                  constraints, see dfk_config_valid)
+ *                  DFK_PATH_MFMA (bf16, and IEEE half with the kernel families kmajor >= 1;
+ *                  shape constraints, see dfk_config_valid)
  *   splits         number of d_ff slices = workgroups of the fused kernel, or of
  *                  the first kernel of the two-kernel variant
  *   waves          wavefronts (64 lanes) per workgroup
@@ -102,18 +102,30 @@ typedef enum { DFK_REDUCE_TICKET = 0, DFK_REDUCE_ATOMIC = 1 } dfk_reduce_t;
  *                  1 = the wavefronts share the workgroup's (at most 4) column blocks
  *                  and divide its d_ff rows (meant for few d_ff splits: a short
  *                  cross-workgroup sum whatever the token count)
- *   kmajor         two-kernel variant, MFMA path: 1 = the pair of kernels that take up to 64
- *                  tokens per launch (the activations travel through the same LDS rings
- *                  as the weight tiles instead of sitting in registers; gate/up kernel
- *                  k-major with all its row tiles accumulating in registers); needs
- *                  k2_rows_by_wave = 0 and d_model a multiple of 128 with at least `waves`
- *                  128-k chunks (512 and up); 0 = the kernels above;
+ *   kmajor         MFMA path, kernel family.
+ *                  two-kernel variant:
+ *                  1 = the pair of kernels that take up to 64 tokens per launch (the activations
+ *                  travel through the same LDS rings as the weight tiles instead of sitting in
+ *                  registers; gate/up kernel k-major with all its row tiles accumulating in
+ *                  registers); needs k2_rows_by_wave = 0 and d_model a multiple of 128 with at
+ *                  least `waves` 128-k chunks (512 and up);
+ *                  0 = the first pair (activations in registers, row-tile-major);
  *                  2 = the pair that takes up to 256 tokens per launch (offered beyond 64
- *                  tokens, and at any token count where d_model rules out the pair above): the wavefronts share every weight tile through LDS and own a
- *                  share of the tokens each; waves = 4 or 8 (wavefronts of the gate/up kernel;
- *                  the down kernel always runs 8), depth = 3 or 4 (buffers of shared tiles),
- *                  k2_col_blocks = d_model / 128; with DFK_REDUCE_TICKET the splits' partial
- *                  sums are added by a third, small launch
+ *                  tokens, and at any token count where d_model rules out pair 1): the wavefronts
+ *                  share every weight tile through LDS and own a share of the tokens each;
+ *                  waves = 4 or 8 (wavefronts of the gate/up kernel; the down kernel always runs
+ *                  8), depth = 3 or 4 (buffers of shared tiles), k2_col_blocks = d_model / 128;
+ *                  with DFK_REDUCE_TICKET the splits' partial sums are added by a third, small
+ *                  launch;
+ *                  3 = gate/up kernel of pair 2 with four wavefronts of one token tile each,
+ *                  down kernel of pair 1 (offered for 33..64 tokens; waves = 8, depth = 3 or 4,
+ *                  the constraints of both pairs).
+ *                  fused variant:
+ *                  1 = the single launch built on pair 1's k-major stage one: each workgroup
+ *                  keeps A_2 of its d_ff slice in LDS and runs both stages over one tile stream
+ *                  (up to 16 tokens per launch, slices of at most 64 rows, waves = 4 or 8,
+ *                  d_model a multiple of 128 with at least `waves` 128-k chunks; bf16 and half);
+ *                  0 = the first single-launch kernel (bf16 only).
  */
 typedef struct dfk_config_t {
     int variant;

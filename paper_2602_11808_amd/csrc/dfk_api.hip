@@ -177,6 +177,15 @@ std::vector<dfk_config_t> candidates(int M, int d_model, int d_ff, dfk_dtype_t d
                             push(make_cfg(DFK_VARIANT_TWO_KERNEL, DFK_PATH_MFMA, clamp_splits(splits, d_ff), wd / 10, wd % 10,
                                           clamp_splits(std::max(1, grid / k2c), d_ff), k2c, (int)dtype, reduce, 0, 1));
             }
+        // two-kernel for 33..64 tokens: gate/up kernel with workgroup-shared weight tiles and one token tile per
+        // wavefront, down kernel of the pair above
+        if (M > 32 && nblk >= 1)
+            for (int splits : {256, 512})
+                for (int grid : {256, 512})
+                    for (int reduce : {DFK_REDUCE_TICKET, DFK_REDUCE_ATOMIC})
+                        for (int depth : {3, 4})
+                            push(make_cfg(DFK_VARIANT_TWO_KERNEL, DFK_PATH_MFMA, clamp_splits(splits, d_ff), 8, depth,
+                                          clamp_splits(std::max(1, grid / nblk), d_ff), nblk, (int)dtype, reduce, 0, 3));
         // two-kernel, workgroup-shared weight tiles: up to 256 tokens per launch.  Offered beyond 64 tokens,
         // and below where d_model rules out the pair above (it needs whole 128-k chunks per wavefront,
         // this one only d_model % 128 == 0)
@@ -217,6 +226,7 @@ bool heuristic(int M, int d_model, int d_ff, dfk_dtype_t dtype, int want_variant
     auto rank = [&](const dfk_config_t& c) {
         if (c.variant == DFK_VARIANT_TWO_KERNEL) {
             if (c.kmajor == 2) return M > 64 ? -1 : 1;     // one launch for up to 256 tokens beats several of 64
+            if (c.kmajor == 3) return 1;
             return c.kmajor ? 0 : c.k2_rows_by_wave ? 1 : 2;
         }
         if (c.path == DFK_PATH_MFMA && c.kmajor == 1)      // of the single-launch forms, the one built on the 64-token pair first

@@ -161,6 +161,9 @@ int mfma_fused_km_tokens_per_launch();
 hipError_t launch_mfma_big(const MlpArgs& a, const dfk_config_t& c, hipStream_t st);
 bool mfma_big_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype);
 int mfma_big_tokens_per_launch();
+// its gate/up kernel with four wavefronts of one token tile each (up to 64 tokens), for the mixed pair (kmajor = 3)
+hipError_t launch_big_gateup_64(const MlpArgs& a, const dfk_config_t& c, hipStream_t st);
+bool big_gateup_64_fits(const dfk_config_t& c, int d_model, int d_ff);
 int valu_max_tokens_per_launch();
 
 // utility kernels

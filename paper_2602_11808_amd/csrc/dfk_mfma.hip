@@ -773,13 +773,37 @@ hipError_t launch_nt(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
 
 }  // namespace
 
+// The mixed pair for 33..64 tokens (kmajor = 3): gate/up kernel with workgroup-shared weight tiles (four
+// wavefronts, one token tile each), down kernel of the 64-token pair.
+dfk_config_t mixed_gateup_cfg(const dfk_config_t& c) { dfk_config_t g = c; g.waves = 4; g.kmajor = 2; return g; }
+dfk_config_t mixed_down_cfg(const dfk_config_t& c) { dfk_config_t d = c; d.kmajor = 1; return d; }
+
+bool mfma_mixed_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype) {
+    if (c.variant != DFK_VARIANT_TWO_KERNEL || c.kmajor != 3 || c.waves != 8) return false;
+    return mfma_km_config_valid(mixed_down_cfg(c), M, d_model, d_ff, dtype) && big_gateup_64_fits(mixed_gateup_cfg(c), d_model, d_ff);
+}
+
+hipError_t launch_mfma_mixed(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
+    if (g_stage_mask & 1) {
+        if (hipError_t e = launch_big_gateup_64(a, mixed_gateup_cfg(c), st); e != hipSuccess) return e;
+    }
+    if (!(g_stage_mask & 2)) return hipSuccess;
+    const int saved = g_stage_mask;
+    g_stage_mask = 2;                                  // the down kernel only
+    const hipError_t e = launch_mfma_km(a, mixed_down_cfg(c), st);
+    g_stage_mask = saved;
+    return e;
+}
+
 int mfma_max_tokens_per_launch(const dfk_config_t& c, int d_model) {
+    if (c.kmajor == 3) return mfma_km_tokens_per_launch();
     if (c.kmajor == 2) return mfma_big_tokens_per_launch();
     if (c.kmajor == 1 && c.variant == DFK_VARIANT_FUSED) return mfma_fused_km_tokens_per_launch();
     return c.kmajor ? mfma_km_tokens_per_launch() : 16 * max_token_tiles(c, d_model);
 }
 
 bool mfma_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype) {
+    if (c.kmajor == 3) return mfma_mixed_config_valid(c, M, d_model, d_ff, dtype);
     if (c.kmajor == 2) return mfma_big_config_valid(c, M, d_model, d_ff, dtype);
     if (c.kmajor == 1 && c.variant == DFK_VARIANT_FUSED) return mfma_fused_km_config_valid(c, M, d_model, d_ff, dtype);
     if (c.kmajor) return mfma_km_config_valid(c, M, d_model, d_ff, dtype);
@@ -820,6 +844,7 @@ bool mfma_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_
 }
 
 hipError_t launch_mfma(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
+    if (c.kmajor == 3) return launch_mfma_mixed(a, c, st);
     if (c.kmajor == 2) return launch_mfma_big(a, c, st);
     if (c.kmajor == 1 && c.variant == DFK_VARIANT_FUSED) return launch_mfma_fused_km(a, c, st);
     if (c.kmajor) return launch_mfma_km(a, c, st);

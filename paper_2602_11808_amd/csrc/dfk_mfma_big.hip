@@ -525,7 +525,9 @@ __global__ __launch_bounds__(256) void k_sum_partials_big(MlpArgs a) {
     template __global__ void k_gateup_big<2, BF16, NTC, 4>(MlpArgs, BigGeom);    \
     template __global__ void k_gateup_big<2, FP16, NTC, 4>(MlpArgs, BigGeom);    \
     template __global__ void k_gateup_big<4, BF16, NTC, 4>(MlpArgs, BigGeom);    \
-    template __global__ void k_gateup_big<4, FP16, NTC, 4>(MlpArgs, BigGeom);
+    template __global__ void k_gateup_big<4, FP16, NTC, 4>(MlpArgs, BigGeom);    \
+    template __global__ void k_gateup_big<1, BF16, NTC, 4>(MlpArgs, BigGeom);    \
+    template __global__ void k_gateup_big<1, FP16, NTC, 4>(MlpArgs, BigGeom);
 DFK_INST_GATEUP(1) DFK_INST_GATEUP(2) DFK_INST_GATEUP(3) DFK_INST_GATEUP(4)
 DFK_INST_GATEUP(5) DFK_INST_GATEUP(6) DFK_INST_GATEUP(7) DFK_INST_GATEUP(8)
 #undef DFK_INST_GATEUP
@@ -617,6 +619,49 @@ hipError_t launch_big_t(const MlpArgs& a, const dfk_config_t& c, hipStream_t st)
 }  // namespace
 
 int mfma_big_tokens_per_launch() { return kBigTokensPerLaunch; }
+
+// The gate/up kernel alone with four wavefronts of one token tile each: up to 64 tokens per launch.  Paired with
+// the down kernel of the 64-token pair for 33..64 tokens (config field kmajor = 3): with three or four token
+// tiles the shared weight tiles (read from L2 once per workgroup instead of once per wavefront) pay, while the
+// down kernel of this family does not yet.
+namespace {
+template <typename E, int NTC>
+hipError_t launch_gateup_64_n(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
+    static LdsAllowance allowed;
+    BigGeom geo{};
+    const size_t lds = big_lds_gateup(c, 1, a.d_ff, &geo);
+    if (hipError_t e = allow_lds(allowed, (const void*)k_gateup_big<1, E, NTC, 4>, lds); e != hipSuccess) return e;
+    hipLaunchKernelGGL((k_gateup_big<1, E, NTC, 4>), dim3(a.splits), dim3(256), lds, st, a, geo);
+    return hipGetLastError();
+}
+template <typename E>
+hipError_t launch_gateup_64_e(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
+    switch (max_slice_rows(a.d_ff, c.splits) / 8) {
+        case 1: return launch_gateup_64_n<E, 1>(a, c, st);
+        case 2: return launch_gateup_64_n<E, 2>(a, c, st);
+        case 3: return launch_gateup_64_n<E, 3>(a, c, st);
+        case 4: return launch_gateup_64_n<E, 4>(a, c, st);
+        case 5: return launch_gateup_64_n<E, 5>(a, c, st);
+        case 6: return launch_gateup_64_n<E, 6>(a, c, st);
+        case 7: return launch_gateup_64_n<E, 7>(a, c, st);
+        case 8: return launch_gateup_64_n<E, 8>(a, c, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+}  // namespace
+
+// c.waves must be 4 here (the caller passes a copy of its configuration with the gate/up kernel's wavefront count)
+hipError_t launch_big_gateup_64(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
+    if (a.norm_w || a.m_count > 64) return hipErrorInvalidValue;
+    return a.dtype == DFK_FP16 ? launch_gateup_64_e<FP16>(a, c, st) : launch_gateup_64_e<BF16>(a, c, st);
+}
+bool big_gateup_64_fits(const dfk_config_t& c, int d_model, int d_ff) {
+    if (d_model < 128 || d_model % kKC || d_model > kMaxDModel) return false;
+    if (c.depth < 3 || c.depth > 4) return false;
+    if (max_slice_rows(d_ff, c.splits) / 8 > kBigMaxRowTiles) return false;
+    BigGeom geo{};
+    return big_lds_gateup(c, 1, d_ff, &geo) <= (size_t)kLdsLimit;
+}
 
 bool mfma_big_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype) {
     if (c.path != DFK_PATH_MFMA || (dtype != DFK_BF16 && dtype != DFK_FP16) || c.variant != DFK_VARIANT_TWO_KERNEL) return false;

@@ -166,8 +166,9 @@ def test_large_token_counts(M):
                          ids=lambda s: "M%d_d%d_ff%d" % s)
 def test_kernels_for_up_to_64_tokens_per_launch(shape):
     """Every candidate of the kernels whose activations travel through the tile rings (config field
-    kmajor = 1: the pair for up to 64 tokens per launch, and the single launch built on its stage one): one to four token tiles, ragged d_ff, both reductions,
-    and a token count that needs two launches; the last five shapes have a d_model whose 128-k chunks do not
+    kmajor = 1: the pair for up to 64 tokens per launch, and the single launch built on its stage one; kmajor = 3:
+    beyond 32 tokens, the gate/up kernel with workgroup-shared weight tiles in front of the same down kernel):
+    one to four token tiles, ragged d_ff, both reductions, and a token count that needs two launches; the last five shapes have a d_model whose 128-k chunks do not
     divide evenly among the wavefronts (6, 10, 18, 7 and 5 chunks for 4 or 8 wavefronts); the last one a d_ff
     beyond 512 slices of 64 rows, which runs with more slices."""
     M, d, ff = shape
@@ -175,9 +176,10 @@ def test_kernels_for_up_to_64_tokens_per_launch(shape):
     ref = oracle.swiglu_mlp(t["X"], t["Wg"], t["Wu"], t["Wd"])
     g = gpu_inputs(t)
     ws = dfk.new_workspace(M, d, ff, DEV)
-    cfgs = _cfgs(M, d, ff, lambda c: c.kmajor == 1)
+    cfgs = _cfgs(M, d, ff, lambda c: c.kmajor in (1, 3))
     assert cfgs
     assert {c.reduce for c in cfgs} == {dfk.DFK_REDUCE_TICKET, dfk.DFK_REDUCE_ATOMIC}
+    assert any(c.kmajor == 3 for c in cfgs) == (M > 32 and d // 128 >= 8)   # its down kernel runs eight wavefronts
     for cfg in cfgs:
         print("case", shape, cfg, flush=True)
         for _ in range(2):
