@@ -125,6 +125,13 @@ typedef enum { DFK_REDUCE_TICKET = 0, DFK_REDUCE_ATOMIC = 1 } dfk_reduce_t;
  *                  keeps A_2 of its d_ff slice in LDS and runs both stages over one tile stream
  *                  (up to 16 tokens per launch, slices of at most 64 rows, waves = 4 or 8,
  *                  d_model a multiple of 128 with at least `waves` 128-k chunks; bf16 and half);
+ *                  4 = both kernels of pair 1 in one launch: the grid holds the gate/up kernel's
+ *                  `splits` workgroups followed by the down kernel's k2_splits * k2_col_blocks;
+ *                  a down workgroup requests its first W_down tiles, then waits (a bounded
+ *                  number of polls) until the gate/up workgroups of its d_ff rows have
+ *                  published A_2, which crosses through device memory as between two kernels.
+ *                  Up to 64 tokens per launch; waves = 8; otherwise the constraints of pair 1,
+ *                  whose k2_splits, k2_col_blocks and reduce fields it uses;
  *                  0 = the first single-launch kernel (bf16 only).
  */
 typedef struct dfk_config_t {

@@ -92,6 +92,9 @@ dfk_status_t check(const void* X, const void* Wg, const void* Wu, const void* Wd
 }
 
 // ---------------------------------------------------------------- candidates and heuristic
+// the single launch that holds both kernels' workgroups: variant FUSED, but partial sums and stages of the pair
+bool roles_launch(const dfk_config_t& c) { return c.variant == DFK_VARIANT_FUSED && c.path == DFK_PATH_MFMA && c.kmajor == 4; }
+
 int clamp_splits(int want, int d_ff) { return std::max(1, std::min(want, d_ff / 8)); }
 
 dfk_config_t make_cfg(int variant, int path, int splits, int waves, int depth, int k2s, int k2c,
@@ -177,6 +180,18 @@ std::vector<dfk_config_t> candidates(int M, int d_model, int d_ff, dfk_dtype_t d
                             push(make_cfg(DFK_VARIANT_TWO_KERNEL, DFK_PATH_MFMA, clamp_splits(splits, d_ff), wd / 10, wd % 10,
                                           clamp_splits(std::max(1, grid / k2c), d_ff), k2c, (int)dtype, reduce, 0, 1));
             }
+        // both kernels of that pair in one launch (gate/up workgroups at the head of the grid, down workgroups
+        // behind them)
+        for (int splits : {256, 512})
+            for (int cbw : {1, 2}) {
+                if (nblk < cbw || nblk % cbw) continue;
+                const int k2c = nblk / cbw;
+                for (int grid : {256, 512})
+                    for (int reduce : {DFK_REDUCE_TICKET, DFK_REDUCE_ATOMIC})
+                        for (int depth : {3, 4})
+                            push(make_cfg(DFK_VARIANT_FUSED, DFK_PATH_MFMA, clamp_splits(splits, d_ff), 8, depth,
+                                          clamp_splits(std::max(1, grid / k2c), d_ff), k2c, (int)dtype, reduce, 0, 4));
+            }
         // two-kernel for 33..64 tokens: gate/up kernel with workgroup-shared weight tiles and one token tile per
         // wavefront, down kernel of the pair above
         if (M > 32 && nblk >= 1)
@@ -217,10 +232,11 @@ std::vector<dfk_config_t> candidates(int M, int d_model, int d_ff, dfk_dtype_t d
     return out;
 }
 
-// Untuned default, from measurements on MI355X.  One token: the single launch on the k-major stage one with
-// the atomic reduction (it saves the boundary between two kernels, and its 256 full-width partial sums are
-// still cheap).  From two tokens on the two-kernel variant: beyond 64 tokens the kernel pair that takes up to
-// 256 per launch, else the pair for up to 64 tokens, then the rows-split down kernel, then the rest.
+// Untuned default, from measurements on MI355X.  One token: the single launch that keeps A_2 in LDS, with the
+// atomic reduction (no boundary between two kernels, and its 256 full-width partial sums are still cheap).  Up to
+// 64 tokens: the single launch that holds both kernels' workgroups (atomic reduction), which saves the launch
+// boundary at every token count.  Of the two-kernel forms: beyond 64 tokens the pair that takes up to 256 per
+// launch, else the pair for up to 64 tokens, then the rows-split down kernel, then the rest.
 bool heuristic(int M, int d_model, int d_ff, dfk_dtype_t dtype, int want_variant, dfk_config_t* out) {
     auto cands = candidates(M, d_model, d_ff, dtype);
     auto rank = [&](const dfk_config_t& c) {
@@ -229,8 +245,9 @@ bool heuristic(int M, int d_model, int d_ff, dfk_dtype_t dtype, int want_variant
             if (c.kmajor == 3) return 1;
             return c.kmajor ? 0 : c.k2_rows_by_wave ? 1 : 2;
         }
-        if (c.path == DFK_PATH_MFMA && c.kmajor == 1)      // of the single-launch forms, the one built on the 64-token pair first
-            return c.reduce == DFK_REDUCE_ATOMIC && c.waves == 8 ? (M == 1 ? -2 : 3) : 4;
+        if (roles_launch(c)) return M <= 64 && c.reduce == DFK_REDUCE_ATOMIC && c.depth == 4 ? -2 : 3;
+        if (c.path == DFK_PATH_MFMA && c.kmajor == 1)      // the single launch with A_2 in LDS
+            return c.reduce == DFK_REDUCE_ATOMIC && c.waves == 8 ? (M == 1 ? -3 : 3) : 4;
         return 5;
     };
     const dfk_config_t* best = nullptr;
@@ -315,7 +332,7 @@ dfk_status_t run_in(const WsLayout& l, const void* X, const void* Wg, const void
     }
     a.trace = nullptr;
     {
-        const size_t grid = (size_t)std::max(c.splits, c.k2_splits * std::max(1, c.k2_col_blocks));
+        const size_t grid = (size_t)c.splits + (size_t)c.k2_splits * std::max(1, c.k2_col_blocks);   // covers every kernel's grid
         const Registered tr = snapshot(g_trace);
         if (tr.ptr && tr.bytes >= grid * 8 * sizeof(unsigned long long))
             a.trace = (unsigned long long*)tr.ptr;
@@ -411,7 +428,7 @@ bool partials_fit_static(const dfk_config_t& c, int M, int d_model, size_t p_byt
     if (c.reduce == DFK_REDUCE_ATOMIC) return true;   // accumulator only, already checked against its fixed size
     const int per = c.path == DFK_PATH_MFMA ? mfma_max_tokens_per_launch(c, d_model) : valu_max_tokens_per_launch();
     const size_t tokens = (size_t)std::min(M, per);
-    const bool fused = c.variant == DFK_VARIANT_FUSED;
+    const bool fused = c.variant == DFK_VARIANT_FUSED && !roles_launch(c);
     const size_t blocks = fused ? (size_t)c.splits : (size_t)c.k2_splits;
     const size_t groups = fused ? (blocks + kGroupSize - 1) / kGroupSize : 0;
     return blocks * tokens * d_model * 4 <= p_bytes && groups * tokens * d_model * 4 <= q_bytes;
@@ -492,7 +509,7 @@ dfk_status_t time_kernels(const dfk_config_t& c, int M, int d_model, int d_ff, d
     if ((e = hipEventCreate(&t0)) != hipSuccess) return hip_fail(e);
     if ((e = hipEventCreate(&t1)) != hipSuccess) { (void)hipEventDestroy(t0); return hip_fail(e); }
     usec2[0] = usec2[1] = 0.0;
-    const int stages = c.variant == DFK_VARIANT_FUSED ? 1 : 2;
+    const int stages = c.variant == DFK_VARIANT_FUSED && !roles_launch(c) ? 1 : 2;   // (head and tail of the launch with both roles)
     for (int k = 0; k < stages && rc == DFK_OK; ++k) {
         g_stage_mask = 1 << k;
         for (int it = -2; it < iters && rc == DFK_OK; ++it) {

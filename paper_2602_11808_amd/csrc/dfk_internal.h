@@ -153,6 +153,9 @@ hipError_t launch_mfma_km(const MlpArgs& a, const dfk_config_t& c, hipStream_t s
 bool mfma_km_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype);
 bool mfma_km_block_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype);
 int mfma_km_tokens_per_launch();
+// both kernels' workgroups in one launch (variant FUSED, kmajor = 4)
+hipError_t launch_mfma_km_roles(const MlpArgs& a, const dfk_config_t& c, hipStream_t st);
+bool mfma_km_roles_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype);
 // the single launch built on that pair (dfk_mfma_fused.hip; variant FUSED with kmajor = 1)
 hipError_t launch_mfma_fused_km(const MlpArgs& a, const dfk_config_t& c, hipStream_t st);
 bool mfma_fused_km_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype);

@@ -28,6 +28,7 @@
 // Rows of X / A_2 past the launch's tokens are fetched from the last real token:
 // they only feed output rows that are never stored.
 #include <atomic>
+#include <cstdlib>
 #include "dfk_mfma_common.h"
 
 namespace dfk {
@@ -40,7 +41,23 @@ struct KmGeom {
     int depth;   // ring slots per wavefront
     int pass;    // gate/up kernel: row tiles whose partial sums LDS holds per pass at the end
     int norm_off;  // gate/up kernel with the normalisation: byte offset in LDS of the weight slices, past rings and stage
+    // the single launch of both kernels' workgroups:
+    int n_gateup;            // workgroups of the gate/up kernel at the head of the grid
+    int role_publish;        // gate/up workgroups count themselves done
+    int role_wait;           // down workgroups wait for the gate/up workgroups of their rows
+    int role_stride;         // words between the counters of adjacent d_ff splits
+    int depth_down;          // ring slots per wavefront of the down workgroups
+    int role_spin_limit;     // polls of the done counter before a down workgroup gives up (its outputs become NaN)
 };
+
+// Counter words of the single launch of both kernels' workgroups, in the counter area of the workspace (column
+// block counters occupy [0, 512), the second reduction level word 512, the slice-local fused kernel word 1023).
+constexpr int kRolePassed = 1022;   // down workgroups that are past their wait: the last one clears the counters below
+constexpr int kRoleCount0 = 520;    // per d_ff split of the down projection: gate/up workgroups that have published
+constexpr int kRoleCountEnd = 1020; //   A_2 rows of that split; geo.role_stride words apart (spread over cache lines)
+
+// the slice (of S) that holds 8-row group gidx of ng: the inverse of slice_rows
+__device__ __forceinline__ int slice_of_group(int ng, int S, int gidx) { return (int)((((long long)gidx + 1) * S - 1) / ng); }
 
 // Bytes between the wavefronts' slices of the normalisation weight in LDS: the longest run of
 // chunks a wavefront can own, 1 KB-aligned (one load instruction writes 1 KB).
@@ -119,9 +136,11 @@ struct KmStream1 {
 // every lane adds up the squares of the H values it holds anyway, and the end scales the
 // summed G and U by s_m in fp32 before the activation.  Each workgroup reads all of X, so
 // it has the whole sum of squares of every token by itself.
-template <int NW, int TT, typename E, bool NORM>
-__global__ __launch_bounds__(NW * 64) void k_gateup_km(MlpArgs a, KmGeom geo) {
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+//
+// PUBLISH (the single launch that holds both kernels' workgroups, further down): A_2 is stored
+// with device-scope stores and the workgroup ends by counting itself done on kRoleDone.
+template <int NW, int TT, typename E, bool NORM, bool PUBLISH>
+__device__ __forceinline__ void gateup_km_body(const MlpArgs& a, const KmGeom& geo, const int wg, unsigned char* lds) {
     constexpr int TOK = 16 * TT;
     constexpr int NTHREADS = NW * 64;
     constexpr int NT = kKmMaxRowTiles;
@@ -130,7 +149,7 @@ __global__ __launch_bounds__(NW * 64) void k_gateup_km(MlpArgs a, KmGeom geo) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int q = lane & 15, g = lane >> 4;
     int j0, j1;
-    slice_rows(a.d_ff, a.splits, blockIdx.x, j0, j1);
+    slice_rows(a.d_ff, a.splits, wg, j0, j1);
     const int nt = (j1 - j0) / 8;                 // <= NT, checked on the host
     // The 128-k chunks of a row are dealt out to the wavefronts in contiguous runs, as evenly as
     // their number allows (equal runs when d_model is a multiple of 128 * NW).
@@ -261,12 +280,30 @@ __global__ __launch_bounds__(NW * 64) void k_gateup_km(MlpArgs a, KmGeom geo) {
                     g0 *= sm; g1 *= sm; u0 *= sm; u1 *= sm;
                 }
                 const size_t o = (size_t)(a.m_base + m) * a.d_ff + j0 + (rt0 + r) * 8 + 2 * pr;
-                *(uint32_t*)((uint16_t*)a.a2 + o) = E::pack2(silu_mul_fast(g0, u0), silu_mul_fast(g1, u1));
+                const uint32_t v = E::pack2(silu_mul_fast(g0, u0), silu_mul_fast(g1, u1));
+                if (PUBLISH) __hip_atomic_store((uint32_t*)((uint16_t*)a.a2 + o), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                else *(uint32_t*)((uint16_t*)a.a2 + o) = v;
             }
         }
         __syncthreads();
     }
     DFK_STAMP(1);   // A_2 stored
+    if (PUBLISH && geo.role_publish) {
+        drain_own_memory_ops();                  // this wavefront's A_2 stores are acknowledged
+        __syncthreads();
+        if (tid == 0) {                          // one count on every split of the down projection these rows belong to
+            const int ng = a.d_ff / 8;
+            const int lo = slice_of_group(ng, a.k2_splits, j0 / 8), hi = slice_of_group(ng, a.k2_splits, j1 / 8 - 1);
+            for (int js = lo; js <= hi; ++js)
+                __hip_atomic_fetch_add(a.tickets + kRoleCount0 + js * geo.role_stride, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+template <int NW, int TT, typename E, bool NORM>
+__global__ __launch_bounds__(NW * 64) void k_gateup_km(MlpArgs a, KmGeom geo) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    gateup_km_body<NW, TT, E, NORM, false>(a, geo, blockIdx.x, lds);
 }
 
 // ---------------------------------------------------------------- down kernel
@@ -284,11 +321,12 @@ struct KmStream2 {
     unsigned char* ring;
     int depth, T, issued, issue_slot, take_slot;
     int p_jbi, p_idx;          // producer: 32-row block, position in it (A tile, then 2 tiles per column block)
+    int a_pos;                 // position of the A tile in a 32-row block: 0, or 2 CB = behind the weight tiles
 
     __device__ __forceinline__ void issue() {
         unsigned char* slot = ring + issue_slot * kTileBytes;
         const int jb = jb_lo + p_jbi;
-        if (p_idx == 0) {      // A tile: instruction u = token tile; lane (q, g): token q, rows 8g .. 8g+7 of the block
+        if (p_idx == a_pos) {  // A tile: instruction u = token tile; lane (q, g): token q, rows 8g .. 8g+7 of the block
             const int j = min(jb * 32 + 8 * g, rows - 8);   // past the split: any valid address (masked at use)
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -297,7 +335,8 @@ struct KmStream2 {
                 __builtin_amdgcn_global_load_lds(src, DFK_LDS_PTR(slot + u * 1024), 16, 0, 0);
             }
         } else {
-            const int b = (p_idx - 1) >> 1, h = (p_idx - 1) & 1;
+            const int wi = p_idx - (p_idx > a_pos ? 1 : 0);  // index among the block's weight tiles
+            const int b = wi >> 1, h = wi & 1;
             const int row0 = j0 + jb * 32 + 4 * h;           // lane adds 8g + u
             const size_t colb = (size_t)(blk_first + b) * 256;
             if (row0 + 28 <= d_ff) {
@@ -319,12 +358,17 @@ struct KmStream2 {
         ++issued;
         if (++issue_slot == depth) issue_slot = 0;
     }
-    __device__ __forceinline__ void start() {
+    // limit: most tiles to request now (the single launch holds back the first A tile until A_2 is complete)
+    __device__ __forceinline__ void start(const int limit) {
         off2 = (unsigned)(8 * g * row_bytes + 16 * q);
         T = njb * (1 + 2 * CB);
         issued = 0; issue_slot = 0; take_slot = 0; p_jbi = 0; p_idx = 0;
-        const int ahead = min(depth - 1, T);
+        const int ahead = min(min(depth - 1, T), limit);
         for (int i = 0; i < ahead; ++i) issue();
+    }
+    __device__ __forceinline__ void top_up() {
+        const int ahead = min(depth - 1, T);
+        while (issued < ahead) issue();
     }
     __device__ __forceinline__ const unsigned char* acquire() {
         DFK_WAIT_LGKM0();
@@ -343,9 +387,12 @@ struct KmStream2 {
 
 __host__ __device__ constexpr int km_col_blocks(int tt) { return tt >= 3 ? 1 : 2; }   // accumulator budget
 
-template <int NW, int TT, typename E>
-__global__ __launch_bounds__(NW * 64) void k_down_km(MlpArgs a, KmGeom geo) {
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+//
+// WAIT (the single launch of both kernels' workgroups): the stream carries the A tile of a 32-row block behind the
+// first column block's weight tiles and starts with those alone; then the workgroup waits until every gate/up
+// workgroup has counted itself done, drops what its caches hold of A_2's lines, and goes on as the kernel does.
+template <int NW, int TT, typename E, bool WAIT>
+__device__ __forceinline__ void down_km_body(const MlpArgs& a, const KmGeom& geo, const int wg, unsigned char* lds) {
     __shared__ int flag;
     constexpr int NTHREADS = NW * 64;
     constexpr int CBM = km_col_blocks(TT);
@@ -353,8 +400,8 @@ __global__ __launch_bounds__(NW * 64) void k_down_km(MlpArgs a, KmGeom geo) {
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int q = lane & 15, g = lane >> 4;
-    const int js = blockIdx.x / a.k2_col_blocks;
-    const int cb = blockIdx.x - js * a.k2_col_blocks;
+    const int js = wg / a.k2_col_blocks;
+    const int cb = wg - js * a.k2_col_blocks;
     int j0, j1;
     slice_rows(a.d_ff, a.k2_splits, js, j0, j1);
     const int rows = j1 - j0;
@@ -373,10 +420,40 @@ __global__ __launch_bounds__(NW * 64) void k_down_km(MlpArgs a, KmGeom geo) {
     ts.blk_first = blk_lo; ts.CB = CB;
     ts.jb_lo = jb_lo; ts.njb = njb;
     ts.q = q; ts.g = g;
-    ts.ring = lds + wave * geo.depth * kTileBytes;
-    ts.depth = geo.depth;
+    const int depth = WAIT ? geo.depth_down : geo.depth;
+    ts.ring = lds + wave * depth * kTileBytes;
+    ts.depth = depth;
+    ts.a_pos = WAIT ? 2 * CB : 0;
     DFK_STAMP(3);
-    ts.start();
+    bool gave_up = false;
+    unsigned passed_before = 0;
+    if (WAIT) {
+        ts.start(2 * CB);                  // the first 32-row block's weight tiles: nothing of A_2 yet
+        if (geo.role_wait > 0) {
+            if (tid == 0) {
+                int polls = 0, ok = 1;
+                const int ng = a.d_ff / 8;
+                const unsigned expected = (unsigned)(slice_of_group(ng, a.splits, j1 / 8 - 1) - slice_of_group(ng, a.splits, j0 / 8) + 1);
+                const unsigned* cnt = a.tickets + kRoleCount0 + js * geo.role_stride;
+                while (__hip_atomic_load(cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < expected) {
+                    if (++polls > geo.role_spin_limit) { ok = 0; break; }
+                    __builtin_amdgcn_s_sleep(8);
+                }
+                // gate/up workgroups of other XCDs wrote parts of lines this XCD's L2 may hold: drop them
+                acquire_device();
+                flag = ok;
+            }
+            __syncthreads();
+            gave_up = flag == 0;
+            __syncthreads();               // flag is used again by the reduction
+            DFK_STAMP(7);
+            // this workgroup is past its wait; the answer is looked at when the stream has ended
+            if (tid == 0) passed_before = __hip_atomic_fetch_add(a.tickets + kRolePassed, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        ts.top_up();
+    } else {
+        ts.start(1 << 30);
+    }
 
     f32x4 acc2[CBM][8][TT];
 #pragma unroll
@@ -389,7 +466,7 @@ __global__ __launch_bounds__(NW * 64) void k_down_km(MlpArgs a, KmGeom geo) {
     for (int jbi = 0; jbi < njb; ++jbi) {
         const int jb = jb_lo + jbi;
         u32x4 av[TT];          // A operand: A_2[token q of tile tt][rows 8g .. 8g+7 of the block]
-        {
+        auto take_a = [&]() {
             const unsigned char* slot = ts.acquire();
             const bool past = jb * 32 + 8 * g >= rows;
 #pragma unroll
@@ -397,34 +474,60 @@ __global__ __launch_bounds__(NW * 64) void k_down_km(MlpArgs a, KmGeom geo) {
                 const u32x4 v = *(const u32x4*)(slot + tt * 1024 + lane * 16);
                 av[tt] = past ? u32x4{0, 0, 0, 0} : v;
             }
-        }
+        };
+        auto take_w = [&](u32x4 (&w)[8]) {
+            const unsigned char* sa = ts.acquire();
 #pragma unroll
-        for (int b = 0; b < CBM; ++b) {
-            if (b < CB) {
-                u32x4 w[8];
-                const unsigned char* sa = ts.acquire();
+            for (int u = 0; u < 4; ++u) w[u] = *(const u32x4*)(sa + u * 1024 + lane * 16);
+            const unsigned char* sb = ts.acquire();
 #pragma unroll
-                for (int u = 0; u < 4; ++u) w[u] = *(const u32x4*)(sa + u * 1024 + lane * 16);
-                const unsigned char* sb = ts.acquire();
+            for (int u = 0; u < 4; ++u) w[4 + u] = *(const u32x4*)(sb + u * 1024 + lane * 16);
+            if (jb * 32 + 32 > rows) {   // rows past the split contribute nothing
 #pragma unroll
-                for (int u = 0; u < 4; ++u) w[4 + u] = *(const u32x4*)(sb + u * 1024 + lane * 16);
-                if (jb * 32 + 32 > rows) {   // rows past the split contribute nothing
+                for (int r = 0; r < 8; ++r)
+                    if (jb * 32 + 8 * g + r >= rows) w[r] = u32x4{0, 0, 0, 0};
+            }
+        };
+        auto multiply = [&](const int b, const u32x4 (&w)[8]) {
 #pragma unroll
-                    for (int r = 0; r < 8; ++r)
-                        if (jb * 32 + 8 * g + r >= rows) w[r] = u32x4{0, 0, 0, 0};
-                }
+            for (int c = 0; c < 8; ++c) {
+                const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
+                u32x4 bb;
 #pragma unroll
-                for (int c = 0; c < 8; ++c) {
-                    const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
-                    u32x4 bb;
+                for (int p = 0; p < 4; ++p) bb[p] = __builtin_amdgcn_perm(w[2 * p + 1][c >> 1], w[2 * p][c >> 1], sel);
 #pragma unroll
-                    for (int p = 0; p < 4; ++p) bb[p] = __builtin_amdgcn_perm(w[2 * p + 1][c >> 1], w[2 * p][c >> 1], sel);
+                for (int tt = 0; tt < TT; ++tt)
+                    acc2[b][c][tt] = mfma16<E>(av[tt], bb, acc2[b][c][tt]);
+            }
+        };
+        if (WAIT) {            // the block's weight tiles come first in the stream, its A tile last
+            u32x4 w[CBM][8];
 #pragma unroll
-                    for (int tt = 0; tt < TT; ++tt)
-                        acc2[b][c][tt] = mfma16<E>(av[tt], bb, acc2[b][c][tt]);
+            for (int b = 0; b < CBM; ++b)
+                if (b < CB) take_w(w[b]);
+            take_a();
+#pragma unroll
+            for (int b = 0; b < CBM; ++b)
+                if (b < CB) multiply(b, w[b]);
+        } else {
+            take_a();
+#pragma unroll
+            for (int b = 0; b < CBM; ++b) {
+                if (b < CB) {
+                    u32x4 w[8];
+                    take_w(w);
+                    multiply(b, w);
                 }
             }
         }
+    }
+    if (WAIT && gave_up) {   // the wait ran out (never, unless a gate/up workgroup cannot run): make the failure visible in Y
+#pragma unroll
+        for (int b = 0; b < CBM; ++b)
+#pragma unroll
+            for (int c = 0; c < 8; ++c)
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) acc2[b][c][tt] = f32x4{NAN, NAN, NAN, NAN};
     }
     DFK_STAMP(4);
 
@@ -471,6 +574,15 @@ __global__ __launch_bounds__(NW * 64) void k_down_km(MlpArgs a, KmGeom geo) {
         }
     }
     const int width = CB * 128;
+    if (WAIT && geo.role_wait > 0 && tid == 0) {
+        // every down workgroup is past its wait once the last one has said so: that one clears the counters for the next launch
+        const unsigned n_down = (unsigned)(a.k2_splits * a.k2_col_blocks);
+        if (passed_before == n_down - 1u) {
+            __hip_atomic_store(a.tickets + kRolePassed, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            for (int x = 0; x < a.k2_splits; ++x)
+                __hip_atomic_store(a.tickets + kRoleCount0 + x * geo.role_stride, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
     if (atomic_mode) {
         drain_own_memory_ops();
         __syncthreads();
@@ -492,6 +604,26 @@ __global__ __launch_bounds__(NW * 64) void k_down_km(MlpArgs a, KmGeom geo) {
         return;
     }
     reduce_store<E>(plan_column_block(a, cb, blk_lo * 128, blk_lo * 128 + width), a.Y, a.m_base, &flag, a.trace, a.resid);
+}
+
+template <int NW, int TT, typename E>
+__global__ __launch_bounds__(NW * 64) void k_down_km(MlpArgs a, KmGeom geo) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    down_km_body<NW, TT, E, false>(a, geo, blockIdx.x, lds);
+}
+
+// ---------------------------------------------------------------- both kernels' workgroups in one launch
+// Grid = the gate/up kernel's workgroups followed by the down kernel's.  Workgroups are dispatched in index
+// order, so no down workgroup starts before every gate/up workgroup (of its XCD's share of the grid) has, and a
+// gate/up workgroup waits for nothing: the down workgroups' wait always ends.  What the single launch buys over
+// two: no launch boundary (drain, dispatch and ramp with HBM idle), and the down workgroups request their first
+// W_down tiles while the last gate/up workgroups are still streaming.  A_2 crosses between workgroups through
+// device memory (2 bytes per token and d_ff row), as between the two kernels.
+template <int NW, int TT, typename E>
+__global__ __launch_bounds__(NW * 64) void k_roles_km(MlpArgs a, KmGeom geo) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    if ((int)blockIdx.x < geo.n_gateup) gateup_km_body<NW, TT, E, false, true>(a, geo, blockIdx.x, lds);
+    else down_km_body<NW, TT, E, true>(a, geo, blockIdx.x - geo.n_gateup, lds);
 }
 
 // ---------------------------------------------------------------- host side
@@ -524,7 +656,7 @@ template <int NW, int TT, typename E>
 hipError_t launch_km_te(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
     static LdsAllowance allowed1, allowed1n, allowed2;   // of the three kernels of this instantiation, per device
     if ((g_stage_mask & 1) && !a.norm_w) {
-        KmGeom geo;
+        KmGeom geo{};
         const size_t lds = km_lds_gateup(c, TT, a.d_model, a.d_ff, false, &geo);
         if (hipError_t e = allow_lds(allowed1, (const void*)k_gateup_km<NW, TT, E, false>, lds); e != hipSuccess) return e;
         hipLaunchKernelGGL((k_gateup_km<NW, TT, E, false>), dim3(a.splits), dim3(NW * 64), lds, st, a, geo);
@@ -532,7 +664,7 @@ hipError_t launch_km_te(const MlpArgs& a, const dfk_config_t& c, hipStream_t st)
         if (e != hipSuccess) return e;
     }
     if ((g_stage_mask & 1) && a.norm_w) {
-        KmGeom geo;
+        KmGeom geo{};
         const size_t lds = km_lds_gateup(c, TT, a.d_model, a.d_ff, true, &geo);
         if (hipError_t e = allow_lds(allowed1n, (const void*)k_gateup_km<NW, TT, E, true>, lds); e != hipSuccess) return e;
         hipLaunchKernelGGL((k_gateup_km<NW, TT, E, true>), dim3(a.splits), dim3(NW * 64), lds, st, a, geo);
@@ -540,7 +672,7 @@ hipError_t launch_km_te(const MlpArgs& a, const dfk_config_t& c, hipStream_t st)
         if (e != hipSuccess) return e;
     }
     if (g_stage_mask & 2) {
-        KmGeom geo;
+        KmGeom geo{};
         const size_t lds = km_lds_down(c, &geo);
         if (hipError_t e = allow_lds(allowed2, (const void*)k_down_km<NW, TT, E>, lds); e != hipSuccess) return e;
         hipLaunchKernelGGL((k_down_km<NW, TT, E>), dim3(a.k2_splits * a.k2_col_blocks), dim3(NW * 64), lds, st, a, geo);
@@ -552,6 +684,35 @@ hipError_t launch_km_te(const MlpArgs& a, const dfk_config_t& c, hipStream_t st)
 template <int NW, int TT>
 hipError_t launch_km_t(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
     return a.dtype == DFK_FP16 ? launch_km_te<NW, TT, FP16>(a, c, st) : launch_km_te<NW, TT, BF16>(a, c, st);
+}
+
+// Both kernels' workgroups in one launch.  The stage mask of the per-kernel timer maps to the head of the grid
+// alone (gate/up workgroups, nothing counted) and to the tail alone (down workgroups that wait for nobody).
+template <int NW, int TT, typename E>
+hipError_t launch_km_roles_te(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
+    static LdsAllowance allowed;
+    if (a.norm_w) return hipErrorInvalidValue;
+    KmGeom geo{}, gd{};
+    size_t lds = std::max(km_lds_gateup(c, TT, a.d_model, a.d_ff, false, &geo), km_lds_down(c, &gd));
+    const bool head = g_stage_mask & 1, tail = g_stage_mask & 2;
+    geo.n_gateup = head ? a.splits : 0;
+    geo.role_publish = head && tail;
+    geo.role_wait = head && tail ? a.splits : 0;
+    geo.role_stride = 1;
+    while (geo.role_stride < 32 && a.k2_splits * geo.role_stride * 2 <= kRoleCountEnd - kRoleCount0) geo.role_stride *= 2;
+    geo.depth_down = std::max(c.depth, std::min(c.depth + 1, (int)((size_t)kLdsLimit / ((size_t)NW * kTileBytes))));
+    lds = std::max(lds, (size_t)NW * geo.depth_down * kTileBytes);
+    geo.role_spin_limit = 1 << 21;          // seconds; a healthy launch needs a handful of polls
+    if (const char* e = std::getenv("DFK_DEBUG_SPIN_LIMIT")) geo.role_spin_limit = std::atoi(e);
+    const int grid = geo.n_gateup + (tail ? a.k2_splits * a.k2_col_blocks : 0);
+    if (grid == 0) return hipSuccess;
+    if (hipError_t e = allow_lds(allowed, (const void*)k_roles_km<NW, TT, E>, lds); e != hipSuccess) return e;
+    hipLaunchKernelGGL((k_roles_km<NW, TT, E>), dim3(grid), dim3(NW * 64), lds, st, a, geo);
+    return hipGetLastError();
+}
+template <int NW, int TT>
+hipError_t launch_km_roles_t(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
+    return a.dtype == DFK_FP16 ? launch_km_roles_te<NW, TT, FP16>(a, c, st) : launch_km_roles_te<NW, TT, BF16>(a, c, st);
 }
 
 }  // namespace
@@ -576,7 +737,7 @@ bool mfma_km_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, d
     const int TT = km_token_tiles(tokens);
     if (nblk / c.k2_col_blocks > km_col_blocks(TT)) return false;
     if (c.reduce == DFK_REDUCE_TICKET && !partials_fit(c.k2_splits, tokens, M, d_model)) return false;
-    KmGeom geo;
+    KmGeom geo{};
     return km_lds_gateup(c, TT, d_model, d_ff, false, &geo) <= (size_t)kLdsLimit && km_lds_down(c, &geo) <= (size_t)kLdsLimit;
 }
 
@@ -584,8 +745,28 @@ bool mfma_km_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, d
 // little more LDS (weight of the normalisation, sums of squares).
 bool mfma_km_block_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype) {
     if (!mfma_km_config_valid(c, M, d_model, d_ff, dtype)) return false;
-    KmGeom geo;
+    KmGeom geo{};
     return km_lds_gateup(c, km_token_tiles(std::min(M, kKmTokensPerLaunch)), d_model, d_ff, true, &geo) <= (size_t)kLdsLimit;
+}
+
+// The single launch of both kernels' workgroups (variant FUSED, kmajor = 4): everything the pair asks of the
+// configuration, and a grid small enough that its 16-bit-safe index arithmetic holds.
+static dfk_config_t roles_as_pair(const dfk_config_t& c) { dfk_config_t p = c; p.variant = DFK_VARIANT_TWO_KERNEL; p.kmajor = 1; return p; }
+bool mfma_km_roles_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype) {
+    if (c.variant != DFK_VARIANT_FUSED || c.kmajor != 4 || c.waves != 8) return false;
+    if ((long long)c.splits + (long long)c.k2_splits * c.k2_col_blocks > 65535) return false;
+    if (c.k2_splits > kRoleCountEnd - kRoleCount0) return false;   // one counter per d_ff split of the down projection
+    return mfma_km_config_valid(roles_as_pair(c), M, d_model, d_ff, dtype);
+}
+hipError_t launch_mfma_km_roles(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
+    const dfk_config_t p = roles_as_pair(c);
+    switch (km_token_tiles(a.m_count)) {
+        case 1: return launch_km_roles_t<8, 1>(a, p, st);
+        case 2: return launch_km_roles_t<8, 2>(a, p, st);
+        case 3: return launch_km_roles_t<8, 3>(a, p, st);
+        case 4: return launch_km_roles_t<8, 4>(a, p, st);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 hipError_t launch_mfma_km(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {

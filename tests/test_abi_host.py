@@ -155,7 +155,9 @@ def test_config_validation():
 
 def test_kernel_families_by_token_count():
     """The 64-token pair is offered at every token count, the 256-token pair beyond 64 tokens only; the
-    untuned default follows; the limits of the 256-token pair are enforced on the host."""
+    untuned default follows (one token: the single launch with A_2 in LDS; up to 64: the single launch of both
+    kernels' workgroups; beyond: the 256-token pair; two-kernel variant asked for: the pairs); the limits of the
+    256-token pair are enforced on the host."""
     import copy
     for dt in (dfk.DFK_BF16, dfk.DFK_FP16):
         for M, want2 in ((1, False), (64, False), (65, True), (128, True), (256, True)):
@@ -165,7 +167,10 @@ def test_kernel_families_by_token_count():
             for c in cands:
                 assert dfk.dfk_config_valid(c, M, D, FF, dt), (M, c)
             pick, tuned = dfk.dfk_get_choice(M, D, FF, dt)
-            assert not tuned and pick.kmajor == (2 if want2 else 1)
+            assert not tuned
+            assert (pick.variant, pick.kmajor) == ((dfk.DFK_VARIANT_TWO_KERNEL, 2) if want2 else
+                                                   (dfk.DFK_VARIANT_FUSED, 1 if M == 1 else 4))
+            assert any(c.kmajor == 4 and c.variant == dfk.DFK_VARIANT_FUSED for c in cands)
     assert dfk.dfk_num_candidates(128, D, FF, dfk.DFK_FP32) > 0          # fp32 test mode: VALU kernels only
     assert all(dfk.dfk_get_candidate(128, D, FF, dfk.DFK_FP32, i).path == dfk.DFK_PATH_VALU
                for i in range(dfk.dfk_num_candidates(128, D, FF, dfk.DFK_FP32)))

@@ -167,7 +167,9 @@ def test_large_token_counts(M):
 def test_kernels_for_up_to_64_tokens_per_launch(shape):
     """Every candidate of the kernels whose activations travel through the tile rings (config field
     kmajor = 1: the pair for up to 64 tokens per launch, and the single launch built on its stage one; kmajor = 3:
-    beyond 32 tokens, the gate/up kernel with workgroup-shared weight tiles in front of the same down kernel):
+    beyond 32 tokens, the gate/up kernel with workgroup-shared weight tiles in front of the same down kernel;
+    kmajor = 4: both kernels' workgroups in one launch, the down workgroups waiting for the gate/up workgroups of
+    their rows):
     one to four token tiles, ragged d_ff, both reductions, and a token count that needs two launches; the last five shapes have a d_model whose 128-k chunks do not
     divide evenly among the wavefronts (6, 10, 18, 7 and 5 chunks for 4 or 8 wavefronts); the last one a d_ff
     beyond 512 slices of 64 rows, which runs with more slices."""
@@ -176,7 +178,8 @@ def test_kernels_for_up_to_64_tokens_per_launch(shape):
     ref = oracle.swiglu_mlp(t["X"], t["Wg"], t["Wu"], t["Wd"])
     g = gpu_inputs(t)
     ws = dfk.new_workspace(M, d, ff, DEV)
-    cfgs = _cfgs(M, d, ff, lambda c: c.kmajor in (1, 3))
+    cfgs = _cfgs(M, d, ff, lambda c: c.kmajor in (1, 3, 4))
+    assert any(c.kmajor == 4 for c in cfgs) == (d // 128 >= 8)
     assert cfgs
     assert {c.reduce for c in cfgs} == {dfk.DFK_REDUCE_TICKET, dfk.DFK_REDUCE_ATOMIC}
     assert any(c.kmajor == 3 for c in cfgs) == (M > 32 and d // 128 >= 8)   # its down kernel runs eight wavefronts
@@ -860,3 +863,37 @@ def test_chained_layers_teacher_forced():
                 assert rel_err(y64(ys[l]), ref) <= TOL_BF16, (M, l)
         finally:
             dfk.dfk_set_workspace(None)
+
+
+def test_wait_of_the_single_launch_with_both_kernels_is_bounded_and_fails_loudly():
+    """The down workgroups of the launch that holds both kernels' workgroups (kmajor = 4) poll a counter of the
+    gate/up workgroups; the number of polls is bounded.  With the bound forced to zero from the host every
+    workgroup that has to wait gives up at once: the launch must still end, and what such a workgroup contributes
+    must be NaN, never a plausible number.  The counters are then out of step with a launch that ran to its end, so
+    the workspace is cleared before the next, ordinary call, which must match the oracle again."""
+    import os
+    M, d, ff = 4, 4096, 14336
+    g = di.mlp_inputs_torch(M, d, ff, seed=83, device=DEV)
+    host = {k: di.to_numpy(v) for k, v in g.items()}
+    ref = oracle.swiglu_mlp(host["X"], host["Wg"], host["Wu"], host["Wd"])
+    ws = dfk.new_workspace(M, d, ff, DEV)
+    cfg = next(c for c in _cfgs(M, d, ff, lambda c: c.kmajor == 4 and c.reduce == dfk.DFK_REDUCE_TICKET))
+    os.environ["DFK_DEBUG_SPIN_LIMIT"] = "0"
+    try:
+        print("case bounded wait", cfg, flush=True)
+        Y = torch.zeros_like(g["X"])
+        dfk.dfk_swiglu_mlp_ex(g["X"], g["Wg"], g["Wu"], g["Wd"], Y, cfg, ws)
+        torch.cuda.synchronize()                     # the launch ended
+    finally:
+        del os.environ["DFK_DEBUG_SPIN_LIMIT"]
+    got = y64(Y)
+    finite = np.isfinite(got)
+    cols = finite.all(axis=0)                        # a column is either given up (NaN) or exact
+    print("columns given up:", int((~cols).sum()), "of", d, flush=True)
+    if cols.any():
+        assert rel_err(got[:, cols], ref[:, cols]) <= TOL_BF16
+    ws.zero_()
+    torch.cuda.synchronize()
+    Y, _ = run_ex(g, cfg, ws)
+    assert_parity(y64(Y), ref, "bf16", ("after the forced give-up", cfg))
+    assert workspace_is_clean(ws, M, d)
