@@ -62,7 +62,15 @@ def committed_traffic():
         return None, None, None
 
 
-VARIANT_NAME = {1: "single launch (fused)", 2: "two kernels"}
+def variant_name(variant, kmajor):
+    """What ran, in words: the two single-launch kernels differ in where A_2 lives."""
+    if variant == 2:
+        return "two kernels"
+    if kmajor == 4:
+        return "single launch (both kernels' workgroups, A_2 through device memory)"
+    if kmajor == 1:
+        return "single launch (fused, A_2 in LDS)"
+    return "single launch (fused)"
 
 
 def stats_4x50(torch, np, fn, n_sets):
@@ -140,7 +148,7 @@ def decode32(args, torch, di, dfk, dev, compact=False):
         c, tuned = dfk.dfk_get_choice(M, D_MODEL, D_FF, dfk.DFK_BF16)
         rows[str(M)] = {"us_per_layer_in_graph": round(us_layer, 2),
                         "tb_per_s": round(algorithmic_bytes(M, D_MODEL, D_FF) / us_layer / 1e6, 3),
-                        "replays_match_eager_layer0": ok, "variant": VARIANT_NAME[c.variant],
+                        "replays_match_eager_layer0": ok, "variant": variant_name(c.variant, c.kmajor),
                         "pick": dict(c.as_dict(), tuned=tuned)}
         del graph
     out = {"workload": "decode32: 32 chained llama3-8b-shaped layers, HIP graph replay; a layer's time includes "
@@ -264,7 +272,7 @@ def shapes(args, torch, di, dfk, dev, compact=False):
             c, tuned = dfk.dfk_get_choice(M, d, ff, dfk.DFK_BF16)
             rows[str(M)] = {"us_per_call": round(us, 2), "tb_per_s": round(algorithmic_bytes(M, d, ff) / us / 1e6, 3),
                             "frac_of_8tbs": round(algorithmic_bytes(M, d, ff) / us / 1e6 / 8.0, 4),
-                            "variant": VARIANT_NAME[c.variant], "pick": dict(c.as_dict(), tuned=tuned)}
+                            "variant": variant_name(c.variant, c.kmajor), "pick": dict(c.as_dict(), tuned=tuned)}
         out[name] = {"d_model": d, "d_ff": ff, "per_M": rows}
         del sets, ws
         torch.cuda.empty_cache()
@@ -273,6 +281,73 @@ def shapes(args, torch, di, dfk, dev, compact=False):
     if compact:
         return res
     print(json.dumps(res))
+
+
+def timeline(args, torch, di, dfk, dev):
+    """Where the microseconds of a call go: the kernels' own time stamps (wall clock, 10 ns ticks, written by thread
+    0 of every workgroup into the buffer given to dfk_set_trace_buffer) for one call of each kernel form on the
+    headline shape, after warm-up calls on rotating weight sets; percentiles over the workgroups, in microseconds
+    from the first workgroup's start."""
+    import numpy as np
+    d, ff = D_MODEL, D_FF
+    forms = [
+        ("single launch, A_2 in LDS (k_fused_local), atomic",
+         dict(variant=1, kmajor=1, splits=256, waves=8, depth=3, reduce=1, k2_splits=0, k2_col_blocks=0),
+         ((0, "start"), (2, "stage one streamed (wave 0)"), (3, "A_2 in LDS"), (4, "stage two streamed (wave 0)"),
+          (5, "adds issued and drained"), (6, "arrived"), (7, "Y written (last workgroup)"))),
+        ("single launch of both kernels' workgroups (k_roles_km), atomic; rows of the down workgroups follow those of the gate/up workgroups",
+         dict(variant=1, kmajor=4, splits=256, waves=8, depth=4, reduce=1, k2_splits=16, k2_col_blocks=16),
+         ((0, "gate/up start"), (2, "gate/up streamed (wave 0)"), (1, "A_2 stored"), (3, "down start"), (7, "down: wait over"),
+          (4, "down streamed (wave 0)"))),
+        ("same, counter reduction",
+         dict(variant=1, kmajor=4, splits=256, waves=8, depth=4, reduce=0, k2_splits=16, k2_col_blocks=16),
+         ((0, "gate/up start"), (1, "A_2 stored"), (3, "down start"), (7, "down: wait over"), (4, "down streamed (wave 0)"),
+          (5, "partial sums published"), (6, "reduced / exit"))),
+        ("two kernels (k_gateup_km, k_down_km), atomic",
+         dict(variant=2, kmajor=1, splits=256, waves=8, depth=4, reduce=1, k2_splits=8, k2_col_blocks=32),
+         ((0, "gate/up start"), (2, "gate/up streamed (wave 0)"), (1, "A_2 stored"), (3, "down start"), (4, "down streamed (wave 0)"))),
+        ("same, counter reduction",
+         dict(variant=2, kmajor=1, splits=256, waves=8, depth=4, reduce=0, k2_splits=8, k2_col_blocks=32),
+         ((0, "gate/up start"), (1, "A_2 stored"), (3, "down start"), (4, "down streamed (wave 0)"), (5, "partial sums published"),
+          (6, "reduced / exit"))),
+    ]
+    out = []
+    for M in (1, 16):
+        L = [di.mlp_inputs_torch(M, d, ff, seed=0, layer=l, device=dev) for l in range(3)]
+        ws = dfk.new_workspace(M, d, ff, dev)
+        for name, f, stamps in forms:
+            c = dfk.dfk_config_t()
+            c.path, c.a2_dtype, c.k2_rows_by_wave = dfk.DFK_PATH_MFMA, dfk.DFK_BF16, 0
+            for k, v in f.items():
+                setattr(c, k, v)
+            if not dfk.dfk_config_valid(c, M, d, ff):
+                continue
+            tr = torch.zeros(1024 * 8, dtype=torch.int64, device=dev)
+            Y = torch.empty_like(L[0]["X"])
+            for i in range(6):
+                w = L[i % 3]
+                if i == 5:
+                    tr.zero_()
+                    dfk.dfk_set_trace_buffer(tr)
+                dfk.dfk_swiglu_mlp_ex(w["X"], w["Wg"], w["Wu"], w["Wd"], Y, c, ws)
+            torch.cuda.synchronize()
+            dfk.dfk_set_trace_buffer(None)
+            t = tr.cpu().numpy().reshape(-1, 8).astype(np.float64)
+            t[t == 0] = np.nan
+            us = (t - np.nanmin(t[:, 0])) / 100.0
+            rows = {}
+            for k, label in stamps:
+                col = us[:, k]
+                col = col[~np.isnan(col)]
+                if col.size:
+                    rows[label] = {"workgroups": int(col.size), "min": round(float(col.min()), 2),
+                                   "p10": round(float(np.percentile(col, 10)), 2), "median": round(float(np.median(col)), 2),
+                                   "p90": round(float(np.percentile(col, 90)), 2), "max": round(float(col.max()), 2)}
+            out.append({"M": M, "form": name, "config": c.as_dict(), "us_from_first_start": rows})
+        del L, ws
+    print(json.dumps({"workload": "timeline: in-kernel time stamps of one call per kernel form, llama3-8b-shaped layer",
+                      "note": "the stamps cost a little: a traced call runs about 1 us longer than an untraced one",
+                      "timelines": out}))
 
 
 def main():
@@ -287,11 +362,12 @@ def main():
     ap.add_argument("--tuning-file", default=None,
                     help="load the scheduler table from this file if it exists, else tune and save it there")
     ap.add_argument("--force", choices=["auto", "fused", "unfused"], default="auto")
-    ap.add_argument("--workload", choices=["layer", "decode32", "block32", "shapes"], default="layer",
+    ap.add_argument("--workload", choices=["layer", "decode32", "block32", "shapes", "timeline"], default="layer",
                     help="layer (default): the headline workload; decode32: 32 chained distinct layers of the "
                          "same shape, captured once in a HIP graph and replayed, M swept 1..256; block32: the "
                          "same chain with RMS normalisation and residual add, folded into the block's launches "
-                         "or as separate launches; shapes: the other layer shapes of the workload list")
+                         "or as separate launches; shapes: the other layer shapes of the workload list; timeline: "
+                         "the kernels' own time stamps of one call per kernel form")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU by design (one MI355X); run with --gpus 1. "
@@ -312,6 +388,8 @@ def main():
         return block32(args, torch, di, dfk, dev)
     if args.workload == "shapes":
         return shapes(args, torch, di, dfk, dev)
+    if args.workload == "timeline":
+        return timeline(args, torch, di, dfk, dev)
     M_WIDE = M_SET + (32, 64)            # the metric is quoted on M = 1..64; the target on M = 1..16
     M_ALL = M_WIDE + (128, 256)
     Mmax = max(M_ALL)
@@ -333,9 +411,9 @@ def main():
         t0 = time.perf_counter()
         scratch = torch.empty(dfk.dfk_tune_scratch_bytes(Mmax, D_MODEL, D_FF, dfk.DFK_BF16, 3),
                               dtype=torch.uint8, device=dev)
-        dfk.dfk_tune(list(M_SET), D_MODEL, D_FF, dfk.DFK_BF16, scratch, sets=3, iters=12)
+        dfk.dfk_tune(list(M_SET), D_MODEL, D_FF, dfk.DFK_BF16, scratch, sets=3, iters=20)
         skipped += dfk.dfk_tune_skipped()[0]
-        dfk.dfk_tune([32, 64, 128, 256], D_MODEL, D_FF, dfk.DFK_BF16, scratch, sets=3, iters=8)
+        dfk.dfk_tune([32, 64, 128, 256], D_MODEL, D_FF, dfk.DFK_BF16, scratch, sets=3, iters=12)
         skipped += dfk.dfk_tune_skipped()[0]
         torch.cuda.synchronize()
         del scratch
@@ -387,7 +465,7 @@ def main():
         st = stats_4x50(torch, np, lambda i, M=M: call(X[M], layers[i]["Wg"], layers[i]["Wu"], layers[i]["Wd"], Y[M]), WEIGHT_SETS)
         b = algorithmic_bytes(M, D_MODEL, D_FF)
         per_m[str(M)] = dict(st, tb_per_s=round(b / st["mean_us"] / 1e6, 3), frac_of_peak=round(b / st["mean_us"] / 1e3 / HBM_PEAK_GBS, 4),
-                             variant=VARIANT_NAME[picks[str(M)]["variant"]] if args.force == "auto" else args.force)
+                             variant=variant_name(picks[str(M)]["variant"], picks[str(M)]["kmajor"]) if args.force == "auto" else args.force)
     mean_wide = float(np.mean([per_m[str(M)]["mean_us"] for M in M_WIDE]))
     frac_wide = float(np.mean([per_m[str(M)]["frac_of_peak"] for M in M_WIDE]))
 
@@ -451,9 +529,17 @@ def main():
     kernels = {}
     for M in M_WIDE:
         c, _ = dfk.dfk_get_choice(M, D_MODEL, D_FF, dfk.DFK_BF16)
-        us1, us2 = dfk.dfk_time_kernels(c, M, D_MODEL, D_FF, dfk.DFK_BF16, scratch, sets=3, iters=max(30, args.steps // 4))
+        iters = max(30, args.steps // 4)
+        us1, us2 = dfk.dfk_time_kernels(c, M, D_MODEL, D_FF, dfk.DFK_BF16, scratch, sets=3, iters=iters)
         kernels[str(M)] = {"first_launch_us": round(us1, 2), "second_launch_us": round(us2, 2),
-                           "variant": VARIANT_NAME[c.variant]}
+                           "variant": variant_name(c.variant, c.kmajor)}
+        if c.variant == dfk.DFK_VARIANT_FUSED and c.kmajor == 4:
+            # one launch that holds the workgroups of both kernels: the launch as a whole, and beside it its two
+            # parts launched alone (gate/up workgroups only; down workgroups only, waiting for nobody)
+            whole_us = dfk.dfk_time_config(c, M, D_MODEL, D_FF, dfk.DFK_BF16, scratch, sets=3, iters=iters)
+            kernels[str(M)] = {"first_launch_us": round(whole_us, 2), "second_launch_us": 0.0,
+                               "gateup_workgroups_alone_us": round(us1, 2), "down_workgroups_alone_us": round(us2, 2),
+                               "variant": variant_name(c.variant, c.kmajor)}
     del scratch
 
     # ---- roofline.  The bound is HBM.  `frac` is the whole call: algorithmic bytes of a call (three matrices
@@ -529,7 +615,7 @@ def main():
         extras["shapes"] = shapes(args, torch, di, dfk, dev, compact=True)
         extras["decode32"] = decode32(args, torch, di, dfk, dev, compact=True)
 
-    variant_per_m = {str(M): (VARIANT_NAME[picks[str(M)]["variant"]] if args.force == "auto" else args.force) for M in M_SET}
+    variant_per_m = {str(M): (variant_name(picks[str(M)]["variant"], picks[str(M)]["kmajor"]) if args.force == "auto" else args.force) for M in M_SET}
     names = sorted(set(variant_per_m.values()))
     out = {
         "metric": "SwiGLU MLP us/call (" + ("scheduler's pick per M: " + ", ".join(

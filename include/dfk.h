@@ -284,7 +284,8 @@ size_t dfk_tune_scratch_bytes(int M_max, int d_model, int d_ff, dfk_dtype_t dtyp
 
 /*
  * Time every candidate for each M in M_list on the current device and record
- * the fastest.  scratch is caller-owned device memory of at least
+ * the fastest, and beside it the fastest of each variant (what dfk_swiglu_mlp_fused
+ * and dfk_swiglu_mlp_unfused, which ask for a variant, then use).  scratch is caller-owned device memory of at least
  * dfk_tune_scratch_bytes(max M, ...) bytes; its previous contents are
  * overwritten with synthetic values.  iters timed launches per candidate
  * (after 2 warm-ups), rotating over `sets` weight copies.  Synchronises
@@ -320,14 +321,16 @@ dfk_status_t dfk_time_kernels(const dfk_config_t* cfg, int M, int d_model, int d
 dfk_status_t dfk_get_choice(int M, int d_model, int d_ff, dfk_dtype_t dtype,
                             dfk_config_t* out, int* tuned_out);
 
-/* Enter / overwrite a table entry by hand (usec <= 0 means unknown). */
+/* Enter / overwrite a table entry by hand (usec <= 0 means unknown): cfg becomes the choice for the
+ * problem and the entry of its variant. */
 dfk_status_t dfk_set_choice(int M, int d_model, int d_ff, dfk_dtype_t dtype,
                             const dfk_config_t* cfg, double usec);
 
 /* Forget all tuned entries. */
 void dfk_clear_tuning(void);
 
-/* Persist / reload the table (plain text, one entry per line). */
+/* Persist / reload the table (plain text, one entry per line; where a problem has entries of both
+ * variants the chosen one is written last, and a loader takes a problem's last line as its choice). */
 dfk_status_t dfk_save_tuning(const char* path);
 dfk_status_t dfk_load_tuning(const char* path);
 

@@ -265,8 +265,14 @@ struct Entry {
     dfk_config_t cfg;
     double usec;
 };
-using Key = std::tuple<int, int, int, int>;  // M, d_model, d_ff, dtype
+// M, d_model, d_ff, dtype, slot.  Slot 0 holds the choice for the problem; slots DFK_VARIANT_FUSED and
+// DFK_VARIANT_TWO_KERNEL the best known configuration of that variant (what a call that asks for a variant gets).
+using Key = std::tuple<int, int, int, int, int>;
 std::map<Key, Entry> g_table;
+void table_put(int M, int d_model, int d_ff, int dtype, const Entry& e, bool chosen) {   // g_mu held
+    g_table[Key(M, d_model, d_ff, dtype, e.cfg.variant)] = e;
+    if (chosen) g_table[Key(M, d_model, d_ff, dtype, 0)] = e;
+}
 
 int m_bucket(int M) {
     int b = 1;
@@ -277,10 +283,9 @@ int m_bucket(int M) {
 bool lookup(int M, int d_model, int d_ff, dfk_dtype_t dtype, int want_variant, dfk_config_t* out) {
     std::lock_guard<std::mutex> lk(g_mu);
     for (int m : {M, m_bucket(M)}) {
-        auto it = g_table.find(Key(m, d_model, d_ff, (int)dtype));
+        auto it = g_table.find(Key(m, d_model, d_ff, (int)dtype, want_variant == DFK_VARIANT_AUTO ? 0 : want_variant));
         if (it == g_table.end()) continue;
         const dfk_config_t& c = it->second.cfg;
-        if (want_variant != DFK_VARIANT_AUTO && c.variant != want_variant) continue;
         if (!config_valid(c, M, d_model, d_ff, dtype)) continue;
         *out = c;
         return true;
@@ -741,8 +746,8 @@ dfk_status_t dfk_tune(const int* M_list, int nM, int d_model, int d_ff, dfk_dtyp
         const int M = M_list[i];
         auto cands = candidates(M, d_model, d_ff, dtype);
         if (cands.empty()) return DFK_ERR_UNSUPPORTED_SHAPE;
-        Entry best;
-        best.usec = -1.0;
+        Entry best, best_of[3];
+        best.usec = best_of[1].usec = best_of[2].usec = -1.0;
         bool fill = true;  // scratch layout depends on M: refill once per M (until a candidate has run)
         for (const auto& c : cands) {
             double us = 0.0;
@@ -755,10 +760,14 @@ dfk_status_t dfk_tune(const int* M_list, int nM, int d_model, int d_ff, dfk_dtyp
             }
             fill = false;
             if (best.usec < 0.0 || us < best.usec) { best.cfg = c; best.usec = us; }
+            Entry& bv = best_of[c.variant == DFK_VARIANT_FUSED ? 1 : 2];
+            if (bv.usec < 0.0 || us < bv.usec) { bv.cfg = c; bv.usec = us; }
         }
         if (best.usec < 0.0) return g_tune_skip_status;   // every candidate of this M failed
         std::lock_guard<std::mutex> lk(g_mu);
-        g_table[Key(M, d_model, d_ff, (int)dtype)] = best;
+        for (int v = 1; v <= 2; ++v)
+            if (best_of[v].usec >= 0.0) table_put(M, d_model, d_ff, (int)dtype, best_of[v], false);
+        table_put(M, d_model, d_ff, (int)dtype, best, true);
     }
     return DFK_OK;
 }
@@ -786,7 +795,7 @@ dfk_status_t dfk_set_choice(int M, int d_model, int d_ff, dfk_dtype_t dtype, con
     Entry e;
     e.cfg = *cfg;
     e.usec = usec;
-    g_table[Key(M, d_model, d_ff, (int)dtype)] = e;
+    table_put(M, d_model, d_ff, (int)dtype, e, true);
     return DFK_OK;
 }
 
@@ -802,13 +811,25 @@ dfk_status_t dfk_save_tuning(const char* path) {
     if (!f) return DFK_ERR_IO;
     std::fprintf(f, "# dfk tuning table v2: M d_model d_ff dtype variant path splits waves depth reduce "
                     "k2_splits k2_col_blocks a2_dtype k2_rows_by_wave kmajor usec\n");
-    for (const auto& kv : g_table) {
-        const dfk_config_t& c = kv.second.cfg;
-        std::fprintf(f, "%d %d %d %d %d %d %d %d %d %d %d %d %d %d %d %.3f\n", std::get<0>(kv.first),
-                     std::get<1>(kv.first), std::get<2>(kv.first), std::get<3>(kv.first), c.variant,
-                     c.path, c.splits, c.waves, c.depth, c.reduce, c.k2_splits, c.k2_col_blocks,
-                     c.a2_dtype, c.k2_rows_by_wave, c.kmajor, kv.second.usec);
-    }
+    // One line per entry; a problem's chosen configuration comes after its other variant's line, and the loader
+    // takes the last line of a problem as the choice.
+    for (int pass = 0; pass < 2; ++pass)
+        for (const auto& kv : g_table) {
+            const int slot = std::get<4>(kv.first);
+            const dfk_config_t& c = kv.second.cfg;
+            if (pass == 0) {
+                if (slot == 0) continue;
+                auto chosen = g_table.find(Key(std::get<0>(kv.first), std::get<1>(kv.first), std::get<2>(kv.first),
+                                               std::get<3>(kv.first), 0));
+                if (chosen != g_table.end() && same_cfg(chosen->second.cfg, c)) continue;   // written in the second pass
+            } else if (slot != 0) {
+                continue;
+            }
+            std::fprintf(f, "%d %d %d %d %d %d %d %d %d %d %d %d %d %d %d %.3f\n", std::get<0>(kv.first),
+                         std::get<1>(kv.first), std::get<2>(kv.first), std::get<3>(kv.first), c.variant,
+                         c.path, c.splits, c.waves, c.depth, c.reduce, c.k2_splits, c.k2_col_blocks,
+                         c.a2_dtype, c.k2_rows_by_wave, c.kmajor, kv.second.usec);
+        }
     const bool ok = std::fclose(f) == 0;
     return ok ? DFK_OK : DFK_ERR_IO;
 }
@@ -817,7 +838,7 @@ dfk_status_t dfk_load_tuning(const char* path) {
     if (!path) return DFK_ERR_INVALID_ARG;
     FILE* f = std::fopen(path, "r");
     if (!f) return DFK_ERR_IO;
-    std::map<Key, Entry> fresh;
+    std::vector<std::pair<Key, Entry>> fresh;   // in file order
     char line[512];
     dfk_status_t rc = DFK_OK;
     while (std::fgets(line, sizeof line, f)) {
@@ -836,12 +857,13 @@ dfk_status_t dfk_load_tuning(const char* path) {
             rc = DFK_ERR_IO;
             break;
         }
-        fresh[Key(M, dm, df, dt)] = e;
+        fresh.emplace_back(Key(M, dm, df, dt, 0), e);
     }
     std::fclose(f);
     if (rc != DFK_OK) return rc;  // table left untouched on a malformed file
     std::lock_guard<std::mutex> lk(g_mu);
-    for (const auto& kv : fresh) g_table[kv.first] = kv.second;
+    for (const auto& kv : fresh)
+        table_put(std::get<0>(kv.first), std::get<1>(kv.first), std::get<2>(kv.first), std::get<3>(kv.first), kv.second, true);
     return DFK_OK;
 }
 
