@@ -19,9 +19,10 @@
 // threads of the workgroup finish SiLU(G)*U and store A_2 to the workspace.
 //
 // Down kernel (Y = A_2 W_down): workgroup (js, cb) owns CB adjacent 128-column blocks
-// over d_ff split js, its wavefronts divide the split's 32-row blocks.  Per 32-row
-// block the stream holds one A_2 tile ([token][8 rows] per lane, the MFMA A operand)
-// and then two W_down tiles per column block, regrouped per lane with v_perm_b32.
+// over d_ff split js, its wavefronts divide the split's 32-row blocks.  Per pair of 32-row
+// blocks the stream holds the A_2 tiles (64 rows x 32 tokens: whole 128-byte lines per token;
+// [token][8 rows] per lane is the MFMA A operand) and then two W_down tiles per block and
+// column block, regrouped per lane with v_perm_b32.
 // The end (per-wavefront LDS stages, ticket or atomic reduction) is that of
 // k_down_rows, one token tile at a time.
 //
@@ -309,6 +310,10 @@ __global__ __launch_bounds__(NW * 64) void k_gateup_km(MlpArgs a, KmGeom geo) {
 // ---------------------------------------------------------------- down kernel
 template <int NW, int TT>
 struct KmStream2 {
+    // A_2 travels in tiles of 64 d_ff rows x 32 tokens: per token 128 contiguous bytes, one whole cache line per
+    // request (a 32-row tile would be 64-byte pieces, twice the requests for the same bytes).  One tile serves
+    // two 32-row blocks; NA tiles cover the launch's token tiles.
+    static constexpr int NA = TT > 2 ? 2 : 1;
     const char *Wd, *A2;
     size_t row_bytes;          // d_model * 2
     size_t a2_row_bytes;       // d_ff * 2
@@ -320,23 +325,32 @@ struct KmStream2 {
     unsigned off2;
     unsigned char* ring;
     int depth, T, issued, issue_slot, take_slot;
-    int p_jbi, p_idx;          // producer: 32-row block, position in it (A tile, then 2 tiles per column block)
-    int a_pos;                 // position of the A tile in a 32-row block: 0, or 2 CB = behind the weight tiles
+    int p_grp, p_idx;          // producer: pair of 32-row blocks, position in the pair's tile sequence
+    int a_pos;                 // position of the pair's A tiles: 0, or 2 CB = behind the first block's weight tiles
 
     __device__ __forceinline__ void issue() {
         unsigned char* slot = ring + issue_slot * kTileBytes;
-        const int jb = jb_lo + p_jbi;
-        if (p_idx == a_pos) {  // A tile: instruction u = token tile; lane (q, g): token q, rows 8g .. 8g+7 of the block
-            const int j = min(jb * 32 + 8 * g, rows - 8);   // past the split: any valid address (masked at use)
+        const int jb0 = jb_lo + 2 * p_grp;
+        const bool two = 2 * p_grp + 1 < njb;
+        if (p_idx >= a_pos && p_idx < a_pos + NA) {
+            // A tile `half`: instruction u = tokens 32 half + 8u .. +7; lanes 8t .. 8t+7 = the 128 bytes of token t,
+            // the 16-byte chunks of odd tokens swapped by four so that the operand reads spread over the banks
+            const int half = p_idx - a_pos;
+            const int lane = 16 * g + q;
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int token = min(min(u, TT - 1) * 16 + q, m_count - 1);
+                const int tl = 32 * half + 8 * u + (lane >> 3);
+                const int chunk = (lane & 7) ^ ((tl & 1) << 2);
+                const int token = min(min(tl, 16 * TT - 1), m_count - 1);
+                const int j = min(jb0 * 32 + 8 * chunk, rows - 8);   // past the split: any valid address (masked at use)
                 const char* src = A2 + a2_base + (size_t)token * a2_row_bytes + (size_t)j * 2;
                 __builtin_amdgcn_global_load_lds(src, DFK_LDS_PTR(slot + u * 1024), 16, 0, 0);
             }
         } else {
-            const int wi = p_idx - (p_idx > a_pos ? 1 : 0);  // index among the block's weight tiles
-            const int b = wi >> 1, h = wi & 1;
+            const int wi = p_idx - (p_idx > a_pos ? NA : 0);   // index among the pair's weight tiles
+            const int jb = jb0 + (wi >= 2 * CB ? 1 : 0);
+            const int wj = wi - (wi >= 2 * CB ? 2 * CB : 0);
+            const int b = wj >> 1, h = wj & 1;
             const int row0 = j0 + jb * 32 + 4 * h;           // lane adds 8g + u
             const size_t colb = (size_t)(blk_first + b) * 256;
             if (row0 + 28 <= d_ff) {
@@ -354,15 +368,15 @@ struct KmStream2 {
                 }
             }
         }
-        if (++p_idx == 1 + 2 * CB) { p_idx = 0; ++p_jbi; }
+        if (++p_idx == NA + 2 * CB * (two ? 2 : 1)) { p_idx = 0; ++p_grp; }
         ++issued;
         if (++issue_slot == depth) issue_slot = 0;
     }
     // limit: most tiles to request now (the single launch holds back the first A tile until A_2 is complete)
     __device__ __forceinline__ void start(const int limit) {
         off2 = (unsigned)(8 * g * row_bytes + 16 * q);
-        T = njb * (1 + 2 * CB);
-        issued = 0; issue_slot = 0; take_slot = 0; p_jbi = 0; p_idx = 0;
+        T = ((njb + 1) / 2) * NA + njb * 2 * CB;
+        issued = 0; issue_slot = 0; take_slot = 0; p_grp = 0; p_idx = 0;
         const int ahead = min(min(depth - 1, T), limit);
         for (int i = 0; i < ahead; ++i) issue();
     }
@@ -423,12 +437,16 @@ __device__ __forceinline__ void down_km_body(const MlpArgs& a, const KmGeom& geo
     const int depth = WAIT ? geo.depth_down : geo.depth;
     ts.ring = lds + wave * depth * kTileBytes;
     ts.depth = depth;
-    ts.a_pos = WAIT ? 2 * CB : 0;
+    // the single launch: with one token tile every column block's weight tiles of a pair's first block precede the
+    // A tiles (more to request before the wait); with more token tiles only the first column block's (registers)
+    constexpr int PRE = TT == 1 ? CBM : 1;
+    const int pre = min(PRE, CB);
+    ts.a_pos = WAIT ? 2 * pre : 0;
     DFK_STAMP(3);
     bool gave_up = false;
     unsigned passed_before = 0;
     if (WAIT) {
-        ts.start(2 * CB);                  // the first 32-row block's weight tiles: nothing of A_2 yet
+        ts.start(2 * pre);                 // weight tiles only: nothing of A_2 yet
         if (geo.role_wait > 0) {
             if (tid == 0) {
                 int polls = 0, ok = 1;
@@ -463,19 +481,29 @@ __device__ __forceinline__ void down_km_body(const MlpArgs& a, const KmGeom& geo
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) acc2[b][c][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    for (int jbi = 0; jbi < njb; ++jbi) {
-        const int jb = jb_lo + jbi;
-        u32x4 av[TT];          // A operand: A_2[token q of tile tt][rows 8g .. 8g+7 of the block]
+    for (int grp = 0; 2 * grp < njb; ++grp) {
+        const int jb0 = jb_lo + 2 * grp;
+        const bool two = 2 * grp + 1 < njb;
+        u32x4 av[2][TT];       // A operands of the pair's two blocks: A_2[token q of tile tt][rows 8g .. 8g+7 of the block]
         auto take_a = [&]() {
-            const unsigned char* slot = ts.acquire();
-            const bool past = jb * 32 + 8 * g >= rows;
 #pragma unroll
-            for (int tt = 0; tt < TT; ++tt) {
-                const u32x4 v = *(const u32x4*)(slot + tt * 1024 + lane * 16);
-                av[tt] = past ? u32x4{0, 0, 0, 0} : v;
+            for (int half = 0; half < KmStream2<NW, TT>::NA; ++half) {
+                const unsigned char* slot = ts.acquire();
+#pragma unroll
+                for (int t2 = 0; t2 < 2; ++t2) {
+                    const int tt = 2 * half + t2;
+                    if (tt < TT) {
+#pragma unroll
+                        for (int h = 0; h < 2; ++h) {
+                            const int idx = (2 * t2 + (q >> 3)) * 64 + (q & 7) * 8 + ((4 * h + g) ^ ((q & 1) << 2));
+                            const u32x4 v = *(const u32x4*)(slot + idx * 16);
+                            av[h][tt] = (jb0 + h) * 32 + 8 * g >= rows ? u32x4{0, 0, 0, 0} : v;
+                        }
+                    }
+                }
             }
         };
-        auto take_w = [&](u32x4 (&w)[8]) {
+        auto take_w = [&](const int jb, u32x4 (&w)[8]) {
             const unsigned char* sa = ts.acquire();
 #pragma unroll
             for (int u = 0; u < 4; ++u) w[u] = *(const u32x4*)(sa + u * 1024 + lane * 16);
@@ -488,7 +516,7 @@ __device__ __forceinline__ void down_km_body(const MlpArgs& a, const KmGeom& geo
                     if (jb * 32 + 8 * g + r >= rows) w[r] = u32x4{0, 0, 0, 0};
             }
         };
-        auto multiply = [&](const int b, const u32x4 (&w)[8]) {
+        auto multiply = [&](const int b, const int h, const u32x4 (&w)[8]) {
 #pragma unroll
             for (int c = 0; c < 8; ++c) {
                 const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
@@ -497,26 +525,44 @@ __device__ __forceinline__ void down_km_body(const MlpArgs& a, const KmGeom& geo
                 for (int p = 0; p < 4; ++p) bb[p] = __builtin_amdgcn_perm(w[2 * p + 1][c >> 1], w[2 * p][c >> 1], sel);
 #pragma unroll
                 for (int tt = 0; tt < TT; ++tt)
-                    acc2[b][c][tt] = mfma16<E>(av[tt], bb, acc2[b][c][tt]);
+                    acc2[b][c][tt] = mfma16<E>(av[h][tt], bb, acc2[b][c][tt]);
             }
         };
-        if (WAIT) {            // the block's weight tiles come first in the stream, its A tile last
-            u32x4 w[CBM][8];
+        if (WAIT) {            // weight tiles of the first block's first `pre` column blocks come first in the stream, then the pair's A tiles
+            u32x4 w[PRE][8];
 #pragma unroll
-            for (int b = 0; b < CBM; ++b)
-                if (b < CB) take_w(w[b]);
+            for (int b = 0; b < PRE; ++b)
+                if (b < pre) take_w(jb0, w[b]);
             take_a();
 #pragma unroll
-            for (int b = 0; b < CBM; ++b)
-                if (b < CB) multiply(b, w[b]);
+            for (int b = 0; b < PRE; ++b)
+                if (b < pre) multiply(b, 0, w[b]);
+#pragma unroll
+            for (int b = PRE; b < CBM; ++b) {
+                if (b < CB) {
+                    u32x4 w2[8];
+                    take_w(jb0, w2);
+                    multiply(b, 0, w2);
+                }
+            }
         } else {
             take_a();
 #pragma unroll
             for (int b = 0; b < CBM; ++b) {
                 if (b < CB) {
                     u32x4 w[8];
-                    take_w(w);
-                    multiply(b, w);
+                    take_w(jb0, w);
+                    multiply(b, 0, w);
+                }
+            }
+        }
+        if (two) {
+#pragma unroll
+            for (int b = 0; b < CBM; ++b) {
+                if (b < CB) {
+                    u32x4 w[8];
+                    take_w(jb0 + 1, w);
+                    multiply(b, 1, w);
                 }
             }
         }
