@@ -117,6 +117,11 @@ typedef enum { DFK_REDUCE_TICKET = 0, DFK_REDUCE_ATOMIC = 1 } dfk_reduce_t;
  *                  8), depth = 3 or 4 (buffers of shared tiles), k2_col_blocks = d_model / 128;
  *                  with DFK_REDUCE_TICKET the splits' partial sums are added by a third, small
  *                  launch;
+ *                  5 = gate/up kernel of pair 1, then a down kernel that takes W_down as
+ *                  [d_model, d_ff] (dfk_swiglu_mlp_wdt only): k2_splits workgroups own a slice of
+ *                  d_model each (whole 16-row tiles, at most 8 per workgroup), k2_col_blocks = 1,
+ *                  reduce = DFK_REDUCE_TICKET (nothing is reduced across workgroups; the result
+ *                  is deterministic), up to 64 tokens per launch;
  *                  3 = gate/up kernel of pair 2 with four wavefronts of one token tile each,
  *                  down kernel of pair 1 (offered for 33..64 tokens; waves = 8, depth = 3 or 4,
  *                  the constraints of both pairs).
@@ -185,6 +190,28 @@ dfk_status_t dfk_swiglu_mlp_ex(const void* X, const void* W_gate, const void* W_
                                int M, int d_model, int d_ff, dfk_dtype_t dtype,
                                const dfk_config_t* cfg,
                                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * dfk_swiglu_mlp_ex with the down projection's weights given as W_down_t [d_model, d_ff], row n = column n of
+ * the paper's W_down (Background, SwiGLU equations: Y = A_2 W_down): the [out, in] layout a linear layer's
+ * weights are stored in, and the layout W_gate and W_up already have here.  Same result.  In this layout a
+ * workgroup of the down kernel owns a slice of d_model over all of d_ff, so nothing is summed across workgroups
+ * (config field kmajor = 5; 16-bit types, d_model a multiple of 128 and d_ff a multiple of 128 with at least
+ * `waves` 128-k chunks each).  cfg == NULL: the scheduler's choice for this layout (dfk_get_choice_wdt); else
+ * cfg must be a kmajor = 5 configuration (the other entry points reject those, and this one rejects the
+ * others, with DFK_ERR_INVALID_ARG: a configuration belongs to one layout).  Shapes the layout's kernels do
+ * not take: DFK_ERR_UNSUPPORTED_SHAPE.
+ */
+dfk_status_t dfk_swiglu_mlp_wdt(const void* X, const void* W_gate, const void* W_up,
+                                const void* W_down_t, void* Y,
+                                int M, int d_model, int d_ff, dfk_dtype_t dtype,
+                                const dfk_config_t* cfg,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+/* W_down_t [d_model, d_ff] from W_down [d_ff, d_model] (device buffers that do not overlap, 16-byte aligned;
+ * any of the three element types), for callers that hold the other layout.  Asynchronous on `stream`. */
+dfk_status_t dfk_transpose_w_down(const void* W_down, void* W_down_t, int d_model, int d_ff,
+                                  dfk_dtype_t dtype, void* stream);
 
 /*
  * dfk_swiglu_mlp_ex for callers that cannot allocate device memory and therefore have no workspace
@@ -320,6 +347,14 @@ dfk_status_t dfk_time_kernels(const dfk_config_t* cfg, int M, int d_model, int d
  * *tuned_out (may be NULL) is set to 1 if it came from the table. */
 dfk_status_t dfk_get_choice(int M, int d_model, int d_ff, dfk_dtype_t dtype,
                             dfk_config_t* out, int* tuned_out);
+
+/* The same three queries for W_down given as [d_model, d_ff] (dfk_swiglu_mlp_wdt): its candidates (none for
+ * shapes or types its kernels do not take), and the configuration a call would use now.  dfk_tune times these
+ * candidates too and keeps the fastest beside the others. */
+int dfk_num_candidates_wdt(int M, int d_model, int d_ff, dfk_dtype_t dtype);
+dfk_status_t dfk_get_candidate_wdt(int M, int d_model, int d_ff, dfk_dtype_t dtype, int i, dfk_config_t* out);
+dfk_status_t dfk_get_choice_wdt(int M, int d_model, int d_ff, dfk_dtype_t dtype,
+                                dfk_config_t* out, int* tuned_out);
 
 /* Enter / overwrite a table entry by hand (usec <= 0 means unknown): cfg becomes the choice for the
  * problem and the entry of its variant. */

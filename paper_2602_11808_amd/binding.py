@@ -61,6 +61,11 @@ SIGNATURES = [
     ("dfk_swiglu_mlp_fused", _ci, [_vp] * 5 + [_ci] * 3 + [_vp]),
     ("dfk_swiglu_mlp_unfused", _ci, [_vp] * 5 + [_ci] * 3 + [_vp]),
     ("dfk_swiglu_mlp_ex", _ci, [_vp] * 5 + [_ci] * 4 + [_cfgp, _vp, _sz, _vp]),
+    ("dfk_swiglu_mlp_wdt", _ci, [_vp] * 5 + [_ci] * 4 + [_cfgp, _vp, _sz, _vp]),
+    ("dfk_transpose_w_down", _ci, [_vp, _vp, _ci, _ci, _ci, _vp]),
+    ("dfk_num_candidates_wdt", _ci, [_ci] * 4),
+    ("dfk_get_candidate_wdt", _ci, [_ci] * 5 + [_cfgp]),
+    ("dfk_get_choice_wdt", _ci, [_ci] * 4 + [_cfgp, ctypes.POINTER(_ci)]),
     ("dfk_swiglu_mlp_static", _ci, [_vp] * 5 + [_ci] * 4 + [_cfgp, _vp]),
     ("dfk_mlp_block", _ci, [_vp, _vp, ctypes.c_float] + [_vp] * 4 + [_ci] * 4 + [_cfgp, _vp, _sz, _vp]),
     ("dfk_check_args", _ci, [_vp] * 5 + [_ci] * 4 + [_cfgp, _vp, _sz]),
@@ -136,7 +141,7 @@ def _dtype_code(t) -> int:
     raise TypeError(f"dfk takes bfloat16, float16 or float32 tensors, got {t.dtype}")
 
 
-def _shapes(X, W_gate, W_up, W_down, Y):
+def _shapes(X, W_gate, W_up, W_down, Y, wd_t=False):
     for t in (X, W_gate, W_up, W_down, Y):
         if not t.is_cuda:
             raise ValueError("dfk tensors must live in device memory")
@@ -147,8 +152,9 @@ def _shapes(X, W_gate, W_up, W_down, Y):
     M, d_model = X.shape
     d_ff = W_gate.shape[0]
     if tuple(W_gate.shape) != (d_ff, d_model) or tuple(W_up.shape) != (d_ff, d_model) \
-            or tuple(W_down.shape) != (d_ff, d_model) or tuple(Y.shape) != (M, d_model):
-        raise ValueError("expected X,Y [M,d_model] and W_gate,W_up,W_down [d_ff,d_model]")
+            or tuple(W_down.shape) != ((d_model, d_ff) if wd_t else (d_ff, d_model)) or tuple(Y.shape) != (M, d_model):
+        raise ValueError("expected X,Y [M,d_model], W_gate,W_up [d_ff,d_model] and W_down [d_ff,d_model] "
+                         "(W_down_t [d_model,d_ff] for the _wdt entry point)")
     return M, d_model, d_ff
 
 
@@ -178,6 +184,25 @@ def dfk_swiglu_mlp_ex(X, W_gate, W_up, W_down, Y, cfg: Optional[dfk_config_t], w
     _check(lib().dfk_swiglu_mlp_ex(_ptr(X), _ptr(W_gate), _ptr(W_up), _ptr(W_down), _ptr(Y), M, d, ff,
                                    _dtype_code(X), ctypes.byref(cfg) if cfg is not None else None,
                                    _ptr(workspace), nbytes, _stream(stream)), "dfk_swiglu_mlp_ex")
+
+
+def dfk_swiglu_mlp_wdt(X, W_gate, W_up, W_down_t, Y, cfg: Optional[dfk_config_t], workspace, stream=None):
+    """The block with the down projection's weights as W_down_t [d_model, d_ff] (a linear layer's own layout)."""
+    M, d, ff = _shapes(X, W_gate, W_up, W_down_t, Y, wd_t=True)
+    nbytes = workspace.numel() * workspace.element_size()
+    _check(lib().dfk_swiglu_mlp_wdt(_ptr(X), _ptr(W_gate), _ptr(W_up), _ptr(W_down_t), _ptr(Y), M, d, ff,
+                                    _dtype_code(X), ctypes.byref(cfg) if cfg is not None else None,
+                                    _ptr(workspace), nbytes, _stream(stream)), "dfk_swiglu_mlp_wdt")
+
+
+def dfk_transpose_w_down(W_down, W_down_t, stream=None):
+    """W_down_t [d_model, d_ff] = transpose of W_down [d_ff, d_model], on the device."""
+    ff, d = W_down.shape
+    if tuple(W_down_t.shape) != (d, ff) or W_down_t.dtype != W_down.dtype or not W_down.is_cuda or not W_down_t.is_cuda \
+            or not W_down.is_contiguous() or not W_down_t.is_contiguous():
+        raise ValueError("expected dense device tensors W_down [d_ff,d_model] and W_down_t [d_model,d_ff] of one type")
+    _check(lib().dfk_transpose_w_down(_ptr(W_down), _ptr(W_down_t), d, ff, _dtype_code(W_down), _stream(stream)),
+           "dfk_transpose_w_down")
 
 
 def dfk_swiglu_mlp_static(X, W_gate, W_up, W_down, Y, cfg: Optional[dfk_config_t] = None, stream=None):
@@ -250,6 +275,24 @@ def dfk_get_candidate(M, d_model, d_ff, dtype, i) -> dfk_config_t:
     c = dfk_config_t()
     _check(lib().dfk_get_candidate(M, d_model, d_ff, dtype, i, ctypes.byref(c)), "dfk_get_candidate")
     return c
+
+
+def dfk_num_candidates_wdt(M, d_model, d_ff, dtype=DFK_BF16) -> int:
+    return int(lib().dfk_num_candidates_wdt(M, d_model, d_ff, dtype))
+
+
+def dfk_get_candidate_wdt(M, d_model, d_ff, dtype, i) -> dfk_config_t:
+    c = dfk_config_t()
+    _check(lib().dfk_get_candidate_wdt(M, d_model, d_ff, dtype, i, ctypes.byref(c)), "dfk_get_candidate_wdt")
+    return c
+
+
+def dfk_get_choice_wdt(M, d_model, d_ff, dtype=DFK_BF16):
+    c = dfk_config_t()
+    tuned = ctypes.c_int(0)
+    _check(lib().dfk_get_choice_wdt(M, d_model, d_ff, dtype, ctypes.byref(c), ctypes.byref(tuned)),
+           "dfk_get_choice_wdt")
+    return c, bool(tuned.value)
 
 
 def dfk_config_valid(cfg, M, d_model, d_ff, dtype=DFK_BF16) -> bool:

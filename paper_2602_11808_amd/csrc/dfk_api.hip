@@ -58,9 +58,12 @@ bool config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype
     return false;
 }
 
+// configurations whose down kernel takes W_down as [d_model, d_ff]
+bool wdt_layout(const dfk_config_t& c) { return c.path == DFK_PATH_MFMA && c.kmajor == 5; }
+
 dfk_status_t check(const void* X, const void* Wg, const void* Wu, const void* Wd, const void* Y,
                    int M, int d_model, int d_ff, dfk_dtype_t dtype, const dfk_config_t* cfg,
-                   const void* ws, size_t ws_bytes, bool need_ws, bool y_may_be_x = false) {
+                   const void* ws, size_t ws_bytes, bool need_ws, bool y_may_be_x = false, bool wd_t = false) {
     if (!X || !Wg || !Wu || !Wd || !Y) return DFK_ERR_INVALID_ARG;
     if (M < 1 || d_model < 1 || d_ff < 1) return DFK_ERR_INVALID_ARG;
     if (dtype != DFK_BF16 && dtype != DFK_FP32 && dtype != DFK_FP16) return DFK_ERR_INVALID_ARG;
@@ -77,6 +80,7 @@ dfk_status_t check(const void* X, const void* Wg, const void* Wu, const void* Wd
         if (cfg->variant != DFK_VARIANT_FUSED && cfg->variant != DFK_VARIANT_TWO_KERNEL)
             return DFK_ERR_INVALID_ARG;
         if (cfg->path != DFK_PATH_VALU && cfg->path != DFK_PATH_MFMA) return DFK_ERR_INVALID_ARG;
+        if (wdt_layout(*cfg) != wd_t) return DFK_ERR_INVALID_ARG;   // the configuration is for the other layout of W_down
         if (!config_valid(*cfg, M, d_model, d_ff, dtype)) return DFK_ERR_UNSUPPORTED_SHAPE;
     }
     if (need_ws || ws || ws_bytes) {
@@ -232,6 +236,26 @@ std::vector<dfk_config_t> candidates(int M, int d_model, int d_ff, dfk_dtype_t d
     return out;
 }
 
+// W_down given as [d_model, d_ff]: the 64-token pair's gate/up kernel, then the down kernel whose workgroups own
+// slices of d_model (no sum across workgroups).  First in the list = the untuned default.
+std::vector<dfk_config_t> candidates_wdt(int M, int d_model, int d_ff, dfk_dtype_t dtype) {
+    std::vector<dfk_config_t> out;
+    if (dtype != DFK_BF16 && dtype != DFK_FP16) return out;
+    const int more_splits = d_ff > 512 * 64 ? ((d_ff + 63) / 64 + 255) / 256 * 256 : 512;
+    const int t16 = d_model / 16;
+    for (int wd : {82, 83, 84, 46})          // wavefronts, ring depth
+        for (int splits : {256, 512, more_splits})
+            for (int k2s : {256, 512, 128}) {
+                dfk_config_t c = make_cfg(DFK_VARIANT_TWO_KERNEL, DFK_PATH_MFMA, clamp_splits(splits, d_ff), wd / 10, wd % 10,
+                                          std::max(1, std::min(k2s, t16)), 1, (int)dtype, DFK_REDUCE_TICKET, 0, 5);
+                if (!config_valid(c, M, d_model, d_ff, dtype)) continue;
+                bool dup = false;
+                for (const auto& o : out) dup = dup || same_cfg(o, c);
+                if (!dup) out.push_back(c);
+            }
+    return out;
+}
+
 // Untuned default, from measurements on MI355X.  One token: the single launch that keeps A_2 in LDS, with the
 // atomic reduction (no boundary between two kernels, and its 256 full-width partial sums are still cheap).  Up to
 // 64 tokens: the single launch that holds both kernels' workgroups (atomic reduction), which saves the launch
@@ -270,6 +294,10 @@ struct Entry {
 using Key = std::tuple<int, int, int, int, int>;
 std::map<Key, Entry> g_table;
 void table_put(int M, int d_model, int d_ff, int dtype, const Entry& e, bool chosen) {   // g_mu held
+    if (wdt_layout(e.cfg)) {   // the other layout of W_down has a slot of its own and never is the plain choice
+        g_table[Key(M, d_model, d_ff, dtype, 3)] = e;
+        return;
+    }
     g_table[Key(M, d_model, d_ff, dtype, e.cfg.variant)] = e;
     if (chosen) g_table[Key(M, d_model, d_ff, dtype, 0)] = e;
 }
@@ -291,6 +319,19 @@ bool lookup(int M, int d_model, int d_ff, dfk_dtype_t dtype, int want_variant, d
         return true;
     }
     return false;
+}
+
+constexpr int kSlotWdt = 3;   // table slot of the best configuration for W_down as [d_model, d_ff]
+bool choose_wdt(int M, int d_model, int d_ff, dfk_dtype_t dtype, dfk_config_t* out, int* tuned) {
+    if (lookup(M, d_model, d_ff, dtype, kSlotWdt, out)) {
+        if (tuned) *tuned = 1;
+        return true;
+    }
+    if (tuned) *tuned = 0;
+    auto cands = candidates_wdt(M, d_model, d_ff, dtype);
+    if (cands.empty()) return false;
+    *out = cands[0];
+    return true;
 }
 
 bool choose(int M, int d_model, int d_ff, dfk_dtype_t dtype, int want_variant, dfk_config_t* out,
@@ -362,12 +403,13 @@ dfk_status_t run(const void* X, const void* Wg, const void* Wu, const void* Wd, 
 
 dfk_status_t call(const void* X, const void* Wg, const void* Wu, const void* Wd, void* Y, int M,
                   int d_model, int d_ff, dfk_dtype_t dtype, const dfk_config_t* cfg, int want_variant,
-                  void* ws, size_t ws_bytes, void* stream) {
-    dfk_status_t s = check(X, Wg, Wu, Wd, Y, M, d_model, d_ff, dtype, cfg, ws, ws_bytes, true);
+                  void* ws, size_t ws_bytes, void* stream, bool wd_t = false) {
+    dfk_status_t s = check(X, Wg, Wu, Wd, Y, M, d_model, d_ff, dtype, cfg, ws, ws_bytes, true, false, wd_t);
     if (s != DFK_OK) return s;
     dfk_config_t c;
     if (cfg) c = *cfg;
-    else if (!choose(M, d_model, d_ff, dtype, want_variant, &c, nullptr)) return DFK_ERR_UNSUPPORTED_SHAPE;
+    else if (wd_t ? !choose_wdt(M, d_model, d_ff, dtype, &c, nullptr)
+                  : !choose(M, d_model, d_ff, dtype, want_variant, &c, nullptr)) return DFK_ERR_UNSUPPORTED_SHAPE;
     return run(X, Wg, Wu, Wd, Y, M, d_model, d_ff, dtype, c, ws, (hipStream_t)stream);
 }
 
@@ -568,6 +610,14 @@ dfk_status_t dfk_swiglu_mlp_ex(const void* X, const void* Wg, const void* Wu, co
                 workspace_bytes, stream);
 }
 
+dfk_status_t dfk_swiglu_mlp_wdt(const void* X, const void* Wg, const void* Wu, const void* Wd_t, void* Y,
+                                int M, int d_model, int d_ff, dfk_dtype_t dtype,
+                                const dfk_config_t* cfg, void* workspace, size_t workspace_bytes,
+                                void* stream) {
+    return call(X, Wg, Wu, Wd_t, Y, M, d_model, d_ff, dtype, cfg, DFK_VARIANT_AUTO, workspace,
+                workspace_bytes, stream, true);
+}
+
 dfk_status_t dfk_swiglu_mlp_static(const void* X, const void* Wg, const void* Wu, const void* Wd, void* Y,
                                    int M, int d_model, int d_ff, dfk_dtype_t dtype, const dfk_config_t* cfg,
                                    void* stream) {
@@ -676,6 +726,27 @@ dfk_status_t dfk_set_trace_buffer(void* buffer, size_t bytes) {
     return DFK_OK;
 }
 
+int dfk_num_candidates_wdt(int M, int d_model, int d_ff, dfk_dtype_t dtype) {
+    if (!shape_supported(M, d_model, d_ff)) return 0;
+    return (int)candidates_wdt(M, d_model, d_ff, dtype).size();
+}
+
+dfk_status_t dfk_get_candidate_wdt(int M, int d_model, int d_ff, dfk_dtype_t dtype, int i, dfk_config_t* out) {
+    if (!out) return DFK_ERR_INVALID_ARG;
+    if (!shape_supported(M, d_model, d_ff)) return DFK_ERR_UNSUPPORTED_SHAPE;
+    auto c = candidates_wdt(M, d_model, d_ff, dtype);
+    if (i < 0 || i >= (int)c.size()) return DFK_ERR_NOT_FOUND;
+    *out = c[i];
+    return DFK_OK;
+}
+
+dfk_status_t dfk_get_choice_wdt(int M, int d_model, int d_ff, dfk_dtype_t dtype, dfk_config_t* out, int* tuned_out) {
+    if (!out) return DFK_ERR_INVALID_ARG;
+    if (M < 1 || d_model < 1 || d_ff < 1) return DFK_ERR_INVALID_ARG;
+    if (!shape_supported(M, d_model, d_ff)) return DFK_ERR_UNSUPPORTED_SHAPE;
+    return choose_wdt(M, d_model, d_ff, dtype, out, tuned_out) ? DFK_OK : DFK_ERR_UNSUPPORTED_SHAPE;
+}
+
 int dfk_num_candidates(int M, int d_model, int d_ff, dfk_dtype_t dtype) {
     if (!shape_supported(M, d_model, d_ff)) return 0;
     return (int)candidates(M, d_model, d_ff, dtype).size();
@@ -764,9 +835,23 @@ dfk_status_t dfk_tune(const int* M_list, int nM, int d_model, int d_ff, dfk_dtyp
             if (bv.usec < 0.0 || us < bv.usec) { bv.cfg = c; bv.usec = us; }
         }
         if (best.usec < 0.0) return g_tune_skip_status;   // every candidate of this M failed
+        // the candidates for W_down as [d_model, d_ff] (timing does not depend on what the synthetic weights mean)
+        Entry best_t;
+        best_t.usec = -1.0;
+        for (const auto& c : candidates_wdt(M, d_model, d_ff, dtype)) {
+            double us = 0.0;
+            dfk_status_t s = time_config(c, M, d_model, d_ff, dtype, scratch, sets, iters, (hipStream_t)stream, false, &us);
+            if (s != DFK_OK) {
+                ++g_tune_skipped;
+                g_tune_skip_status = s;
+                continue;
+            }
+            if (best_t.usec < 0.0 || us < best_t.usec) { best_t.cfg = c; best_t.usec = us; }
+        }
         std::lock_guard<std::mutex> lk(g_mu);
         for (int v = 1; v <= 2; ++v)
             if (best_of[v].usec >= 0.0) table_put(M, d_model, d_ff, (int)dtype, best_of[v], false);
+        if (best_t.usec >= 0.0) table_put(M, d_model, d_ff, (int)dtype, best_t, false);
         table_put(M, d_model, d_ff, (int)dtype, best, true);
     }
     return DFK_OK;
@@ -865,6 +950,17 @@ dfk_status_t dfk_load_tuning(const char* path) {
     for (const auto& kv : fresh)
         table_put(std::get<0>(kv.first), std::get<1>(kv.first), std::get<2>(kv.first), std::get<3>(kv.first), kv.second, true);
     return DFK_OK;
+}
+
+dfk_status_t dfk_transpose_w_down(const void* Wd, void* Wd_t, int d_model, int d_ff, dfk_dtype_t dtype, void* stream) {
+    if (!Wd || !Wd_t || d_model < 1 || d_ff < 1) return DFK_ERR_INVALID_ARG;
+    if (dtype != DFK_BF16 && dtype != DFK_FP32 && dtype != DFK_FP16) return DFK_ERR_INVALID_ARG;
+    if ((uintptr_t)Wd % 16 || (uintptr_t)Wd_t % 16) return DFK_ERR_ALIGNMENT;
+    if ((d_ff + 31) / 32 > 65535) return DFK_ERR_UNSUPPORTED_SHAPE;
+    const size_t nw = (size_t)d_ff * d_model * elt_bytes(dtype);
+    if (overlaps(Wd, nw, Wd_t, nw)) return DFK_ERR_ALIAS;
+    hipError_t e = launch_transpose(Wd, Wd_t, d_ff, d_model, dtype, (hipStream_t)stream);
+    return e == hipSuccess ? DFK_OK : hip_fail(e);
 }
 
 dfk_status_t dfk_rms_normalize(const void* in, void* out, int M, int d_model, void* stream) {

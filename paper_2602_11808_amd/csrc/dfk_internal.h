@@ -153,6 +153,8 @@ hipError_t launch_mfma_km(const MlpArgs& a, const dfk_config_t& c, hipStream_t s
 bool mfma_km_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype);
 bool mfma_km_block_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype);
 int mfma_km_tokens_per_launch();
+// the pair whose down kernel takes W_down as [d_model, d_ff] (kmajor = 5)
+bool mfma_km_t_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype);
 // both kernels' workgroups in one launch (variant FUSED, kmajor = 4)
 hipError_t launch_mfma_km_roles(const MlpArgs& a, const dfk_config_t& c, hipStream_t st);
 bool mfma_km_roles_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype);
@@ -171,6 +173,7 @@ int valu_max_tokens_per_launch();
 
 // utility kernels
 hipError_t launch_zero(void* p, size_t bytes, hipStream_t st);
+hipError_t launch_transpose(const void* in, void* out, int rows, int cols, dfk_dtype_t dtype, hipStream_t st);
 hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, hipStream_t st);
 hipError_t launch_read_gateup_pattern(const void* Wg, const void* Wu, int d_model, int d_ff, int splits, int waves,
                                       void* sink, hipStream_t st);

@@ -796,7 +796,7 @@ hipError_t launch_mfma_mixed(const MlpArgs& a, const dfk_config_t& c, hipStream_
 }
 
 int mfma_max_tokens_per_launch(const dfk_config_t& c, int d_model) {
-    if (c.kmajor == 4) return mfma_km_tokens_per_launch();
+    if (c.kmajor == 4 || c.kmajor == 5) return mfma_km_tokens_per_launch();
     if (c.kmajor == 3) return mfma_km_tokens_per_launch();
     if (c.kmajor == 2) return mfma_big_tokens_per_launch();
     if (c.kmajor == 1 && c.variant == DFK_VARIANT_FUSED) return mfma_fused_km_tokens_per_launch();
@@ -805,6 +805,7 @@ int mfma_max_tokens_per_launch(const dfk_config_t& c, int d_model) {
 
 bool mfma_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype) {
     if (c.kmajor == 4) return mfma_km_roles_config_valid(c, M, d_model, d_ff, dtype);
+    if (c.kmajor == 5) return mfma_km_t_config_valid(c, M, d_model, d_ff, dtype);
     if (c.kmajor == 3) return mfma_mixed_config_valid(c, M, d_model, d_ff, dtype);
     if (c.kmajor == 2) return mfma_big_config_valid(c, M, d_model, d_ff, dtype);
     if (c.kmajor == 1 && c.variant == DFK_VARIANT_FUSED) return mfma_fused_km_config_valid(c, M, d_model, d_ff, dtype);

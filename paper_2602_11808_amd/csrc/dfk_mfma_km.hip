@@ -75,6 +75,7 @@ struct KmStream1 {
     size_t w_base;             // byte offset of (row j0, this wavefront's first k)
     size_t x_base;             // byte offset of (token m_base, this wavefront's first k)
     int nt, nkc, m_count;
+    int tile_rows;             // weight rows between consecutive row tiles (8: gate and up rows side by side; 16: one matrix)
     int q, g;
     unsigned off1[4];
     unsigned char* ring;
@@ -92,7 +93,7 @@ struct KmStream1 {
                 __builtin_amdgcn_global_load_lds(src, DFK_LDS_PTR(slot + u * 1024), 16, 0, 0);
             }
         } else {               // weight tile of row tile p_idx - TT: 8 rows of W_gate, the same 8 of W_up
-            const size_t tb = w_base + (size_t)(p_idx - TT) * 8 * row_bytes + (size_t)p_kc * (kKC * 2);
+            const size_t tb = w_base + (size_t)(p_idx - TT) * tile_rows * row_bytes + (size_t)p_kc * (kKC * 2);
             const char* gb = Wg + tb;
             const char* ub = Wu + tb;
 #pragma unroll
@@ -140,7 +141,12 @@ struct KmStream1 {
 //
 // PUBLISH (the single launch that holds both kernels' workgroups, further down): A_2 is stored
 // with device-scope stores and the workgroup ends by counting itself done on kRoleDone.
-template <int NW, int TT, typename E, bool NORM, bool PUBLISH>
+//
+// DOWN_T: the same stream and accumulation computes the down projection from W_down given as [d_model, d_ff]
+// (a linear layer's own [out, in] layout): Y^T = W_down^T A_2^T has the shape of stage one, with d_ff as the k
+// range, a row tile = 16 rows of one matrix, A_2 in X's place, and workgroup s owning a slice of d_model whole:
+// nothing is summed across workgroups, the end just adds the wavefronts' k-partial sums and stores Y.
+template <int NW, int TT, typename E, bool NORM, bool PUBLISH, bool DOWN_T = false>
 __device__ __forceinline__ void gateup_km_body(const MlpArgs& a, const KmGeom& geo, const int wg, unsigned char* lds) {
     constexpr int TOK = 16 * TT;
     constexpr int NTHREADS = NW * 64;
@@ -150,24 +156,37 @@ __device__ __forceinline__ void gateup_km_body(const MlpArgs& a, const KmGeom& g
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int q = lane & 15, g = lane >> 4;
     int j0, j1;
-    slice_rows(a.d_ff, a.splits, wg, j0, j1);
-    const int nt = (j1 - j0) / 8;                 // <= NT, checked on the host
+    if (DOWN_T) {            // slices of d_model, in whole 16-row tiles
+        const long long t16 = a.d_model / 16;
+        j0 = (int)(t16 * wg / a.k2_splits) * 16;
+        j1 = (int)(t16 * (wg + 1) / a.k2_splits) * 16;
+    } else {
+        slice_rows(a.d_ff, a.splits, wg, j0, j1);
+    }
+    const int nt = (j1 - j0) / (DOWN_T ? 16 : 8);   // <= NT, checked on the host
     // The 128-k chunks of a row are dealt out to the wavefronts in contiguous runs, as evenly as
-    // their number allows (equal runs when d_model is a multiple of 128 * NW).
-    const int nchunks = a.d_model / kKC;
+    // their number allows (equal runs when the k range is a multiple of 128 * NW).
+    const int kdim = DOWN_T ? a.d_ff : a.d_model;
+    const int nchunks = kdim / kKC;
     const int c0 = wave * nchunks / NW, c1 = (wave + 1) * nchunks / NW;
     const size_t kbase = (size_t)c0 * (kKC * 2);          // bytes into a row
 
     KmStream1<NW, TT> ts;
-    ts.Wg = (const char*)a.Wg; ts.Wu = (const char*)a.Wu; ts.X = (const char*)a.X;
-    ts.row_bytes = (size_t)a.d_model * 2;
+    ts.row_bytes = (size_t)kdim * 2;
+    if (DOWN_T) {
+        ts.Wg = (const char*)a.Wd; ts.Wu = (const char*)a.Wd + 8 * ts.row_bytes; ts.X = (const char*)a.a2;
+        ts.tile_rows = 16;
+    } else {
+        ts.Wg = (const char*)a.Wg; ts.Wu = (const char*)a.Wu; ts.X = (const char*)a.X;
+        ts.tile_rows = 8;
+    }
     ts.w_base = (size_t)j0 * ts.row_bytes + kbase;
     ts.x_base = (size_t)a.m_base * ts.row_bytes + kbase;
     ts.nt = nt; ts.nkc = c1 - c0; ts.m_count = a.m_count;
     ts.q = q; ts.g = g;
     ts.ring = lds + wave * geo.depth * kTileBytes;
     ts.depth = geo.depth;
-    DFK_STAMP(0);
+    DFK_STAMP(DOWN_T ? 3 : 0);
     // The wavefront's slice of the normalisation weight travels to LDS by the same asynchronous
     // loads as the tiles, issued ahead of them: they are the oldest in the queue, so the first
     // tile's counted wait covers them and no register or extra wait is involved.  Slices sit
@@ -233,7 +252,7 @@ __device__ __forceinline__ void gateup_km_body(const MlpArgs& a, const KmGeom& g
             }
         }
     }
-    DFK_STAMP(2);
+    DFK_STAMP(DOWN_T ? 4 : 2);
     if (NORM) {   // lanes (q, 0..3) hold the four k groups' shares of token q's squares
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt) {
@@ -260,6 +279,28 @@ __device__ __forceinline__ void gateup_km_body(const MlpArgs& a, const KmGeom& g
             }
         }
         __syncthreads();
+        if (DOWN_T) {
+            // task (row tile r of the pass, token m, row quad): four adjacent outputs of Y's row m
+            for (int t = tid; t < cnt * TOK * 4; t += NTHREADS) {
+                const int r = t / (TOK * 4), rem = t - r * (TOK * 4);
+                const int m = rem >> 2, quad = rem & 3;
+                if (m < a.m_count) {
+                    const float* src = stage + ((size_t)(r * NW) * TOK + m) * 16 + 4 * quad;
+                    f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int w = 0; w < NW; ++w) v += *(const f32x4*)(src + (size_t)w * TOK * 16);
+                    const size_t o = (size_t)(a.m_base + m) * a.d_model + j0 + (rt0 + r) * 16 + 4 * quad;
+                    if (a.resid) {
+                        float rr[4];
+                        E::load4(a.resid, o, rr);
+                        v[0] += rr[0]; v[1] += rr[1]; v[2] += rr[2]; v[3] += rr[3];
+                    }
+                    E::store4(a.Y, o, v[0], v[1], v[2], v[3]);
+                }
+            }
+            __syncthreads();
+            continue;
+        }
         // task (row tile r of the pass, token m, row pair pr): rows 2pr, 2pr+1 (gate) and 8 further on (up)
         for (int t = tid; t < cnt * TOK * 4; t += NTHREADS) {
             const int r = t / (TOK * 4), rem = t - r * (TOK * 4);
@@ -288,7 +329,7 @@ __device__ __forceinline__ void gateup_km_body(const MlpArgs& a, const KmGeom& g
         }
         __syncthreads();
     }
-    DFK_STAMP(1);   // A_2 stored
+    DFK_STAMP(DOWN_T ? 6 : 1);   // A_2 (or Y) stored
     if (PUBLISH && geo.role_publish) {
         drain_own_memory_ops();                  // this wavefront's A_2 stores are acknowledged
         __syncthreads();
@@ -305,6 +346,13 @@ template <int NW, int TT, typename E, bool NORM>
 __global__ __launch_bounds__(NW * 64) void k_gateup_km(MlpArgs a, KmGeom geo) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     gateup_km_body<NW, TT, E, NORM, false>(a, geo, blockIdx.x, lds);
+}
+
+// Down projection from W_down given as [d_model, d_ff]: k2_splits workgroups, a slice of d_model each.
+template <int NW, int TT, typename E>
+__global__ __launch_bounds__(NW * 64) void k_down_t_km(MlpArgs a, KmGeom geo) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    gateup_km_body<NW, TT, E, false, false, true>(a, geo, blockIdx.x, lds);
 }
 
 // ---------------------------------------------------------------- down kernel
@@ -698,6 +746,18 @@ size_t km_lds_down(const dfk_config_t& c, KmGeom* geo) {
     return std::max((size_t)c.waves * c.depth * kTileBytes, (size_t)c.waves * 16 * 128 * 4);
 }
 
+// down kernel on W_down as [d_model, d_ff]: rings, or the k-partial sums of as many 16-row tiles as fit
+int km_down_t_max_tiles(int d_model, int k2_splits) { return (d_model / 16 + k2_splits - 1) / k2_splits; }
+size_t km_lds_down_t(const dfk_config_t& c, int TT, int d_model, KmGeom* geo) {
+    const int nt_max = km_down_t_max_tiles(d_model, c.k2_splits);
+    const size_t ring = (size_t)c.waves * c.depth * kTileBytes;
+    const size_t per_tile = (size_t)c.waves * 16 * TT * 16 * 4;
+    geo->depth = c.depth;
+    geo->pass = std::max(1, std::min(nt_max, (int)((size_t)kLdsLimit / per_tile)));
+    geo->norm_off = 0;
+    return std::max(ring, (size_t)geo->pass * per_tile);
+}
+
 template <int NW, int TT, typename E>
 hipError_t launch_km_te(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
     static LdsAllowance allowed1, allowed1n, allowed2;   // of the three kernels of this instantiation, per device
@@ -716,6 +776,14 @@ hipError_t launch_km_te(const MlpArgs& a, const dfk_config_t& c, hipStream_t st)
         hipLaunchKernelGGL((k_gateup_km<NW, TT, E, true>), dim3(a.splits), dim3(NW * 64), lds, st, a, geo);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
+    }
+    if ((g_stage_mask & 2) && c.kmajor == 5) {
+        static LdsAllowance allowed2t;
+        KmGeom geo{};
+        const size_t lds = km_lds_down_t(c, TT, a.d_model, &geo);
+        if (hipError_t e = allow_lds(allowed2t, (const void*)k_down_t_km<NW, TT, E>, lds); e != hipSuccess) return e;
+        hipLaunchKernelGGL((k_down_t_km<NW, TT, E>), dim3(a.k2_splits), dim3(NW * 64), lds, st, a, geo);
+        return hipGetLastError();
     }
     if (g_stage_mask & 2) {
         KmGeom geo{};
@@ -785,6 +853,26 @@ bool mfma_km_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, d
     if (c.reduce == DFK_REDUCE_TICKET && !partials_fit(c.k2_splits, tokens, M, d_model)) return false;
     KmGeom geo{};
     return km_lds_gateup(c, TT, d_model, d_ff, false, &geo) <= (size_t)kLdsLimit && km_lds_down(c, &geo) <= (size_t)kLdsLimit;
+}
+
+// The pair whose down kernel takes W_down as [d_model, d_ff] (kmajor = 5): the gate/up kernel of the pair above, then
+// k2_splits workgroups that own a slice of d_model each.  d_ff is that kernel's k range: whole 128-k chunks, at
+// least one per wavefront.
+bool mfma_km_t_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype) {
+    if (c.path != DFK_PATH_MFMA || (dtype != DFK_BF16 && dtype != DFK_FP16) || c.variant != DFK_VARIANT_TWO_KERNEL) return false;
+    if (c.kmajor != 5 || c.k2_rows_by_wave != 0 || c.a2_dtype != (int)dtype || c.reduce != DFK_REDUCE_TICKET) return false;
+    if ((c.waves != 4 && c.waves != 8) || c.depth < 2 || c.depth > 16) return false;
+    if (M < 1 || d_model < 16 || d_ff < 8 || d_ff % 8 || d_model > kMaxDModel) return false;
+    if (d_model % kKC || d_model / kKC < c.waves) return false;          // gate/up kernel
+    if (d_ff % kKC || d_ff / kKC < c.waves || d_model % 16) return false; // down kernel
+    const int ng = d_ff / 8;
+    if (c.splits < 1 || c.splits > ng || c.splits > 65535) return false;
+    if (max_slice_rows(d_ff, c.splits) / 8 > kKmMaxRowTiles) return false;
+    if (c.k2_col_blocks != 1 || c.k2_splits < 1 || c.k2_splits > d_model / 16 || c.k2_splits > 65535) return false;
+    if (km_down_t_max_tiles(d_model, c.k2_splits) > kKmMaxRowTiles) return false;
+    const int TT = km_token_tiles(std::min(M, kKmTokensPerLaunch));
+    KmGeom geo{};
+    return km_lds_gateup(c, TT, d_model, d_ff, false, &geo) <= (size_t)kLdsLimit && km_lds_down_t(c, TT, d_model, &geo) <= (size_t)kLdsLimit;
 }
 
 // The pre-norm residual form runs on this kernel pair only; its gate/up kernel needs a

@@ -110,7 +110,30 @@ __global__ __launch_bounds__(256) void k_rmsnorm_weighted(const void* __restrict
     }
 }
 
+// out[c][r] = in[r][c] for a [rows][cols] matrix of 16- or 32-bit elements: 32 x 32 tiles through LDS (padded
+// against bank conflicts), reads and writes both along rows.
+template <typename T>
+__global__ __launch_bounds__(256) void k_transpose(const T* in, T* out, int rows, int cols) {
+    __shared__ T tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8 threads
+    const int c0 = blockIdx.x * 32, r0 = blockIdx.y * 32;
+    for (int i = ty; i < 32; i += 8)
+        if (r0 + i < rows && c0 + tx < cols) tile[i][tx] = in[(size_t)(r0 + i) * cols + c0 + tx];
+    __syncthreads();
+    for (int i = ty; i < 32; i += 8)
+        if (c0 + i < cols && r0 + tx < rows) out[(size_t)(c0 + i) * rows + r0 + tx] = tile[tx][i];
+}
+
 }  // namespace
+
+hipError_t launch_transpose(const void* in, void* out, int rows, int cols, dfk_dtype_t dtype, hipStream_t st) {
+    const dim3 grid((unsigned)((cols + 31) / 32), (unsigned)((rows + 31) / 32));
+    if (dtype == DFK_FP32)
+        hipLaunchKernelGGL(k_transpose<uint32_t>, grid, dim3(256), 0, st, (const uint32_t*)in, (uint32_t*)out, rows, cols);
+    else
+        hipLaunchKernelGGL(k_transpose<uint16_t>, grid, dim3(256), 0, st, (const uint16_t*)in, (uint16_t*)out, rows, cols);
+    return hipGetLastError();
+}
 
 hipError_t launch_rmsnorm_weighted(const void* in, const void* w, void* out, int M, int d_model, float eps, dfk_dtype_t dtype,
                                    hipStream_t st) {

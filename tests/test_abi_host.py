@@ -442,3 +442,58 @@ def test_valu_configuration_at_the_lds_boundary_is_refused_on_the_host():
 def test_tune_skip_report_starts_empty():
     n, status = dfk.dfk_tune_skipped()
     assert n == 0 and status == dfk.DFK_OK
+
+
+def test_a_configuration_belongs_to_one_layout_of_w_down(tmp_path):
+    """The kernels for W_down given as [d_model, d_ff] (kmajor = 5) are listed, chosen, stored and called apart
+    from the others; every mix-up is refused on the host, before any HIP call."""
+    import ctypes
+    L = dfk.lib()
+    dfk.dfk_clear_tuning()
+    n = dfk.dfk_workspace_bytes(16, D, FF)
+    wdt = [dfk.dfk_get_candidate_wdt(16, D, FF, dfk.DFK_BF16, i) for i in range(dfk.dfk_num_candidates_wdt(16, D, FF, dfk.DFK_BF16))]
+    plain = [dfk.dfk_get_candidate(16, D, FF, dfk.DFK_BF16, i) for i in range(dfk.dfk_num_candidates(16, D, FF, dfk.DFK_BF16))]
+    assert wdt and all(c.kmajor == 5 and dfk.dfk_config_valid(c, 16, D, FF, dfk.DFK_BF16) for c in wdt)
+    assert all(c.kmajor != 5 for c in plain)
+    args = (X, WG, WU, WD, Y, 16, D, FF, dfk.DFK_BF16)
+    # the wrong kind of configuration for an entry point
+    assert L.dfk_swiglu_mlp_ex(*args, ctypes.byref(wdt[0]), WS, n, None) == dfk.DFK_ERR_INVALID_ARG
+    assert L.dfk_swiglu_mlp_static(*args, ctypes.byref(wdt[0]), None) == dfk.DFK_ERR_INVALID_ARG
+    assert L.dfk_check_args(*args, ctypes.byref(wdt[0]), WS, n) == dfk.DFK_ERR_INVALID_ARG
+    assert L.dfk_swiglu_mlp_wdt(*args, ctypes.byref(plain[0]), WS, n, None) == dfk.DFK_ERR_INVALID_ARG
+    # argument checks of the entry point itself
+    assert L.dfk_swiglu_mlp_wdt(X, WG, WU, None, Y, 16, D, FF, dfk.DFK_BF16, None, WS, n, None) == dfk.DFK_ERR_INVALID_ARG
+    assert L.dfk_swiglu_mlp_wdt(*args, None, None, 0, None) == dfk.DFK_ERR_WORKSPACE
+    assert L.dfk_swiglu_mlp_wdt(*args, None, WS, n - 1, None) == dfk.DFK_ERR_WORKSPACE
+    assert L.dfk_swiglu_mlp_wdt(X, WG, WU, WD + 8, Y, 16, D, FF, dfk.DFK_BF16, None, WS, n, None) == dfk.DFK_ERR_ALIGNMENT
+    assert L.dfk_swiglu_mlp_wdt(X, WG, WU, Y, Y, 16, D, FF, dfk.DFK_BF16, None, WS, n, None) == dfk.DFK_ERR_ALIAS
+    # shapes and types its kernels do not take: no candidates, and the call says unsupported
+    for M_, d_, ff_, dt_ in ((16, D, FF, dfk.DFK_FP32), (16, D, FF + 8, dfk.DFK_BF16), (16, 264, 1024, dfk.DFK_BF16),
+                             (16, 4096, 384, dfk.DFK_BF16)):   # (fewer 128-k chunks of d_ff than wavefronts)
+        assert dfk.dfk_num_candidates_wdt(M_, d_, ff_, dt_) == 0
+        assert L.dfk_swiglu_mlp_wdt(X, WG, WU, WD, Y, M_, d_, ff_, dt_, None, WS, 1 << 40, None) == dfk.DFK_ERR_UNSUPPORTED_SHAPE
+        with pytest.raises(dfk.DfkError):
+            dfk.dfk_get_choice_wdt(M_, d_, ff_, dt_)
+    # the table keeps the layouts apart, also through a file
+    pick, tuned = dfk.dfk_get_choice_wdt(16, D, FF, dfk.DFK_BF16)
+    assert not tuned and pick.as_dict() == wdt[0].as_dict()
+    dfk.dfk_set_choice(16, D, FF, dfk.DFK_BF16, wdt[-1], 60.0)
+    dfk.dfk_set_choice(16, D, FF, dfk.DFK_BF16, plain[3], 61.0)
+    assert dfk.dfk_get_choice_wdt(16, D, FF, dfk.DFK_BF16)[0].as_dict() == wdt[-1].as_dict()
+    assert dfk.dfk_get_choice(16, D, FF, dfk.DFK_BF16)[0].as_dict() == plain[3].as_dict()
+    path = str(tmp_path / "tuning.txt")
+    dfk.dfk_save_tuning(path)
+    dfk.dfk_clear_tuning()
+    dfk.dfk_load_tuning(path)
+    got, tuned = dfk.dfk_get_choice_wdt(16, D, FF, dfk.DFK_BF16)
+    assert tuned and got.as_dict() == wdt[-1].as_dict()
+    got, tuned = dfk.dfk_get_choice(16, D, FF, dfk.DFK_BF16)
+    assert tuned and got.as_dict() == plain[3].as_dict()
+    dfk.dfk_clear_tuning()
+    # the transpose helper
+    tr = L.dfk_transpose_w_down
+    assert tr(None, WD, D, FF, dfk.DFK_BF16, None) == dfk.DFK_ERR_INVALID_ARG
+    assert tr(WD, WD + 2 * A, 0, FF, dfk.DFK_BF16, None) == dfk.DFK_ERR_INVALID_ARG
+    assert tr(WD, WD + 2 * A, D, FF, 9, None) == dfk.DFK_ERR_INVALID_ARG
+    assert tr(WD + 4, WD + 2 * A, D, FF, dfk.DFK_BF16, None) == dfk.DFK_ERR_ALIGNMENT
+    assert tr(WD, WD + 4096, D, FF, dfk.DFK_BF16, None) == dfk.DFK_ERR_ALIAS
