@@ -475,6 +475,27 @@ def main():
         per_variant[name] = {str(M): stats_4x50(torch, np, lambda i, M=M, fn=fn: fn(X[M], layers[i]["Wg"], layers[i]["Wu"], layers[i]["Wd"], Y[M]),
                                                 WEIGHT_SETS) for M in M_SET}
 
+    # ---- the same block with the down projection's weights in a linear layer's own [out, in] layout
+    # (W_down_t [d_model, d_ff], dfk_swiglu_mlp_wdt): its down kernel sums nothing across workgroups.  Beside the
+    # headline, which stays on the layout the paper writes (Y = A_2 W_down with W_down [d_ff, d_model]).
+    wdt = {}
+    wd_t = []
+    for l in layers:
+        t = torch.empty((D_MODEL, D_FF), dtype=l["Wd"].dtype, device=dev)
+        dfk.dfk_transpose_w_down(l["Wd"], t)
+        wd_t.append(t)
+    for M in M_WIDE:
+        c, tuned = dfk.dfk_get_choice_wdt(M, D_MODEL, D_FF, dfk.DFK_BF16)
+        st = stats_4x50(torch, np, lambda i, M=M: dfk.dfk_swiglu_mlp_wdt(X[M], layers[i]["Wg"], layers[i]["Wu"], wd_t[i], Y[M], None, ws),
+                        WEIGHT_SETS)
+        b = algorithmic_bytes(M, D_MODEL, D_FF)
+        wdt[str(M)] = dict(st, frac_of_peak=round(b / st["mean_us"] / 1e3 / HBM_PEAK_GBS, 4), pick=dict(c.as_dict(), tuned=tuned))
+    wdt_block = {"layout": "W_down_t [d_model, d_ff]; two kernels, the down kernel's workgroups own slices of d_model",
+                 "mean_us_per_call_M_1_to_16": round(float(np.mean([wdt[str(M)]["mean_us"] for M in M_SET])), 2),
+                 "mean_frac_of_peak_M_1_to_16": round(float(np.mean([wdt[str(M)]["frac_of_peak"] for M in M_SET])), 4),
+                 "per_M_4x50": wdt}
+    del wd_t
+
     # ---- read-stream ceiling of this machine (plain 128-bit streaming reads), and one write-only kernel of known
     # size; both also calibrate the FETCH_SIZE / WRITE_SIZE counters
     sink = torch.zeros(2, dtype=torch.int32, device=dev)
@@ -632,7 +653,8 @@ def main():
         "achieved_tb_per_s": round(achieved / 1e3, 3),
         "second_headline_M_1_to_64": {"mean_us_per_call": round(mean_wide, 2), "mean_frac_of_peak": round(frac_wide, 4),
                                       "token_counts": list(M_WIDE), "protocol": "4 repeats x 50 launches per M"},
-        "per_M_4x50": per_m, "per_variant_4x50": per_variant, "per_M_launches": kernels, "scheduler_picks": picks,
+        "per_M_4x50": per_m, "per_variant_4x50": per_variant, "w_down_t_layout": wdt_block,
+        "per_M_launches": kernels, "scheduler_picks": picks,
         "tune_seconds": round(tune_s, 2), "tune_candidates_skipped": skipped,
         "roofline": roofline, "cpu_baseline": cpu, "parity": parity,
     }
