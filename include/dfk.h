@@ -266,6 +266,15 @@ dfk_status_t dfk_mlp_block(const void* H, const void* norm_weight, float eps,
                            const dfk_config_t* cfg,
                            void* workspace, size_t workspace_bytes, void* stream);
 
+/* The same with the down projection's weights given as W_down_t [d_model, d_ff] (see dfk_swiglu_mlp_wdt):
+ * cfg == NULL or a kmajor = 5 configuration; the normalisation is folded into the gate/up kernel as with
+ * kmajor = 1, the residual is added where the down kernel stores Y. */
+dfk_status_t dfk_mlp_block_wdt(const void* H, const void* norm_weight, float eps,
+                               const void* W_gate, const void* W_up, const void* W_down_t,
+                               void* H_out, int M, int d_model, int d_ff, dfk_dtype_t dtype,
+                               const dfk_config_t* cfg,
+                               void* workspace, size_t workspace_bytes, void* stream);
+
 /* Host-only argument check: exactly the validation the calls above perform,
  * with no HIP call.  cfg may be NULL.  workspace may be NULL only if
  * workspace_bytes is 0, in which case the workspace checks are skipped. */

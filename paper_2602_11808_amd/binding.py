@@ -68,6 +68,7 @@ SIGNATURES = [
     ("dfk_get_choice_wdt", _ci, [_ci] * 4 + [_cfgp, ctypes.POINTER(_ci)]),
     ("dfk_swiglu_mlp_static", _ci, [_vp] * 5 + [_ci] * 4 + [_cfgp, _vp]),
     ("dfk_mlp_block", _ci, [_vp, _vp, ctypes.c_float] + [_vp] * 4 + [_ci] * 4 + [_cfgp, _vp, _sz, _vp]),
+    ("dfk_mlp_block_wdt", _ci, [_vp, _vp, ctypes.c_float] + [_vp] * 4 + [_ci] * 4 + [_cfgp, _vp, _sz, _vp]),
     ("dfk_check_args", _ci, [_vp] * 5 + [_ci] * 4 + [_cfgp, _vp, _sz]),
     ("dfk_workspace_bytes", _sz, [_ci] * 3),
     ("dfk_workspace_init", _ci, [_vp, _sz, _vp]),
@@ -225,6 +226,20 @@ def dfk_mlp_block(H, norm_weight, eps: float, W_gate, W_up, W_down, H_out, cfg: 
                                _ptr(H_out), M, d, ff, _dtype_code(H),
                                ctypes.byref(cfg) if cfg is not None else None,
                                _ptr(workspace), nbytes, _stream(stream)), "dfk_mlp_block")
+
+
+def dfk_mlp_block_wdt(H, norm_weight, eps: float, W_gate, W_up, W_down_t, H_out, cfg: Optional[dfk_config_t], workspace,
+                      stream=None):
+    """dfk_mlp_block with the down projection's weights as W_down_t [d_model, d_ff]."""
+    M, d, ff = _shapes(H, W_gate, W_up, W_down_t, H_out, wd_t=True)
+    if not norm_weight.is_cuda or not norm_weight.is_contiguous() or norm_weight.dtype != H.dtype \
+            or tuple(norm_weight.shape) != (d,):
+        raise ValueError("norm_weight must be a dense device vector [d_model] of the inputs' type")
+    nbytes = workspace.numel() * workspace.element_size()
+    _check(lib().dfk_mlp_block_wdt(_ptr(H), _ptr(norm_weight), float(eps), _ptr(W_gate), _ptr(W_up), _ptr(W_down_t),
+                                   _ptr(H_out), M, d, ff, _dtype_code(H),
+                                   ctypes.byref(cfg) if cfg is not None else None,
+                                   _ptr(workspace), nbytes, _stream(stream)), "dfk_mlp_block_wdt")
 
 
 def dfk_check_args(X, W_gate, W_up, W_down, Y, M, d_model, d_ff, dtype=DFK_BF16, cfg=None,

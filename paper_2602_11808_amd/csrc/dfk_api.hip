@@ -364,7 +364,7 @@ dfk_status_t run_in(const WsLayout& l, const void* X, const void* Wg, const void
     a.Q = (float*)((char*)ws + l.q_off);
     a.a2 = (char*)ws + l.a2_off;
     a.norm_w = norm_w; a.eps = eps; a.resid = resid;
-    if (norm_w && (c.kmajor == 2 || !mfma_km_block_config_valid(c, M, d_model, d_ff, dtype))) {
+    if (norm_w && (c.kmajor == 2 || !mfma_km_block_config_valid(c, M, d_model, d_ff, dtype))) {   // (kmajor 1 and 5 fold it)
         // The 256-token pair is paced by its MFMA and LDS work, so scaling X inside every workgroup
         // costs more there than one small launch that writes the normalised input once.  The
         // 64-token pair folds the normalisation into its gate/up kernel unless the slices of the
@@ -653,10 +653,11 @@ dfk_status_t dfk_swiglu_mlp_static(const void* X, const void* Wg, const void* Wu
     return run_in(l, X, Wg, Wu, Wd, Y, M, d_model, d_ff, dtype, c, ws, (hipStream_t)stream);
 }
 
-dfk_status_t dfk_mlp_block(const void* H, const void* norm_weight, float eps, const void* Wg,
-                           const void* Wu, const void* Wd, void* H_out, int M, int d_model, int d_ff,
-                           dfk_dtype_t dtype, const dfk_config_t* cfg, void* workspace,
-                           size_t workspace_bytes, void* stream) {
+namespace {
+dfk_status_t mlp_block(const void* H, const void* norm_weight, float eps, const void* Wg,
+                       const void* Wu, const void* Wd, void* H_out, int M, int d_model, int d_ff,
+                       dfk_dtype_t dtype, const dfk_config_t* cfg, void* workspace,
+                       size_t workspace_bytes, void* stream, bool wd_t) {
     if (!H || !norm_weight || !H_out) return DFK_ERR_INVALID_ARG;
     if (!(eps >= 0.f) || !(eps < 1e30f)) return DFK_ERR_INVALID_ARG;
     if (dtype != DFK_BF16 && dtype != DFK_FP16)
@@ -664,7 +665,7 @@ dfk_status_t dfk_mlp_block(const void* H, const void* norm_weight, float eps, co
     if ((uintptr_t)norm_weight % 16) return DFK_ERR_ALIGNMENT;
     // The output may be the input itself (the residual stream updated in place); any other
     // overlap is refused.
-    dfk_status_t s = check(H, Wg, Wu, Wd, H_out, M, d_model, d_ff, dtype, cfg, workspace, workspace_bytes, true, true);
+    dfk_status_t s = check(H, Wg, Wu, Wd, H_out, M, d_model, d_ff, dtype, cfg, workspace, workspace_bytes, true, true, wd_t);
     if (s != DFK_OK) return s;
     {
         const size_t nx = (size_t)M * d_model * 2, nv = (size_t)d_model * 2;
@@ -672,6 +673,7 @@ dfk_status_t dfk_mlp_block(const void* H, const void* norm_weight, float eps, co
             return DFK_ERR_ALIAS;
     }
     auto carries = [&](const dfk_config_t& k) {
+        if (wd_t) return k.path == DFK_PATH_MFMA && k.kmajor == 5 && mfma_km_t_config_valid(k, M, d_model, d_ff, dtype);
         return k.path == DFK_PATH_MFMA &&
                ((k.kmajor == 1 && mfma_km_config_valid(k, M, d_model, d_ff, dtype)) ||
                 (k.kmajor == 2 && mfma_big_config_valid(k, M, d_model, d_ff, dtype)));
@@ -679,16 +681,32 @@ dfk_status_t dfk_mlp_block(const void* H, const void* norm_weight, float eps, co
     dfk_config_t c;
     if (cfg) c = *cfg;
     else {
-        if (!choose(M, d_model, d_ff, dtype, DFK_VARIANT_TWO_KERNEL, &c, nullptr)) return DFK_ERR_UNSUPPORTED_SHAPE;
+        if (wd_t ? !choose_wdt(M, d_model, d_ff, dtype, &c, nullptr)
+                 : !choose(M, d_model, d_ff, dtype, DFK_VARIANT_TWO_KERNEL, &c, nullptr)) return DFK_ERR_UNSUPPORTED_SHAPE;
         if (!carries(c)) {   // the scheduler's pick is another kernel family: first candidate that carries this form
             bool found = false;
-            for (const auto& k : candidates(M, d_model, d_ff, dtype))
+            for (const auto& k : wd_t ? candidates_wdt(M, d_model, d_ff, dtype) : candidates(M, d_model, d_ff, dtype))
                 if (k.variant == DFK_VARIANT_TWO_KERNEL && carries(k)) { c = k; found = true; break; }
             if (!found) return DFK_ERR_UNSUPPORTED_SHAPE;
         }
     }
     if (!carries(c)) return DFK_ERR_UNSUPPORTED_SHAPE;
     return run(H, Wg, Wu, Wd, H_out, M, d_model, d_ff, dtype, c, workspace, (hipStream_t)stream, norm_weight, eps, H);
+}
+}  // namespace
+
+dfk_status_t dfk_mlp_block(const void* H, const void* norm_weight, float eps, const void* Wg,
+                           const void* Wu, const void* Wd, void* H_out, int M, int d_model, int d_ff,
+                           dfk_dtype_t dtype, const dfk_config_t* cfg, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+    return mlp_block(H, norm_weight, eps, Wg, Wu, Wd, H_out, M, d_model, d_ff, dtype, cfg, workspace, workspace_bytes, stream, false);
+}
+
+dfk_status_t dfk_mlp_block_wdt(const void* H, const void* norm_weight, float eps, const void* Wg,
+                               const void* Wu, const void* Wd_t, void* H_out, int M, int d_model, int d_ff,
+                               dfk_dtype_t dtype, const dfk_config_t* cfg, void* workspace,
+                               size_t workspace_bytes, void* stream) {
+    return mlp_block(H, norm_weight, eps, Wg, Wu, Wd_t, H_out, M, d_model, d_ff, dtype, cfg, workspace, workspace_bytes, stream, true);
 }
 
 dfk_status_t dfk_check_args(const void* X, const void* Wg, const void* Wu, const void* Wd,

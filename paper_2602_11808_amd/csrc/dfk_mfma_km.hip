@@ -878,7 +878,7 @@ bool mfma_km_t_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff,
 // The pre-norm residual form runs on this kernel pair only; its gate/up kernel needs a
 // little more LDS (weight of the normalisation, sums of squares).
 bool mfma_km_block_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype) {
-    if (!mfma_km_config_valid(c, M, d_model, d_ff, dtype)) return false;
+    if (c.kmajor == 5 ? !mfma_km_t_config_valid(c, M, d_model, d_ff, dtype) : !mfma_km_config_valid(c, M, d_model, d_ff, dtype)) return false;
     KmGeom geo{};
     return km_lds_gateup(c, km_token_tiles(std::min(M, kKmTokensPerLaunch)), d_model, d_ff, true, &geo) <= (size_t)kLdsLimit;
 }

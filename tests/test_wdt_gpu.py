@@ -159,3 +159,45 @@ def test_transposed_layout_in_a_replayed_graph_and_after_tuning():
         assert rel_err(y64(Y), ref) <= TOL_BF16
     finally:
         dfk.dfk_clear_tuning()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp16"])
+@pytest.mark.parametrize("shape", [(1, 1024, 2816), (16, 1024, 4224), (17, 2048, 3968), (64, 1024, 8192), (70, 1024, 2816),
+                                   (9, 640, 1152), (4, 4096, 14336)],
+                         ids=lambda s: "M%d_d%d_ff%d" % s)
+def test_mlp_block_with_norm_and_residual_transposed_layout(shape, dtype):
+    """H + MLP(RMSNorm(H)) with W_down_t, against the oracle's composition: every candidate of the layout, out of
+    place and in place (bit-identical: nothing depends on arrival order), the input untouched, and a configuration
+    of the other layout refused."""
+    M, d, ff = shape
+    eps = 1e-5
+    t = di.mlp_inputs(M, d, ff, seed=53, dtype=dtype)
+    t["w"] = di.tensor(1053, (d,), 1.0, dtype)
+    ref = oracle.mlp_block(t["X"], t["w"], eps, t["Wg"], t["Wu"], t["Wd"])
+    H64 = di.as_f64(t["X"])
+    g = {k: di.to_torch(v, DEV) for k, v in t.items()}
+    Wd_t = transposed(g["Wd"])
+    ws = dfk.new_workspace(M, d, ff, DEV)
+    tol = {"bf16": TOL_BF16, "fp16": 2e-3}[dtype]
+    other = dfk.dfk_get_candidate(M, d, ff, DT[dtype], 0)
+    with pytest.raises(dfk.DfkError) as ei:
+        dfk.dfk_mlp_block_wdt(g["X"], g["w"], eps, g["Wg"], g["Wu"], Wd_t, torch.empty_like(g["X"]), other, ws)
+    assert ei.value.status == dfk.DFK_ERR_INVALID_ARG
+    cfgs = cands(M, d, ff, DT[dtype])
+    if d * ff > 1 << 24:
+        cfgs = cfgs[:2]
+    for cfg in [None] + cfgs:
+        print("case block", shape, dtype, cfg, flush=True)
+        out = torch.full_like(g["X"], float("nan"))
+        dfk.dfk_mlp_block_wdt(g["X"], g["w"], eps, g["Wg"], g["Wu"], Wd_t, out, cfg, ws)
+        torch.cuda.synchronize()
+        got = y64(out)
+        assert_parity(got, ref, dtype, (shape, cfg))
+        assert rel_err(got - H64, ref - H64) <= tol, (shape, cfg, rel_err(got - H64, ref - H64))
+        assert clean(ws)
+        assert torch.equal(g["X"], di.to_torch(t["X"], DEV))
+        h = g["X"].clone()
+        dfk.dfk_mlp_block_wdt(h, g["w"], eps, g["Wg"], g["Wu"], Wd_t, h, cfg, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(h.view(torch.int16), out.view(torch.int16)), (shape, cfg)
+        assert clean(ws)
