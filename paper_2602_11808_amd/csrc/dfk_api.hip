@@ -1033,6 +1033,6 @@ const char* dfk_status_string(dfk_status_t s) {
 
 int dfk_last_hip_error(void) { return g_last_hip_error; }
 
-const char* dfk_version(void) { return "dfk 0.1 (gfx950)"; }
+const char* dfk_version(void) { return "dfk 0.2 (gfx950)"; }
 
 }  // extern "C"
