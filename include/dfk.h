@@ -16,7 +16,10 @@
  *     W_up   [d_ff, d_model]   transposed mathematical shape
  *     W_down [d_ff, d_model]   the mathematical shape
  *     Y      [M,    d_model]   output, fully overwritten (never accumulated into)
- * so that every d_ff slice of each weight matrix is one contiguous block.
+ * so that every d_ff slice of each weight matrix is one contiguous block.  The entry points with the
+ * suffix _wdt take the down projection's weights the other way round instead:
+ *     W_down_t [d_model, d_ff]  transposed mathematical shape (row n = column n of W_down)
+ * which is how a linear layer stores them ([out, in]), and how W_gate and W_up are stored here.
  * Element type: bfloat16 or IEEE half (inputs and Y; fp32 accumulation; A_2 is
  * rounded to the same 16-bit type on the MFMA path) or, in the fp32 test mode,
  * IEEE fp32 for inputs and Y.  Y must not overlap any input.
@@ -27,7 +30,8 @@
  * hipStream_t passed as void*, NULL = the default stream) and the call
  * returns at once.  The workspace holds arrival counters and the fp32
  * accumulator of the atomic reduction (its first 8 MiB + 4 KiB), the fp32
- * partial sums of Y and (two-kernel variant) A_2.  Counters and accumulator
+ * partial sums of Y and A_2 (two-kernel variant, and the single launch that holds both
+ * kernels' workgroups).  Counters and accumulator
  * must be zero before the first call (dfk_workspace_init) and every call leaves
  * them zero again, so a workspace may be reused by successive calls, of any
  * shape that fits, on ONE stream.  Calls that share a workspace and overlap in

@@ -84,10 +84,6 @@ __device__ __forceinline__ u32x4 lds_read_b128_raw(unsigned addr) {
     asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(addr) : "memory");
     return v;
 }
-// 16 bytes from an LDS byte address (the compiler schedules the wait).
-__device__ __forceinline__ u32x4 lds_ld16(unsigned addr) {
-    return *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)addr;
-}
 // LDS counter increment that returns the previous value (waits for it).
 __device__ __forceinline__ unsigned lds_inc_rtn_raw(unsigned addr) {
     unsigned old, one = 1u;
