@@ -273,6 +273,20 @@ def shapes(args, torch, di, dfk, dev, compact=False):
             rows[str(M)] = {"us_per_call": round(us, 2), "tb_per_s": round(algorithmic_bytes(M, d, ff) / us / 1e6, 3),
                             "frac_of_8tbs": round(algorithmic_bytes(M, d, ff) / us / 1e6 / 8.0, 4),
                             "variant": variant_name(c.variant, c.kmajor), "pick": dict(c.as_dict(), tuned=tuned)}
+            if M <= 16 and dfk.dfk_num_candidates_wdt(M, d, ff, dfk.DFK_BF16):
+                # the same call with W_down as [d_model, d_ff] (the weights' values do not matter for the time)
+                for it in range(-10, n):
+                    if it == 0:
+                        torch.cuda.synchronize()
+                        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        a.record()
+                    w = sets[it % 3]
+                    dfk.dfk_swiglu_mlp_wdt(X, w["Wg"], w["Wu"], w["Wd"].view(d, ff), Y, None, ws)
+                b.record()
+                torch.cuda.synchronize()
+                us_t = a.elapsed_time(b) * 1e3 / n
+                rows[str(M)]["w_down_t_layout"] = {"us_per_call": round(us_t, 2),
+                                                   "frac_of_8tbs": round(algorithmic_bytes(M, d, ff) / us_t / 1e6 / 8.0, 4)}
         out[name] = {"d_model": d, "d_ff": ff, "per_M": rows}
         del sets, ws
         torch.cuda.empty_cache()
