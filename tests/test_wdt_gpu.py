@@ -201,3 +201,24 @@ def test_mlp_block_with_norm_and_residual_transposed_layout(shape, dtype):
         torch.cuda.synchronize()
         assert torch.equal(h.view(torch.int16), out.view(torch.int16)), (shape, cfg)
         assert clean(ws)
+
+
+def test_a_thousand_launches_in_the_transposed_layout_give_identical_bits():
+    """No workgroup of this layout's down kernel sums another's partial result, so at the headline shape 1000 launches
+    in a row must reproduce the first result bit for bit, whatever order the workgroups run in; stops at the first
+    mismatch."""
+    d, ff = 4096, 14336
+    for M in (4, 16):
+        g = di.mlp_inputs_torch(M, d, ff, seed=59, device=DEV)
+        Wd_t = transposed(g["Wd"])
+        ws = dfk.new_workspace(M, d, ff, DEV)
+        first = torch.empty_like(g["X"])
+        dfk.dfk_swiglu_mlp_wdt(g["X"], g["Wg"], g["Wu"], Wd_t, first, None, ws)
+        Y = torch.empty_like(first)
+        print("case 1000 launches M", M, flush=True)
+        for i in range(1000):
+            dfk.dfk_swiglu_mlp_wdt(g["X"], g["Wg"], g["Wu"], Wd_t, Y, None, ws)
+            if i % 10 == 9 or i < 10:
+                assert torch.equal(first.view(torch.int16), Y.view(torch.int16)), (M, i)
+                Y.fill_(float("nan"))
+        torch.cuda.synchronize()
