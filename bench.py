@@ -164,10 +164,10 @@ def decode32(args, torch, di, dfk, dev, compact=False):
 
 def block32(args, torch, di, dfk, dev):
     """The block with its neighbours in a pre-norm decoder layer, 32 distinct layers chained and
-    replayed from a HIP graph: H <- H + MLP(RMSNorm(H; w_l)).  Two ways per token count: the one
-    call that folds normalisation and residual add into the block's two launches, and the same
+    replayed from a HIP graph: H <- H + MLP(RMSNorm(H; w_l)).  Per token count: the one
+    call that folds normalisation and residual add into the block's two launches, the same
     arithmetic as separate launches around the plain block (a normalisation kernel without the
-    weight, the block, an elementwise add)."""
+    weight, the block, an elementwise add), and the folded call with W_down as [d_model, d_ff]."""
     L = 32
     sweep = (1, 4, 16, 64, 256)
     eps = 1e-5
@@ -198,8 +198,17 @@ def block32(args, torch, di, dfk, dev):
                 dfk.dfk_swiglu_mlp(xn, w["Wg"], w["Wu"], w["Wd"], y, stream=stream)
                 torch.add(bufs[l], y, out=bufs[l + 1])
 
+        def folded_wdt(stream=None):     # the same weights read as W_down_t [d_model, d_ff]: the time does not depend on their values
+            for l in range(L):
+                w = layers[l]
+                dfk.dfk_mlp_block_wdt(bufs[l], nws[l], eps, w["Wg"], w["Wu"], w["Wd"].view(D_MODEL, D_FF), bufs[l + 1], None, ws,
+                                      stream=stream)
+
         row = {}
-        for name, chain in (("folded", folded), ("separate_launches", separate)):
+        chains = [("folded", folded), ("separate_launches", separate)]
+        if M <= 64:
+            chains.append(("folded_w_down_t_layout", folded_wdt))
+        for name, chain in chains:
             bufs[0].copy_(X0)
             chain()
             torch.cuda.synchronize()
