@@ -125,7 +125,9 @@ typedef enum { DFK_REDUCE_TICKET = 0, DFK_REDUCE_ATOMIC = 1 } dfk_reduce_t;
  *                  [d_model, d_ff] (dfk_swiglu_mlp_wdt only): k2_splits workgroups own a slice of
  *                  d_model each (whole 16-row tiles, at most 8 per workgroup), k2_col_blocks = 1,
  *                  reduce = DFK_REDUCE_TICKET (nothing is reduced across workgroups; the result
- *                  is deterministic), up to 64 tokens per launch;
+ *                  is deterministic), up to 64 tokens per launch.  With path = DFK_PATH_VALU the
+ *                  same pair in plain fp32 FMAs (any shape and type; k2_splits = workgroups of
+ *                  the down kernel, whose wavefronts own output columns whole);
  *                  3 = gate/up kernel of pair 2 with four wavefronts of one token tile each,
  *                  down kernel of pair 1 (offered for 33..64 tokens; waves = 8, depth = 3 or 4,
  *                  the constraints of both pairs).
@@ -200,11 +202,11 @@ dfk_status_t dfk_swiglu_mlp_ex(const void* X, const void* W_gate, const void* W_
  * the paper's W_down (Background, SwiGLU equations: Y = A_2 W_down): the [out, in] layout a linear layer's
  * weights are stored in, and the layout W_gate and W_up already have here.  Same result.  In this layout a
  * workgroup of the down kernel owns a slice of d_model over all of d_ff, so nothing is summed across workgroups
- * (config field kmajor = 5; 16-bit types, d_model a multiple of 128 and d_ff a multiple of 128 with at least
- * `waves` 128-k chunks each).  cfg == NULL: the scheduler's choice for this layout (dfk_get_choice_wdt); else
- * cfg must be a kmajor = 5 configuration (the other entry points reject those, and this one rejects the
- * others, with DFK_ERR_INVALID_ARG: a configuration belongs to one layout).  Shapes the layout's kernels do
- * not take: DFK_ERR_UNSUPPORTED_SHAPE.
+ * (config field kmajor = 5: on the MFMA path for the 16-bit types with d_model a multiple of 128 and d_ff a
+ * multiple of 128 with at least `waves` 128-k chunks each; on the VALU path for every supported shape and type).
+ * cfg == NULL: the scheduler's choice for this layout (dfk_get_choice_wdt); else cfg must be a kmajor = 5
+ * configuration (the other entry points reject those, and this one rejects the others, with
+ * DFK_ERR_INVALID_ARG: a configuration belongs to one layout).
  */
 dfk_status_t dfk_swiglu_mlp_wdt(const void* X, const void* W_gate, const void* W_up,
                                 const void* W_down_t, void* Y,
@@ -361,8 +363,8 @@ dfk_status_t dfk_time_kernels(const dfk_config_t* cfg, int M, int d_model, int d
 dfk_status_t dfk_get_choice(int M, int d_model, int d_ff, dfk_dtype_t dtype,
                             dfk_config_t* out, int* tuned_out);
 
-/* The same three queries for W_down given as [d_model, d_ff] (dfk_swiglu_mlp_wdt): its candidates (none for
- * shapes or types its kernels do not take), and the configuration a call would use now.  dfk_tune times these
+/* The same three queries for W_down given as [d_model, d_ff] (dfk_swiglu_mlp_wdt): its candidates, and the
+ * configuration a call would use now.  dfk_tune times these
  * candidates too and keeps the fastest beside the others. */
 int dfk_num_candidates_wdt(int M, int d_model, int d_ff, dfk_dtype_t dtype);
 dfk_status_t dfk_get_candidate_wdt(int M, int d_model, int d_ff, dfk_dtype_t dtype, int i, dfk_config_t* out);

@@ -59,7 +59,7 @@ bool config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype
 }
 
 // configurations whose down kernel takes W_down as [d_model, d_ff]
-bool wdt_layout(const dfk_config_t& c) { return c.path == DFK_PATH_MFMA && c.kmajor == 5; }
+bool wdt_layout(const dfk_config_t& c) { return c.kmajor == 5; }
 
 dfk_status_t check(const void* X, const void* Wg, const void* Wu, const void* Wd, const void* Y,
                    int M, int d_model, int d_ff, dfk_dtype_t dtype, const dfk_config_t* cfg,
@@ -240,7 +240,23 @@ std::vector<dfk_config_t> candidates(int M, int d_model, int d_ff, dfk_dtype_t d
 // slices of d_model (no sum across workgroups).  First in the list = the untuned default.
 std::vector<dfk_config_t> candidates_wdt(int M, int d_model, int d_ff, dfk_dtype_t dtype) {
     std::vector<dfk_config_t> out;
-    if (dtype != DFK_BF16 && dtype != DFK_FP16) return out;
+    // plain fp32-FMA kernels for every shape and type (after the MFMA pair in the list, where there is one)
+    auto valu = [&]() {
+        const int a2dt = dtype == DFK_BF16 ? DFK_BF16 : DFK_FP32;
+        for (int splits : {512, 1024})
+            for (int k2s : {256, 512}) {
+                dfk_config_t c = make_cfg(DFK_VARIANT_TWO_KERNEL, DFK_PATH_VALU, clamp_splits(splits, d_ff), 8, 0,
+                                          std::max(1, std::min(k2s, (d_model + 7) / 8)), 1, a2dt, DFK_REDUCE_TICKET, 0, 5);
+                if (!config_valid(c, M, d_model, d_ff, dtype)) continue;
+                bool dup = false;
+                for (const auto& o : out) dup = dup || same_cfg(o, c);
+                if (!dup) out.push_back(c);
+            }
+    };
+    if (dtype != DFK_BF16 && dtype != DFK_FP16) {
+        valu();
+        return out;
+    }
     const int more_splits = d_ff > 512 * 64 ? ((d_ff + 63) / 64 + 255) / 256 * 256 : 512;
     const int t16 = d_model / 16;
     for (int wd : {82, 83, 84, 46})          // wavefronts, ring depth
@@ -253,6 +269,7 @@ std::vector<dfk_config_t> candidates_wdt(int M, int d_model, int d_ff, dfk_dtype
                 for (const auto& o : out) dup = dup || same_cfg(o, c);
                 if (!dup) out.push_back(c);
             }
+    valu();
     return out;
 }
 

@@ -159,6 +159,56 @@ __global__ __launch_bounds__(512) void k_down_valu(MlpArgs a, int a2_stride) {
     reduce_store<E>(plan_column_block(a, cb, c_lo * E::VEC, c_hi * E::VEC), a.Y, a.m_base, &flag);
 }
 
+// Second kernel for W_down given as [d_model, d_ff] (config field kmajor = 5): row n of it is output column n over
+// all of d_ff, so each wavefront owns output columns whole, streams their rows with 128-bit loads against A_2 of the
+// launch's tokens and stores Y; nothing is summed across workgroups.
+template <typename E, int MT>
+__global__ __launch_bounds__(512) void k_down_t_valu(MlpArgs a) {
+    constexpr int VEC = E::VEC;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int nwaves = blockDim.x >> 6;
+    const int nchunk = a.d_ff / VEC;
+    for (int n = blockIdx.x * nwaves + wave; n < a.d_model; n += gridDim.x * nwaves) {
+        float acc[MT];
+#pragma unroll
+        for (int m = 0; m < MT; ++m) acc[m] = 0.f;
+#pragma unroll 2
+        for (int c = lane; c < nchunk; c += 64) {
+            float w[VEC];
+            E::widen(ld16_stream(a.Wd, (size_t)n * nchunk + c), w);
+#pragma unroll
+            for (int m = 0; m < MT; ++m) {
+                if (m < a.m_count) {
+                    const size_t o = (size_t)(a.m_base + m) * a.d_ff + (size_t)c * VEC;
+                    float s[VEC];
+                    if (a.a2_is_fp32) {
+#pragma unroll
+                        for (int v = 0; v < VEC; v += 4) {
+                            const float4 f = *(const float4*)((const float*)a.a2 + o + v);
+                            s[v] = f.x; s[v + 1] = f.y; s[v + 2] = f.z; s[v + 3] = f.w;
+                        }
+                    } else {     // bf16 A_2 (bf16 inputs only, VEC = 8): one 16-byte load
+#pragma unroll
+                        for (int v = 0; v < VEC; v += 2) {
+                            const uint32_t pk = *(const uint32_t*)((const uint16_t*)a.a2 + o + v);
+                            s[v] = bf16_lo(pk); s[v + 1] = bf16_hi(pk);
+                        }
+                    }
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) acc[m] = fmaf(s[v], w[v], acc[m]);
+                }
+            }
+        }
+#pragma unroll
+        for (int m = 0; m < MT; ++m) {
+#pragma unroll
+            for (int o = 32; o >= 1; o >>= 1) acc[m] += __shfl_xor(acc[m], o);
+            if (lane == 0 && m < a.m_count) E::store(a.Y, (size_t)(a.m_base + m) * a.d_model + n, acc[m]);
+        }
+    }
+}
+
 // smallest token-tile width that holds the launch's tokens (a launch has at most 8)
 int pick_mt(int m_count) { return m_count > 4 ? 8 : m_count > 2 ? 4 : m_count > 1 ? 2 : 1; }
 
@@ -180,6 +230,10 @@ hipError_t launch_t(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
         if (e != hipSuccess) return e;
     }
     if (!(g_stage_mask & 2)) return hipSuccess;
+    if (c.kmajor == 5) {
+        hipLaunchKernelGGL((k_down_t_valu<E, MT>), dim3(a.k2_splits), dim3(threads), 0, st, a);
+        return hipGetLastError();
+    }
     const int s2 = max_slice_rows(a.d_ff, a.k2_splits);
     hipLaunchKernelGGL((k_down_valu<E, MT>), dim3(a.k2_splits * a.k2_col_blocks), dim3(threads),
                        (size_t)MT * s2 * sizeof(float), st, a, s2);
@@ -201,7 +255,7 @@ hipError_t launch_e(const MlpArgs& a, const dfk_config_t& c, hipStream_t st) {
 bool valu_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_dtype_t dtype) {
     if (c.path != DFK_PATH_VALU) return false;
     if (c.variant != DFK_VARIANT_FUSED && c.variant != DFK_VARIANT_TWO_KERNEL) return false;
-    if (c.kmajor != 0) return false;
+    if (c.kmajor != 0 && !(c.kmajor == 5 && c.variant == DFK_VARIANT_TWO_KERNEL)) return false;   // 5: W_down as [d_model, d_ff]
     if (c.reduce != DFK_REDUCE_TICKET || c.k2_rows_by_wave != 0) return false;
     if (c.waves < 1 || c.waves > 8) return false;  // kernels are built for <= 512 threads
     if (M < 1 || d_model < 8 || d_ff < 8 || d_model % 8 || d_ff % 8) return false;
@@ -213,6 +267,10 @@ bool valu_config_valid(const dfk_config_t& c, int M, int d_model, int d_ff, dfk_
     if (c.variant == DFK_VARIANT_FUSED) {
         if ((c.splits + kGroupSize - 1) / kGroupSize > kTicketLevel2) return false;
         if (!partials_fit(c.splits, tokens, M, d_model)) return false;
+    }
+    if (c.variant == DFK_VARIANT_TWO_KERNEL && c.kmajor == 5) {
+        if (c.waves < 1 || c.k2_splits < 1 || c.k2_splits > 65535 || c.k2_col_blocks != 1) return false;
+        return c.a2_dtype == DFK_FP32 || (c.a2_dtype == DFK_BF16 && dtype == DFK_BF16);
     }
     if (c.variant == DFK_VARIANT_TWO_KERNEL) {
         if (c.k2_splits < 1 || c.k2_splits > ng) return false;

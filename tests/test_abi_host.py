@@ -467,13 +467,18 @@ def test_a_configuration_belongs_to_one_layout_of_w_down(tmp_path):
     assert L.dfk_swiglu_mlp_wdt(*args, None, WS, n - 1, None) == dfk.DFK_ERR_WORKSPACE
     assert L.dfk_swiglu_mlp_wdt(X, WG, WU, WD + 8, Y, 16, D, FF, dfk.DFK_BF16, None, WS, n, None) == dfk.DFK_ERR_ALIGNMENT
     assert L.dfk_swiglu_mlp_wdt(X, WG, WU, Y, Y, 16, D, FF, dfk.DFK_BF16, None, WS, n, None) == dfk.DFK_ERR_ALIAS
-    # shapes and types its kernels do not take: no candidates, and the call says unsupported
+    # shapes and types the MFMA kernels of this layout do not take are served by its plain-FMA pair
     for M_, d_, ff_, dt_ in ((16, D, FF, dfk.DFK_FP32), (16, D, FF + 8, dfk.DFK_BF16), (16, 264, 1024, dfk.DFK_BF16),
                              (16, 4096, 384, dfk.DFK_BF16)):   # (fewer 128-k chunks of d_ff than wavefronts)
-        assert dfk.dfk_num_candidates_wdt(M_, d_, ff_, dt_) == 0
-        assert L.dfk_swiglu_mlp_wdt(X, WG, WU, WD, Y, M_, d_, ff_, dt_, None, WS, 1 << 40, None) == dfk.DFK_ERR_UNSUPPORTED_SHAPE
-        with pytest.raises(dfk.DfkError):
-            dfk.dfk_get_choice_wdt(M_, d_, ff_, dt_)
+        cs = [dfk.dfk_get_candidate_wdt(M_, d_, ff_, dt_, i) for i in range(dfk.dfk_num_candidates_wdt(M_, d_, ff_, dt_))]
+        assert cs and all(c.kmajor == 5 and c.path == dfk.DFK_PATH_VALU for c in cs)
+        assert dfk.dfk_get_choice_wdt(M_, d_, ff_, dt_)[0].as_dict() == cs[0].as_dict()
+        assert L.dfk_swiglu_mlp_ex(X, WG, WU, WD, Y, M_, d_, ff_, dt_, ctypes.byref(cs[0]), WS, 1 << 40, None) == dfk.DFK_ERR_INVALID_ARG
+    # where both exist the MFMA pair comes first (the untuned default)
+    assert wdt[0].path == dfk.DFK_PATH_MFMA and wdt[-1].path == dfk.DFK_PATH_VALU
+    # unsupported shapes stay unsupported
+    assert dfk.dfk_num_candidates_wdt(16, 4100, FF, dfk.DFK_BF16) == 0
+    assert L.dfk_swiglu_mlp_wdt(X, WG, WU, WD, Y, 16, 4100, FF, dfk.DFK_BF16, None, WS, 1 << 40, None) == dfk.DFK_ERR_UNSUPPORTED_SHAPE
     # the table keeps the layouts apart, also through a file
     pick, tuned = dfk.dfk_get_choice_wdt(16, D, FF, dfk.DFK_BF16)
     assert not tuned and pick.as_dict() == wdt[0].as_dict()

@@ -46,16 +46,18 @@ def test_device_transpose_matches_numpy(shape, dtype):
     assert np.array_equal(got.view(np.uint8), np.ascontiguousarray(W.T).view(np.uint8))
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "fp16"])
+@pytest.mark.parametrize("dtype", ["bf16", "fp16", "fp32"])
 @pytest.mark.parametrize("shape", [(1, 1024, 2816), (16, 1024, 4224), (17, 2048, 3968), (33, 2048, 4096), (48, 1024, 2816),
                                    (64, 1024, 8192), (100, 1024, 2816), (3, 640, 1152), (40, 2304, 1536), (5, 512, 40960),
-                                   (16, 4096, 1024)],
+                                   (16, 4096, 1024), (1, 8, 8), (3, 264, 1000), (9, 520, 4104), (20, 1024, 2056)],
                          ids=lambda s: "M%d_d%d_ff%d" % s)
 def test_every_candidate_of_the_transposed_layout(shape, dtype):
     """One to four token tiles, a token count that needs two launches, d_model with 5 and 18 128-k chunks (uneven k
     split in the gate/up kernel; 144 sixteen-row tiles for the down kernel's slices), a d_ff beyond 512 slices of 64
-    rows, d_ff with 8 to 320 chunks for the down kernel's wavefronts; every call twice (the workspace must come back
-    clean, the result identical bit for bit: nothing is summed in an order that depends on arrival)."""
+    rows, d_ff with 8 to 320 chunks for the down kernel's wavefronts; the last four shapes and the fp32 test mode have
+    only the plain-FMA pair of this layout (widths that are no multiple of 128, a d_ff that is no multiple of 128);
+    every call twice (the workspace must come back clean, the result identical bit for bit: nothing is summed in an
+    order that depends on arrival)."""
     M, d, ff = shape
     t = di.mlp_inputs(M, d, ff, seed=41, dtype=dtype)
     ref = oracle.swiglu_mlp(t["X"], t["Wg"], t["Wu"], t["Wd"])
@@ -64,6 +66,9 @@ def test_every_candidate_of_the_transposed_layout(shape, dtype):
     ws = dfk.new_workspace(M, d, ff, DEV)
     cfgs = cands(M, d, ff, DT[dtype])
     assert cfgs and all(c.kmajor == 5 and dfk.dfk_config_valid(c, M, d, ff, DT[dtype]) for c in cfgs)
+    mfma_ok = dtype != "fp32" and d % 128 == 0 and ff % 128 == 0 and d // 128 >= 4 and ff // 128 >= 4
+    assert any(c.path == dfk.DFK_PATH_MFMA for c in cfgs) == mfma_ok
+    assert any(c.path == dfk.DFK_PATH_VALU for c in cfgs)
     for cfg in [None] + cfgs:
         print("case", shape, dtype, cfg, flush=True)
         first = None
@@ -76,7 +81,7 @@ def test_every_candidate_of_the_transposed_layout(shape, dtype):
             if first is None:
                 first = Y.clone()
             else:
-                assert torch.equal(first.view(torch.int16), Y.view(torch.int16)), (shape, cfg)
+                assert torch.equal(first.view(torch.uint8), Y.view(torch.uint8)), (shape, cfg)
 
 
 @pytest.mark.parametrize("d,ff", [(4096, 14336), (5120, 27648), (8192, 28672), (8192, 7168)],
@@ -183,7 +188,11 @@ def test_mlp_block_with_norm_and_residual_transposed_layout(shape, dtype):
     with pytest.raises(dfk.DfkError) as ei:
         dfk.dfk_mlp_block_wdt(g["X"], g["w"], eps, g["Wg"], g["Wu"], Wd_t, torch.empty_like(g["X"]), other, ws)
     assert ei.value.status == dfk.DFK_ERR_INVALID_ARG
-    cfgs = cands(M, d, ff, DT[dtype])
+    cfgs = [c for c in cands(M, d, ff, DT[dtype]) if c.path == dfk.DFK_PATH_MFMA]   # the plain-FMA pair does not carry the block
+    valu = next(c for c in cands(M, d, ff, DT[dtype]) if c.path == dfk.DFK_PATH_VALU)
+    with pytest.raises(dfk.DfkError) as ei:
+        dfk.dfk_mlp_block_wdt(g["X"], g["w"], eps, g["Wg"], g["Wu"], Wd_t, torch.empty_like(g["X"]), valu, ws)
+    assert ei.value.status == dfk.DFK_ERR_UNSUPPORTED_SHAPE
     if d * ff > 1 << 24:
         cfgs = cfgs[:2]
     for cfg in [None] + cfgs:
