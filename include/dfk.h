@@ -142,7 +142,10 @@ typedef enum { DFK_REDUCE_TICKET = 0, DFK_REDUCE_ATOMIC = 1 } dfk_reduce_t;
  *                  number of polls) until the gate/up workgroups of its d_ff rows have
  *                  published A_2, which crosses through device memory as between two kernels.
  *                  Up to 64 tokens per launch; waves = 8; otherwise the constraints of pair 1,
- *                  whose k2_splits, k2_col_blocks and reduce fields it uses;
+ *                  whose k2_splits, k2_col_blocks and reduce fields it uses.  The bound of the wait is
+ *                  about two million polls (seconds); a workgroup whose wait runs out turns its
+ *                  share of Y into NaN.  (Tests force that path from the host with the environment
+ *                  variable DFK_DEBUG_SPIN_LIMIT = number of polls; leave it unset otherwise.);
  *                  0 = the first single-launch kernel (bf16 only).
  */
 typedef struct dfk_config_t {

@@ -310,9 +310,10 @@ struct Entry {
 // DFK_VARIANT_TWO_KERNEL the best known configuration of that variant (what a call that asks for a variant gets).
 using Key = std::tuple<int, int, int, int, int>;
 std::map<Key, Entry> g_table;
+constexpr int kSlotWdt = 3;   // slot of the best configuration for W_down given as [d_model, d_ff]
 void table_put(int M, int d_model, int d_ff, int dtype, const Entry& e, bool chosen) {   // g_mu held
     if (wdt_layout(e.cfg)) {   // the other layout of W_down has a slot of its own and never is the plain choice
-        g_table[Key(M, d_model, d_ff, dtype, 3)] = e;
+        g_table[Key(M, d_model, d_ff, dtype, kSlotWdt)] = e;
         return;
     }
     g_table[Key(M, d_model, d_ff, dtype, e.cfg.variant)] = e;
@@ -338,7 +339,6 @@ bool lookup(int M, int d_model, int d_ff, dfk_dtype_t dtype, int want_variant, d
     return false;
 }
 
-constexpr int kSlotWdt = 3;   // table slot of the best configuration for W_down as [d_model, d_ff]
 bool choose_wdt(int M, int d_model, int d_ff, dfk_dtype_t dtype, dfk_config_t* out, int* tuned) {
     if (lookup(M, d_model, d_ff, dtype, kSlotWdt, out)) {
         if (tuned) *tuned = 1;
